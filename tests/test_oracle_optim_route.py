@@ -1,0 +1,203 @@
+"""Pins for the oracle's AdamW, outer step, path composition and routing (CPU only).
+
+Expected values come from closed forms, hand expansions with python floats, special cases the paper names
+(a path-specific module still takes the outer step; all-shared modules reduce to DiLoCo) and brute force.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import dipaco_inputs as gen
+from oracle import dipaco_oracle as orc
+
+
+# ------------------------------------------------------------------------------------------- AdamW
+def test_adamw_first_step_closed_form():
+    rng = np.random.default_rng(0)
+    theta = rng.standard_normal(50)
+    g = rng.standard_normal(50)
+    g[:3] = [0.0, 1e-12, -1e-12]
+    mask = (np.arange(50) % 2).astype(float)
+    lr, eps, wd = 1e-3, 1e-8, 0.1
+    new, m, v = orc.adamw_step(theta, g, np.zeros(50), np.zeros(50), 1, lr, 0.9, 0.95, eps, wd, mask)
+    # from zero state the bias corrections cancel the (1-beta) factors exactly: mhat = g, vhat = g^2
+    want = theta - lr * (g / (np.abs(g) + eps) + wd * mask * theta)
+    assert np.allclose(new, want, rtol=1e-13, atol=1e-18)
+    assert np.allclose(m, 0.1 * g) and np.allclose(v, 0.05 * g * g)
+    # no decay: the step has size lr*|g|/(|g|+eps) and opposes the gradient
+    new2, _, _ = orc.adamw_step(theta, g, np.zeros(50), np.zeros(50), 1, lr, 0.9, 0.95, eps, 0.0, mask)
+    assert np.allclose(np.abs(new2 - theta), lr * np.abs(g) / (np.abs(g) + eps), rtol=1e-9, atol=1e-20)
+    assert np.all((new2 - theta) * g <= 0)
+
+
+def test_adamw_two_steps_scalar_by_hand():
+    th, m, v = 0.5, 0.0, 0.0
+    b1, b2, lr, eps, wd = 0.9, 0.95, 0.01, 1e-8, 0.1
+    want = th
+    mm = vv = 0.0
+    for t, g in enumerate([0.3, -0.7], start=1):
+        mm = b1 * mm + (1 - b1) * g
+        vv = b2 * vv + (1 - b2) * g * g
+        want = want - lr * ((mm / (1 - b1 ** t)) / (math.sqrt(vv / (1 - b2 ** t)) + eps) + wd * want)
+    T, M, V = np.array([th]), np.array([m]), np.array([v])
+    for t, g in enumerate([0.3, -0.7], start=1):
+        T, M, V = orc.adamw_step(T, np.array([g]), M, V, t, lr, b1, b2, eps, wd, np.ones(1))
+    assert abs(T[0] - want) < 1e-15
+    assert abs(M[0] - mm) < 1e-16 and abs(V[0] - vv) < 1e-16
+
+
+def test_adamw_mask_switches_decay_off():
+    theta = np.array([2.0, 2.0]); g = np.array([1.0, 1.0])
+    new, _, _ = orc.adamw_step(theta, g, np.zeros(2), np.zeros(2), 1, 0.1, 0.9, 0.95, 0.0, 0.5, np.array([1.0, 0.0]))
+    assert np.allclose(new, [2.0 - 0.1 * (1 + 0.5 * 2.0), 2.0 - 0.1])
+
+
+def test_decay_mask_covers_matrices_only():
+    a = orc.Arch((1, 1), 8, 2, 4, 16, 11, 6)
+    lay = orc.param_layout(a)
+    mask = orc.decay_mask(a)
+    for name, (off, shape, _) in lay.items():
+        seg = mask[off:off + int(np.prod(shape))]
+        assert np.all(seg == (1.0 if len(shape) == 2 else 0.0)), name
+
+
+# ------------------------------------------------------------------------------------------- outer step
+def _mod(n=40, seed=0):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal(n), rng.standard_normal(n) * 0.1
+
+
+def test_outer_one_path_no_momentum_is_sgd_on_delta():
+    theta, _ = _mod()
+    local = theta + np.random.default_rng(1).standard_normal(40) * 0.01
+    new, buf = orc.outer_step(theta, np.zeros(40), [local], None, False, 0.3, 0.0)
+    assert np.allclose(new, theta - 0.3 * (theta - local), rtol=1e-14)
+    assert np.allclose(buf, theta - local)
+    new1, _ = orc.outer_step(theta, np.zeros(40), [local], None, False, 1.0, 0.0)
+    assert np.allclose(new1, local, rtol=1e-14)            # lr 1: the module becomes the path's copy
+
+
+def test_outer_equal_inputs_equal_single_input_and_delta_form():
+    theta, buf = _mod()
+    local = theta - 0.02
+    a, ba = orc.outer_step(theta, buf, [local] * 5, gen.shard_weights(5, 1), False, 0.7, 0.9)
+    b, bb = orc.outer_step(theta, buf, [local], None, False, 0.7, 0.9)
+    c, bc = orc.outer_step(theta, buf, [theta - local], None, True, 0.7, 0.9)
+    assert np.allclose(a, b, rtol=1e-13) and np.allclose(ba, bb, rtol=1e-13)
+    assert np.allclose(b, c, rtol=1e-15) and np.allclose(bb, bc, rtol=1e-15)
+
+
+def test_outer_weights_scale_and_permutation_invariance_and_uniform_mean():
+    theta, buf = _mod(seed=2)
+    rng = np.random.default_rng(3)
+    locs = [theta + rng.standard_normal(40) * 0.01 for _ in range(6)]
+    w = gen.shard_weights(6, 5).astype(np.float64)
+    a, ba = orc.outer_step(theta, buf, locs, w, False, 0.7, 0.9)
+    b, bb = orc.outer_step(theta, buf, locs, 17.0 * w, False, 0.7, 0.9)
+    assert np.allclose(a, b, rtol=1e-13) and np.allclose(ba, bb, rtol=1e-13)
+    perm = [3, 0, 5, 1, 4, 2]
+    c, bc = orc.outer_step(theta, buf, [locs[i] for i in perm], w[perm], False, 0.7, 0.9)
+    assert np.allclose(a, c, rtol=1e-13) and np.allclose(ba, bc, rtol=1e-13)
+    # uniform weights: Delta is the plain mean of Algorithm 1
+    u, bu = orc.outer_step(theta, np.zeros(40), locs, None, False, 1.0, 0.0)
+    assert np.allclose(bu, theta - np.mean(locs, axis=0), rtol=1e-12, atol=1e-15)
+    # weighted: Delta = sum w_i (theta - theta_i) / sum w_i, written out
+    _, bw = orc.outer_step(theta, np.zeros(40), locs, w, False, 1.0, 0.0)
+    want = sum(w[i] * (theta - locs[i]) for i in range(6)) / w.sum()
+    assert np.allclose(bw, want, rtol=1e-12, atol=1e-15)
+
+
+def test_outer_two_steps_match_hand_expanded_momentum():
+    th, lr, mu = 1.25, 0.7, 0.9
+    d1, d2 = 0.04, -0.03
+    b1 = d1
+    t1 = th - lr * (d1 + mu * b1)
+    b2 = mu * b1 + d2
+    t2 = t1 - lr * (d2 + mu * b2)
+    T, B = np.array([th]), np.zeros(1)
+    T, B = orc.outer_step(T, B, [np.array([d1])], None, True, lr, mu)
+    assert abs(T[0] - (th - lr * (1 + mu) * d1)) < 1e-15   # first step from zero buffer
+    T, B = orc.outer_step(T, B, [np.array([d2])], None, True, lr, mu)
+    assert abs(T[0] - t2) < 1e-15 and abs(B[0] - b2) < 1e-16
+
+
+# ------------------------------------------------------------------------------------------- paths / compose
+def test_path_index_round_trip_and_sharing_counts():
+    for K in [(2, 2), (16, 16), (3, 1, 4), (5,)]:
+        P = int(np.prod(K))
+        seen = set()
+        for mods in itertools.product(*[range(k) for k in K]):
+            j = orc.path_index(mods, K)
+            assert orc.modules_of_path(j, K) == mods
+            seen.add(j)
+        assert seen == set(range(P))
+        for l, kl in enumerate(K):
+            for e in range(kl):
+                assert len(orc.paths_through_module(l, e, K)) == P // kl
+    assert orc.path_index((1, 0), (2, 2)) == 2               # level 1 is the most significant digit
+    assert orc.paths_through_module(0, 3, (16, 16)) == list(range(48, 64))
+
+
+def test_compose_round_trip():
+    a = orc.Arch((2, 1), 8, 2, 4, 16, 11, 6)
+    bounds = orc.segment_bounds(a)
+    assert bounds[0][0] == 0 and bounds[-1][1] == orc.param_count(a)
+    assert all(bounds[i][1] == bounds[i + 1][0] for i in range(len(bounds) - 1))
+    rng = np.random.default_rng(0)
+    segs = [rng.standard_normal(e - s) for s, e in bounds]
+    flat = orc.compose_path(segs)
+    for (s, e), seg in zip(bounds, segs):
+        assert np.array_equal(flat[s:e], seg)
+    lay = orc.param_layout(a)
+    assert lay["blk0.ln1_g"][0] == bounds[1][0] and lay["blk2.ln1_g"][0] == bounds[2][0]
+    assert lay["lnf_g"][0] == bounds[3][0]
+
+
+# ------------------------------------------------------------------------------------------- routing
+def test_route_brute_force_with_constructed_ties():
+    rng = np.random.default_rng(0)
+    N, K, D = 64, 8, 5
+    c = rng.integers(-3, 4, size=(K, D)).astype(np.float64)
+    c[5] = c[2]                                            # duplicate centroid: exact ties, lowest index wins
+    z = rng.integers(-3, 4, size=(N, D)).astype(np.float64)
+    z[:8] = c                                              # points sitting on centroids
+    idx, hist, margin = orc.route_prefix(z, c)
+    for n in range(N):
+        best, best_k, second = None, -1, None
+        ds = []
+        for k in range(K):
+            d = 0.0
+            for j in range(D):
+                d += (z[n, j] - c[k, j]) ** 2
+            ds.append(d)
+            if best is None or d < best:
+                best, best_k = d, k
+        rest = sorted(ds[:best_k] + ds[best_k + 1:])
+        assert idx[n] == best_k
+        assert margin[n] == rest[0] - best
+    assert idx[2] == 2 and idx[5] == 2 and margin[2] == 0.0
+    assert hist.sum() == N and np.array_equal(hist, np.bincount(idx, minlength=K))
+    assert hist[5] == 0
+
+
+def test_route_point_on_centroid_and_translation_invariance():
+    z, c, _ = gen.gaussian_mixture(200, 16, 12, 0.3, seed=4, dtype=np.float64)
+    idx, hist, margin = orc.route_prefix(c, c)
+    assert np.array_equal(idx, np.arange(12))
+    idx0, hist0, m0 = orc.route_prefix(z, c)
+    shift = np.random.default_rng(1).standard_normal(16)
+    idx1, hist1, m1 = orc.route_prefix(z + shift, c + shift)
+    assert np.array_equal(idx0, idx1) and np.array_equal(hist0, hist1)
+    assert np.allclose(m0, m1, rtol=1e-9, atol=1e-12)
+    assert np.all(m0 >= 0)
+
+
+def test_route_matches_expanded_square_form_away_from_ties():
+    z, c, _ = gen.gaussian_mixture(500, 32, 20, 0.3, seed=9, dtype=np.float64)
+    idx, _, margin = orc.route_prefix(z, c)
+    score = (c * c).sum(1)[None, :] - 2.0 * z @ c.T          # same argmin, ||z||^2 dropped
+    alt = score.argmin(1)
+    far = margin > 1e-9
+    assert far.sum() > 400 and np.array_equal(idx[far], alt[far])
