@@ -1,0 +1,148 @@
+/*
+ * dipaco.h - C ABI of libdipaco.so: the data-parallel hot path of DiPaCo (arXiv 2403.10616) on one
+ * MI355X (gfx950).  One path = one decoder-only transformer LM assembled from one module per level of the
+ * module grid (Section 2.3, Section 2.6); the library runs its inner step (Algorithm 1, inner loop: loss,
+ * gradient, AdamW), the per-module outer step (Algorithm 1, outer loop, with the shard-size weights of
+ * Section 2.7) and k-means prefix routing (Section 2.4.1, eq. 1).
+ *
+ * Conventions common to every call
+ *   - Every "device" pointer is HIP device memory owned by the caller; "host" pointers are ordinary host
+ *     memory read during the call only.  The library allocates device memory in dipaco_create only (a few
+ *     KB of tables) and frees it in dipaco_destroy.  It keeps no numerical state between calls: optimiser
+ *     moments, momentum and step counters are arguments.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate on the host,
+ *     enqueue kernels on that stream and return without synchronising.  A non-zero status means nothing
+ *     was enqueued; dipaco_last_error() then describes why (per host thread).
+ *   - Device pointers must be 16-byte aligned.
+ *   - Flat path buffer layout (elements): stem | level 1 | ... | level L | head, where
+ *       stem  = tok_emb [vocab, d_model], pos_emb [max_seq, d_model]
+ *       level = its decoder blocks in order, each block =
+ *               ln1_g[d] ln1_b[d] w_qkv[d,3A] b_qkv[3A] w_o[A,d] b_o[d] ln2_g[d] ln2_b[d]
+ *               w_up[d,F] b_up[F] w_down[F,d] b_down[d]          (A = n_heads*d_head, F = d_mlp)
+ *       head  = lnf_g[d] lnf_b[d] w_head[d, vocab]
+ *     Matrices are row-major [in, out] (y = x W + b).  Columns of w_qkv: q heads, then k heads, then v heads.
+ *     dipaco_tensor_info enumerates exactly this.
+ */
+#ifndef DIPACO_H
+#define DIPACO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dipaco_ctx dipaco_ctx; /* opaque: shapes, offsets and small device tables; no numerical state */
+
+typedef enum {
+  DIPACO_OK = 0,
+  DIPACO_EINVAL = -1,       /* null pointer, negative size, bad enum                       */
+  DIPACO_ESHAPE = -2,       /* a size the kernels do not support (see dipaco_create)        */
+  DIPACO_EALIGN = -3,       /* a device pointer is not 16-byte aligned                      */
+  DIPACO_EWORKSPACE = -4,   /* workspace smaller than dipaco_workspace_bytes                */
+  DIPACO_EHIP = -5,         /* a HIP runtime call failed (message has hipGetErrorString)    */
+  DIPACO_EUNSUPPORTED = -6
+} dipaco_status;
+
+typedef enum { DIPACO_F32 = 0, DIPACO_BF16 = 1 } dipaco_dtype;
+
+/* One path's architecture (Section 4 and the hyper-parameter table: blocks, width, heads, key/value size,
+ * vocabulary).  Pre-LN blocks, learned positions, untied head, biases on the linears, exact-erf GELU. */
+typedef struct {
+  int32_t n_levels;                /* L (Section 2.3)                                                   */
+  const int32_t* layers_per_level; /* host, [L]: decoder blocks contributed by each level's module      */
+  int32_t d_model, n_heads, d_head, d_mlp, vocab, max_seq;
+  float ln_eps;
+  int32_t compute;                 /* dipaco_dtype: arithmetic of activations and matrix operands.
+                                      Master weights, gradients and optimiser state are always fp32.     */
+} dipaco_arch;
+
+/* Requirements: d_model, n_heads*d_head, d_mlp, vocab multiples of 8; d_head in {32, 64, 128};
+ * n_levels >= 1, every layers_per_level >= 0.  Otherwise DIPACO_ESHAPE.  Uses the current HIP device. */
+dipaco_status dipaco_create(dipaco_ctx** out, const dipaco_arch* arch);
+void dipaco_destroy(dipaco_ctx* ctx);
+
+/* Message for the last non-OK status returned on this host thread ("" if none). */
+const char* dipaco_last_error(void);
+
+/* Layout queries.  Segment s: 0 = stem, 1..L = levels, L+1 = head. */
+size_t dipaco_path_param_count(const dipaco_ctx* ctx);
+int32_t dipaco_segment_count(const dipaco_ctx* ctx);                  /* L + 2 */
+size_t dipaco_segment_offset(const dipaco_ctx* ctx, int32_t segment); /* elements from the buffer start */
+size_t dipaco_segment_size(const dipaco_ctx* ctx, int32_t segment);
+int32_t dipaco_tensor_count(const dipaco_ctx* ctx);
+/* Tensor i in storage order: name copied into name_out (host, capacity name_cap, NUL-terminated);
+ * rows/cols (cols = 1 for vectors); decayed = 1 if AdamW applies weight decay to it. */
+dipaco_status dipaco_tensor_info(const dipaco_ctx* ctx, int32_t i, char* name_out, size_t name_cap,
+                                 size_t* offset, int64_t* rows, int64_t* cols, int32_t* decayed);
+
+/* Path id <-> module tuple (Section 2.3): j = sum_l j_l * prod_{m>l} K_m, 0-based, level 1 most significant.
+ * K, modules: host [L].  Returns -1 / DIPACO_EINVAL on out-of-range input. */
+int64_t dipaco_path_index(const int32_t* modules, const int32_t* K, int32_t L);
+dipaco_status dipaco_path_modules(int64_t j, const int32_t* K, int32_t L, int32_t* modules_out);
+
+/* Bytes of device workspace dipaco_path_fwd_bwd needs for a [batch, seq] input. */
+size_t dipaco_workspace_bytes(const dipaco_ctx* ctx, int32_t batch, int32_t seq);
+
+/* Start-of-round copy of the global modules into one path's local parameters (Algorithm 1: theta_i^t =
+ * theta_i^{t-1}; Section 2.6).  segment_ptrs: host array of L+2 device pointers (stem, the chosen module of
+ * each level, head), each holding dipaco_segment_size fp32 elements.  Writes the flat fp32 buffer
+ * path_master [dipaco_path_param_count] and, if path_lowp is not NULL, its bf16 (round-to-nearest-even)
+ * image of the same length. */
+dipaco_status dipaco_compose_path(dipaco_ctx* ctx, const float* const* segment_ptrs, float* path_master,
+                                  void* path_lowp, void* stream);
+
+/* L = f(x, theta_i) and its gradient (Algorithm 1, inner loop): mean next-token negative log-likelihood
+ * over positions with target >= 0, natural log.
+ *   path_master  device fp32 [param_count]; read when compute = F32.
+ *   path_lowp    device bf16 [param_count]; read when compute = BF16 (must be the image of path_master
+ *                written by dipaco_compose_path / dipaco_inner_adamw); may be NULL for F32.
+ *   tokens       device int32 [batch, seq], ids in [0, vocab) (out-of-range ids are clamped).
+ *   targets      device int32 [batch, seq]; negative = position ignored.  At least one must be >= 0.
+ *   loss_out     device float, overwritten.     token_nll_out  device float [batch, seq] or NULL:
+ *                per-position NLL (0 at ignored positions).
+ *   grads        device fp32 [param_count], overwritten (same layout as path_master; rows of pos_emb
+ *                beyond seq get 0).
+ *   workspace    device, >= dipaco_workspace_bytes(ctx, batch, seq), contents undefined on return.
+ * seq <= max_seq.  Results are bit-reproducible from call to call on the same inputs. */
+dipaco_status dipaco_path_fwd_bwd(dipaco_ctx* ctx, const float* path_master, const void* path_lowp,
+                                  const int32_t* tokens, const int32_t* targets, int32_t batch, int32_t seq,
+                                  float* loss_out, float* token_nll_out, float* grads, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/* InnerOpt = AdamW (Algorithm 1, inner loop; Section 2.5), over the whole flat path buffer, in place:
+ *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+ *   theta <- theta - lr * ( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + weight_decay * theta ),
+ * weight decay applied to matrices and embeddings only.  step counts from 1.  If path_lowp is not NULL the
+ * bf16 image of the new theta is written there. */
+dipaco_status dipaco_inner_adamw(dipaco_ctx* ctx, float* path_master, const float* grads, float* m, float* v,
+                                 void* path_lowp, int64_t step, float lr, float beta1, float beta2, float eps,
+                                 float weight_decay, void* stream);
+
+#define DIPACO_MAX_PATHS_PER_MODULE 256
+
+/* Outer step of one module (Algorithm 1, outer loop; weights per Section 2.7), in place on theta/momentum:
+ *   Delta = sum_i alpha_i (theta - input_i)   (is_delta = 0: inputs are the paths' local copies theta_i)
+ *         = sum_i alpha_i  input_i            (is_delta = 1: inputs are ready-made deltas)
+ *   alpha_i = weights_i / sum(weights)        (weights NULL = uniform: the plain mean over P_le paths)
+ *   momentum <- mu * momentum + Delta;   theta <- theta - outer_lr * (Delta + mu * momentum)   (Nesterov)
+ * inputs: host array of n_paths device pointers, fp32 [n_elems] each; weights: host [n_paths], positive.
+ * 1 <= n_paths <= DIPACO_MAX_PATHS_PER_MODULE.  The sum runs in index order, so the result is reproducible. */
+dipaco_status dipaco_module_outer_step(float* theta, float* momentum, const float* const* inputs,
+                                       const float* weights, int32_t n_paths, size_t n_elems, int32_t is_delta,
+                                       float outer_lr, float outer_momentum, void* stream);
+
+/* Generative routing (Section 2.4.1, eq. 1): idx[n] = argmin_k ||z_n - c_k||^2, lowest k on exact ties of the
+ * computed scores; hist[k] = number of n routed to k.  The kernel minimises ||c_k||^2 - 2 z_n.c_k (same
+ * argmin) in fp32.
+ *   z device fp32 [N, D] row-major; centroids device fp32 [K, D]; idx_out device int32 [N];
+ *   hist_out device int64 [K], overwritten; margin_out device fp32 [N] or NULL: second-best minus best score
+ *   (+inf when K = 1).  D multiple of 4, 1 <= K <= 4096, N >= 0. */
+dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_t N, int32_t D, int32_t K,
+                                  int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIPACO_H */

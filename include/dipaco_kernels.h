@@ -1,0 +1,45 @@
+/*
+ * dipaco_kernels.h - kernel-level entry points of libdipaco.so.
+ *
+ * These expose single kernels of the path step (Algorithm 1 inner loop of arXiv 2403.10616: the pieces of
+ * f(x, theta_i) and its gradient) so that each can be checked against its plain definition and timed against
+ * its own roofline.  They follow the conventions of dipaco.h: caller-owned device pointers, 16-byte aligned,
+ * work enqueued on `stream`, non-zero status = nothing enqueued.  dtype is a dipaco_dtype: the element type of
+ * every `void*` operand (fp32 or bf16); accumulation is always fp32.
+ */
+#ifndef DIPACO_KERNELS_H
+#define DIPACO_KERNELS_H
+
+#include "dipaco.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] = opA(A) . opB(B) on the matrix cores.
+ *   trans_a = 0: A is [M,K] row-major; 1: A is [K,M] row-major.   trans_b = 0: B is [K,N]; 1: B is [N,K].
+ *   Supported: (0,0) forward, (0,1) input gradient, (1,0) with out_f32 = 1 weight gradient.
+ * Epilogue in this order, each optional: + bias[N];  act = 1: aux_out[M,N] = value, value = GELU(value);
+ * act = 2: value *= GELU'(aux_in[M,N]);  + resid[M,N].  out_f32 = 1: C is fp32, else dtype.
+ * splits > 1 (needs out_f32, no epilogue): K is cut into ranges whose partial products are written to
+ * partial ([splits, M, N] fp32) and summed in index order.  The contiguous extent of each operand must be a
+ * multiple of 16 bytes. */
+dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t out_f32, int32_t M, int32_t N,
+                            int32_t K, const void* A, const void* B, void* C, const void* bias, const void* resid,
+                            void* aux_out, const void* aux_in, int32_t act, int32_t splits, float* partial,
+                            void* stream);
+
+/* Causal softmax attention.  qkv: [B*S, 3*H*dh], row = q | k | v, head h at columns h*dh of each third;
+ * o: [B*S, H*dh];  lse: fp32 [B, H, S] = log sum_j exp(q_i.k_j / sqrt(dh)), j <= i.  dh in {32, 64, 128}. */
+dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,
+                                     int32_t H, int32_t dh, void* stream);
+
+/* Gradient of the above: d_o [B*S, H*dh] -> dqkv [B*S, 3*H*dh].  dsum: fp32 [B, H, S] scratch. */
+dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* d_o, const float* lse,
+                                     void* dqkv, float* dsum, int32_t B, int32_t S, int32_t H, int32_t dh,
+                                     void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIPACO_KERNELS_H */

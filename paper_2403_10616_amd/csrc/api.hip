@@ -1,0 +1,484 @@
+// C ABI of libdipaco: argument validation, parameter layout, workspace planning and the launch order of the
+// path step.  All arithmetic lives in the kernels; this file only decides which kernel runs on which buffer.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/dipaco_kernels.h"
+#include "kernels.h"
+
+namespace dipaco {
+
+static thread_local std::string g_last_error;
+void set_error(const std::string& msg) { g_last_error = msg; }
+dipaco_status fail(dipaco_status st, const std::string& msg) {
+  g_last_error = msg;
+  return st;
+}
+dipaco_status check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return DIPACO_OK;
+  return fail(DIPACO_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+struct TensorInfo {
+  std::string name;
+  size_t off;
+  int64_t rows, cols;
+  bool decay;
+};
+
+struct BlockOff {
+  size_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_up, b_up, w_down, b_down;
+};
+
+}  // namespace dipaco
+
+using namespace dipaco;
+
+struct dipaco_ctx {
+  dipaco_arch arch;
+  std::vector<int32_t> layers_per_level;
+  int n_layers = 0;
+  int A = 0;   // n_heads * d_head
+  std::vector<TensorInfo> tensors;
+  std::vector<BlockOff> blocks;
+  size_t tok_emb = 0, pos_emb = 0, lnf_g = 0, lnf_b = 0, w_head = 0;
+  std::vector<size_t> seg_off, seg_size;
+  size_t n_params = 0;
+  AdamLayout adam;
+};
+
+namespace dipaco {
+
+// ---- workspace plan --------------------------------------------------------------------------------------
+struct LayerBufs {
+  size_t x_in, h1, mean1, rstd1, qkv, o, lse, x_mid, h2, mean2, rstd2, u, act;
+};
+struct Plan {
+  std::vector<LayerBufs> layers;
+  size_t x_final, meanf, rstdf, y, logits, nll, n_valid;
+  size_t dxa, dxb, dh, du, dqkv, d_o, dsum;
+  size_t ln_partial, cs_partial, splitk_partial, embed_ints;
+  size_t total;
+};
+
+static int dw_splits(int M, int N, int K) {
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  long s = (512 + tiles - 1) / tiles;
+  s = std::min<long>(s, 16);
+  s = std::min<long>(s, std::max(1, K / 256));
+  return (int)std::max<long>(s, 1);
+}
+
+static Plan make_plan(const dipaco_ctx* c, int B, int S) {
+  const dipaco_arch& a = c->arch;
+  const size_t T = (size_t)B * S, d = a.d_model, A = c->A, F = a.d_mlp, V = a.vocab;
+  const size_t es = a.compute == DIPACO_BF16 ? 2 : 4;
+  size_t pos = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = pos;
+    pos += (bytes + 255) & ~(size_t)255;
+    return at;
+  };
+  Plan p;
+  p.layers.resize(c->n_layers);
+  for (auto& L : p.layers) {
+    L.x_in = take(T * d * es); L.h1 = take(T * d * es); L.mean1 = take(T * 4); L.rstd1 = take(T * 4);
+    L.qkv = take(T * 3 * A * es); L.o = take(T * A * es); L.lse = take((size_t)B * a.n_heads * S * 4);
+    L.x_mid = take(T * d * es); L.h2 = take(T * d * es); L.mean2 = take(T * 4); L.rstd2 = take(T * 4);
+    L.u = take(T * F * es); L.act = take(T * F * es);
+  }
+  p.x_final = take(T * d * es); p.meanf = take(T * 4); p.rstdf = take(T * 4); p.y = take(T * d * es);
+  p.logits = take(T * V * es); p.nll = take(T * 4); p.n_valid = take(256);
+  p.dxa = take(T * d * es); p.dxb = take(T * d * es); p.dh = take(T * d * es); p.du = take(T * F * es);
+  p.dqkv = take(T * 3 * A * es); p.d_o = take(T * A * es); p.dsum = take((size_t)B * a.n_heads * S * 4);
+  p.ln_partial = take(ln_bwd_partial_floats((int)T, (int)d) * 4);
+  const size_t widest = std::max(std::max(F, 3 * A), d);
+  p.cs_partial = take(colsum_partial_floats((int)T, (int)widest) * 4);
+  size_t sk = 0;
+  auto need = [&](size_t M, size_t N) { sk = std::max(sk, (size_t)dw_splits((int)M, (int)N, (int)T) * M * N); };
+  need(d, 3 * A); need(A, d); need(d, F); need(F, d); need(d, V);
+  p.splitk_partial = take(sk * 4);
+  p.embed_ints = take(embed_bwd_scratch_ints((int)T, (int)V) * 4);
+  p.total = pos;
+  return p;
+}
+
+// ---- the path step ---------------------------------------------------------------------------------------
+template <typename T>
+static dipaco_status gemm(const T* A, const T* B, void* C, int M, int N, int K, long lda, long ldb, long ldc,
+                          bool ta, bool tb, const T* bias, const T* resid, T* aux_out, const T* aux_in, int act,
+                          bool out_f32, int splits, float* partial, hipStream_t s) {
+  GemmArgs g;
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.bias = bias; g.resid = resid; g.aux_out = aux_out; g.aux_in = aux_in; g.act = act;
+  g.trans_a = ta; g.trans_b = tb; g.out_f32 = out_f32; g.splits = splits; g.partial = partial;
+  return launch_gemm<T>(g, s);
+}
+
+#define TRY(expr)                          \
+  do {                                     \
+    dipaco_status _s = (expr);             \
+    if (_s != DIPACO_OK) return _s;        \
+  } while (0)
+
+template <typename T>
+static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tokens, const int* targets, int B, int S,
+                                 float* loss_out, float* nll_out, float* G, char* ws, hipStream_t st) {
+  const dipaco_arch& a = c->arch;
+  const int T_ = B * S, d = a.d_model, A = c->A, F = a.d_mlp, V = a.vocab, H = a.n_heads, dh = a.d_head;
+  const Plan p = make_plan(c, B, S);
+  auto buf = [&](size_t off) { return reinterpret_cast<T*>(ws + off); };
+  auto fbuf = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  float* skp = fbuf(p.splitk_partial);
+  float* csp = fbuf(p.cs_partial);
+  float* lnp = fbuf(p.ln_partial);
+  int* n_valid = reinterpret_cast<int*>(ws + p.n_valid);
+  float* nll = nll_out ? nll_out : fbuf(p.nll);
+  const int NL = c->n_layers;
+
+  // weight gradient dW[K_in, N_out] = X^T . dY (contraction over the tokens), fp32 into the gradient buffer
+  auto dweight = [&](const T* X, const T* dY, size_t w_off, int K_in, int N_out) {
+    return gemm<T>(X, dY, G + w_off, K_in, N_out, T_, K_in, N_out, N_out, true, false, nullptr, nullptr, nullptr, nullptr,
+                   0, true, dw_splits(K_in, N_out, T_), skp, st);
+  };
+
+  // ---------------- forward ----------------
+  T* x0 = NL > 0 ? buf(p.layers[0].x_in) : buf(p.x_final);
+  TRY(launch_embed<T>(W + c->tok_emb, W + c->pos_emb, tokens, x0, B, S, d, V, st));
+  for (int l = 0; l < NL; ++l) {
+    const LayerBufs& L = p.layers[l];
+    const BlockOff& o = c->blocks[l];
+    T* x_next = l + 1 < NL ? buf(p.layers[l + 1].x_in) : buf(p.x_final);
+    TRY(launch_layernorm_fwd<T>(buf(L.x_in), W + o.ln1_g, W + o.ln1_b, buf(L.h1), fbuf(L.mean1), fbuf(L.rstd1), T_, d,
+                                a.ln_eps, st));
+    TRY(gemm<T>(buf(L.h1), W + o.w_qkv, buf(L.qkv), T_, 3 * A, d, d, 3 * A, 3 * A, false, false, W + o.b_qkv, nullptr,
+                nullptr, nullptr, 0, false, 1, nullptr, st));
+    TRY(launch_attention_fwd<T>(buf(L.qkv), buf(L.o), fbuf(L.lse), B, S, H, dh, st));
+    TRY(gemm<T>(buf(L.o), W + o.w_o, buf(L.x_mid), T_, d, A, A, d, d, false, false, W + o.b_o, buf(L.x_in), nullptr,
+                nullptr, 0, false, 1, nullptr, st));
+    TRY(launch_layernorm_fwd<T>(buf(L.x_mid), W + o.ln2_g, W + o.ln2_b, buf(L.h2), fbuf(L.mean2), fbuf(L.rstd2), T_, d,
+                                a.ln_eps, st));
+    TRY(gemm<T>(buf(L.h2), W + o.w_up, buf(L.act), T_, F, d, d, F, F, false, false, W + o.b_up, nullptr, buf(L.u),
+                nullptr, 1, false, 1, nullptr, st));
+    TRY(gemm<T>(buf(L.act), W + o.w_down, x_next, T_, d, F, F, d, d, false, false, W + o.b_down, buf(L.x_mid), nullptr,
+                nullptr, 0, false, 1, nullptr, st));
+  }
+  TRY(launch_layernorm_fwd<T>(buf(p.x_final), W + c->lnf_g, W + c->lnf_b, buf(p.y), fbuf(p.meanf), fbuf(p.rstdf), T_, d,
+                              a.ln_eps, st));
+  TRY(gemm<T>(buf(p.y), W + c->w_head, buf(p.logits), T_, V, d, d, V, V, false, false, nullptr, nullptr, nullptr,
+              nullptr, 0, false, 1, nullptr, st));
+  TRY(launch_count_valid(targets, T_, n_valid, st));
+  TRY(launch_softmax_xent<T>(buf(p.logits), targets, n_valid, nll, T_, V, st));
+  TRY(launch_mean_loss(nll, n_valid, loss_out, T_, st));
+
+  // ---------------- backward ----------------
+  T* dlogits = buf(p.logits);
+  TRY(dweight(buf(p.y), dlogits, c->w_head, d, V));
+  TRY(gemm<T>(dlogits, W + c->w_head, buf(p.dh), T_, d, V, V, V, d, false, true, nullptr, nullptr, nullptr, nullptr, 0,
+              false, 1, nullptr, st));
+  T* dx = buf(p.dxa);
+  T* dx_other = buf(p.dxb);
+  TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(p.x_final), W + c->lnf_g, fbuf(p.meanf), fbuf(p.rstdf), nullptr, dx,
+                              G + c->lnf_g, G + c->lnf_b, lnp, T_, d, st));
+  for (int l = NL - 1; l >= 0; --l) {
+    const LayerBufs& L = p.layers[l];
+    const BlockOff& o = c->blocks[l];
+    // x_next = x_mid + gelu(u) W_down + b_down
+    TRY(dweight(buf(L.act), dx, o.w_down, F, d));
+    TRY(launch_colsum<T>(dx, G + o.b_down, csp, T_, d, st));
+    TRY(gemm<T>(dx, W + o.w_down, buf(p.du), T_, F, d, d, d, F, false, true, nullptr, nullptr, nullptr, buf(L.u), 2,
+                false, 1, nullptr, st));
+    TRY(dweight(buf(L.h2), buf(p.du), o.w_up, d, F));
+    TRY(launch_colsum<T>(buf(p.du), G + o.b_up, csp, T_, F, st));
+    TRY(gemm<T>(buf(p.du), W + o.w_up, buf(p.dh), T_, d, F, F, F, d, false, true, nullptr, nullptr, nullptr, nullptr, 0,
+                false, 1, nullptr, st));
+    TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_mid), W + o.ln2_g, fbuf(L.mean2), fbuf(L.rstd2), dx, dx_other,
+                                G + o.ln2_g, G + o.ln2_b, lnp, T_, d, st));
+    // x_mid = x_in + attn(...) W_o + b_o          (dx_other = gradient at x_mid)
+    TRY(dweight(buf(L.o), dx_other, o.w_o, A, d));
+    TRY(launch_colsum<T>(dx_other, G + o.b_o, csp, T_, d, st));
+    TRY(gemm<T>(dx_other, W + o.w_o, buf(p.d_o), T_, A, d, d, d, A, false, true, nullptr, nullptr, nullptr, nullptr, 0,
+                false, 1, nullptr, st));
+    TRY(launch_attention_bwd<T>(buf(L.qkv), buf(L.o), buf(p.d_o), fbuf(L.lse), buf(p.dqkv), fbuf(p.dsum), B, S, H, dh,
+                                st));
+    TRY(dweight(buf(L.h1), buf(p.dqkv), o.w_qkv, d, 3 * A));
+    TRY(launch_colsum<T>(buf(p.dqkv), G + o.b_qkv, csp, T_, 3 * A, st));
+    TRY(gemm<T>(buf(p.dqkv), W + o.w_qkv, buf(p.dh), T_, d, 3 * A, 3 * A, 3 * A, d, false, true, nullptr, nullptr,
+                nullptr, nullptr, 0, false, 1, nullptr, st));
+    TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_in), W + o.ln1_g, fbuf(L.mean1), fbuf(L.rstd1), dx_other, dx,
+                                G + o.ln1_g, G + o.ln1_b, lnp, T_, d, st));
+  }
+  TRY(launch_embed_bwd<T>(dx, tokens, G + c->tok_emb, G + c->pos_emb, reinterpret_cast<int*>(ws + p.embed_ints), B, S,
+                          d, V, a.max_seq, st));
+  return DIPACO_OK;
+}
+
+static dipaco_status check_ptr(const void* p, const char* name) {
+  if (!p) return fail(DIPACO_EINVAL, std::string(name) + " is NULL");
+  if (!aligned16(p)) return fail(DIPACO_EALIGN, std::string(name) + " is not 16-byte aligned");
+  return DIPACO_OK;
+}
+
+}  // namespace dipaco
+
+// ==========================================================================================================
+extern "C" {
+
+const char* dipaco_last_error(void) { return g_last_error.c_str(); }
+
+dipaco_status dipaco_create(dipaco_ctx** out, const dipaco_arch* arch) {
+  if (!out || !arch || !arch->layers_per_level) return fail(DIPACO_EINVAL, "dipaco_create: NULL argument");
+  *out = nullptr;
+  const dipaco_arch& a = *arch;
+  if (a.n_levels < 1) return fail(DIPACO_ESHAPE, "n_levels must be >= 1");
+  if (a.compute != DIPACO_F32 && a.compute != DIPACO_BF16) return fail(DIPACO_EINVAL, "unknown compute dtype");
+  if (a.d_model <= 0 || a.n_heads <= 0 || a.d_mlp <= 0 || a.vocab <= 0 || a.max_seq <= 0)
+    return fail(DIPACO_ESHAPE, "sizes must be positive");
+  if (a.d_head != 32 && a.d_head != 64 && a.d_head != 128) return fail(DIPACO_ESHAPE, "d_head must be 32, 64 or 128");
+  if (a.d_model % 8 || a.d_mlp % 8 || a.vocab % 8) return fail(DIPACO_ESHAPE, "d_model, d_mlp and vocab must be multiples of 8");
+  if (a.d_model > 2048) return fail(DIPACO_ESHAPE, "d_model above 2048 is not supported");
+  if (!(a.ln_eps > 0.f)) return fail(DIPACO_EINVAL, "ln_eps must be positive");
+  dipaco_ctx* c = new dipaco_ctx();
+  c->arch = a;
+  c->layers_per_level.assign(a.layers_per_level, a.layers_per_level + a.n_levels);
+  c->arch.layers_per_level = c->layers_per_level.data();
+  for (int v : c->layers_per_level) {
+    if (v < 0) { delete c; return fail(DIPACO_ESHAPE, "layers_per_level must be >= 0"); }
+    c->n_layers += v;
+  }
+  c->A = a.n_heads * a.d_head;
+  const size_t d = a.d_model, A = c->A, F = a.d_mlp, V = a.vocab;
+  size_t off = 0;
+  auto put = [&](const std::string& name, int64_t rows, int64_t cols, bool decay) {
+    c->tensors.push_back({name, off, rows, cols, decay});
+    size_t at = off;
+    off += (size_t)rows * cols;
+    return at;
+  };
+  c->seg_off.push_back(0);
+  c->tok_emb = put("tok_emb", V, d, true);
+  c->pos_emb = put("pos_emb", a.max_seq, d, true);
+  c->seg_size.push_back(off);
+  int layer = 0;
+  for (int lv = 0; lv < a.n_levels; ++lv) {
+    c->seg_off.push_back(off);
+    for (int i = 0; i < c->layers_per_level[lv]; ++i, ++layer) {
+      const std::string p = "blk" + std::to_string(layer) + ".";
+      BlockOff b;
+      b.ln1_g = put(p + "ln1_g", d, 1, false); b.ln1_b = put(p + "ln1_b", d, 1, false);
+      b.w_qkv = put(p + "w_qkv", d, 3 * A, true); b.b_qkv = put(p + "b_qkv", 3 * A, 1, false);
+      b.w_o = put(p + "w_o", A, d, true); b.b_o = put(p + "b_o", d, 1, false);
+      b.ln2_g = put(p + "ln2_g", d, 1, false); b.ln2_b = put(p + "ln2_b", d, 1, false);
+      b.w_up = put(p + "w_up", d, F, true); b.b_up = put(p + "b_up", F, 1, false);
+      b.w_down = put(p + "w_down", F, d, true); b.b_down = put(p + "b_down", d, 1, false);
+      c->blocks.push_back(b);
+    }
+    c->seg_size.push_back(off - c->seg_off.back());
+  }
+  c->seg_off.push_back(off);
+  c->lnf_g = put("lnf_g", d, 1, false);
+  c->lnf_b = put("lnf_b", d, 1, false);
+  c->w_head = put("w_head", d, V, true);
+  c->seg_size.push_back(off - c->seg_off.back());
+  c->n_params = off;
+
+  c->adam.stem_end = c->seg_off[1];
+  c->adam.blocks_end = c->lnf_g;
+  c->adam.head_matrix = c->w_head;
+  c->adam.block_size = 0;
+  for (int i = 0; i < 8; ++i) c->adam.edge[i] = 0;
+  if (c->n_layers > 0) {
+    const BlockOff& b0 = c->blocks[0];
+    const size_t base = b0.ln1_g;
+    c->adam.block_size = b0.b_down + d - base;
+    const size_t e[8] = {b0.w_qkv, b0.b_qkv, b0.w_o, b0.b_o, b0.w_up, b0.b_up, b0.w_down, b0.b_down};
+    for (int i = 0; i < 8; ++i) c->adam.edge[i] = (unsigned int)(e[i] - base);
+    if (c->adam.blocks_end - c->adam.stem_end >= (1ull << 32)) {
+      delete c;
+      return fail(DIPACO_ESHAPE, "decoder blocks above 2^32 elements in total");
+    }
+  }
+  *out = c;
+  return DIPACO_OK;
+}
+
+void dipaco_destroy(dipaco_ctx* c) { delete c; }
+
+size_t dipaco_path_param_count(const dipaco_ctx* c) { return c ? c->n_params : 0; }
+int32_t dipaco_segment_count(const dipaco_ctx* c) { return c ? (int32_t)c->seg_off.size() : 0; }
+size_t dipaco_segment_offset(const dipaco_ctx* c, int32_t s) {
+  return (c && s >= 0 && s < (int32_t)c->seg_off.size()) ? c->seg_off[s] : 0;
+}
+size_t dipaco_segment_size(const dipaco_ctx* c, int32_t s) {
+  return (c && s >= 0 && s < (int32_t)c->seg_size.size()) ? c->seg_size[s] : 0;
+}
+int32_t dipaco_tensor_count(const dipaco_ctx* c) { return c ? (int32_t)c->tensors.size() : 0; }
+
+dipaco_status dipaco_tensor_info(const dipaco_ctx* c, int32_t i, char* name_out, size_t name_cap, size_t* offset,
+                                 int64_t* rows, int64_t* cols, int32_t* decayed) {
+  if (!c || i < 0 || i >= (int32_t)c->tensors.size()) return fail(DIPACO_EINVAL, "dipaco_tensor_info: bad index");
+  const TensorInfo& t = c->tensors[i];
+  if (name_out && name_cap) {
+    std::strncpy(name_out, t.name.c_str(), name_cap - 1);
+    name_out[name_cap - 1] = 0;
+  }
+  if (offset) *offset = t.off;
+  if (rows) *rows = t.rows;
+  if (cols) *cols = t.cols;
+  if (decayed) *decayed = t.decay ? 1 : 0;
+  return DIPACO_OK;
+}
+
+int64_t dipaco_path_index(const int32_t* modules, const int32_t* K, int32_t L) {
+  if (!modules || !K || L < 1) return -1;
+  int64_t j = 0;
+  for (int l = 0; l < L; ++l) {
+    if (K[l] < 1 || modules[l] < 0 || modules[l] >= K[l]) return -1;
+    j = j * K[l] + modules[l];
+  }
+  return j;
+}
+
+dipaco_status dipaco_path_modules(int64_t j, const int32_t* K, int32_t L, int32_t* out) {
+  if (!K || !out || L < 1 || j < 0) return fail(DIPACO_EINVAL, "dipaco_path_modules: bad argument");
+  for (int l = L - 1; l >= 0; --l) {
+    if (K[l] < 1) return fail(DIPACO_EINVAL, "dipaco_path_modules: K must be >= 1");
+    out[l] = (int32_t)(j % K[l]);
+    j /= K[l];
+  }
+  if (j != 0) return fail(DIPACO_EINVAL, "dipaco_path_modules: path index out of range");
+  return DIPACO_OK;
+}
+
+size_t dipaco_workspace_bytes(const dipaco_ctx* c, int32_t batch, int32_t seq) {
+  if (!c || batch < 1 || seq < 1) return 0;
+  return make_plan(c, batch, seq).total;
+}
+
+dipaco_status dipaco_compose_path(dipaco_ctx* c, const float* const* segs, float* master, void* lowp, void* stream) {
+  if (!c || !segs) return fail(DIPACO_EINVAL, "dipaco_compose_path: NULL argument");
+  TRY(check_ptr(master, "path_master"));
+  if (lowp && !aligned16(lowp)) return fail(DIPACO_EALIGN, "path_lowp is not 16-byte aligned");
+  const int n = (int)c->seg_off.size();
+  for (int s = 0; s < n; ++s)
+    if (c->seg_size[s]) TRY(check_ptr(segs[s], "segment pointer"));
+  for (int s = 0; s < n; ++s) {
+    bf16* lp = lowp ? static_cast<bf16*>(lowp) + c->seg_off[s] : nullptr;
+    TRY(launch_copy_cast(segs[s], master + c->seg_off[s], lp, c->seg_size[s], static_cast<hipStream_t>(stream)));
+  }
+  return DIPACO_OK;
+}
+
+dipaco_status dipaco_path_fwd_bwd(dipaco_ctx* c, const float* master, const void* lowp, const int32_t* tokens,
+                                  const int32_t* targets, int32_t B, int32_t S, float* loss_out, float* nll_out,
+                                  float* grads, void* ws, size_t ws_bytes, void* stream) {
+  if (!c) return fail(DIPACO_EINVAL, "dipaco_path_fwd_bwd: NULL context");
+  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
+  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  const bool lowprec = c->arch.compute == DIPACO_BF16;
+  TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
+  TRY(check_ptr(tokens, "tokens"));
+  TRY(check_ptr(targets, "targets"));
+  TRY(check_ptr(grads, "grads"));
+  TRY(check_ptr(ws, "workspace"));
+  if (!loss_out) return fail(DIPACO_EINVAL, "loss_out is NULL");
+  if (ws_bytes < make_plan(c, B, S).total) return fail(DIPACO_EWORKSPACE, "workspace too small");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (lowprec)
+    return run_fwd_bwd<bf16>(c, static_cast<const bf16*>(lowp), tokens, targets, B, S, loss_out, nll_out, grads,
+                             static_cast<char*>(ws), st);
+  return run_fwd_bwd<float>(c, master, tokens, targets, B, S, loss_out, nll_out, grads, static_cast<char*>(ws), st);
+}
+
+dipaco_status dipaco_inner_adamw(dipaco_ctx* c, float* master, const float* grads, float* m, float* v, void* lowp,
+                                 int64_t step, float lr, float beta1, float beta2, float eps, float wd, void* stream) {
+  if (!c) return fail(DIPACO_EINVAL, "dipaco_inner_adamw: NULL context");
+  if (step < 1) return fail(DIPACO_EINVAL, "step counts from 1");
+  if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f)) return fail(DIPACO_EINVAL, "betas must be in [0,1)");
+  TRY(check_ptr(master, "path_master"));
+  TRY(check_ptr(grads, "grads"));
+  TRY(check_ptr(m, "m"));
+  TRY(check_ptr(v, "v"));
+  if (lowp && !aligned16(lowp)) return fail(DIPACO_EALIGN, "path_lowp is not 16-byte aligned");
+  return launch_adamw(master, grads, m, v, static_cast<bf16*>(lowp), c->adam, c->n_params, step, lr, beta1, beta2, eps, wd, static_cast<hipStream_t>(stream));
+}
+
+dipaco_status dipaco_module_outer_step(float* theta, float* momentum, const float* const* inputs, const float* weights,
+                                       int32_t n_paths, size_t n_elems, int32_t is_delta, float outer_lr,
+                                       float outer_momentum, void* stream) {
+  if (!inputs) return fail(DIPACO_EINVAL, "inputs is NULL");
+  if (n_paths < 1 || n_paths > DIPACO_MAX_PATHS_PER_MODULE)
+    return fail(DIPACO_ESHAPE, "n_paths must be in [1, DIPACO_MAX_PATHS_PER_MODULE]");
+  TRY(check_ptr(theta, "theta"));
+  TRY(check_ptr(momentum, "momentum"));
+  for (int i = 0; i < n_paths; ++i) TRY(check_ptr(inputs[i], "input pointer"));
+  float alpha[DIPACO_MAX_PATHS_PER_MODULE];
+  double sum = 0.0;
+  for (int i = 0; i < n_paths; ++i) {
+    const double w = weights ? (double)weights[i] : 1.0;
+    if (!(w > 0.0) || !std::isfinite(w)) return fail(DIPACO_EINVAL, "weights must be positive and finite");
+    sum += w;
+  }
+  for (int i = 0; i < n_paths; ++i) alpha[i] = (float)((weights ? (double)weights[i] : 1.0) / sum);
+  return launch_outer(theta, momentum, inputs, alpha, n_paths, n_elems, is_delta ? 1 : 0, outer_lr, outer_momentum,
+                      static_cast<hipStream_t>(stream));
+}
+
+dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_t N, int32_t D, int32_t K,
+                                  int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream) {
+  if (N < 0) return fail(DIPACO_EINVAL, "N must be >= 0");
+  if (D < 4 || D % 4) return fail(DIPACO_ESHAPE, "D must be a positive multiple of 4");
+  if (K < 1 || K > 4096) return fail(DIPACO_ESHAPE, "K must be in [1, 4096]");
+  TRY(check_ptr(centroids, "centroids"));
+  TRY(check_ptr(hist_out, "hist_out"));
+  if (N > 0) {
+    TRY(check_ptr(z, "z"));
+    TRY(check_ptr(idx_out, "idx_out"));
+  }
+  return launch_route(z, centroids, N, D, K, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
+                      static_cast<hipStream_t>(stream));
+}
+
+// ---- kernel-level entry points (include/dipaco_kernels.h) -------------------------------------------------
+dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t out_f32, int32_t M, int32_t N,
+                            int32_t K, const void* A, const void* B, void* C, const void* bias, const void* resid,
+                            void* aux_out, const void* aux_in, int32_t act, int32_t splits, float* partial,
+                            void* stream) {
+  GemmArgs g;
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K;
+  g.lda = trans_a ? M : K; g.ldb = trans_b ? K : N; g.ldc = N;
+  g.bias = bias; g.resid = resid; g.aux_out = aux_out; g.aux_in = aux_in; g.act = act;
+  g.trans_a = trans_a; g.trans_b = trans_b; g.out_f32 = out_f32; g.splits = splits; g.partial = partial;
+  if (!A || !B || !C) return fail(DIPACO_EINVAL, "dipaco_k_gemm: NULL operand");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return dtype == DIPACO_BF16 ? launch_gemm<bf16>(g, st) : launch_gemm<float>(g, st);
+}
+
+dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,
+                                     int32_t H, int32_t dh, void* stream) {
+  if (!qkv || !o || !lse || B < 1 || S < 1 || H < 1) return fail(DIPACO_EINVAL, "dipaco_k_attention_fwd: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return dtype == DIPACO_BF16
+             ? launch_attention_fwd<bf16>(static_cast<const bf16*>(qkv), static_cast<bf16*>(o), lse, B, S, H, dh, st)
+             : launch_attention_fwd<float>(static_cast<const float*>(qkv), static_cast<float*>(o), lse, B, S, H, dh, st);
+}
+
+dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* d_o, const float* lse,
+                                     void* dqkv, float* dsum, int32_t B, int32_t S, int32_t H, int32_t dh,
+                                     void* stream) {
+  if (!qkv || !o || !d_o || !lse || !dqkv || !dsum || B < 1 || S < 1 || H < 1)
+    return fail(DIPACO_EINVAL, "dipaco_k_attention_bwd: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return dtype == DIPACO_BF16
+             ? launch_attention_bwd<bf16>(static_cast<const bf16*>(qkv), static_cast<const bf16*>(o),
+                                          static_cast<const bf16*>(d_o), lse, static_cast<bf16*>(dqkv), dsum, B, S, H,
+                                          dh, st)
+             : launch_attention_bwd<float>(static_cast<const float*>(qkv), static_cast<const float*>(o),
+                                           static_cast<const float*>(d_o), lse, static_cast<float*>(dqkv), dsum, B, S,
+                                           H, dh, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,225 @@
+// Bandwidth-bound kernels: path composition (copy + bf16 image), AdamW, the module outer step, fills.
+// All are one-pass float4 streams: every parameter byte is read once and written once.
+#include "kernels.h"
+
+namespace dipaco {
+
+namespace {
+
+constexpr int EW_THREADS = 256;
+
+inline int ew_blocks(size_t n_vec, int per_thread = 1) {
+  size_t b = (n_vec + (size_t)EW_THREADS * per_thread - 1) / ((size_t)EW_THREADS * per_thread);
+  if (b < 1) b = 1;
+  if (b > 256u * 64u) b = 256u * 64u;  // grid-stride beyond this: 64 blocks per CU
+  return (int)b;
+}
+
+__device__ __forceinline__ void store_bf16x4(bf16* dst, float4 v) {
+  bf16x4 o = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
+  *reinterpret_cast<bf16x4*>(dst) = o;
+}
+
+// ---- compose: dst[i] = src[i], lowp[i] = bf16(src[i]) ------------------------------------------------
+__global__ void __launch_bounds__(EW_THREADS) copy_cast_kernel(const float* __restrict__ src,
+                                                                float* __restrict__ dst, bf16* __restrict__ lowp,
+                                                                size_t n) {
+  size_t nv = n >> 2;
+  size_t stride = (size_t)gridDim.x * EW_THREADS;
+  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
+    float4 v = reinterpret_cast<const float4*>(src)[i];
+    reinterpret_cast<float4*>(dst)[i] = v;
+    if (lowp) store_bf16x4(lowp + 4 * i, v);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {  // tail
+    size_t i = (nv << 2) + threadIdx.x;
+    float v = src[i];
+    dst[i] = v;
+    if (lowp) lowp[i] = (bf16)v;
+  }
+}
+
+// ---- AdamW ---------------------------------------------------------------------------------------------
+// Which elements are weight-decayed follows from the flat layout: the stem (embeddings) entirely, inside every
+// decoder block the four matrices (between in-block edges 0-1, 2-3, 4-5, 6-7), in the head only w_head.
+struct AdamArgs {
+  float* theta;
+  const float* grad;
+  float* m;
+  float* v;
+  bf16* lowp;
+  size_t n;
+  unsigned long long stem_end, blocks_end, block_size, head_matrix;
+  unsigned int edge[8];
+  float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2;
+};
+
+__device__ __forceinline__ bool adam_decayed(const AdamArgs& a, unsigned long long pos) {
+  if (pos < a.stem_end) return true;
+  if (pos >= a.blocks_end) return pos >= a.head_matrix;
+  const unsigned int off = (unsigned int)(pos - a.stem_end) % (unsigned int)a.block_size;   // block region < 2^32 elements
+  int c = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) c += off >= a.edge[i];
+  return c & 1;
+}
+
+__device__ __forceinline__ float adam_one(float th, float g, float& m, float& v, const AdamArgs& a, float decay) {
+  m = a.beta1 * m + (1.0f - a.beta1) * g;
+  v = a.beta2 * v + (1.0f - a.beta2) * g * g;
+  float mhat = m * a.inv_bc1;
+  float vhat = v * a.inv_bc2;
+  return th - a.lr * (mhat / (sqrtf(vhat) + a.eps) + decay * th);
+}
+
+__global__ void __launch_bounds__(EW_THREADS) adamw_kernel(const AdamArgs a) {
+  size_t nv = a.n >> 2;  // every tensor starts and ends on a multiple of 4 elements (checked at create)
+  size_t stride = (size_t)gridDim.x * EW_THREADS;
+  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
+    const float decay = adam_decayed(a, (unsigned long long)i << 2) ? a.wd : 0.0f;
+    float4 th = reinterpret_cast<float4*>(a.theta)[i];
+    float4 g = reinterpret_cast<const float4*>(a.grad)[i];
+    float4 m = reinterpret_cast<float4*>(a.m)[i];
+    float4 v = reinterpret_cast<float4*>(a.v)[i];
+    th.x = adam_one(th.x, g.x, m.x, v.x, a, decay);
+    th.y = adam_one(th.y, g.y, m.y, v.y, a, decay);
+    th.z = adam_one(th.z, g.z, m.z, v.z, a, decay);
+    th.w = adam_one(th.w, g.w, m.w, v.w, a, decay);
+    reinterpret_cast<float4*>(a.theta)[i] = th;
+    reinterpret_cast<float4*>(a.m)[i] = m;
+    reinterpret_cast<float4*>(a.v)[i] = v;
+    if (a.lowp) store_bf16x4(a.lowp + 4 * i, th);
+  }
+}
+
+// ---- outer step ----------------------------------------------------------------------------------------
+struct OuterArgs {
+  const float* in[DIPACO_MAX_PATHS_PER_MODULE];
+  float alpha[DIPACO_MAX_PATHS_PER_MODULE];
+  float* theta;
+  float* buf;
+  size_t n;
+  int n_paths;
+  int is_delta;
+  float lr, mu;
+};
+
+__device__ __forceinline__ float4 outer_one(float4 th, float4 d, float4& b, float lr, float mu) {
+  b.x = mu * b.x + d.x; b.y = mu * b.y + d.y; b.z = mu * b.z + d.z; b.w = mu * b.w + d.w;
+  th.x -= lr * (d.x + mu * b.x); th.y -= lr * (d.y + mu * b.y);
+  th.z -= lr * (d.z + mu * b.z); th.w -= lr * (d.w + mu * b.w);
+  return th;
+}
+
+// NP > 0: path count known at compile time (loads of all inputs are issued together); NP = 0: runtime loop.
+template <int NP>
+__global__ void __launch_bounds__(EW_THREADS) outer_kernel(const OuterArgs a) {
+  size_t nv = a.n >> 2;
+  size_t stride = (size_t)gridDim.x * EW_THREADS;
+  const int np = NP > 0 ? NP : a.n_paths;
+  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
+    float4 th = reinterpret_cast<const float4*>(a.theta)[i];
+    float4 b = reinterpret_cast<const float4*>(a.buf)[i];
+    float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (NP > 0) {
+      float4 x[NP > 0 ? NP : 1];
+#pragma unroll
+      for (int p = 0; p < NP; ++p) x[p] = reinterpret_cast<const float4*>(a.in[p])[i];
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        float al = a.alpha[p];
+        if (a.is_delta) { d.x += al * x[p].x; d.y += al * x[p].y; d.z += al * x[p].z; d.w += al * x[p].w; }
+        else { d.x += al * (th.x - x[p].x); d.y += al * (th.y - x[p].y); d.z += al * (th.z - x[p].z); d.w += al * (th.w - x[p].w); }
+      }
+    } else {
+      for (int p = 0; p < np; ++p) {
+        float4 x = reinterpret_cast<const float4*>(a.in[p])[i];
+        float al = a.alpha[p];
+        if (a.is_delta) { d.x += al * x.x; d.y += al * x.y; d.z += al * x.z; d.w += al * x.w; }
+        else { d.x += al * (th.x - x.x); d.y += al * (th.y - x.y); d.z += al * (th.z - x.z); d.w += al * (th.w - x.w); }
+      }
+    }
+    th = outer_one(th, d, b, a.lr, a.mu);
+    reinterpret_cast<float4*>(a.theta)[i] = th;
+    reinterpret_cast<float4*>(a.buf)[i] = b;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (a.n & 3)) {  // tail elements
+    size_t i = (nv << 2) + threadIdx.x;
+    float th = a.theta[i], b = a.buf[i], d = 0.f;
+    for (int p = 0; p < np; ++p) {
+      float x = a.in[p][i];
+      d += a.alpha[p] * (a.is_delta ? x : (th - x));
+    }
+    b = a.mu * b + d;
+    a.theta[i] = th - a.lr * (d + a.mu * b);
+    a.buf[i] = b;
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(EW_THREADS) fill_kernel(T* p, T value, size_t n) {
+  size_t stride = (size_t)gridDim.x * EW_THREADS;
+  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) p[i] = value;
+}
+
+}  // namespace
+
+dipaco_status launch_copy_cast(const float* src, float* dst, bf16* lowp, size_t n, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  copy_cast_kernel<<<ew_blocks(n >> 2), EW_THREADS, 0, s>>>(src, dst, lowp, n);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_adamw(float* theta, const float* grad, float* m, float* v, bf16* lowp, const AdamLayout& lay,
+                           size_t n, int64_t step, float lr, float beta1, float beta2, float eps, float wd,
+                           hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  AdamArgs a;
+  a.theta = theta; a.grad = grad; a.m = m; a.v = v; a.lowp = lowp; a.n = n;
+  a.stem_end = lay.stem_end; a.blocks_end = lay.blocks_end; a.block_size = lay.block_size ? lay.block_size : 1;
+  a.head_matrix = lay.head_matrix;
+  for (int i = 0; i < 8; ++i) a.edge[i] = lay.edge[i];
+  a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps; a.wd = wd;
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+  adamw_kernel<<<ew_blocks(n >> 2), EW_THREADS, 0, s>>>(a);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_outer(float* theta, float* momentum, const float* const* inputs, const float* alpha,
+                           int n_paths, size_t n, int is_delta, float lr, float mu, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  OuterArgs a;
+  for (int p = 0; p < n_paths; ++p) { a.in[p] = inputs[p]; a.alpha[p] = alpha[p]; }
+  for (int p = n_paths; p < DIPACO_MAX_PATHS_PER_MODULE; ++p) { a.in[p] = nullptr; a.alpha[p] = 0.f; }
+  a.theta = theta; a.buf = momentum; a.n = n; a.n_paths = n_paths; a.is_delta = is_delta; a.lr = lr; a.mu = mu;
+  int blocks = ew_blocks(n >> 2);
+  switch (n_paths) {
+    case 1: outer_kernel<1><<<blocks, EW_THREADS, 0, s>>>(a); break;
+    case 2: outer_kernel<2><<<blocks, EW_THREADS, 0, s>>>(a); break;
+    case 4: outer_kernel<4><<<blocks, EW_THREADS, 0, s>>>(a); break;
+    case 8: outer_kernel<8><<<blocks, EW_THREADS, 0, s>>>(a); break;
+    case 16: outer_kernel<16><<<blocks, EW_THREADS, 0, s>>>(a); break;
+    default: outer_kernel<0><<<blocks, EW_THREADS, 0, s>>>(a); break;
+  }
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  fill_kernel<float><<<ew_blocks(n), EW_THREADS, 0, s>>>(p, value, n);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  fill_kernel<long long><<<ew_blocks(n), EW_THREADS, 0, s>>>(p, value, n);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+}  // namespace dipaco

@@ -1,0 +1,92 @@
+// Host-side launchers of every kernel in libdipaco (one per .hip file group).  All enqueue on `s` and return.
+#pragma once
+#include "common.h"
+
+namespace dipaco {
+
+// ---- elementwise.hip ---------------------------------------------------------------------------------
+dipaco_status launch_copy_cast(const float* src, float* dst, bf16* lowp, size_t n, hipStream_t s);
+// where weight decay applies in the flat path buffer: [0, stem_end) all; blocks of block_size elements up to
+// blocks_end, decayed between in-block edges 0-1, 2-3, 4-5, 6-7; in the head from head_matrix on.
+struct AdamLayout {
+  unsigned long long stem_end, blocks_end, block_size, head_matrix;
+  unsigned int edge[8];
+};
+dipaco_status launch_adamw(float* theta, const float* grad, float* m, float* v, bf16* lowp, const AdamLayout& lay,
+                           size_t n, int64_t step, float lr, float beta1, float beta2, float eps, float wd,
+                           hipStream_t s);
+dipaco_status launch_outer(float* theta, float* momentum, const float* const* inputs, const float* alpha,
+                           int n_paths, size_t n, int is_delta, float lr, float mu, hipStream_t s);
+dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s);
+dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s);
+
+// ---- route.hip ---------------------------------------------------------------------------------------
+dipaco_status launch_route(const float* z, const float* c, int64_t N, int D, int K, int* idx, long long* hist,
+                           float* margin, hipStream_t s);
+
+// ---- gemm.hip ----------------------------------------------------------------------------------------
+// C[M,N] = opA(A) . opB(B)  (+ epilogue), fp32 accumulation on the matrix cores.
+//   trans_a = 0: A is [M,K] row-major (lda);  1: A is [K,M] row-major (lda)
+//   trans_b = 0: B is [K,N] row-major (ldb);  1: B is [N,K] row-major (ldb)
+// Epilogue (all optional, applied in this order): + bias[n];  act = 1: aux_out = value, value = GELU(value);
+// act = 2: value *= GELU'(aux_in);  + resid[m,n].  aux and resid have row stride ldc.
+// out_f32 = 1 writes fp32 (used for weight gradients), else T.
+// splits > 1 (only with out_f32 and no epilogue): K is cut into `splits` ranges whose partial products go to
+// `partial` ([splits, M, N] fp32) and are then summed in index order.
+struct GemmArgs {
+  const void* A; const void* B; void* C;
+  int M, N, K;
+  long lda, ldb, ldc;
+  const void* bias;
+  const void* resid;
+  void* aux_out;
+  const void* aux_in;
+  int act;
+  int trans_a, trans_b;
+  int out_f32;
+  int splits;
+  float* partial;
+};
+template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s);
+
+// ---- transformer.hip ---------------------------------------------------------------------------------
+template <typename T>
+dipaco_status launch_embed(const T* tok_emb, const T* pos_emb, const int* tokens, T* x, int B, int S, int d,
+                           int vocab, hipStream_t s);
+template <typename T>
+dipaco_status launch_layernorm_fwd(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows,
+                                   int d, float eps, hipStream_t s);
+// dx = resid_grad (nullable) + LN backward of dy;  dg/db fp32 via `partial` ([ln_bwd_partial_floats] scratch).
+template <typename T>
+dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const float* mean, const float* rstd,
+                                   const T* resid_grad, T* dx, float* dg, float* db, float* partial, int rows,
+                                   int d, hipStream_t s);
+size_t ln_bwd_partial_floats(int rows, int d);
+// out[n] = sum_m x[m,n] (fp32, fixed order);  partial: colsum_partial_floats scratch
+template <typename T>
+dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, int cols, hipStream_t s);
+size_t colsum_partial_floats(int rows, int cols);
+// n_valid[0] = #targets >= 0
+dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStream_t s);
+// logits [rows, V] (T) -> nll[rows] fp32 and, in place, dlogits = (softmax - onehot)/n_valid (0 on ignored rows)
+template <typename T>
+dipaco_status launch_softmax_xent(T* logits, const int* targets, const int* n_valid, float* nll, int rows, int V,
+                                  hipStream_t s);
+// loss = sum(nll) / n_valid, fixed-order tree
+dipaco_status launch_mean_loss(const float* nll, const int* n_valid, float* loss, int rows, hipStream_t s);
+// token/position embedding gradients (deterministic).  ints: embed_bwd_scratch_ints(rows, vocab) scratch.
+template <typename T>
+dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, float* d_pos, int* scratch, int B,
+                               int S, int d, int vocab, int max_seq, hipStream_t s);
+size_t embed_bwd_scratch_ints(int rows, int vocab);
+
+// ---- attention.hip -----------------------------------------------------------------------------------
+// qkv: [B*S, 3A] (q | k | v, head h at columns h*dh), o: [B*S, A], lse: [B, H, S] fp32.
+template <typename T>
+dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S, int H, int dh, hipStream_t s);
+// dqkv: [B*S, 3A];  dscratch: [B, H, S] fp32 (rowsum(dO*O))
+template <typename T>
+dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv,
+                                   float* dscratch, int B, int S, int H, int dh, hipStream_t s);
+
+}  // namespace dipaco

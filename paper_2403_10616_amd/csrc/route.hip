@@ -1,0 +1,194 @@
+// k-means prefix routing: idx[n] = argmin_k ||z_n - c_k||^2, per-centroid histogram, and the gap between the
+// two best scores.  The argmin is taken over s(n,k) = ||c_k||^2 - 2 z_n.c_k (||z_n||^2 is common to all k), so
+// the work is one fp32 contraction z.C^T on the matrix cores (v_mfma_f32_32x32x2_f32) with the reduction over
+// centroids done in the epilogue: scores never reach memory.
+//
+// One workgroup (4 waves, 2 x 2) owns 128 points and walks the centroids in tiles of 256; every wave holds a
+// 64 x 128 block of scores in accumulators.  ||c_k||^2 is accumulated by the threads that stage the centroid
+// tile, from the very values they put into LDS.
+#include "kernels.h"
+#include "mma_tile.h"
+
+namespace dipaco {
+
+namespace {
+
+constexpr int RBM = 128;   // points per workgroup
+constexpr int RBN = 256;   // centroids per tile
+constexpr int RBK = 32;    // fp32 K tile
+constexpr int R_STAGE = (RBM + RBN) * TILE_ROW_BYTES;
+constexpr int R_MAX_K_LDS_HIST = 4096;
+
+struct Best {
+  float s1; int i1; float s2;
+};
+
+__device__ __forceinline__ void best_insert(Best& b, float s, int i) {
+  if (s < b.s1 || (s == b.s1 && i < b.i1)) { b.s2 = b.s1; b.s1 = s; b.i1 = i; }
+  else if (s < b.s2) b.s2 = s;
+}
+__device__ __forceinline__ void best_merge(Best& a, float s1, int i1, float s2) {
+  if (s1 < a.s1 || (s1 == a.s1 && i1 < a.i1)) { a.s2 = fminf(a.s1, s2); a.s1 = s1; a.i1 = i1; }
+  else a.s2 = fminf(a.s2, s1);
+}
+
+__global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __restrict__ z, const float* __restrict__ c,
+                                                             long N, int D, int K, int* __restrict__ idx,
+                                                             unsigned long long* __restrict__ hist,
+                                                             float* __restrict__ margin) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ float cnorm[RBN];
+  __shared__ float red_s1[2][RBM], red_s2[2][RBM];
+  __shared__ int red_i1[2][RBM];
+  __shared__ unsigned int lhist[R_MAX_K_LDS_HIST];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const long m0 = (long)blockIdx.x * RBM;
+  const int rows_left = (int)min((long)RBM, N - m0);
+  const float* zb = z + m0 * D;
+  const bool use_lhist = K <= R_MAX_K_LDS_HIST;
+  if (use_lhist) for (int k = tid; k < K; k += GEMM_THREADS) lhist[k] = 0;
+
+  using LZ = TileLoader<float, RBM, false>;
+  using LC = TileLoader<float, RBN, false>;
+  const int nkt = (D + RBK - 1) / RBK;
+
+  // running best / second best for the 32 rows (2 row tiles x 16) this lane sees
+  Best best[2][16];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { best[i][e].s1 = INFINITY; best[i][e].i1 = 0x7fffffff; best[i][e].s2 = INFINITY; }
+
+  for (int n0 = 0; n0 < K; n0 += RBN) {
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    float nrm[LC::NLD];
+#pragma unroll
+    for (int i = 0; i < LC::NLD; ++i) nrm[i] = 0.f;
+
+    uint4 rz[LZ::NLD], rc[LC::NLD];
+    const float* cb = c + (long)n0 * D;
+    const int crow_left = min(RBN, K - n0);
+    LZ::load(rz, zb, D, 0, rows_left, 0, D, tid);
+    LC::load(rc, cb, D, 0, crow_left, 0, D, tid);
+    __syncthreads();   // previous centroid tile's readers of LDS and of cnorm are done
+    LZ::store(rz, smem, tid);
+    LC::store(rc, smem + RBM * TILE_ROW_BYTES, tid);
+#pragma unroll
+    for (int i = 0; i < LC::NLD; ++i) {
+      float4 v = *reinterpret_cast<float4*>(&rc[i]);
+      nrm[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nkt; ++kt) {
+      char* cur = smem + (kt & 1) * R_STAGE;
+      char* nxt = smem + ((kt + 1) & 1) * R_STAGE;
+      const bool more = kt + 1 < nkt;
+      if (more) {
+        LZ::load(rz, zb, D, 0, rows_left, (kt + 1) * RBK, D, tid);
+        LC::load(rc, cb, D, 0, crow_left, (kt + 1) * RBK, D, tid);
+      }
+      mma_ktile<float, 2, 4>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 128, lane);
+      if (more) {
+        LZ::store(rz, nxt, tid);
+        LC::store(rc, nxt + RBM * TILE_ROW_BYTES, tid);
+#pragma unroll
+        for (int i = 0; i < LC::NLD; ++i) {
+          float4 v = *reinterpret_cast<float4*>(&rc[i]);
+          nrm[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+      }
+      __syncthreads();
+    }
+    // ||c||^2: thread tid staged chunk (tid & 7) of centroid rows (tid >> 3) + 32 i
+#pragma unroll
+    for (int i = 0; i < LC::NLD; ++i) {
+      float v = nrm[i];
+      v += __shfl_xor(v, 1, WAVE);
+      v += __shfl_xor(v, 2, WAVE);
+      v += __shfl_xor(v, 4, WAVE);
+      if ((tid & 7) == 0) cnorm[(tid >> 3) + 32 * i] = v;
+    }
+    __syncthreads();
+    // fold this centroid tile into the running best of every row this lane sees
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = wn * 128 + 32 * j + (lane & 31);
+      const int k = n0 + col;
+      const float cn = cnorm[col];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float s = (k < K) ? cn - 2.0f * acc[i][j][e] : INFINITY;
+          best_insert(best[i][e], s, k < K ? k : 0x7fffffff);
+        }
+    }
+  }
+
+  // reduce over the 32 lanes that share a row (same lane half), then over the two waves along N
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      Best b = best[i][e];
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {
+        float s1 = __shfl_xor(b.s1, o, WAVE);
+        int i1 = __shfl_xor(b.i1, o, WAVE);
+        float s2 = __shfl_xor(b.s2, o, WAVE);
+        best_merge(b, s1, i1, s2);
+      }
+      if ((lane & 31) == 0) {
+        const int row = wm * 64 + 32 * i + acc_row(e, lane);
+        red_s1[wn][row] = b.s1; red_i1[wn][row] = b.i1; red_s2[wn][row] = b.s2;
+      }
+    }
+  __syncthreads();
+  if (tid < RBM && tid < rows_left) {
+    Best b; b.s1 = red_s1[0][tid]; b.i1 = red_i1[0][tid]; b.s2 = red_s2[0][tid];
+    best_merge(b, red_s1[1][tid], red_i1[1][tid], red_s2[1][tid]);
+    idx[m0 + tid] = b.i1;
+    if (margin) margin[m0 + tid] = b.s2 - b.s1;
+    if (use_lhist) atomicAdd(&lhist[b.i1], 1u);
+    else atomicAdd(&hist[b.i1], 1ull);
+  }
+  if (use_lhist) {
+    __syncthreads();
+    for (int k = tid; k < K; k += GEMM_THREADS) {
+      unsigned int v = lhist[k];
+      if (v) atomicAdd(&hist[k], (unsigned long long)v);
+    }
+  }
+}
+
+}  // namespace
+
+dipaco_status launch_route(const float* z, const float* c, int64_t N, int D, int K, int* idx, long long* hist,
+                           float* margin, hipStream_t s) {
+  dipaco_status st = launch_fill_i64(hist, 0, (size_t)K, s);
+  if (st != DIPACO_OK) return st;
+  if (N == 0) return DIPACO_OK;
+  constexpr size_t smem = 2 * (size_t)R_STAGE;
+  static bool attr_set = false;
+  if (!attr_set) {
+    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  const int64_t blocks = (N + RBM - 1) / RBM;
+  if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "route: N too large");
+  route_kernel<<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, c, (long)N, D, K, idx,
+                                                           reinterpret_cast<unsigned long long*>(hist), margin);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+}  // namespace dipaco

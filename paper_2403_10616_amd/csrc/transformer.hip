@@ -1,0 +1,533 @@
+// Row-wise kernels of the path transformer: embedding gather, LayerNorm forward/backward, column sums (bias
+// gradients), softmax cross-entropy over the vocabulary, and the deterministic embedding gradient.
+// All are HBM-bound: I/O in the activation type T (fp32 or bf16), arithmetic in fp32, 16-byte accesses.
+#include <algorithm>
+
+#include "kernels.h"
+
+namespace dipaco {
+
+namespace {
+
+constexpr int ROW_THREADS = 256;
+constexpr int ROWS_PER_BLOCK = ROW_THREADS / WAVE;  // one wave per row
+
+// ---- embedding -------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(ROW_THREADS) embed_kernel(const T* __restrict__ E, const T* __restrict__ P,
+                                                            const int* __restrict__ tok, T* __restrict__ x, int rows,
+                                                            int S, int d, int vocab) {
+  constexpr int VEC = Vec16<T>::N;
+  const int row = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  int t = tok[row];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  const T* e = E + (size_t)t * d;
+  const T* p = P + (size_t)(row % S) * d;
+  T* o = x + (size_t)row * d;
+  for (int c = lane * VEC; c < d; c += WAVE * VEC) {
+    float a[VEC], b[VEC];
+    load_vec16(e + c, a);
+    load_vec16(p + c, b);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) a[i] += b[i];
+    store_vec16(o + c, a);
+  }
+}
+
+// ---- LayerNorm forward: one wave per row ------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(ROW_THREADS) ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                             const T* __restrict__ b, T* __restrict__ y,
+                                                             float* __restrict__ mean, float* __restrict__ rstd,
+                                                             int rows, int d, float eps) {
+  constexpr int VEC = Vec16<T>::N;
+  const int row = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const T* xr = x + (size_t)row * d;
+  float s = 0.f;
+  for (int c = lane * VEC; c < d; c += WAVE * VEC) {
+    float a[VEC];
+    load_vec16(xr + c, a);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) s += a[i];
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+  for (int c = lane * VEC; c < d; c += WAVE * VEC) {
+    float a[VEC];
+    load_vec16(xr + c, a);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { float t = a[i] - mu; q += t * t; }
+  }
+  const float rs = 1.0f / sqrtf(wave_sum(q) / d + eps);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  T* yr = y + (size_t)row * d;
+  for (int c = lane * VEC; c < d; c += WAVE * VEC) {
+    float a[VEC], gg[VEC], bb[VEC];
+    load_vec16(xr + c, a);
+    load_vec16(g + c, gg);
+    load_vec16(b + c, bb);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) a[i] = (a[i] - mu) * rs * gg[i] + bb[i];
+    store_vec16(yr + c, a);
+  }
+}
+
+// ---- LayerNorm backward -----------------------------------------------------------------------------------
+// Each workgroup owns LN_BWD_ROWS consecutive rows (one wave per row at a time), writes dx for them and one
+// partial row of dg / db; a second kernel sums the partial rows in block order.
+constexpr int LN_BWD_ROWS = 64;
+constexpr int LN_MAX_IT = 4;   // column chunks per lane: d <= 64 * VEC * LN_MAX_IT
+
+template <typename T>
+__global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                             const T* __restrict__ g, const float* __restrict__ mean,
+                                                             const float* __restrict__ rstd,
+                                                             const T* __restrict__ resid_grad, T* __restrict__ dx,
+                                                             float* __restrict__ partial, int rows, int d) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int NIT = (sizeof(T) == 4) ? 2 * LN_MAX_IT : LN_MAX_IT;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row0 = blockIdx.x * LN_BWD_ROWS;
+  float ag[NIT][VEC], ab[NIT][VEC];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { ag[it][i] = 0.f; ab[it][i] = 0.f; }
+
+  for (int r = wave; r < LN_BWD_ROWS; r += ROWS_PER_BLOCK) {
+    const int row = row0 + r;
+    if (row >= rows) break;
+    const float mu = mean[row], rs = rstd[row];
+    const T* xr = x + (size_t)row * d;
+    const T* dyr = dy + (size_t)row * d;
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = (lane + WAVE * it) * VEC;
+      if (c < d) {
+        float xv[VEC], dv[VEC], gv[VEC];
+        load_vec16(xr + c, xv);
+        load_vec16(dyr + c, dv);
+        load_vec16(g + c, gv);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          const float xh = (xv[i] - mu) * rs;
+          const float dxh = dv[i] * gv[i];
+          s1 += dxh;
+          s2 += dxh * xh;
+          ag[it][i] += dv[i] * xh;
+          ab[it][i] += dv[i];
+        }
+      }
+    }
+    const float c1 = wave_sum(s1) / d, c2 = wave_sum(s2) / d;
+    T* dxr = dx + (size_t)row * d;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = (lane + WAVE * it) * VEC;
+      if (c < d) {
+        float xv[VEC], dv[VEC], gv[VEC], out[VEC];
+        load_vec16(xr + c, xv);
+        load_vec16(dyr + c, dv);
+        load_vec16(g + c, gv);
+        if (resid_grad) load_vec16(resid_grad + (size_t)row * d + c, out);
+        else {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) out[i] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          const float xh = (xv[i] - mu) * rs;
+          out[i] += rs * (dv[i] * gv[i] - c1 - xh * c2);
+        }
+        store_vec16(dxr + c, out);
+      }
+    }
+  }
+  // combine the four waves' column sums in wave order: each wave in turn adds into a [2][d] LDS row
+  extern __shared__ float cols[];
+  for (int w = 0; w < ROWS_PER_BLOCK; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int c = (lane + WAVE * it) * VEC;
+        if (c < d) {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) {
+            if (w == 0) { cols[c + i] = ag[it][i]; cols[d + c + i] = ab[it][i]; }
+            else { cols[c + i] += ag[it][i]; cols[d + c + i] += ab[it][i]; }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  float* out = partial + (size_t)blockIdx.x * 2 * d;
+  for (int c = threadIdx.x; c < 2 * d; c += ROW_THREADS) out[c] = cols[c];
+}
+
+// out[c] = sum over p of partial[p * stride + c], p in index order
+__global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restrict__ partial, float* __restrict__ out0,
+                                                           float* __restrict__ out1, int n_partials, int stride,
+                                                           int d) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= stride) return;
+  float s = 0.f;
+  for (int p = 0; p < n_partials; ++p) s += partial[(size_t)p * stride + c];
+  if (c < d) out0[c] = s;
+  else out1[c - d] = s;
+}
+
+// ---- column sums -----------------------------------------------------------------------------------------
+constexpr int CS_ROWS = 256;   // rows per workgroup
+template <typename T>
+__global__ void __launch_bounds__(ROW_THREADS) colsum_kernel(const T* __restrict__ x, float* __restrict__ partial,
+                                                             int rows, int cols) {
+  constexpr int VEC = Vec16<T>::N;
+  // workgroup: 64 column chunks (16 B each) x 4 row phases
+  __shared__ float red[ROWS_PER_BLOCK][WAVE * VEC];
+  const int lane = threadIdx.x & 63, phase = threadIdx.x >> 6;
+  const int c = (blockIdx.x * WAVE + lane) * VEC;
+  const int row0 = blockIdx.y * CS_ROWS;
+  const int row1 = min(rows, row0 + CS_ROWS);
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  if (c < cols) {
+    for (int r = row0 + phase; r < row1; r += ROWS_PER_BLOCK) {
+      float v[VEC];
+      load_vec16(x + (size_t)r * cols + c, v);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += v[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) red[phase][lane * VEC + i] = acc[i];
+  __syncthreads();
+  if (phase == 0 && c < cols) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      float s = red[0][lane * VEC + i];
+      for (int p = 1; p < ROWS_PER_BLOCK; ++p) s += red[p][lane * VEC + i];
+      partial[(size_t)blockIdx.y * cols + c + i] = s;
+    }
+  }
+}
+
+// ---- loss ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) count_valid_kernel(const int* __restrict__ targets, int n,
+                                                           int* __restrict__ n_valid) {
+  __shared__ int red[16];
+  int c = 0;
+  for (int i = threadIdx.x; i < n; i += 1024) c += targets[i] >= 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, WAVE);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int s = 0;
+    for (int i = 0; i < 16; ++i) s += red[i];
+    n_valid[0] = s;
+  }
+}
+
+__device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = is_max ? fmaxf(r, red[i]) : r + red[i];
+  return r;
+}
+
+// one workgroup per row of logits
+template <typename T>
+__global__ void __launch_bounds__(ROW_THREADS) softmax_xent_kernel(T* __restrict__ logits,
+                                                                   const int* __restrict__ targets,
+                                                                   const int* __restrict__ n_valid,
+                                                                   float* __restrict__ nll, int V) {
+  constexpr int VEC = Vec16<T>::N;
+  __shared__ float red[ROWS_PER_BLOCK];
+  const int row = blockIdx.x;
+  T* lr = logits + (size_t)row * V;
+  const int tgt = targets[row];
+  if (tgt < 0) {   // ignored position: no loss, no gradient (uniform branch: tgt is per workgroup)
+    float zero[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) zero[i] = 0.f;
+    for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) store_vec16(lr + c, zero);
+    if (threadIdx.x == 0) nll[row] = 0.f;
+    return;
+  }
+  float mx = -INFINITY;
+  for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) {
+    float v[VEC];
+    load_vec16(lr + c, v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) mx = fmaxf(mx, v[i]);
+  }
+  mx = block_reduce(mx, red, true);
+  float se = 0.f;
+  for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) {
+    float v[VEC];
+    load_vec16(lr + c, v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) se += expf(v[i] - mx);
+  }
+  se = block_reduce(se, red, false);
+  const int t = tgt >= V ? V - 1 : tgt;
+  if (threadIdx.x == 0) nll[row] = logf(se) - (to_f32(lr[t]) - mx);
+  __syncthreads();   // lr[t] is read before anyone overwrites it
+  const float inv = 1.0f / se;
+  const float scale = 1.0f / (float)n_valid[0];
+  for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) {
+    float v[VEC];
+    load_vec16(lr + c, v);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      float p = expf(v[i] - mx) * inv;
+      if (c + i == t) p -= 1.0f;
+      v[i] = p * scale;
+    }
+    store_vec16(lr + c, v);
+  }
+}
+
+// loss = (sum of nll in a fixed tree order) / n_valid; one workgroup
+__global__ void __launch_bounds__(1024) mean_loss_kernel(const float* __restrict__ nll, const int* __restrict__ n_valid,
+                                                         float* __restrict__ loss, int rows) {
+  __shared__ float red[16];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < rows; i += 1024) s += nll[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int i = 0; i < 16; ++i) t += red[i];
+    loss[0] = t / (float)n_valid[0];
+  }
+}
+
+// ---- embedding gradient ----------------------------------------------------------------------------------
+// d_tok[v] = sum of dx rows whose token is v, added in increasing position order (no float atomics):
+//   count tokens -> exclusive scan -> stable slot of every position -> one workgroup per vocabulary row.
+__global__ void __launch_bounds__(256) tok_count_kernel(const int* __restrict__ tok, int rows, int vocab,
+                                                        int* __restrict__ count) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows) return;
+  int t = tok[i];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  atomicAdd(&count[t], 1);
+}
+
+// offsets[v] = sum_{u<v} count[u], offsets[vocab] = total; single workgroup
+__global__ void __launch_bounds__(1024) exclusive_scan_kernel(const int* __restrict__ count, int* __restrict__ offsets,
+                                                              int vocab) {
+  __shared__ int sums[1024];
+  const int per = (vocab + 1023) / 1024;
+  const int lo = min(vocab, (int)threadIdx.x * per), hi = min(vocab, lo + per);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += count[i];
+  sums[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int i = 0; i < 1024; ++i) { int t = sums[i]; sums[i] = run; run += t; }
+    offsets[vocab] = run;
+  }
+  __syncthreads();
+  int run = sums[threadIdx.x];
+  for (int i = lo; i < hi; ++i) { offsets[i] = run; run += count[i]; }
+}
+
+// order[offsets[tok[i]] + #{j < i : tok[j] == tok[i]}] = i
+__global__ void __launch_bounds__(256) tok_slot_kernel(const int* __restrict__ tok, const int* __restrict__ offsets,
+                                                       int rows, int vocab, int* __restrict__ order) {
+  __shared__ int tile[256];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  int mine = -1;
+  if (i < rows) { mine = tok[i]; mine = mine < 0 ? 0 : (mine >= vocab ? vocab - 1 : mine); }
+  int rank = 0;
+  for (int base = 0; base <= (int)blockIdx.x * 256; base += 256) {
+    const int j = base + threadIdx.x;
+    int t = -2;
+    if (j < rows) { t = tok[j]; t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t); }
+    __syncthreads();
+    tile[threadIdx.x] = t;
+    __syncthreads();
+    const int lim = min(256, i - base);   // only positions before i
+    for (int k = 0; k < lim; ++k) rank += tile[k] == mine;
+  }
+  if (i < rows) order[offsets[mine] + rank] = i;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(128) tok_grad_kernel(const T* __restrict__ dx, const int* __restrict__ offsets,
+                                                       const int* __restrict__ order, float* __restrict__ d_tok, int d) {
+  constexpr int VEC = Vec16<T>::N;
+  const int v = blockIdx.x;
+  const int lo = offsets[v], hi = offsets[v + 1];
+  for (int c = threadIdx.x * VEC; c < d; c += 128 * VEC) {
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    for (int j = lo; j < hi; ++j) {
+      float a[VEC];
+      load_vec16(dx + (size_t)order[j] * d + c, a);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += a[i];
+    }
+    float* o = d_tok + (size_t)v * d + c;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] = acc[i];
+  }
+}
+
+// d_pos[s] = sum_b dx[b*S + s] for s < S, 0 for S <= s < max_seq
+template <typename T>
+__global__ void __launch_bounds__(128) pos_grad_kernel(const T* __restrict__ dx, float* __restrict__ d_pos, int B, int S,
+                                                       int d) {
+  constexpr int VEC = Vec16<T>::N;
+  const int s = blockIdx.x;
+  for (int c = threadIdx.x * VEC; c < d; c += 128 * VEC) {
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    if (s < S) {
+      for (int b = 0; b < B; ++b) {
+        float a[VEC];
+        load_vec16(dx + ((size_t)b * S + s) * d + c, a);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += a[i];
+      }
+    }
+    float* o = d_pos + (size_t)s * d + c;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] = acc[i];
+  }
+}
+
+__global__ void __launch_bounds__(256) fill_int_kernel(int* p, int v, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+inline int row_blocks(int rows) { return (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK; }
+
+}  // namespace
+
+template <typename T>
+dipaco_status launch_embed(const T* E, const T* P, const int* tokens, T* x, int B, int S, int d, int vocab,
+                           hipStream_t s) {
+  const int rows = B * S;
+  embed_kernel<T><<<row_blocks(rows), ROW_THREADS, 0, s>>>(E, P, tokens, x, rows, S, d, vocab);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+template <typename T>
+dipaco_status launch_layernorm_fwd(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows,
+                                   int d, float eps, hipStream_t s) {
+  ln_fwd_kernel<T><<<row_blocks(rows), ROW_THREADS, 0, s>>>(x, g, b, y, mean, rstd, rows, d, eps);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+size_t ln_bwd_partial_floats(int rows, int d) {
+  return (size_t)((rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS) * 2 * d;
+}
+
+template <typename T>
+dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const float* mean, const float* rstd,
+                                   const T* resid_grad, T* dx, float* dg, float* db, float* partial, int rows,
+                                   int d, hipStream_t s) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int NIT = (sizeof(T) == 4) ? 2 * LN_MAX_IT : LN_MAX_IT;
+  if (d > WAVE * VEC * NIT) return fail(DIPACO_ESHAPE, "layernorm backward: d_model above 2048");
+  const int blocks = (rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS;
+  ln_bwd_kernel<T><<<blocks, ROW_THREADS, 2 * d * sizeof(float), s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial,
+                                                                     rows, d);
+  DIPACO_LAUNCH_CHECK();
+  sum_partials_kernel<<<(2 * d + 255) / 256, 256, 0, s>>>(partial, dg, db, blocks, 2 * d, d);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+size_t colsum_partial_floats(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols; }
+
+template <typename T>
+dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, int cols, hipStream_t s) {
+  constexpr int VEC = Vec16<T>::N;
+  const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
+  dim3 grid((cols + WAVE * VEC - 1) / (WAVE * VEC), chunks);
+  colsum_kernel<T><<<grid, ROW_THREADS, 0, s>>>(x, partial, rows, cols);
+  DIPACO_LAUNCH_CHECK();
+  sum_partials_kernel<<<(cols + 255) / 256, 256, 0, s>>>(partial, out, out, chunks, cols, cols);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStream_t s) {
+  count_valid_kernel<<<1, 1024, 0, s>>>(targets, n, n_valid);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+template <typename T>
+dipaco_status launch_softmax_xent(T* logits, const int* targets, const int* n_valid, float* nll, int rows, int V,
+                                  hipStream_t s) {
+  softmax_xent_kernel<T><<<rows, ROW_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_mean_loss(const float* nll, const int* n_valid, float* loss, int rows, hipStream_t s) {
+  mean_loss_kernel<<<1, 1024, 0, s>>>(nll, n_valid, loss, rows);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+size_t embed_bwd_scratch_ints(int rows, int vocab) { return (size_t)vocab + (size_t)vocab + 1 + (size_t)rows; }
+
+template <typename T>
+dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, float* d_pos, int* scratch, int B,
+                               int S, int d, int vocab, int max_seq, hipStream_t s) {
+  const int rows = B * S;
+  int* count = scratch;
+  int* offsets = scratch + vocab;
+  int* order = offsets + vocab + 1;
+  fill_int_kernel<<<(vocab + 255) / 256, 256, 0, s>>>(count, 0, vocab);
+  DIPACO_LAUNCH_CHECK();
+  tok_count_kernel<<<(rows + 255) / 256, 256, 0, s>>>(tokens, rows, vocab, count);
+  DIPACO_LAUNCH_CHECK();
+  exclusive_scan_kernel<<<1, 1024, 0, s>>>(count, offsets, vocab);
+  DIPACO_LAUNCH_CHECK();
+  tok_slot_kernel<<<(rows + 255) / 256, 256, 0, s>>>(tokens, offsets, rows, vocab, order);
+  DIPACO_LAUNCH_CHECK();
+  tok_grad_kernel<T><<<vocab, 128, 0, s>>>(dx, offsets, order, d_tok, d);
+  DIPACO_LAUNCH_CHECK();
+  pos_grad_kernel<T><<<max_seq, 128, 0, s>>>(dx, d_pos, B, S, d);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+#define INSTANTIATE(T)                                                                                              \
+  template dipaco_status launch_embed<T>(const T*, const T*, const int*, T*, int, int, int, int, hipStream_t);       \
+  template dipaco_status launch_layernorm_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float,  \
+                                                 hipStream_t);                                                      \
+  template dipaco_status launch_layernorm_bwd<T>(const T*, const T*, const T*, const float*, const float*, const T*, \
+                                                 T*, float*, float*, float*, int, int, hipStream_t);                \
+  template dipaco_status launch_colsum<T>(const T*, float*, float*, int, int, hipStream_t);                          \
+  template dipaco_status launch_softmax_xent<T>(T*, const int*, const int*, float*, int, int, hipStream_t);          \
+  template dipaco_status launch_embed_bwd<T>(const T*, const int*, float*, float*, int*, int, int, int, int, int,    \
+                                             hipStream_t);
+INSTANTIATE(float)
+INSTANTIATE(bf16)
+
+}  // namespace dipaco

@@ -1,0 +1,135 @@
+"""GPU parity of single kernels (through the C ABI) against their plain definitions in fp64."""
+import math
+
+import numpy as np
+import pytest
+import torch
+from scipy.special import erf
+
+import paper_2403_10616_amd as dp
+from oracle import dipaco_oracle as orc
+from gpu_util import DEV, dev, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TDT = {dp.F32: torch.float32, dp.BF16: torch.bfloat16}
+
+
+def _rand(shape, seed, dtype):
+    """fp32 draws, rounded to the kernel's operand type so that the fp64 reference sees the same values."""
+    x = np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
+    t = torch.from_numpy(x).to(TDT[dtype])
+    return t.to(DEV), t.to(torch.float64).numpy()
+
+
+# (M, N, K): several tiles with ragged tails in every direction; K not a multiple of the K tile
+GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (1, 8, 8), (300, 264, 520), (64, 512, 1000)]
+
+
+@pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_forward_layout_with_epilogues(dtype, M, N, K):
+    print(f"gemm fwd dtype={dtype} M={M} N={N} K={K}", flush=True)
+    A, Ar = _rand((M, K), 1, dtype)
+    B, Br = _rand((K, N), 2, dtype)
+    bias, br = _rand((N,), 3, dtype)
+    resid, rr = _rand((M, N), 4, dtype)
+    tol = 1e-5 if dtype == dp.F32 else 6e-3
+    scale = math.sqrt(K)
+    # plain
+    C = torch.empty((M, N), dtype=TDT[dtype], device=DEV)
+    dp.dipaco_k_gemm(dtype, False, False, False, M, N, K, A, B, C)
+    ref = Ar @ Br
+    assert np.abs(host(C) - ref).max() <= tol * scale * 4
+    assert rel_l2(host(C), ref) <= tol
+    # bias + residual
+    dp.dipaco_k_gemm(dtype, False, False, False, M, N, K, A, B, C, bias=bias, resid=resid)
+    assert rel_l2(host(C), ref + br + rr) <= tol
+    # bias + GELU, pre-activation saved
+    U = torch.empty_like(C)
+    dp.dipaco_k_gemm(dtype, False, False, False, M, N, K, A, B, C, bias=bias, aux_out=U, act=1)
+    u_ref = ref + br
+    assert rel_l2(host(U), u_ref) <= tol
+    u_seen = host(U).astype(np.float64)
+    g_ref = 0.5 * u_seen * (1 + erf(u_seen / math.sqrt(2)))
+    assert rel_l2(host(C), g_ref) <= tol
+
+
+@pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_input_gradient_layout(dtype, M, N, K):
+    print(f"gemm dX dtype={dtype} M={M} N={N} K={K}", flush=True)
+    A, Ar = _rand((M, K), 5, dtype)
+    Bt, Btr = _rand((N, K), 6, dtype)          # B stored [N, K]
+    U, Ur = _rand((M, N), 7, dtype)
+    tol = 1e-5 if dtype == dp.F32 else 6e-3
+    C = torch.empty((M, N), dtype=TDT[dtype], device=DEV)
+    dp.dipaco_k_gemm(dtype, False, True, False, M, N, K, A, Bt, C)
+    ref = Ar @ Btr.T
+    assert rel_l2(host(C), ref) <= tol
+    dp.dipaco_k_gemm(dtype, False, True, False, M, N, K, A, Bt, C, aux_in=U, act=2)
+    gp = 0.5 * (1 + erf(Ur / math.sqrt(2))) + Ur * np.exp(-0.5 * Ur * Ur) / math.sqrt(2 * math.pi)
+    assert rel_l2(host(C), ref * gp) <= tol
+
+
+@pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
+@pytest.mark.parametrize("M,N,K,splits", [(128, 128, 64, 1), (200, 136, 77, 1), (72, 264, 1000, 4), (8, 8, 5, 1),
+                                          (136, 64, 4099, 16)])
+def test_gemm_weight_gradient_layout_and_split_k(dtype, M, N, K, splits):
+    print(f"gemm dW dtype={dtype} M={M} N={N} K={K} splits={splits}", flush=True)
+    At, Atr = _rand((K, M), 8, dtype)          # A stored [K, M]: contraction over rows (tokens)
+    B, Br = _rand((K, N), 9, dtype)
+    C = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    partial = torch.empty((splits, M, N), dtype=torch.float32, device=DEV) if splits > 1 else None
+    dp.dipaco_k_gemm(dtype, True, False, True, M, N, K, At, B, C, splits=splits, partial=partial)
+    ref = Atr.T @ Br
+    assert rel_l2(host(C), ref) <= 2e-6
+    first = host(C).copy()
+    dp.dipaco_k_gemm(dtype, True, False, True, M, N, K, At, B, C, splits=splits, partial=partial)
+    assert np.array_equal(first, host(C))       # fixed summation order: bit-identical from call to call
+
+
+def _attn_ref(qkv, B, S, H, dh):
+    a = orc.Arch((1,), H * dh, H, dh, 8, 8, S)
+    A = H * dh
+    o = np.empty((B * S, A))
+    lse = np.empty((B, H, S))
+    probs = []
+    for b in range(B):
+        x = qkv[b * S:(b + 1) * S]
+        ob, pb = orc._attention(x[:, :A], x[:, A:2 * A], x[:, 2 * A:], a)
+        o[b * S:(b + 1) * S] = ob
+        probs.append(pb)
+        for h in range(H):
+            s = (x[:, h * dh:(h + 1) * dh] @ x[:, A + h * dh:A + (h + 1) * dh].T) / math.sqrt(dh)
+            s = np.where(np.tril(np.ones((S, S), bool)), s, -np.inf)
+            mx = s.max(-1)
+            lse[b, h] = mx + np.log(np.exp(s - mx[:, None]).sum(-1))
+    return a, o, lse, probs
+
+
+@pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
+@pytest.mark.parametrize("B,S,H,dh", [(2, 64, 2, 32), (1, 200, 3, 64), (2, 77, 1, 128), (1, 1, 2, 64), (1, 333, 2, 64)])
+def test_attention_forward_backward(dtype, B, S, H, dh):
+    print(f"attention dtype={dtype} B={B} S={S} H={H} dh={dh}", flush=True)
+    A = H * dh
+    qkv, qr = _rand((B * S, 3 * A), 10, dtype)
+    d_o, gr = _rand((B * S, A), 11, dtype)
+    o = torch.empty((B * S, A), dtype=TDT[dtype], device=DEV)
+    lse = torch.empty((B, H, S), dtype=torch.float32, device=DEV)
+    dp.dipaco_k_attention_fwd(dtype, qkv, o, lse, B, S, H, dh)
+    a, o_ref, lse_ref, probs = _attn_ref(qr, B, S, H, dh)
+    tol = 2e-5 if dtype == dp.F32 else 1e-2
+    assert rel_l2(host(o), o_ref) <= tol
+    assert np.abs(host(lse) - lse_ref).max() <= (1e-5 if dtype == dp.F32 else 2e-2)
+    dqkv = torch.empty_like(qkv)
+    dsum = torch.empty((B, H, S), dtype=torch.float32, device=DEV)
+    dp.dipaco_k_attention_bwd(dtype, qkv, o, d_o, lse, dqkv, dsum, B, S, H, dh)
+    ref = np.empty((B * S, 3 * A))
+    for b in range(B):
+        x = qr[b * S:(b + 1) * S]
+        dq, dk, dv = orc._attention_bwd(gr[b * S:(b + 1) * S], x[:, :A], x[:, A:2 * A], x[:, 2 * A:], probs[b], a)
+        ref[b * S:(b + 1) * S] = np.concatenate([dq, dk, dv], axis=1)
+    got = host(dqkv)
+    for name, sl in (("dq", slice(0, A)), ("dk", slice(A, 2 * A)), ("dv", slice(2 * A, 3 * A))):
+        assert rel_l2(got[:, sl], ref[:, sl]) <= (2e-5 if dtype == dp.F32 else 2e-2), name

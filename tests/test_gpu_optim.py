@@ -1,0 +1,105 @@
+"""GPU parity of compose, AdamW and the module outer step against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import dipaco_inputs as gen
+import paper_2403_10616_amd as dp
+from oracle import dipaco_oracle as orc
+from gpu_util import DEV, dev, host, make_arch, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+SMALL = dict(layers_per_level=(2, 1), d_model=64, n_heads=2, d_head=32, d_mlp=136, vocab=264, max_seq=40)
+
+
+@pytest.mark.parametrize("compute", [dp.F32, dp.BF16])
+def test_compose_path_round_trip_and_bf16_image(compute):
+    a, ctx = make_arch(SMALL, compute)
+    bounds = orc.segment_bounds(a)
+    rng = np.random.default_rng(0)
+    segs = [rng.standard_normal(hi - lo).astype(np.float32) for lo, hi in bounds]
+    want = orc.compose_path(segs)
+    n = dp.dipaco_path_param_count(ctx)
+    master = torch.zeros(n, dtype=torch.float32, device=DEV)
+    lowp = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    dp.dipaco_compose_path(ctx, [dev(s) for s in segs], master, lowp)
+    assert np.array_equal(host(master).astype(np.float64), want)
+    # bf16 image: round-to-nearest-even of every element, bit-exact against torch's cast
+    assert torch.equal(lowp.cpu(), torch.from_numpy(want.astype(np.float32)).to(torch.bfloat16))
+    master.zero_()
+    dp.dipaco_compose_path(ctx, [dev(s) for s in segs], master, None)
+    assert np.array_equal(host(master).astype(np.float64), want)
+
+
+@pytest.mark.parametrize("compute", [dp.F32, dp.BF16])
+def test_adamw_three_steps_match_oracle(compute):
+    a, ctx = make_arch(SMALL, compute)
+    n = orc.param_count(a)
+    mask = orc.decay_mask(a)
+    rng = np.random.default_rng(1)
+    theta = rng.standard_normal(n).astype(np.float32)
+    th_d = dev(theta)
+    m_d = torch.zeros(n, dtype=torch.float32, device=DEV)
+    v_d = torch.zeros(n, dtype=torch.float32, device=DEV)
+    lowp = torch.zeros(n, dtype=torch.bfloat16, device=DEV) if compute == dp.BF16 else None
+    th_o, m_o, v_o = theta.astype(np.float64), np.zeros(n), np.zeros(n)
+    for step in (1, 2, 3):
+        g = (rng.standard_normal(n) * 10.0 ** rng.integers(-6, 1, size=n)).astype(np.float32)
+        g[::97] = 0.0
+        dp.dipaco_inner_adamw(ctx, th_d, dev(g), m_d, v_d, lowp, step, 1e-3, 0.9, 0.95, 1e-8, 0.1)
+        th_o, m_o, v_o = orc.adamw_step(th_o, g, m_o, v_o, step, 1e-3, 0.9, 0.95, 1e-8, 0.1, mask)
+        assert np.abs(host(th_d) - th_o).max() <= 2e-6 * np.abs(th_o).max()
+        assert rel_l2(host(th_d), th_o) <= 1e-6 and rel_l2(host(m_d), m_o) <= 1e-6 and rel_l2(host(v_d), v_o) <= 1e-6
+    # decay really is confined to the matrices: a zero-gradient step moves only decayed entries
+    before = host(th_d).copy()
+    m_d.zero_(); v_d.zero_()
+    dp.dipaco_inner_adamw(ctx, th_d, torch.zeros_like(th_d), m_d, v_d, lowp, 1, 1e-2, 0.9, 0.95, 1e-8, 0.5)
+    moved = host(th_d) != before
+    assert np.array_equal(moved, (mask > 0) & (before != 0))
+    if lowp is not None:
+        assert torch.equal(lowp.cpu(), th_d.cpu().to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("n_paths,n_elems,weighted,is_delta", [
+    (1, 1000, False, False), (2, 4096 + 3, True, False), (16, 70_001, True, True), (16, 1 << 20, True, False),
+    (5, 12_345, False, True), (37, 9_999, True, False), (256, 2_048, True, False)])
+def test_outer_step_matches_oracle_over_two_steps(n_paths, n_elems, weighted, is_delta):
+    rng = np.random.default_rng(n_paths)
+    theta = (rng.standard_normal(n_elems) * 0.02).astype(np.float32)
+    th_d, buf_d = dev(theta), torch.zeros(n_elems, dtype=torch.float32, device=DEV)
+    th_o, buf_o = theta.astype(np.float64), np.zeros(n_elems)
+    w = gen.shard_weights(n_paths, 3) if weighted else None
+    for step in range(2):
+        eps = [gen.perturbation(n_elems, 1e-3, 300 + 16 * step + i) for i in range(n_paths)]
+        cur = host(th_d).copy()
+        ins = [(-e if is_delta else cur + e) for e in eps]         # theta_i = theta + eps  =>  delta_i = -eps
+        ins = [np.asarray(x, dtype=np.float32) for x in ins]
+        dp.dipaco_module_outer_step(th_d, buf_d, [dev(x) for x in ins], w, n_elems, is_delta, 0.7, 0.9)
+        th_o, buf_o = orc.outer_step(cur, buf_o, ins, w, is_delta, 0.7, 0.9)
+        assert rel_l2(host(th_d), th_o) <= 1e-6
+        assert rel_l2(host(buf_d), buf_o) <= 2e-5      # delta is a small difference of fp32 numbers
+        buf_o = host(buf_d).astype(np.float64)          # continue from the device state, as th does
+
+
+def test_outer_step_special_cases():
+    n = 5000
+    rng = np.random.default_rng(0)
+    theta = rng.standard_normal(n).astype(np.float32)
+    local = (theta + rng.standard_normal(n).astype(np.float32) * 0.01).astype(np.float32)
+    # one path, no momentum, lr 1: the module becomes the path's copy (plain SGD on the delta)
+    th_d, buf_d = dev(theta), torch.zeros(n, dtype=torch.float32, device=DEV)
+    dp.dipaco_module_outer_step(th_d, buf_d, [dev(local)], None, n, False, 1.0, 0.0)
+    assert np.abs(host(th_d) - local).max() <= 1e-6
+    # permutation of the inputs changes nothing beyond fp32 reassociation
+    ins = [(theta + gen.perturbation(n, 1e-3, i)).astype(np.float32) for i in range(8)]
+    w = gen.shard_weights(8, 1)
+    outs = []
+    for perm in (list(range(8)), [3, 1, 7, 0, 2, 6, 5, 4]):
+        th_d, buf_d = dev(theta), torch.zeros(n, dtype=torch.float32, device=DEV)
+        dp.dipaco_module_outer_step(th_d, buf_d, [dev(ins[i]) for i in perm], w[perm], n, False, 0.7, 0.9)
+        outs.append(host(th_d).copy())
+    assert np.abs(outs[0] - outs[1]).max() <= 1e-6
+    # rejected inputs
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_module_outer_step(th_d, buf_d, [dev(ins[0])], [0.0], n, False, 0.7, 0.9)

@@ -1,0 +1,153 @@
+"""GPU parity of the path step (loss, per-token NLL, every gradient tensor) and of the whole inner/outer round
+against the oracle, through the five C-ABI calls.
+
+Tolerances (fp32): loss rel <= 1e-5, gradients and parameters rel <= 1e-4 per tensor (L2).  bf16: loss rel <= 2e-2;
+gradients are checked per tensor at rel <= 6e-2 as a supplementary bound (operands and activations are rounded to
+8 significant bits, accumulation is fp32).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import dipaco_inputs as gen
+import paper_2403_10616_amd as dp
+from oracle import dipaco_oracle as orc
+from gpu_util import DEV, PathState, dev, host, make_arch, per_tensor_rel, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = {
+    # several GEMM tiles with ragged tails (tokens = 3*50 = 150, widths not multiples of 128), heads*d_head != d_model
+    "ragged": dict(layers_per_level=(1, 2), d_model=72, n_heads=3, d_head=32, d_mlp=200, vocab=264, max_seq=56),
+    "wide": dict(layers_per_level=(1, 1), d_model=256, n_heads=2, d_head=64, d_mlp=520, vocab=1000, max_seq=160),
+    "one_level": dict(layers_per_level=(2,), d_model=64, n_heads=1, d_head=128, d_mlp=64, vocab=64, max_seq=16),
+}
+
+
+def _batch(cfg, B, S, seed, mask_prefix=0, zipf=False):
+    if zipf:
+        seqs = gen.zipf_tokens((B, S + 1), cfg["vocab"], 1.1, seed)
+    else:
+        seqs = gen.uniform_tokens((B, S + 1), cfg["vocab"], seed)
+    tok, tgt = gen.split_inputs_targets(seqs)
+    tgt = tgt.copy()
+    if mask_prefix:
+        tgt[:, :mask_prefix] = -1
+    return tok, tgt
+
+
+@pytest.mark.parametrize("name,B,S,mask", [("ragged", 3, 50, 0), ("ragged", 2, 56, 5), ("wide", 2, 160, 32),
+                                           ("one_level", 5, 16, 0), ("one_level", 1, 1, 0)])
+def test_fp32_loss_and_gradients_match_oracle(name, B, S, mask):
+    print(f"fp32 path {name} B={B} S={S} mask={mask}", flush=True)
+    cfg = SHAPES[name]
+    a, ctx = make_arch(cfg, dp.F32)
+    lay = orc.param_layout(a)
+    theta = gen.random_params(orc.param_count(a), seed=5, scale=0.08)
+    # LayerNorm gains near 1 so that activations keep a realistic scale
+    for n_, (off, shape, _) in lay.items():
+        if n_.endswith("_g"):
+            theta[off:off + shape[0]] += 1.0
+    tok, tgt = _batch(cfg, B, S, seed=6, mask_prefix=mask)
+    st = PathState(ctx, theta, B, S)
+    loss = st.fwd_bwd(tok, tgt)
+    o_loss, o_grad = orc.path_loss_and_grad(theta, a, tok, tgt)
+    assert abs(loss - o_loss) <= 1e-5 * abs(o_loss)
+    nll = host(st.nll).reshape(B, S)
+    o_nll = orc.path_token_nll(theta, a, tok, tgt)
+    assert np.abs(nll - o_nll).max() <= 2e-5 * max(1.0, np.abs(o_nll).max())
+    assert np.all(nll[tgt < 0] == 0.0)
+    worst, where = per_tensor_rel(lay, host(st.grads), o_grad)
+    assert worst <= 1e-4, (where, worst)
+    # bit-reproducible
+    g0 = host(st.grads).copy()
+    loss2 = st.fwd_bwd(tok, tgt)
+    assert loss2 == loss and np.array_equal(g0, host(st.grads))
+
+
+def test_config1_full_round_matches_oracle():
+    """Tiny 2x2 grid, fp32: compose -> 2 inner AdamW steps on each of the 4 paths -> outer Nesterov step of the
+    4 block modules (2 paths each) and of the stem and head (shared by all 4 paths)."""
+    cfg = gen.CONFIGS[1]
+    a, ctx = make_arch(cfg, dp.F32)
+    K = cfg["K"]
+    B, S, steps = cfg["batch"], cfg["seq"], cfg["inner_steps"]
+    lay = orc.param_layout(a)
+    bounds = orc.segment_bounds(a)
+    n = orc.param_count(a)
+    # global modules: stem, K[0] level-1 modules, K[1] level-2 modules, head -- distinct seeded inits
+    def seg(level, e):
+        full = gen.init_params(lay, a.n_layers, seed=1000 * level + e)
+        lo, hi = bounds[level]
+        return full[lo:hi].copy()
+    glob = {(0, 0): seg(0, 0), (3, 0): seg(3, 0)}
+    for l in (1, 2):
+        for e in range(K[l - 1]):
+            glob[(l, e)] = seg(l, e)
+    seqs = gen.uniform_tokens((4, steps, B, S + 1), cfg["vocab"], cfg["seed"])
+    mask = orc.decay_mask(a)
+
+    gpu_local, orc_local, losses = {}, {}, []
+    for j in range(4):
+        mods = dp.dipaco_path_modules(j, K)
+        assert mods == orc.modules_of_path(j, K)
+        keys = [(0, 0), (1, mods[0]), (2, mods[1]), (3, 0)]
+        segs = [glob[k] for k in keys]
+        master = torch.empty(n, dtype=torch.float32, device=DEV)
+        dp.dipaco_compose_path(ctx, [dev(s) for s in segs], master, None)
+        th_o = orc.compose_path(segs)
+        assert np.array_equal(host(master).astype(np.float64), th_o)
+        st = PathState(ctx, host(master), B, S)
+        m_o, v_o = np.zeros(n), np.zeros(n)
+        for t in range(steps):
+            tok, tgt = gen.split_inputs_targets(seqs[j, t])
+            loss = st.fwd_bwd(tok, tgt)
+            st.adamw(t + 1, cfg["lr"], cfg["beta1"], cfg["beta2"], cfg["eps"], cfg["wd"])
+            o_loss, o_g = orc.path_loss_and_grad(th_o, a, tok, tgt)
+            assert abs(loss - o_loss) <= 1e-5 * abs(o_loss), (j, t)
+            th_o, m_o, v_o = orc.adamw_step(th_o, o_g, m_o, v_o, t + 1, cfg["lr"], cfg["beta1"], cfg["beta2"],
+                                            cfg["eps"], cfg["wd"], mask)
+            losses.append((loss, o_loss))
+        worst, where = per_tensor_rel(lay, host(st.master), th_o)
+        assert worst <= 1e-4, (j, where, worst)
+        gpu_local[j], orc_local[j] = st.master, th_o
+    # outer step per module
+    for (level, e), theta_prev in glob.items():
+        lo, hi = bounds[level]
+        if level in (0, 3):
+            sharing = list(range(4))
+        else:
+            sharing = orc.paths_through_module(level - 1, e, K)
+            assert len(sharing) == 2
+        th_d = dev(theta_prev)
+        buf_d = torch.zeros(hi - lo, dtype=torch.float32, device=DEV)
+        ins = [gpu_local[j][lo:hi].clone() for j in sharing]     # 16-byte aligned copies of the paths' segments
+        dp.dipaco_module_outer_step(th_d, buf_d, ins, None, hi - lo, False, cfg["outer_lr"], cfg["outer_momentum"])
+        th_o, buf_o = orc.outer_step(theta_prev, np.zeros(hi - lo), [orc_local[j][lo:hi] for j in sharing], None, False,
+                                     cfg["outer_lr"], cfg["outer_momentum"])
+        assert rel_l2(host(th_d), th_o) <= 1e-4, (level, e)
+        # the update itself (theta - theta_prev) is small against theta: check it on its own scale too
+        assert rel_l2(host(th_d) - theta_prev, th_o - theta_prev) <= 2e-3, (level, e)
+
+
+@pytest.mark.parametrize("name,B,S,mask", [("ragged", 3, 50, 4), ("wide", 2, 160, 0)])
+def test_bf16_loss_and_gradients_close_to_oracle(name, B, S, mask):
+    print(f"bf16 path {name} B={B} S={S}", flush=True)
+    cfg = SHAPES[name]
+    a, ctx = make_arch(cfg, dp.BF16)
+    lay = orc.param_layout(a)
+    theta = gen.init_params(lay, a.n_layers, seed=8)
+    theta += gen.random_params(theta.size, seed=9, scale=0.02)          # non-zero biases, gains off 1
+    theta = torch.from_numpy(theta).to(torch.bfloat16).float().numpy()  # masters exactly representable in bf16
+    tok, tgt = _batch(cfg, B, S, seed=10, mask_prefix=mask, zipf=True)
+    st = PathState(ctx, theta, B, S)
+    loss = st.fwd_bwd(tok, tgt)
+    o_loss, o_grad = orc.path_loss_and_grad(theta, a, tok, tgt)
+    assert abs(loss - o_loss) <= 2e-2 * abs(o_loss)
+    assert abs(loss - o_loss) <= 2e-3 * abs(o_loss)      # in practice an order of magnitude closer
+    worst, where = per_tensor_rel(lay, host(st.grads), o_grad)
+    assert worst <= 6e-2, (where, worst)
+    g0 = host(st.grads).copy()
+    assert st.fwd_bwd(tok, tgt) == loss and np.array_equal(g0, host(st.grads))
