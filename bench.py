@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the DiPaCo path step on one MI355X.
+
+Default workload ("path_step"): one inner step of a 174M-parameter path -- forward, backward and AdamW over a
+[32, 1024] batch of Zipf(1.1) tokens, bf16 compute with fp32 master weights and optimiser state -- through the
+C-ABI calls dipaco_path_fwd_bwd + dipaco_inner_adamw.  Prints ONE JSON line.
+
+Other workloads (for profiling the bandwidth / routing kernels; same JSON shape):
+  --workload outer_step   16 deltas x 57,872,640 parameters, weighted mean + Nesterov
+  --workload route        2^20 x 768 prefix embeddings against 256 centroids
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # MI355X fp32 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def _arch_kwargs(cfg, compute):
+    return dict(layers_per_level=list(cfg["layers_per_level"]), d_model=cfg["d_model"], n_heads=cfg["n_heads"],
+                d_head=cfg["d_head"], d_mlp=cfg["d_mlp"], vocab=cfg["vocab"], max_seq=cfg["max_seq"], compute=compute)
+
+
+def step_gemm_shapes(cfg, B, S):
+    """(M, N, K) of every GEMM launch of one step, by kernel instantiation (operand layout)."""
+    T, d, A, F, V = B * S, cfg["d_model"], cfg["n_heads"] * cfg["d_head"], cfg["d_mlp"], cfg["vocab"]
+    NL = sum(cfg["layers_per_level"])
+    fwd = [(T, 3 * A, d), (T, d, A), (T, F, d), (T, d, F)] * NL + [(T, V, d)]
+    dx = [(T, F, d), (T, d, F), (T, A, d), (T, d, 3 * A)] * NL + [(T, d, V)]
+    dw = [(F, d, T), (d, F, T), (A, d, T), (d, 3 * A, T)] * NL + [(d, V, T)]
+    return fwd, dx, dw
+
+
+def attention_flops(cfg, B, S):
+    H, dh = cfg["n_heads"], cfg["d_head"]
+    NL = sum(cfg["layers_per_level"])
+    fwd = NL * B * H * (2 * 2 * S * S * dh) / 2          # QK^T and PV over the causal half
+    return fwd, 2.5 * fwd                                 # backward: five matmuls of the same size
+
+
+def bench_path_step(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+
+    cfg = gen.CONFIGS[2]
+    B, S = cfg["batch"], cfg["seq"]
+    ctx = dp.Context(**_arch_kwargs(cfg, dp.BF16))
+    n = dp.dipaco_path_param_count(ctx)
+    layout = {}
+    for i in range(dp.dipaco_tensor_count(ctx)):
+        name, off, rows, cols, dec = dp.dipaco_tensor_info(ctx, i)
+        layout[name] = (off, (rows, cols) if cols > 1 else (rows,), dec)
+    n_layers = sum(cfg["layers_per_level"])
+    theta = gen.init_params(layout, n_layers, cfg["seed"])
+    dev = "cuda"
+    # the path is composed from its four global segments, as at the start of a round
+    segs = []
+    for s_ in range(dp.dipaco_segment_count(ctx)):
+        lo = dp.dipaco_segment_offset(ctx, s_)
+        segs.append(torch.from_numpy(theta[lo:lo + dp.dipaco_segment_size(ctx, s_)]).to(dev))
+    master = torch.empty(n, dtype=torch.float32, device=dev)
+    lowp = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    dp.dipaco_compose_path(ctx, segs, master, lowp)
+    del segs
+    grads = torch.empty(n, dtype=torch.float32, device=dev)
+    m = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    ws = torch.empty(dp.dipaco_workspace_bytes(ctx, B, S), dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    n_batches = min(4, args.steps + args.warmup)
+    seqs = gen.zipf_tokens((n_batches, B, S + 1), cfg["vocab"], cfg["zipf_s"], cfg["seed"])
+    toks = [torch.from_numpy(np.ascontiguousarray(seqs[i, :, :-1])).to(dev) for i in range(n_batches)]
+    tgts = [torch.from_numpy(np.ascontiguousarray(seqs[i, :, 1:])).to(dev) for i in range(n_batches)]
+
+    def step(i):
+        dp.dipaco_path_fwd_bwd(ctx, master, lowp, toks[i % n_batches], tgts[i % n_batches], B, S, loss, None, grads, ws)
+        dp.dipaco_inner_adamw(ctx, master, grads, m, v, lowp, i + 1, cfg["lr"], cfg["beta1"], cfg["beta2"], cfg["eps"],
+                              cfg["wd"])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    final_loss = float(loss.item())
+
+    # ---- roofline of the dominant kernel: the forward-layout bf16 GEMM (projections, MLP, vocabulary head) ----
+    fwd, dx, dw = step_gemm_shapes(cfg, B, S)
+    T = B * S
+    big = max(max(M * N for M, N, K in fwd), max(M * K for M, N, K in fwd))
+    a_buf = torch.empty(big, dtype=torch.bfloat16, device=dev).normal_()
+    b_buf = torch.empty(max(K * N for M, N, K in fwd), dtype=torch.bfloat16, device=dev).normal_(std=0.02)
+    c_buf = torch.empty(big, dtype=torch.bfloat16, device=dev)
+
+    def replay():
+        for (M, N, K) in fwd:
+            dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, a_buf, b_buf, c_buf)
+    replay()
+    torch.cuda.synchronize()
+    reps = max(1, min(args.steps, 5))
+    e0.record()
+    for _ in range(reps):
+        replay()
+    e1.record()
+    torch.cuda.synchronize()
+    gemm_ms = e0.elapsed_time(e1) / reps
+    fwd_flops = sum(2.0 * M * N * K for M, N, K in fwd)
+    achieved = fwd_flops / (gemm_ms * 1e-3) / 1e12
+    att_f, att_b = attention_flops(cfg, B, S)
+    step_flops = 3.0 * fwd_flops + att_f + att_b
+    out = {
+        "metric": "path-step tokens/sec on 1 MI355X (~150M path fwd+bwd+AdamW)", "value": B * S / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 2: 174.0M-parameter path (12 blocks, d 896, 14x64 heads, MLP 3584, vocab 32000), "
+                               "batch 32 x seq 1024 Zipf(1.1) tokens, one fwd+bwd+AdamW step",
+                   "params": n, "tokens_per_step": B * S, "final_loss": final_loss,
+                   "model_tflops_per_step": step_flops / 1e12,
+                   "model_flops_utilisation": step_flops / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)},
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<bf16,bf16,A row-major,B row-major,128,128>",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": None, "launches_per_step": len(fwd), "flops_per_launch": fwd_flops / len(fwd),
+                     "avg_launch_us": gemm_ms * 1e3 / len(fwd)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_path_step(cfg, theta, seqs[0, :1], layout)
+    return out
+
+
+def cpu_baseline_path_step(cfg, theta, seqs, layout):
+    """The oracle (numpy fp64, as it stands) on one sequence of the same batch: forward, backward, AdamW."""
+    from oracle import dipaco_oracle as orc
+    a = orc.Arch(tuple(cfg["layers_per_level"]), cfg["d_model"], cfg["n_heads"], cfg["d_head"], cfg["d_mlp"],
+                 cfg["vocab"], cfg["max_seq"])
+    tok, tgt = seqs[:, :-1], seqs[:, 1:]
+    mask = orc.decay_mask(a)
+    t0 = time.perf_counter()
+    loss, g = orc.path_loss_and_grad(theta, a, tok, tgt)
+    orc.adamw_step(theta, g, np.zeros_like(g), np.zeros_like(g), 1, cfg["lr"], cfg["beta1"], cfg["beta2"], cfg["eps"],
+                   cfg["wd"], mask)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": tok.size / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of the 32 sequences (1024 tokens) of the same batch, fwd+bwd+AdamW in fp64 numpy, {dt:.1f} s",
+            "loss": loss}
+
+
+def bench_outer_step(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[3]
+    n, P = cfg["n_elems"], cfg["n_paths"]
+    dev = "cuda"
+    theta = torch.randn(n, device=dev) * 0.02
+    buf = torch.zeros(n, device=dev)
+    deltas = [torch.randn(n, device=dev) * cfg["delta_std"] for _ in range(P)]
+    w = gen.shard_weights(P, cfg["seed"])
+
+    def step():
+        dp.dipaco_module_outer_step(theta, buf, deltas, w, n, True, cfg["outer_lr"], cfg["outer_momentum"])
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / args.steps
+    bytes_ = (P + 4) * n * 4.0
+    ach = bytes_ / (ms * 1e-3) / 1e9
+    return {"metric": "module outer-step parameters/sec on 1 MI355X", "value": n / (wall / args.steps), "unit": "params/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "config 3: 57,872,640-parameter module, 16 weighted deltas, Nesterov"},
+            "roofline": {"bound": "hbm", "kernel": "outer_kernel<16>", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_}}
+
+
+def bench_route(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[4]
+    N, D, K = cfg["N"], cfg["D"], cfg["K"]
+    dev = "cuda"
+    z, c, _ = gen.gaussian_mixture(N, D, K, cfg["noise_std"], cfg["seed"])
+    zd, cd = torch.from_numpy(z).to(dev), torch.from_numpy(c).to(dev)
+    idx = torch.empty(N, dtype=torch.int32, device=dev)
+    hist = torch.empty(K, dtype=torch.int64, device=dev)
+    margin = torch.empty(N, dtype=torch.float32, device=dev)
+
+    def step():
+        dp.dipaco_route_prefix(zd, cd, N, D, K, idx, hist, margin)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * N * D * K
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"metric": "prefix-routing documents/sec on 1 MI355X", "value": N / (wall / args.steps), "unit": "documents/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "config 4: 1,048,576 x 768 embeddings from a 256-Gaussian mixture vs 256 centroids"},
+            "roofline": {"bound": "mfma", "kernel": "route_kernel", "achieved": ach, "peak": PEAK_F32_TFLOPS,
+                         "unit": "TFLOP/s", "frac": ach / PEAK_F32_TFLOPS, "traffic": None, "flops_per_launch": flops,
+                         "hbm_gbs": (N * D * 4.0 + N * 8.0) / (ms * 1e-3) / 1e9}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "route"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs one path on ONE GPU (no collectives, no sharding); use --gpus 1")
+    import paper_2403_10616_amd as dp
+    dp.load()   # fails loudly if libdipaco.so is not built
+    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route}[args.workload]
+    print(json.dumps(fn(args)))
+
+
+if __name__ == "__main__":
+    main()

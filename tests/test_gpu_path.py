@@ -110,7 +110,19 @@ def test_config1_full_round_matches_oracle():
             th_o, m_o, v_o = orc.adamw_step(th_o, o_g, m_o, v_o, t + 1, cfg["lr"], cfg["beta1"], cfg["beta2"],
                                             cfg["eps"], cfg["wd"], mask)
             losses.append((loss, o_loss))
-        worst, where = per_tensor_rel(lay, host(st.master), th_o)
+        # The key bias has an identically zero gradient (adding one vector to every key shifts all scores of a
+        # query equally, which softmax ignores), so what either side feeds AdamW there is rounding noise, and
+        # AdamW's g/(|g|+eps) turns noise of size ~eps into steps of size ~lr.  Those entries are compared
+        # against AdamW's step bound instead of the oracle's value.
+        got = host(st.master).astype(np.float64)
+        A = a.d_attn
+        for layer in range(a.n_layers):
+            off = lay[f"blk{layer}.b_qkv"][0]
+            ksl = slice(off + A, off + 2 * A)
+            assert np.abs(o_g[ksl]).max() <= 1e-9 * np.abs(o_g[off:off + A]).max()
+            assert np.abs(got[ksl]).max() <= steps * cfg["lr"] * 1.001
+            got[ksl] = th_o[ksl]
+        worst, where = per_tensor_rel(lay, got, th_o)
         assert worst <= 1e-4, (j, where, worst)
         gpu_local[j], orc_local[j] = st.master, th_o
     # outer step per module
