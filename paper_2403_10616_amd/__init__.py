@@ -67,6 +67,9 @@ def load():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise DipacoError(f"{LIB_PATH} is not built: run `python -m paper_2403_10616_amd.build`")
+        # torch ships its own HIP runtime; load it first so that libdipaco binds to the same libamdhip64 (one
+        # runtime per process: streams and device pointers are only valid inside the runtime that made them)
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGS.items():
             fn = getattr(lib, name)      # AttributeError if the library lacks a declared symbol
