@@ -5,7 +5,8 @@
 //
 // Reference kernels ("scalar" path): one thread per query row (forward, dQ) or per key row (dK, dV), fp32
 // arithmetic, online softmax, no atomics, so every output element is produced by one thread in a fixed order.
-// They serve fp32 runs and any head size; the bf16 matrix-core kernels live in attention_mfma.hip.
+// They serve fp32 runs and head sizes 32 / 128; bf16 with head size 64 runs on the matrix cores
+// (attention_mfma.hip).
 #include "kernels.h"
 
 namespace dipaco {
@@ -201,8 +202,12 @@ dipaco_status bwd_scalar(const T* qkv, const T* o, const T* d_o, const float* ls
 
 }  // namespace
 
+template <typename T> constexpr bool is_bf16() { return sizeof(T) == 2; }
+
 template <typename T>
 dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S, int H, int dh, hipStream_t s) {
+  if (is_bf16<T>() && dh == 64)
+    return launch_attention_fwd_mfma(reinterpret_cast<const bf16*>(qkv), reinterpret_cast<bf16*>(o), lse, B, S, H, s);
   switch (dh) {
     case 32: return fwd_scalar<T, 32>(qkv, o, lse, B, S, H, s);
     case 64: return fwd_scalar<T, 64>(qkv, o, lse, B, S, H, s);
@@ -214,6 +219,10 @@ dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S,
 template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv, float* dsum,
                                    int B, int S, int H, int dh, hipStream_t s) {
+  if (is_bf16<T>() && dh == 64)
+    return launch_attention_bwd_mfma(reinterpret_cast<const bf16*>(qkv), reinterpret_cast<const bf16*>(o),
+                                     reinterpret_cast<const bf16*>(d_o), lse, reinterpret_cast<bf16*>(dqkv), dsum, B, S,
+                                     H, s);
   switch (dh) {
     case 32: return bwd_scalar<T, 32>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s);
     case 64: return bwd_scalar<T, 64>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s);

@@ -89,4 +89,9 @@ template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv,
                                    float* dscratch, int B, int S, int H, int dh, hipStream_t s);
 
+// ---- attention_mfma.hip: bf16, head size 64, matrix cores ---------------------------------------------
+dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, int B, int S, int H, hipStream_t s);
+dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf16* d_o, const float* lse, bf16* dqkv,
+                                        float* dsum, int B, int S, int H, hipStream_t s);
+
 }  // namespace dipaco

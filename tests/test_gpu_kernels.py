@@ -109,7 +109,8 @@ def _attn_ref(qkv, B, S, H, dh):
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
-@pytest.mark.parametrize("B,S,H,dh", [(2, 64, 2, 32), (1, 200, 3, 64), (2, 77, 1, 128), (1, 1, 2, 64), (1, 333, 2, 64)])
+@pytest.mark.parametrize("B,S,H,dh", [(2, 64, 2, 32), (1, 200, 3, 64), (2, 77, 1, 128), (1, 1, 2, 64), (1, 333, 2, 64),
+                                      (2, 1024, 2, 64), (1, 130, 1, 64)])
 def test_attention_forward_backward(dtype, B, S, H, dh):
     print(f"attention dtype={dtype} B={B} S={S} H={H} dh={dh}", flush=True)
     A = H * dh
