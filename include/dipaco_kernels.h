@@ -29,6 +29,10 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
                             void* aux_out, const void* aux_in, int32_t act, int32_t splits, float* partial,
                             void* stream);
 
+/* Force the GEMM workgroup tile for every later call in this process: 0 = automatic (default), 1 = 128x128,
+ * 2 = 256x128, 3 = 256x256.  For tests (every tile shape must give the same parity) and tuning. */
+dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
+
 /* Causal softmax attention.  qkv: [B*S, 3*H*dh], row = q | k | v, head h at columns h*dh of each third;
  * o: [B*S, H*dh];  lse: fp32 [B, H, S] = log sum_j exp(q_i.k_j / sqrt(dh)), j <= i.  dh in {32, 64, 128}. */
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,

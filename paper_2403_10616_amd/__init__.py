@@ -53,6 +53,7 @@ _SIGS = {
     "dipaco_route_prefix": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
     "dipaco_k_gemm": (C.c_int, [C.c_int32] * 7 + [C.c_void_p] * 7 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "dipaco_k_set_gemm_tile": (C.c_int, [C.c_int32]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]),
     "dipaco_k_attention_bwd": (C.c_int, [C.c_int32] + [C.c_void_p] * 6 + [C.c_int32] * 4 + [C.c_void_p]),
@@ -211,6 +212,10 @@ def dipaco_k_gemm(dtype: int, trans_a: bool, trans_b: bool, out_f32: bool, M: in
     _check(load().dipaco_k_gemm(dtype, int(trans_a), int(trans_b), int(out_f32), M, N, K, _ptr(A), _ptr(B), _ptr(Cout),
                                 _ptr(bias), _ptr(resid), _ptr(aux_out), _ptr(aux_in), act, splits, _ptr(partial),
                                 _stream(stream)))
+
+
+def dipaco_k_set_gemm_tile(tile: int):
+    _check(load().dipaco_k_set_gemm_tile(tile))
 
 
 def dipaco_k_attention_fwd(dtype: int, qkv, o, lse, B: int, S: int, H: int, dh: int, stream=None):

@@ -457,6 +457,12 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
   return dtype == DIPACO_BF16 ? launch_gemm<bf16>(g, st) : launch_gemm<float>(g, st);
 }
 
+dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
+  if (tile < 0 || tile > 3) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..3");
+  set_gemm_tile(tile);
+  return DIPACO_OK;
+}
+
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,
                                      int32_t H, int32_t dh, void* stream) {
   if (!qkv || !o || !lse || B < 1 || S < 1 || H < 1) return fail(DIPACO_EINVAL, "dipaco_k_attention_fwd: bad argument");

@@ -2,9 +2,15 @@
 // gradients.  bf16 or fp32 operands, fp32 accumulation (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x2_f32).
 //
 // One workgroup of 4 waves (2 x 2) computes a BM x BN tile of C; each wave owns (BM/64) x (BN/64) MFMA tiles of
-// 32x32.  Both operands are staged in LDS K-contiguous (mma_tile.h); the next K tile is fetched into registers
-// while the current one is multiplied, LDS is double-buffered, one barrier per K tile.
+// 32x32.  Both operands are staged in LDS K-contiguous (mma_tile.h), double-buffered.  Global loads run three K
+// tiles ahead of the MFMAs: two tiles are in flight in registers (two register sets, used alternately) and one
+// waits in the second LDS buffer, so a round trip to memory is covered by two full K steps of matrix work.
+// The result goes back through LDS, 32 rows of the wave's tile at a time, so that bias / GELU / residual are
+// applied on, and C is written with, 16-byte row-contiguous accesses.
+// Workgroup ids are remapped so that each of the 8 XCDs (which receive consecutive ids round-robin and own a
+// private L2) works on one contiguous range of tiles, walked in groups of 8 tile rows sharing the B panels.
 #include <algorithm>
+#include <type_traits>
 
 #include "kernels.h"
 #include "mma_tile.h"
@@ -25,21 +31,46 @@ struct GemmDev {
   int tiles_m, tiles_n;
 };
 
+constexpr int N_XCD = 8;
+
+template <typename T> struct OutVec;   // 8 consecutive output elements
+template <> struct OutVec<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct OutVec<bf16> {
+  static __device__ __forceinline__ void load(const bf16* p, float (&v)[8]) { load_vec16<bf16>(p, v); }
+  static __device__ __forceinline__ void store(bf16* p, const float (&v)[8]) { store_vec16<bf16>(p, v); }
+};
+
 template <typename T, typename TC, bool TA, bool TB, int BM, int BN>
 __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
   constexpr int BK = MmaTraits<T>::BK;
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int STAGE = (BM + BN) * TILE_ROW_BYTES;
+  constexpr int WN = BN / 2;            // columns per wave
+  constexpr int LDW = WN + 4;           // padded row of the epilogue staging buffer (floats)
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  int bid = blockIdx.x;
+  // ---- which tile ----
   const int tiles = g.tiles_m * g.tiles_n;
+  int bid = blockIdx.x;
   const int split = bid / tiles;
   bid -= split * tiles;
-  // tile order: N fastest inside groups of 8 M-tiles, so that concurrently running workgroups share operand panels
+  {  // XCD x gets the contiguous range of tile ids [x * per, ...): ids are dealt to XCDs round-robin
+    const int per = tiles / N_XCD, rem = tiles % N_XCD;
+    const int x = bid % N_XCD, i = bid / N_XCD;
+    bid = x * per + min(x, rem) + i;
+  }
   const int group = 8;
   const int per_group = group * g.tiles_n;
   const int gidx = bid / per_group;
@@ -67,79 +98,128 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 ra[LA::NLD], rb[LB::NLD];
-  if (nkt > 0) {
-    LA::load(ra, A, g.lda, m0, g.M, k_begin, k_end, tid);
-    LB::load(rb, B, g.ldb, n0, g.N, k_begin, k_end, tid);
-    LA::store(ra, smem, tid);
-    LB::store(rb, smem + BM * TILE_ROW_BYTES, tid);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      const int k0 = k_begin + (kt + 1) * BK;
-      LA::load(ra, A, g.lda, m0, g.M, k0, k_end, tid);
-      LB::load(rb, B, g.ldb, n0, g.N, k0, k_end, tid);
-    }
+  uint4 ra[2][LA::NLD], rb[2][LB::NLD];
+  auto gload = [&](auto R, int kt) {
+    constexpr int r = decltype(R)::value;
+    const int k0 = k_begin + kt * BK;
+    LA::load(ra[r], A, g.lda, m0, g.M, k0, k_end, tid);
+    LB::load(rb[r], B, g.ldb, n0, g.N, k0, k_end, tid);
+  };
+  auto sstore = [&](auto R, int stage, int kt) {
+    constexpr int r = decltype(R)::value;
+    const int k0 = k_begin + kt * BK;
+    char* st = smem + stage * STAGE;
+    LA::store(ra[r], st, tid, k0, k_end);
+    LB::store(rb[r], st + BM * TILE_ROW_BYTES, tid, k0, k_end);
+  };
+  // K tile kt is multiplied from LDS buffer kt&1 while tile kt+1 moves from register set (kt+1)&1 to the other
+  // buffer and tile kt+3 starts loading into that register set (tile kt+2 is in flight in set kt&1).
+  auto step = [&](auto R, int kt) {
+    constexpr int r = decltype(R)::value;
+    using Other = std::integral_constant<int, 1 - r>;
+    sstore(Other{}, 1 - r, kt + 1);
+    gload(Other{}, kt + 3);
+    char* cur = smem + r * STAGE;
     mma_ktile<T, TM, TN>(acc, cur, cur + BM * TILE_ROW_BYTES, wm * (BM / 2), wn * (BN / 2), lane);
-    if (more) {
-      LA::store(ra, nxt, tid);
-      LB::store(rb, nxt + BM * TILE_ROW_BYTES, tid);
-    }
     __syncthreads();
+  };
+  using R0 = std::integral_constant<int, 0>;
+  using R1 = std::integral_constant<int, 1>;
+  // tiles at or beyond nkt load as zeros, so the loop runs an even number of steps without conditions
+  gload(R0{}, 0);
+  gload(R1{}, 1);
+  sstore(R0{}, 0, 0);
+  gload(R0{}, 2);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; kt += 2) {
+    step(R0{}, kt);
+    step(R1{}, kt + 1);
   }
 
-  // ---- epilogue ----
+  // ---- epilogue: accumulators -> LDS (this wave's private region) -> 8 consecutive columns per lane ----
+  float* stg = reinterpret_cast<float*>(smem) + wave * (32 * LDW);
   const int col_l = lane & 31;
-  if (g.splits > 1) {
-    float* P = g.partial + (size_t)split * g.M * g.N;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * (BN / 2) + 32 * j + col_l;
-        if (col >= g.N) continue;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = m0 + wm * (BM / 2) + 32 * i + acc_row(e, lane);
-          if (row < g.M) P[(size_t)row * g.N + col] = acc[i][j][e];
-        }
-      }
-    return;
-  }
+  constexpr int GROUPS = WN / 8;                 // 8-column groups per row
+  constexpr int ITERS = 32 * GROUPS / WAVE;
   const T* bias = static_cast<const T*>(g.bias);
   const T* resid = static_cast<const T*>(g.resid);
   const T* aux_in = static_cast<const T*>(g.aux_in);
   T* aux_out = static_cast<T*>(g.aux_out);
-  TC* C = static_cast<TC*>(g.C);
+  const bool to_partial = g.splits > 1;
+  float* P = to_partial ? g.partial + (size_t)split * g.M * g.N : nullptr;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * (BN / 2) + 32 * j + col_l;
-      if (col >= g.N) continue;
-      const float bv = bias ? to_f32(bias[col]) : 0.f;
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * (BM / 2) + 32 * i + acc_row(e, lane);
-        if (row >= g.M) continue;
-        const size_t off = (size_t)row * g.ldc + col;
-        float v = acc[i][j][e] + bv;
-        if (g.act == 1) {
-          // the saved pre-activation is what backward differentiates at: apply GELU to the stored value
-          T pre = from_f32<T>(v);
-          aux_out[off] = pre;
-          v = gelu_f(to_f32(pre));
-        } else if (g.act == 2) {
-          v *= gelu_grad_f(to_f32(aux_in[off]));
+      for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int item = lane + WAVE * it;
+      const int rr = item / GROUPS, cg = item % GROUPS;
+      const int row = m0 + wm * (BM / 2) + 32 * i + rr;
+      const int col = n0 + wn * WN + 8 * cg;
+      const float4 lo = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg);
+      const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
+      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      if (row >= g.M || col >= g.N) continue;
+      const bool full = col + 8 <= g.N;
+      if (to_partial) {
+        float* dst = P + (size_t)row * g.N + col;
+        if (full && (g.N & 3) == 0) OutVec<float>::store(dst, v);
+        else {
+#pragma unroll
+          for (int c = 0; c < 8; ++c)
+            if (col + c < g.N) dst[c] = v[c];
         }
-        if (resid) v += to_f32(resid[off]);
-        C[off] = from_f32<TC>(v);
+        continue;
+      }
+      const size_t off = (size_t)row * g.ldc + col;
+      if (full) {
+        if (bias) {
+          float b[8];
+          OutVec<T>::load(bias + col, b);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] += b[c];
+        }
+        if (g.act == 1) {
+          // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
+          OutVec<T>::store(aux_out + off, v);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] = gelu_f(to_f32(from_f32<T>(v[c])));
+        } else if (g.act == 2) {
+          float u[8];
+          OutVec<T>::load(aux_in + off, u);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_f(u[c]);
+        }
+        if (resid) {
+          float rv[8];
+          OutVec<T>::load(resid + off, rv);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] += rv[c];
+        }
+        OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          if (col + c >= g.N) break;
+          float x = v[c] + (bias ? to_f32(bias[col + c]) : 0.f);
+          if (g.act == 1) {
+            const T pre = from_f32<T>(x);
+            aux_out[off + c] = pre;
+            x = gelu_f(to_f32(pre));
+          } else if (g.act == 2) {
+            x *= gelu_grad_f(to_f32(aux_in[off + c]));
+          }
+          if (resid) x += to_f32(resid[off + c]);
+          static_cast<TC*>(g.C)[off + c] = from_f32<TC>(x);
+        }
       }
     }
+  }
 }
 
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ C,
@@ -157,7 +237,9 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
 template <typename T, typename TC, bool TA, bool TB, int BM, int BN>
 dipaco_status run(const GemmArgs& a, hipStream_t s) {
   constexpr int BK = MmaTraits<T>::BK;
-  constexpr size_t smem = 2 * (size_t)(BM + BN) * TILE_ROW_BYTES;
+  constexpr size_t smem_loop = 2 * (size_t)(BM + BN) * TILE_ROW_BYTES;
+  constexpr size_t smem_epi = 4 * 32 * (size_t)(BN / 2 + 4) * sizeof(float);
+  constexpr size_t smem = smem_loop > smem_epi ? smem_loop : smem_epi;
   auto kern = gemm_kernel<T, TC, TA, TB, BM, BN>;
   static bool attr_set = false;   // one attribute call per instantiation and process
   if (!attr_set) {
@@ -191,23 +273,47 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   return DIPACO_OK;
 }
 
+int g_forced_tile = 0;
+
+// Tile choice.  256-wide tiles halve the LDS and L2 traffic per MFMA and give each K step enough matrix work to
+// cover a round trip to memory; smaller tiles keep small problems from leaving compute units idle.
+int pick_tile(int M, int N) {
+  if (g_forced_tile) return g_forced_tile;
+  (void)M; (void)N;
+  return 1;
+}
+
+template <typename T, typename TC, bool TA, bool TB>
+dipaco_status run_tiled(const GemmArgs& a, hipStream_t s) {
+  switch (pick_tile(a.M, a.N)) {
+    case 3: return run<T, TC, TA, TB, 256, 256>(a, s);
+    case 2: return run<T, TC, TA, TB, 256, 128>(a, s);
+    default: return run<T, TC, TA, TB, 128, 128>(a, s);
+  }
+}
+
 }  // namespace
+
+void set_gemm_tile(int t) { g_forced_tile = t; }
 
 template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s) {
   constexpr int VEC = MmaTraits<T>::VEC;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(DIPACO_ESHAPE, "gemm: empty operand");
-  // 16-byte vectors run along the contiguous index of each operand
+  // 16-byte vectors run along the contiguous index of each operand and along the rows of C
   if ((a.trans_a ? a.M : a.K) % VEC || (a.trans_b ? a.K : a.N) % VEC || a.lda % VEC || a.ldb % VEC)
     return fail(DIPACO_ESHAPE, "gemm: contiguous extents and leading dimensions must be multiples of 16 bytes");
-  if (!aligned16(a.A) || !aligned16(a.B)) return fail(DIPACO_EALIGN, "gemm: operand not 16-byte aligned");
+  if (a.ldc % 8) return fail(DIPACO_ESHAPE, "gemm: ldc must be a multiple of 8");
+  if (!aligned16(a.A) || !aligned16(a.B) || !aligned16(a.C) || !aligned16(a.bias) || !aligned16(a.resid) ||
+      !aligned16(a.aux_in) || !aligned16(a.aux_out) || !aligned16(a.partial))
+    return fail(DIPACO_EALIGN, "gemm: operand not 16-byte aligned");
   if (a.splits > 1 && (!a.out_f32 || a.bias || a.resid || a.act || !a.partial))
     return fail(DIPACO_EINVAL, "gemm: split-K needs fp32 output, a partial buffer and no epilogue");
   if (a.out_f32) {
-    if (a.trans_a && !a.trans_b) return run<T, float, true, false, 128, 128>(a, s);
+    if (a.trans_a && !a.trans_b) return run_tiled<T, float, true, false>(a, s);
     return fail(DIPACO_EUNSUPPORTED, "gemm: fp32 output only for A^T.B");
   }
-  if (!a.trans_a && !a.trans_b) return run<T, T, false, false, 128, 128>(a, s);
-  if (!a.trans_a && a.trans_b) return run<T, T, false, true, 128, 128>(a, s);
+  if (!a.trans_a && !a.trans_b) return run_tiled<T, T, false, false>(a, s);
+  if (!a.trans_a && a.trans_b) return run_tiled<T, T, false, true>(a, s);
   return fail(DIPACO_EUNSUPPORTED, "gemm: operand layout not instantiated");
 }
 

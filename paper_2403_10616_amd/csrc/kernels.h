@@ -48,6 +48,8 @@ struct GemmArgs {
   float* partial;
 };
 template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s);
+// 0 = automatic; 1 = 128x128, 2 = 256x128, 3 = 256x256 workgroup tiles (tuning and tests)
+void set_gemm_tile(int t);
 
 // ---- transformer.hip ---------------------------------------------------------------------------------
 template <typename T>

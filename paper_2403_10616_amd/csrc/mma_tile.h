@@ -7,8 +7,11 @@
 // of bank conflicts: 16-byte fragment reads by 8 consecutive rows, 16-byte row-major stores, and the 8-byte
 // (bf16) / 16-byte (fp32) stores of the transposing loader, whose lanes walk rows 8 (or 4) apart.
 //
-// Loaders move global memory -> registers (so the next tile's loads are in flight during the MFMAs of the
-// current one) and registers -> LDS.  The direct loader takes a K-contiguous source.  The transposing loader
+// Loaders move global memory -> registers (so the next tiles' loads are in flight during the MFMAs of the
+// current one) and registers -> LDS.  Loads are unconditional: a tile row beyond the operand is read from the
+// operand's last row (it only feeds output rows / columns that are never stored), a K index beyond the range is
+// read from the last valid one and replaced by zero.  No branch surrounds a load, so the loads of a tile issue
+// back to back and the compiler can wait for exactly the tile it needs.  The direct loader takes a K-contiguous source.  The transposing loader
 // takes a source whose rows are K and whose contiguous index is the tile's row: each thread reads a 4 (K) x
 // 16-byte block, transposes it in registers and writes K-contiguous pieces.
 #pragma once
@@ -22,6 +25,12 @@ constexpr int GEMM_THREADS = 256;
 template <typename T> struct MmaTraits;
 template <> struct MmaTraits<bf16> { static constexpr int VEC = 8; static constexpr int BK = 64; };
 template <> struct MmaTraits<float> { static constexpr int VEC = 4; static constexpr int BK = 32; };
+
+// v if keep, else zero -- as a bitwise AND, so that the compiler cannot turn the load of v into a conditional one
+__device__ __forceinline__ uint4 keep_or_zero(const uint4& v, bool keep) {
+  const uint32_t m = keep ? 0xffffffffu : 0u;
+  return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+}
 
 __device__ __forceinline__ int swz(int row) { return ((row & 7) + (row >> 3)) & 7; }
 
@@ -59,17 +68,26 @@ template <typename T, int ROWS> struct TileLoader<T, ROWS, false> {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       int idx = tid + GEMM_THREADS * i;
-      int row = row0 + (idx >> 3);
+      int row = min(row0 + (idx >> 3), rows_total - 1);
       int k = k0 + (idx & 7) * VEC;
-      r[i] = (row < rows_total && k < k_end) ? *reinterpret_cast<const uint4*>(src + (long)row * ld + k)
-                                             : make_uint4(0, 0, 0, 0);
+      r[i] = *reinterpret_cast<const uint4*>(src + (long)row * ld + min(k, k_end - VEC));
     }
   }
-  __device__ static __forceinline__ void store(const uint4 (&r)[NLD], char* tile, int tid) {
+  // k0, k_end: those of the load that filled r
+  __device__ static __forceinline__ void store(const uint4 (&r)[NLD], char* tile, int tid, int k0, int k_end) {
+    if (k0 + MmaTraits<T>::BK <= k_end) {   // whole tile inside the K range (uniform branch)
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      int idx = tid + GEMM_THREADS * i;
-      *reinterpret_cast<uint4*>(tile_chunk(tile, idx >> 3, idx & 7)) = r[i];
+      for (int i = 0; i < NLD; ++i) {
+        int idx = tid + GEMM_THREADS * i;
+        *reinterpret_cast<uint4*>(tile_chunk(tile, idx >> 3, idx & 7)) = r[i];
+      }
+    } else {
+      const bool keep = k0 + (tid & 7) * VEC < k_end;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        int idx = tid + GEMM_THREADS * i;
+        *reinterpret_cast<uint4*>(tile_chunk(tile, idx >> 3, idx & 7)) = keep_or_zero(r[i], keep);
+      }
     }
   }
 };
@@ -89,24 +107,31 @@ template <int ROWS> struct TileLoader<bf16, ROWS, true> {
     for (int sb = 0; sb < NSB; ++sb) {
       int kq, mq;
       coords(tid, sb, kq, mq);
-      int row = row0 + 8 * mq;
+      int row = min(row0 + 8 * mq, rows_total - 8);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         int k = k0 + 4 * kq + j;
-        r[4 * sb + j] = (row < rows_total && k < k_end) ? *reinterpret_cast<const uint4*>(src + (long)k * ld + row)
-                                                        : make_uint4(0, 0, 0, 0);
+        r[4 * sb + j] = *reinterpret_cast<const uint4*>(src + (long)min(k, k_end - 1) * ld + row);
       }
     }
   }
-  __device__ static __forceinline__ void store(const uint4 (&r)[NLD], char* tile, int tid) {
+  __device__ static __forceinline__ void store(const uint4 (&r)[NLD], char* tile, int tid, int k0, int k_end) {
+    if (k0 + MmaTraits<bf16>::BK <= k_end) store_impl<false>(r, tile, tid, k0, k_end);   // uniform branch
+    else store_impl<true>(r, tile, tid, k0, k_end);
+  }
+  template <bool TAIL>
+  __device__ static __forceinline__ void store_impl(const uint4 (&r)[NLD], char* tile, int tid, int k0, int k_end) {
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       int kq, mq;
       coords(tid, sb, kq, mq);
-      const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&r[4 * sb + 0]);
-      const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&r[4 * sb + 1]);
-      const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&r[4 * sb + 2]);
-      const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&r[4 * sb + 3]);
+      const int kk = k0 + 4 * kq;
+      const uint4 m0 = keep_or_zero(r[4 * sb + 0], !TAIL || kk + 0 < k_end), m1 = keep_or_zero(r[4 * sb + 1], !TAIL || kk + 1 < k_end);
+      const uint4 m2 = keep_or_zero(r[4 * sb + 2], !TAIL || kk + 2 < k_end), m3 = keep_or_zero(r[4 * sb + 3], !TAIL || kk + 3 < k_end);
+      const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&m0);
+      const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&m1);
+      const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&m2);
+      const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&m3);
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         int j = c >> 1;
@@ -140,24 +165,27 @@ template <int ROWS> struct TileLoader<float, ROWS, true> {
     for (int sb = 0; sb < NSB; ++sb) {
       int kq, mq;
       coords(tid, sb, kq, mq);
-      int row = row0 + 4 * mq;
+      int row = min(row0 + 4 * mq, rows_total - 4);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         int k = k0 + 4 * kq + j;
-        r[4 * sb + j] = (row < rows_total && k < k_end) ? *reinterpret_cast<const uint4*>(src + (long)k * ld + row)
-                                                        : make_uint4(0, 0, 0, 0);
+        r[4 * sb + j] = *reinterpret_cast<const uint4*>(src + (long)min(k, k_end - 1) * ld + row);
       }
     }
   }
-  __device__ static __forceinline__ void store(const uint4 (&r)[NLD], char* tile, int tid) {
+  __device__ static __forceinline__ void store(const uint4 (&r)[NLD], char* tile, int tid, int k0, int k_end) {
+    if (k0 + MmaTraits<float>::BK <= k_end) store_impl<false>(r, tile, tid, k0, k_end);   // uniform branch
+    else store_impl<true>(r, tile, tid, k0, k_end);
+  }
+  template <bool TAIL>
+  __device__ static __forceinline__ void store_impl(const uint4 (&r)[NLD], char* tile, int tid, int k0, int k_end) {
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       int kq, mq;
       coords(tid, sb, kq, mq);
-      const uint4& a = r[4 * sb + 0];
-      const uint4& b = r[4 * sb + 1];
-      const uint4& c = r[4 * sb + 2];
-      const uint4& d = r[4 * sb + 3];
+      const int kk = k0 + 4 * kq;
+      const uint4 a = keep_or_zero(r[4 * sb + 0], !TAIL || kk + 0 < k_end), b = keep_or_zero(r[4 * sb + 1], !TAIL || kk + 1 < k_end);
+      const uint4 c = keep_or_zero(r[4 * sb + 2], !TAIL || kk + 2 < k_end), d = keep_or_zero(r[4 * sb + 3], !TAIL || kk + 3 < k_end);
       *reinterpret_cast<uint4*>(tile_chunk(tile, 4 * mq + 0, kq)) = make_uint4(a.x, b.x, c.x, d.x);
       *reinterpret_cast<uint4*>(tile_chunk(tile, 4 * mq + 1, kq)) = make_uint4(a.y, b.y, c.y, d.y);
       *reinterpret_cast<uint4*>(tile_chunk(tile, 4 * mq + 2, kq)) = make_uint4(a.z, b.z, c.z, d.z);

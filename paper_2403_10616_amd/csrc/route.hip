@@ -79,12 +79,13 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
     LZ::load(rz, zb, D, 0, rows_left, 0, D, tid);
     LC::load(rc, cb, D, 0, crow_left, 0, D, tid);
     __syncthreads();   // previous centroid tile's readers of LDS and of cnorm are done
-    LZ::store(rz, smem, tid);
-    LC::store(rc, smem + RBM * TILE_ROW_BYTES, tid);
+    LZ::store(rz, smem, tid, 0, D);
+    LC::store(rc, smem + RBM * TILE_ROW_BYTES, tid, 0, D);
+    const bool keep0 = (tid & 7) * 4 < D;
 #pragma unroll
     for (int i = 0; i < LC::NLD; ++i) {
       float4 v = *reinterpret_cast<float4*>(&rc[i]);
-      nrm[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      if (keep0) nrm[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     __syncthreads();
     for (int kt = 0; kt < nkt; ++kt) {
@@ -97,12 +98,14 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       }
       mma_ktile<float, 2, 4>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 128, lane);
       if (more) {
-        LZ::store(rz, nxt, tid);
-        LC::store(rc, nxt + RBM * TILE_ROW_BYTES, tid);
+        const int k0n = (kt + 1) * RBK;
+        LZ::store(rz, nxt, tid, k0n, D);
+        LC::store(rc, nxt + RBM * TILE_ROW_BYTES, tid, k0n, D);
+        const bool keep = k0n + (tid & 7) * 4 < D;
 #pragma unroll
         for (int i = 0; i < LC::NLD; ++i) {
           float4 v = *reinterpret_cast<float4*>(&rc[i]);
-          nrm[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+          if (keep) nrm[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         }
       }
       __syncthreads();
