@@ -43,18 +43,24 @@ template <int E0> __device__ __forceinline__ uint4 pack8(const f32x16& v) {
 
 // ---- 64 x 64 bf16 tile, loaded by 128 threads as 4 (rows) x 8 (columns) blocks -----------------------------
 struct SubBlock { uint4 r[4]; };
+// lane l of loader wave w2: 8-column block mq = (l&1) + 2*((l>>4)&3), 4-row block kq = ((l>>1)&7) + 8*w2.  A load
+// instruction reads 128 contiguous bytes of 8 rows; 16 consecutive lanes of a transposed 8-byte store write 8
+// row-granules of two LDS rows whose swizzles differ by 4 (no bank conflicts, see mma_tile.h).
 __device__ __forceinline__ void sb_coords(int t128, int& kq, int& mq) {
-  mq = t128 & 7;     // block of 8 columns (16 bytes)
-  kq = t128 >> 3;    // block of 4 rows, 0..15
+  const int l = t128 & 63;
+  mq = (l & 1) + 2 * ((l >> 4) & 3);
+  kq = ((l >> 1) & 7) + 8 * (t128 >> 6);
 }
-// src points at the tile's first row and column; rows at or beyond rows_valid read as zero
+// src points at the tile's first row and column; rows at or beyond rows_valid (>= 1) re-read the last valid row:
+// callers give such rows zero weight (masked probabilities), so any finite value will do, and no branch
+// surrounds the loads
 __device__ __forceinline__ void sb_load(SubBlock& s, const bf16* __restrict__ src, long ld, int rows_valid, int t128) {
   int kq, mq;
   sb_coords(t128, kq, mq);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int row = 4 * kq + j;
-    s.r[j] = row < rows_valid ? *reinterpret_cast<const uint4*>(src + (long)row * ld + 8 * mq) : make_uint4(0, 0, 0, 0);
+    const int row = min(4 * kq + j, rows_valid - 1);
+    s.r[j] = *reinterpret_cast<const uint4*>(src + (long)row * ld + 8 * mq);
   }
 }
 // LDS tile[row][column]: operand whose contraction index is the column

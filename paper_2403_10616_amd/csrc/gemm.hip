@@ -49,7 +49,7 @@ template <> struct OutVec<bf16> {
   static __device__ __forceinline__ void store(bf16* p, const float (&v)[8]) { store_vec16<bf16>(p, v); }
 };
 
-template <typename T, typename TC, bool TA, bool TB, int BM, int BN>
+template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int NS>
 __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
   constexpr int BK = MmaTraits<T>::BK;
   constexpr int TM = BM / 64, TN = BN / 64;
@@ -98,42 +98,84 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 ra[2][LA::NLD], rb[2][LB::NLD];
-  auto gload = [&](auto R, int kt) {
+  uint4 ra[NS][LA::NLD], rb[NS][LB::NLD];   // NS register sets of tiles in flight
+  uint32_t offa[LA::NLD], offb[LB::NLD];
+  LA::offsets(offa, g.lda, m0, g.M, tid);
+  LB::offsets(offb, g.ldb, n0, g.N, tid);
+  const long ka = LA::k_step(g.lda), kb = LB::k_step(g.ldb);
+  const int nfull = (k_end - k_begin) / BK;   // K tiles completely inside the range; nkt - nfull is 0 or 1
+  const int a_row0 = wm * (BM / 2), b_row0 = wn * (BN / 2);
+
+  auto stage_a = [&](int st) { return smem + st * STAGE; };
+  auto stage_b = [&](int st) { return smem + st * STAGE + BM * TILE_ROW_BYTES; };
+  auto gload = [&](auto R, auto FULL, int kt) {
     constexpr int r = decltype(R)::value;
     const int k0 = k_begin + kt * BK;
-    LA::load(ra[r], A, g.lda, m0, g.M, k0, k_end, tid);
-    LB::load(rb[r], B, g.ldb, n0, g.N, k0, k_end, tid);
+    if (decltype(FULL)::value || k0 + BK <= k_end) {
+      LA::load_full(ra[r], A + k0 * ka, offa);
+      LB::load_full(rb[r], B + k0 * kb, offb);
+    } else {
+      LA::load_tail(ra[r], A, g.lda, m0, g.M, k0, k_end, tid);
+      LB::load_tail(rb[r], B, g.ldb, n0, g.N, k0, k_end, tid);
+    }
   };
-  auto sstore = [&](auto R, int stage, int kt) {
-    constexpr int r = decltype(R)::value;
-    const int k0 = k_begin + kt * BK;
-    char* st = smem + stage * STAGE;
-    LA::store(ra[r], st, tid, k0, k_end);
-    LB::store(rb[r], st + BM * TILE_ROW_BYTES, tid, k0, k_end);
+  auto sstore = [&](auto R, auto BUF, auto FULL, int kt) {   // register set R -> LDS buffer BUF (= kt & 1)
+    constexpr int r = decltype(R)::value, buf = decltype(BUF)::value;
+    if (decltype(FULL)::value) {
+      LA::store_full(ra[r], stage_a(buf), tid);
+      LB::store_full(rb[r], stage_b(buf), tid);
+    } else {
+      const int k0 = k_begin + kt * BK;
+      LA::store(ra[r], stage_a(buf), tid, k0, k_end);
+      LB::store(rb[r], stage_b(buf), tid, k0, k_end);
+    }
   };
-  // K tile kt is multiplied from LDS buffer kt&1 while tile kt+1 moves from register set (kt+1)&1 to the other
-  // buffer and tile kt+3 starts loading into that register set (tile kt+2 is in flight in set kt&1).
-  auto step = [&](auto R, int kt) {
-    constexpr int r = decltype(R)::value;
-    using Other = std::integral_constant<int, 1 - r>;
-    sstore(Other{}, 1 - r, kt + 1);
-    gload(Other{}, kt + 3);
-    char* cur = smem + r * STAGE;
-    mma_ktile<T, TM, TN>(acc, cur, cur + BM * TILE_ROW_BYTES, wm * (BM / 2), wn * (BN / 2), lane);
-    __syncthreads();
-  };
+
+  // Fragment double buffer.  At the top of a step, f*[0] holds K group 0 of the tile about to be multiplied.
+  uint4 fa[2][TM], fb[2][TN];
   using R0 = std::integral_constant<int, 0>;
   using R1 = std::integral_constant<int, 1>;
-  // tiles at or beyond nkt load as zeros, so the loop runs an even number of steps without conditions
-  gload(R0{}, 0);
-  gload(R1{}, 1);
-  sstore(R0{}, 0, 0);
-  gload(R0{}, 2);
+  using Full = std::true_type;
+  using Any = std::false_type;
+  // One K tile.  Tile t sits in LDS buffer t&1 (= r).  Tile t+1 waits in a register set; it goes to the other
+  // LDS buffer and its register set is refilled with tile t+1+NS while K groups 0-1 of tile t are multiplied (so
+  // NS tiles are in flight in registers).  After the first barrier the other buffer is complete, so group 0 of
+  // tile t+1 is fetched under the MFMAs of group 3 and the matrix cores never wait for a tile's first fragments.
+  // The second barrier keeps buffer r from being overwritten (next step) while a wave still reads it.
+  auto step = [&](auto R, auto FULL, int t) {
+    constexpr int r = decltype(R)::value;
+    constexpr bool full = decltype(FULL)::value;
+    using Set = std::integral_constant<int, NS == 2 ? 1 - r : 0>;   // register set of tile t+1
+    using Buf = std::integral_constant<int, 1 - r>;
+    const bool have_next = full || t + 1 < nkt;
+    if (have_next) sstore(Set{}, Buf{}, FULL, t + 1);
+    if (full || t + 1 + NS < nkt) gload(Set{}, FULL, t + 1 + NS);
+    load_frags<TM, TN>(fa[1], fb[1], stage_a(r), stage_b(r), a_row0, b_row0, lane, 1);
+    mma_group<T, TM, TN>(acc, fa[0], fb[0]);
+    load_frags<TM, TN>(fa[0], fb[0], stage_a(r), stage_b(r), a_row0, b_row0, lane, 2);
+    mma_group<T, TM, TN>(acc, fa[1], fb[1]);
+    __syncthreads();
+    load_frags<TM, TN>(fa[1], fb[1], stage_a(r), stage_b(r), a_row0, b_row0, lane, 3);
+    mma_group<T, TM, TN>(acc, fa[0], fb[0]);
+    if (have_next) load_frags<TM, TN>(fa[0], fb[0], stage_a(1 - r), stage_b(1 - r), a_row0, b_row0, lane, 0);
+    mma_group<T, TM, TN>(acc, fa[1], fb[1]);
+    __syncthreads();
+  };
+
+  gload(R0{}, Any{}, 0);
+  if (NS == 2 && nkt > 1) gload(R1{}, Any{}, 1);
+  sstore(R0{}, R0{}, Any{}, 0);
+  if (nkt > NS) gload(R0{}, Any{}, NS);
   __syncthreads();
-  for (int kt = 0; kt < nkt; kt += 2) {
-    step(R0{}, kt);
-    step(R1{}, kt + 1);
+  load_frags<TM, TN>(fa[0], fb[0], stage_a(0), stage_b(0), a_row0, b_row0, lane, 0);
+  int t = 0;
+  for (; t + 2 + NS < nfull; t += 2) {   // steady state: every tile touched is complete, no conditions
+    step(R0{}, Full{}, t);
+    step(R1{}, Full{}, t + 1);
+  }
+  for (; t < nkt; t += 2) {              // drain (and short K): same steps with existence / tail checks
+    step(R0{}, Any{}, t);
+    if (t + 1 < nkt) step(R1{}, Any{}, t + 1);
   }
 
   // ---- epilogue: accumulators -> LDS (this wave's private region) -> 8 consecutive columns per lane ----
@@ -234,13 +276,13 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   }
 }
 
-template <typename T, typename TC, bool TA, bool TB, int BM, int BN>
+template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int NS>
 dipaco_status run(const GemmArgs& a, hipStream_t s) {
   constexpr int BK = MmaTraits<T>::BK;
   constexpr size_t smem_loop = 2 * (size_t)(BM + BN) * TILE_ROW_BYTES;
   constexpr size_t smem_epi = 4 * 32 * (size_t)(BN / 2 + 4) * sizeof(float);
   constexpr size_t smem = smem_loop > smem_epi ? smem_loop : smem_epi;
-  auto kern = gemm_kernel<T, TC, TA, TB, BM, BN>;
+  auto kern = gemm_kernel<T, TC, TA, TB, BM, BN, NS>;
   static bool attr_set = false;   // one attribute call per instantiation and process
   if (!attr_set) {
     DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -275,20 +317,21 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
 
 int g_forced_tile = 0;
 
-// Tile choice.  256-wide tiles halve the LDS and L2 traffic per MFMA and give each K step enough matrix work to
-// cover a round trip to memory; smaller tiles keep small problems from leaving compute units idle.
-int pick_tile(int M, int N) {
+int pick_tile(int M, int N, int K) {
   if (g_forced_tile) return g_forced_tile;
-  (void)M; (void)N;
+  // measured on the path's shapes: 256 x 256 tiles only pay once the K loop is long enough to amortise their
+  // prologue and epilogue and the problem still fills the chip with them
+  const long t3 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (K >= 16384 && t3 >= 256) return 3;
   return 1;
 }
 
 template <typename T, typename TC, bool TA, bool TB>
 dipaco_status run_tiled(const GemmArgs& a, hipStream_t s) {
-  switch (pick_tile(a.M, a.N)) {
-    case 3: return run<T, TC, TA, TB, 256, 256>(a, s);
-    case 2: return run<T, TC, TA, TB, 256, 128>(a, s);
-    default: return run<T, TC, TA, TB, 128, 128>(a, s);
+  switch (pick_tile(a.M, a.N, a.K)) {
+    case 3: return run<T, TC, TA, TB, 256, 256, 1>(a, s);
+    case 2: return run<T, TC, TA, TB, 256, 128, 2>(a, s);
+    default: return run<T, TC, TA, TB, 128, 128, 2>(a, s);
   }
 }
 
@@ -303,6 +346,9 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s
   if ((a.trans_a ? a.M : a.K) % VEC || (a.trans_b ? a.K : a.N) % VEC || a.lda % VEC || a.ldb % VEC)
     return fail(DIPACO_ESHAPE, "gemm: contiguous extents and leading dimensions must be multiples of 16 bytes");
   if (a.ldc % 8) return fail(DIPACO_ESHAPE, "gemm: ldc must be a multiple of 8");
+  // per-thread element offsets are 32-bit
+  const long ext_a = (a.trans_a ? 64 : (long)a.M) * a.lda + a.M, ext_b = (a.trans_b ? (long)a.N : 64) * a.ldb + a.N;
+  if (ext_a >= (1L << 32) || ext_b >= (1L << 32)) return fail(DIPACO_ESHAPE, "gemm: operand above 2^32 elements");
   if (!aligned16(a.A) || !aligned16(a.B) || !aligned16(a.C) || !aligned16(a.bias) || !aligned16(a.resid) ||
       !aligned16(a.aux_in) || !aligned16(a.aux_out) || !aligned16(a.partial))
     return fail(DIPACO_EALIGN, "gemm: operand not 16-byte aligned");

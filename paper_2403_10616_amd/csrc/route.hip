@@ -76,8 +76,8 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
     uint4 rz[LZ::NLD], rc[LC::NLD];
     const float* cb = c + (long)n0 * D;
     const int crow_left = min(RBN, K - n0);
-    LZ::load(rz, zb, D, 0, rows_left, 0, D, tid);
-    LC::load(rc, cb, D, 0, crow_left, 0, D, tid);
+    LZ::load_tail(rz, zb, D, 0, rows_left, 0, D, tid);
+    LC::load_tail(rc, cb, D, 0, crow_left, 0, D, tid);
     __syncthreads();   // previous centroid tile's readers of LDS and of cnorm are done
     LZ::store(rz, smem, tid, 0, D);
     LC::store(rc, smem + RBM * TILE_ROW_BYTES, tid, 0, D);
@@ -93,8 +93,8 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       char* nxt = smem + ((kt + 1) & 1) * R_STAGE;
       const bool more = kt + 1 < nkt;
       if (more) {
-        LZ::load(rz, zb, D, 0, rows_left, (kt + 1) * RBK, D, tid);
-        LC::load(rc, cb, D, 0, crow_left, (kt + 1) * RBK, D, tid);
+        LZ::load_tail(rz, zb, D, 0, rows_left, (kt + 1) * RBK, D, tid);
+        LC::load_tail(rc, cb, D, 0, crow_left, (kt + 1) * RBK, D, tid);
       }
       mma_ktile<float, 2, 4>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 128, lane);
       if (more) {
