@@ -170,16 +170,31 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
   for (int c = threadIdx.x; c < 2 * d; c += ROW_THREADS) out[c] = cols[c];
 }
 
-// out[c] = sum over p of partial[p * stride + c], p in index order
+// out[c] = sum over p of partial[p * stride + c].  64 columns x 4 partial phases per workgroup: phase y adds
+// partials y, y+4, ... in order, then the four phase sums are added in phase order (a fixed tree).
 __global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restrict__ partial, float* __restrict__ out0,
                                                            float* __restrict__ out1, int n_partials, int stride,
                                                            int d) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= stride) return;
+  __shared__ float red[4][64];
+  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + x;
   float s = 0.f;
-  for (int p = 0; p < n_partials; ++p) s += partial[(size_t)p * stride + c];
-  if (c < d) out0[c] = s;
-  else out1[c - d] = s;
+  if (c < stride) {
+    int p = y;
+    for (; p + 12 < n_partials; p += 16) {   // four independent loads in flight
+      const float a0 = partial[(size_t)p * stride + c], a1 = partial[(size_t)(p + 4) * stride + c];
+      const float a2 = partial[(size_t)(p + 8) * stride + c], a3 = partial[(size_t)(p + 12) * stride + c];
+      s += a0; s += a1; s += a2; s += a3;
+    }
+    for (; p < n_partials; p += 4) s += partial[(size_t)p * stride + c];
+  }
+  red[y][x] = s;
+  __syncthreads();
+  if (y == 0 && c < stride) {
+    const float t = ((red[0][x] + red[1][x]) + red[2][x]) + red[3][x];
+    if (c < d) out0[c] = t;
+    else out1[c - d] = t;
+  }
 }
 
 // ---- column sums -----------------------------------------------------------------------------------------
@@ -367,25 +382,63 @@ __global__ void __launch_bounds__(256) tok_slot_kernel(const int* __restrict__ t
   if (i < rows) order[offsets[mine] + rank] = i;
 }
 
+// One workgroup (8 waves) per vocabulary row.  Wave w adds the row's positions w, w+8, ... in order (lanes over
+// 16-byte column chunks), then the eight wave sums are added in wave order: a fixed tree, so the frequent tokens
+// of a Zipf batch (thousands of positions) are spread over the workgroup without any atomics.
+constexpr int TG_WAVES = 8;
 template <typename T>
-__global__ void __launch_bounds__(128) tok_grad_kernel(const T* __restrict__ dx, const int* __restrict__ offsets,
-                                                       const int* __restrict__ order, float* __restrict__ d_tok, int d) {
+__global__ void __launch_bounds__(TG_WAVES * WAVE) tok_grad_kernel(const T* __restrict__ dx,
+                                                                   const int* __restrict__ offsets,
+                                                                   const int* __restrict__ order,
+                                                                   float* __restrict__ d_tok, int d) {
   constexpr int VEC = Vec16<T>::N;
+  extern __shared__ float tg_red[];   // [TG_WAVES][d]
   const int v = blockIdx.x;
   const int lo = offsets[v], hi = offsets[v + 1];
-  for (int c = threadIdx.x * VEC; c < d; c += 128 * VEC) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float* o = d_tok + (size_t)v * d;
+  if (hi - lo <= 1) {   // most of the vocabulary: nothing to add
+    for (int c = threadIdx.x * VEC; c < d; c += TG_WAVES * WAVE * VEC) {
+      float a[VEC];
+      if (hi > lo) load_vec16(dx + (size_t)order[lo] * d + c, a);
+      else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) a[i] = 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) o[c + i] = a[i];
+    }
+    return;
+  }
+  for (int c = lane * VEC; c < d; c += WAVE * VEC) {
     float acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-    for (int j = lo; j < hi; ++j) {
+    int j = lo + wave;
+    for (; j + 3 * TG_WAVES < hi; j += 4 * TG_WAVES) {
+      float a0[VEC], a1[VEC], a2[VEC], a3[VEC];
+      load_vec16(dx + (size_t)order[j] * d + c, a0);
+      load_vec16(dx + (size_t)order[j + TG_WAVES] * d + c, a1);
+      load_vec16(dx + (size_t)order[j + 2 * TG_WAVES] * d + c, a2);
+      load_vec16(dx + (size_t)order[j + 3 * TG_WAVES] * d + c, a3);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) { acc[i] += a0[i]; acc[i] += a1[i]; acc[i] += a2[i]; acc[i] += a3[i]; }
+    }
+    for (; j < hi; j += TG_WAVES) {
       float a[VEC];
       load_vec16(dx + (size_t)order[j] * d + c, a);
 #pragma unroll
       for (int i = 0; i < VEC; ++i) acc[i] += a[i];
     }
-    float* o = d_tok + (size_t)v * d + c;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) o[i] = acc[i];
+    for (int i = 0; i < VEC; ++i) tg_red[wave * d + c + i] = acc[i];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += TG_WAVES * WAVE) {
+    float t = tg_red[c];
+#pragma unroll
+    for (int w = 1; w < TG_WAVES; ++w) t += tg_red[w * d + c];
+    o[c] = t;
   }
 }
 
@@ -454,7 +507,7 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
   ln_bwd_kernel<T><<<blocks, ROW_THREADS, 2 * d * sizeof(float), s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial,
                                                                      rows, d);
   DIPACO_LAUNCH_CHECK();
-  sum_partials_kernel<<<(2 * d + 255) / 256, 256, 0, s>>>(partial, dg, db, blocks, 2 * d, d);
+  sum_partials_kernel<<<(2 * d + 63) / 64, 256, 0, s>>>(partial, dg, db, blocks, 2 * d, d);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -468,7 +521,7 @@ dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, in
   dim3 grid((cols + WAVE * VEC - 1) / (WAVE * VEC), chunks);
   colsum_kernel<T><<<grid, ROW_THREADS, 0, s>>>(x, partial, rows, cols);
   DIPACO_LAUNCH_CHECK();
-  sum_partials_kernel<<<(cols + 255) / 256, 256, 0, s>>>(partial, out, out, chunks, cols, cols);
+  sum_partials_kernel<<<(cols + 63) / 64, 256, 0, s>>>(partial, out, out, chunks, cols, cols);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -510,7 +563,7 @@ dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, flo
   DIPACO_LAUNCH_CHECK();
   tok_slot_kernel<<<(rows + 255) / 256, 256, 0, s>>>(tokens, offsets, rows, vocab, order);
   DIPACO_LAUNCH_CHECK();
-  tok_grad_kernel<T><<<vocab, 128, 0, s>>>(dx, offsets, order, d_tok, d);
+  tok_grad_kernel<T><<<vocab, TG_WAVES * WAVE, TG_WAVES * d * sizeof(float), s>>>(dx, offsets, order, d_tok, d);
   DIPACO_LAUNCH_CHECK();
   pos_grad_kernel<T><<<max_seq, 128, 0, s>>>(dx, d_pos, B, S, d);
   DIPACO_LAUNCH_CHECK();
