@@ -97,9 +97,19 @@ __device__ __forceinline__ void sb_store_transposed(const SubBlock& s, char* til
   }
 }
 
-__device__ __forceinline__ uint4 ld_frag(const char* tile, int row, int chunk) {
-  return *reinterpret_cast<const uint4*>(tile_chunk(const_cast<char*>(tile), row, chunk));
+// Byte offsets of this lane's fragments inside a 64-row tile.  Lane l reads row 32*t + r (r = l%32) and chunk
+// c ^ swz(row); swz does not depend on t (32*t >> 1 is a multiple of 8) and every chunk index used here is an even
+// number plus h = l/32, so chunk ^ swz = even ^ (h ^ swz(r)): four values per lane, b[k] for even = 2k.  A fragment
+// read is then tile + b[k] + 4096*t with t a compile-time constant: no address arithmetic in the loops.
+struct FragOff { int b[4]; };
+__device__ __forceinline__ FragOff frag_offsets(int lane) {
+  const int r = lane & 31, u = (lane >> 5) ^ swz(r);
+  FragOff f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) f.b[k] = r * TILE_ROW_BYTES + ((u ^ (2 * k)) << 4);
+  return f;
 }
+__device__ __forceinline__ uint4 ld16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
 
 // store 4 consecutive head columns (accumulator elements 4g..4g+3 of a transposed-output tile) as bf16
 __device__ __forceinline__ void store4(bf16* dst, const f32x16& v, int g, float scale) {
@@ -126,6 +136,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_fwd_mfma(const bf16* __restri
   const long ld = 3L * A;
   const bf16* base = qkv + (long)b * S * ld + hd * DH;
   const int q0 = qb * 128, qw0 = q0 + 32 * wave, q = qw0 + r;
+  const FragOff fo = frag_offsets(lane);
 
   uint4 qf[4];
 #pragma unroll
@@ -158,49 +169,53 @@ __global__ void __launch_bounds__(AT_THREADS) attn_fwd_mfma(const bf16* __restri
     if (more) gload(kt + 1);
     const int kv0 = kt * 64;
     if (kv0 <= qw0 + 31) {   // wave-uniform: at least one query of this wave sees this tile
+      const char* kt_ = smem[cur][0];
+      const char* vt_ = smem[cur][1];
       f32x16 st[2];
       zero(st[0]); zero(st[1]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) st[t] = mfma16(ld_frag(smem[cur][0], 32 * t + r, 2 * ks + h), qf[ks], st[t]);
-      const bool diag = kv0 + 63 > qw0;
-      float mx = -INFINITY;
+        for (int t = 0; t < 2; ++t) st[t] = mfma16(ld16(kt_ + fo.b[ks] + 4096 * t), qf[ks], st[t]);
+      if (kv0 + 63 > qw0) {   // wave-uniform: the tile crosses the diagonal of some query
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float s = st[t][e] * sc;
-          if (diag && kv0 + 32 * t + acc_row(e, lane) > q) s = -INFINITY;
-          st[t][e] = s;
-          mx = fmaxf(mx, s);
-        }
+          for (int e = 0; e < 16; ++e)
+            if (kv0 + 32 * t + acc_row(e, lane) > q) st[t][e] = -INFINITY;
+      }
+      float mx = fmaxf(st[0][0], st[1][0]);
+#pragma unroll
+      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(st[0][e], st[1][e]));
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-      const float mn = fmaxf(m, mx);   // finite: key 0 is visible to every query
-      const float corr = __builtin_amdgcn_exp2f(m - mn);
+      const float mn = fmaxf(m, mx * sc);   // finite: key 0 is visible to every query
       float rs = 0.f;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(st[t][e] - mn);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, -mn));
           st[t][e] = p;
           rs += p;
         }
       rs += __shfl_xor(rs, 32, WAVE);
-      l = l * corr + rs;
-      m = mn;
+      if (__builtin_amdgcn_ballot_w64(mn != m) != 0) {   // wave-uniform: somebody's running maximum moved
+        const float corr = __builtin_amdgcn_exp2f(m - mn);
+        l *= corr;
 #pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
+        for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) ot[dt][e] *= corr;
+          for (int e = 0; e < 16; ++e) ot[dt][e] *= corr;
+        m = mn;
+      }
+      l += rs;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const uint4 p0 = pack8<0>(st[t]), p1 = pack8<8>(st[t]);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-          ot[dt] = mfma16(ld_frag(smem[cur][1], 32 * dt + r, 4 * t + h), p0, ot[dt]);
-          ot[dt] = mfma16(ld_frag(smem[cur][1], 32 * dt + r, 4 * t + 2 + h), p1, ot[dt]);
+          ot[dt] = mfma16(ld16(vt_ + fo.b[2 * t] + 4096 * dt), p0, ot[dt]);
+          ot[dt] = mfma16(ld16(vt_ + fo.b[2 * t + 1] + 4096 * dt), p1, ot[dt]);
         }
       }
     }
@@ -226,6 +241,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dq_mfma(const bf16* __res
   const long ld = 3L * A;
   const bf16* base = qkv + (long)b * S * ld + hd * DH;
   const int q0 = qb * 128, qw0 = q0 + 32 * wave, q = qw0 + r;
+  const FragOff fo = frag_offsets(lane);
 
   uint4 qf[4], gf[4];
   float D = 0.f;
@@ -247,7 +263,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dq_mfma(const bf16* __res
   }
   D += __shfl_xor(D, 32, WAVE);
   if (q < S && h == 0) dsum[(long)bh * S + q] = D;
-  const float lse2 = q < S ? lse[(long)bh * S + q] * LOG2E : INFINITY;
+  const float nlse2 = q < S ? -lse[(long)bh * S + q] * LOG2E : -INFINITY;
 
   const int kv_end = min(S, q0 + 128);
   const int ntiles = (kv_end + 63) / 64;
@@ -274,41 +290,49 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dq_mfma(const bf16* __res
     if (more) gload(kt + 1);
     const int kv0 = kt * 64;
     if (kv0 <= qw0 + 31) {
+      const char* k_rows = smem[cur][0];
+      const char* v_rows = smem[cur][1];
+      const char* k_t = smem[cur][2];
       f32x16 st[2], dp[2];
       zero(st[0]); zero(st[1]); zero(dp[0]); zero(dp[1]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          st[t] = mfma16(ld_frag(smem[cur][0], 32 * t + r, 2 * ks + h), qf[ks], st[t]);
-          dp[t] = mfma16(ld_frag(smem[cur][1], 32 * t + r, 2 * ks + h), gf[ks], dp[t]);
+          st[t] = mfma16(ld16(k_rows + fo.b[ks] + 4096 * t), qf[ks], st[t]);
+          dp[t] = mfma16(ld16(v_rows + fo.b[ks] + 4096 * t), gf[ks], dp[t]);
         }
+      // dS^T without the 1/sqrt(d_head) factor (applied once when dQ is stored)
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = kv0 + 32 * t + acc_row(e, lane);
-          const float p = key <= q ? __builtin_amdgcn_exp2f(st[t][e] * sc - lse2) : 0.f;
-          st[t][e] = p * (dp[t][e] - D) * 0.125f;
-        }
+        for (int e = 0; e < 16; ++e)
+          st[t][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, nlse2)) * (dp[t][e] - D);
+      if (kv0 + 63 > qw0) {   // wave-uniform: the tile crosses the diagonal
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (kv0 + 32 * t + acc_row(e, lane) > q) st[t][e] = 0.f;
+      }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const uint4 s0 = pack8<0>(st[t]), s1 = pack8<8>(st[t]);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-          dqt[dt] = mfma16(ld_frag(smem[cur][2], 32 * dt + r, 4 * t + h), s0, dqt[dt]);
-          dqt[dt] = mfma16(ld_frag(smem[cur][2], 32 * dt + r, 4 * t + 2 + h), s1, dqt[dt]);
+          dqt[dt] = mfma16(ld16(k_t + fo.b[2 * t] + 4096 * dt), s0, dqt[dt]);
+          dqt[dt] = mfma16(ld16(k_t + fo.b[2 * t + 1] + 4096 * dt), s1, dqt[dt]);
         }
       }
     }
     if (more) sstore(cur ^ 1);
     __syncthreads();
   }
-  if (q < S) store_transposed_out(dqkv + ((long)b * S + q) * ld + hd * DH, dqt, h, 1.0f);
+  if (q < S) store_transposed_out(dqkv + ((long)b * S + q) * ld + hd * DH, dqt, h, 0.125f);
 }
 
 // ---- backward, dK and dV ------------------------------------------------------------------------------------------
-constexpr int DKV_STAGE = 4 * TILE_BYTES + 2 * 64 * (int)sizeof(float);   // Q rows | Q^T | dO rows | dO^T | lse2 | D
+constexpr int DKV_STAGE = 4 * TILE_BYTES + 2 * 64 * (int)sizeof(float);   // Q rows | Q^T | dO rows | dO^T | -lse2 | D
 
 __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dkv_mfma(const bf16* __restrict__ qkv,
                                                                 const bf16* __restrict__ d_o,
@@ -324,6 +348,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dkv_mfma(const bf16* __re
   const bf16* base = qkv + (long)b * S * ld + hd * DH;
   const bf16* gbase = d_o + (long)b * S * A + hd * DH;
   const int k0 = kb * 128, kw0 = k0 + 32 * wave, key = kw0 + r;
+  const FragOff fo = frag_offsets(lane);
 
   uint4 kf[4], vf[4];
 #pragma unroll
@@ -342,12 +367,19 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dkv_mfma(const bf16* __re
   const bool load_g = tid >= 128;
   SubBlock sb;
   float stat = 0.f;
+  // per-query statistics of the tile: threads 0-63 fetch -lse*log2(e) (-inf beyond S: probability 0), threads
+  // 64-127 fetch D (0 beyond S).  The index is clamped and the override is bitwise, so the load stays unconditional.
+  const float* stat_src = (tid & 64) ? dsum + (long)bh * S : lse + (long)bh * S;
+  const float stat_mul = (tid & 64) ? 1.0f : -LOG2E;
+  const uint32_t stat_fill = (tid & 64) ? 0u : 0xff800000u;
   auto gload = [&](int qt) {
     const int row0 = qt * 64;
     if (load_g) sb_load(sb, gbase + (long)row0 * A, A, S - row0, t128);
     else sb_load(sb, base + (long)row0 * ld, ld, S - row0, t128);
-    if (tid < 64) stat = row0 + tid < S ? lse[(long)bh * S + row0 + tid] * LOG2E : INFINITY;
-    else if (tid < 128) stat = row0 + tid - 64 < S ? dsum[(long)bh * S + row0 + tid - 64] : 0.f;
+    const int qi = row0 + (tid & 63);
+    const float v = stat_src[min(qi, S - 1)] * stat_mul;
+    const uint32_t keep = qi < S ? 0xffffffffu : 0u;
+    stat = __uint_as_float((__float_as_uint(v) & keep) | (stat_fill & ~keep));
   };
   auto sstore = [&](int stage) {
     char* st = dsmem + stage * DKV_STAGE;
@@ -372,36 +404,50 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dkv_mfma(const bf16* __re
       const char* q_t = stg + TILE_BYTES;
       const char* g_rows = stg + 2 * TILE_BYTES;
       const char* g_t = stg + 3 * TILE_BYTES;
-      const float* lse2s = reinterpret_cast<const float*>(stg + 4 * TILE_BYTES);
-      const float* Ds = lse2s + 64;
+      const float* nlse2s = reinterpret_cast<const float*>(stg + 4 * TILE_BYTES);
+      const float* Ds = nlse2s + 64;
       f32x16 st[2], dp[2];
       zero(st[0]); zero(st[1]); zero(dp[0]); zero(dp[1]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          st[t] = mfma16(ld_frag(q_rows, 32 * t + r, 2 * ks + h), kf[ks], st[t]);
-          dp[t] = mfma16(ld_frag(g_rows, 32 * t + r, 2 * ks + h), vf[ks], dp[t]);
+          st[t] = mfma16(ld16(q_rows + fo.b[ks] + 4096 * t), kf[ks], st[t]);
+          dp[t] = mfma16(ld16(g_rows + fo.b[ks] + 4096 * t), vf[ks], dp[t]);
         }
+      // accumulator elements 4g..4g+3 are queries 32t + 8g + 4h + (0..3): their statistics are 16 contiguous bytes
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int qi = 32 * t + acc_row(e, lane);
-          const float p = q0 + qi >= key ? __builtin_amdgcn_exp2f(st[t][e] * sc - lse2s[qi]) : 0.f;
-          st[t][e] = p;
-          dp[t][e] = p * (dp[t][e] - Ds[qi]) * 0.125f;
+        for (int g = 0; g < 4; ++g) {
+          const float4 L = *reinterpret_cast<const float4*>(nlse2s + 32 * t + 8 * g + 4 * h);
+          const float4 Dv = *reinterpret_cast<const float4*>(Ds + 32 * t + 8 * g + 4 * h);
+          const float Ls[4] = {L.x, L.y, L.z, L.w}, Dd[4] = {Dv.x, Dv.y, Dv.z, Dv.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int e = 4 * g + i;
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, Ls[i]));
+            st[t][e] = p;
+            dp[t][e] = p * (dp[t][e] - Dd[i]);   // dS without 1/sqrt(d_head) (applied when dK is stored)
+          }
         }
+      if (q0 < kw0 + 31) {   // wave-uniform: the tile crosses the diagonal of some key
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (q0 + 32 * t + acc_row(e, lane) < key) { st[t][e] = 0.f; dp[t][e] = 0.f; }
+      }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const uint4 p0 = pack8<0>(st[t]), p1 = pack8<8>(st[t]);
         const uint4 s0 = pack8<0>(dp[t]), s1 = pack8<8>(dp[t]);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-          dvt[dt] = mfma16(ld_frag(g_t, 32 * dt + r, 4 * t + h), p0, dvt[dt]);
-          dvt[dt] = mfma16(ld_frag(g_t, 32 * dt + r, 4 * t + 2 + h), p1, dvt[dt]);
-          dkt[dt] = mfma16(ld_frag(q_t, 32 * dt + r, 4 * t + h), s0, dkt[dt]);
-          dkt[dt] = mfma16(ld_frag(q_t, 32 * dt + r, 4 * t + 2 + h), s1, dkt[dt]);
+          dvt[dt] = mfma16(ld16(g_t + fo.b[2 * t] + 4096 * dt), p0, dvt[dt]);
+          dvt[dt] = mfma16(ld16(g_t + fo.b[2 * t + 1] + 4096 * dt), p1, dvt[dt]);
+          dkt[dt] = mfma16(ld16(q_t + fo.b[2 * t] + 4096 * dt), s0, dkt[dt]);
+          dkt[dt] = mfma16(ld16(q_t + fo.b[2 * t + 1] + 4096 * dt), s1, dkt[dt]);
         }
       }
     }
@@ -410,7 +456,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dkv_mfma(const bf16* __re
   }
   if (key < S) {
     bf16* out = dqkv + ((long)b * S + key) * ld + hd * DH;
-    store_transposed_out(out + A, dkt, h, 1.0f);
+    store_transposed_out(out + A, dkt, h, 0.125f);
     store_transposed_out(out + 2 * A, dvt, h, 1.0f);
   }
 }
