@@ -30,7 +30,7 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
                             void* stream);
 
 /* Force the GEMM workgroup tile for every later call in this process: 0 = automatic (default), 1 = 128x128,
- * 2 = 256x128, 3 = 256x256.  For tests (every tile shape must give the same parity) and tuning. */
+ * 2 = 256x128, 3 = 256x256 with four waves, 4 = 256x256 with eight waves.  For tests (every tile shape must give the same parity) and tuning. */
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 
 /* Causal softmax attention.  qkv: [B*S, 3*H*dh], row = q | k | v, head h at columns h*dh of each third;

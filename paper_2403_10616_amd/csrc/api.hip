@@ -64,13 +64,7 @@ struct Plan {
   size_t total;
 };
 
-static int dw_splits(int M, int N, int K) {
-  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-  long s = (512 + tiles - 1) / tiles;
-  s = std::min<long>(s, 16);
-  s = std::min<long>(s, std::max(1, K / 256));
-  return (int)std::max<long>(s, 1);
-}
+static int dw_splits(int M, int N, int K) { return gemm_plan_splits(M, N, K); }
 
 static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   const dipaco_arch& a = c->arch;
@@ -98,7 +92,7 @@ static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   const size_t widest = std::max(std::max(F, 3 * A), d);
   p.cs_partial = take(colsum_partial_floats((int)T, (int)widest) * 4);
   size_t sk = 0;
-  auto need = [&](size_t M, size_t N) { sk = std::max(sk, (size_t)dw_splits((int)M, (int)N, (int)T) * M * N); };
+  auto need = [&](size_t M, size_t N) { sk = std::max(sk, (size_t)gemm_max_splits((int)M, (int)N, (int)T) * M * N); };
   need(d, 3 * A); need(A, d); need(d, F); need(F, d); need(d, V);
   p.splitk_partial = take(sk * 4);
   p.embed_ints = take(embed_bwd_scratch_ints((int)T, (int)V) * 4);
@@ -458,7 +452,7 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
 }
 
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
-  if (tile < 0 || tile > 3) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..3");
+  if (tile < 0 || tile > 4) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..4");
   set_gemm_tile(tile);
   return DIPACO_OK;
 }

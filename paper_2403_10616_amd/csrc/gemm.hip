@@ -49,17 +49,19 @@ template <> struct OutVec<bf16> {
   static __device__ __forceinline__ void store(bf16* p, const float (&v)[8]) { store_vec16<bf16>(p, v); }
 };
 
-template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int NS>
-__global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
+// BM x BN tile, WGM x WGN waves, NS register sets of K tiles in flight
+template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int WGM, int WGN, int NS>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_kernel(const GemmDev g) {
   constexpr int BK = MmaTraits<T>::BK;
-  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
   constexpr int STAGE = (BM + BN) * TILE_ROW_BYTES;
-  constexpr int WN = BN / 2;            // columns per wave
+  constexpr int WN = BN / WGN;          // columns per wave
   constexpr int LDW = WN + 4;           // padded row of the epilogue staging buffer (floats)
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // ---- which tile ----
   const int tiles = g.tiles_m * g.tiles_n;
@@ -87,8 +89,8 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
 
   const T* A = static_cast<const T*>(g.A);
   const T* B = static_cast<const T*>(g.B);
-  using LA = TileLoader<T, BM, TA>;
-  using LB = TileLoader<T, BN, !TB>;   // B as stored [K,N] is row(N)-contiguous: needs the transposing loader
+  using LA = TileLoader<T, BM, TA, NT>;
+  using LB = TileLoader<T, BN, !TB, NT>;   // B as stored [K,N] is row(N)-contiguous: needs the transposing loader
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -104,7 +106,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
   LB::offsets(offb, g.ldb, n0, g.N, tid);
   const long ka = LA::k_step(g.lda), kb = LB::k_step(g.ldb);
   const int nfull = (k_end - k_begin) / BK;   // K tiles completely inside the range; nkt - nfull is 0 or 1
-  const int a_row0 = wm * (BM / 2), b_row0 = wn * (BN / 2);
+  const int a_row0 = wm * (BM / WGM), b_row0 = wn * (BN / WGN);
 
   auto stage_a = [&](int st) { return smem + st * STAGE; };
   auto stage_b = [&](int st) { return smem + st * STAGE + BM * TILE_ROW_BYTES; };
@@ -132,7 +134,8 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
   };
 
   // Fragment double buffer.  At the top of a step, f*[0] holds K group 0 of the tile about to be multiplied.
-  uint4 fa[2][TM], fb[2][TN];
+  constexpr bool PIPE = WGM * WGN == 4;   // one wave per SIMD: software-pipeline the fragments
+  uint4 fa[PIPE ? 2 : 1][TM], fb[PIPE ? 2 : 1][TN];
   using R0 = std::integral_constant<int, 0>;
   using R1 = std::integral_constant<int, 1>;
   using Full = std::true_type;
@@ -150,16 +153,26 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
     const bool have_next = full || t + 1 < nkt;
     if (have_next) sstore(Set{}, Buf{}, FULL, t + 1);
     if (full || t + 1 + NS < nkt) gload(Set{}, FULL, t + 1 + NS);
-    load_frags<TM, TN>(fa[1], fb[1], stage_a(r), stage_b(r), a_row0, b_row0, lane, 1);
-    mma_group<T, TM, TN>(acc, fa[0], fb[0]);
-    load_frags<TM, TN>(fa[0], fb[0], stage_a(r), stage_b(r), a_row0, b_row0, lane, 2);
-    mma_group<T, TM, TN>(acc, fa[1], fb[1]);
-    __syncthreads();
-    load_frags<TM, TN>(fa[1], fb[1], stage_a(r), stage_b(r), a_row0, b_row0, lane, 3);
-    mma_group<T, TM, TN>(acc, fa[0], fb[0]);
-    if (have_next) load_frags<TM, TN>(fa[0], fb[0], stage_a(1 - r), stage_b(1 - r), a_row0, b_row0, lane, 0);
-    mma_group<T, TM, TN>(acc, fa[1], fb[1]);
-    __syncthreads();
+    if constexpr (PIPE) {
+      load_frags<TM, TN>(fa[1], fb[1], stage_a(r), stage_b(r), a_row0, b_row0, lane, 1);
+      mma_group<T, TM, TN>(acc, fa[0], fb[0]);
+      load_frags<TM, TN>(fa[0], fb[0], stage_a(r), stage_b(r), a_row0, b_row0, lane, 2);
+      mma_group<T, TM, TN>(acc, fa[1], fb[1]);
+      __syncthreads();
+      load_frags<TM, TN>(fa[1], fb[1], stage_a(r), stage_b(r), a_row0, b_row0, lane, 3);
+      mma_group<T, TM, TN>(acc, fa[0], fb[0]);
+      if (have_next) load_frags<TM, TN>(fa[0], fb[0], stage_a(1 - r), stage_b(1 - r), a_row0, b_row0, lane, 0);
+      mma_group<T, TM, TN>(acc, fa[1], fb[1]);
+      __syncthreads();
+    } else {
+      // two waves per SIMD hide each other's LDS latency: one fragment set, one barrier per K tile
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        load_frags<TM, TN>(fa[0], fb[0], stage_a(r), stage_b(r), a_row0, b_row0, lane, ks);
+        mma_group<T, TM, TN>(acc, fa[0], fb[0]);
+      }
+      __syncthreads();
+    }
   };
 
   gload(R0{}, Any{}, 0);
@@ -167,7 +180,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
   sstore(R0{}, R0{}, Any{}, 0);
   if (nkt > NS) gload(R0{}, Any{}, NS);
   __syncthreads();
-  load_frags<TM, TN>(fa[0], fb[0], stage_a(0), stage_b(0), a_row0, b_row0, lane, 0);
+  if constexpr (PIPE) load_frags<TM, TN>(fa[0], fb[0], stage_a(0), stage_b(0), a_row0, b_row0, lane, 0);
   int t = 0;
   for (; t + 2 + NS < nfull; t += 2) {   // steady state: every tile touched is complete, no conditions
     step(R0{}, Full{}, t);
@@ -201,7 +214,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) gemm_kernel(const GemmDev g) {
     for (int it = 0; it < ITERS; ++it) {
       const int item = lane + WAVE * it;
       const int rr = item / GROUPS, cg = item % GROUPS;
-      const int row = m0 + wm * (BM / 2) + 32 * i + rr;
+      const int row = m0 + wm * (BM / WGM) + 32 * i + rr;
       const int col = n0 + wn * WN + 8 * cg;
       const float4 lo = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg);
       const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
@@ -276,13 +289,13 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   }
 }
 
-template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int NS>
+template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int WGM, int WGN, int NS>
 dipaco_status run(const GemmArgs& a, hipStream_t s) {
   constexpr int BK = MmaTraits<T>::BK;
   constexpr size_t smem_loop = 2 * (size_t)(BM + BN) * TILE_ROW_BYTES;
-  constexpr size_t smem_epi = 4 * 32 * (size_t)(BN / 2 + 4) * sizeof(float);
+  constexpr size_t smem_epi = (size_t)WGM * WGN * 32 * (size_t)(BN / WGN + 4) * sizeof(float);
   constexpr size_t smem = smem_loop > smem_epi ? smem_loop : smem_epi;
-  auto kern = gemm_kernel<T, TC, TA, TB, BM, BN, NS>;
+  auto kern = gemm_kernel<T, TC, TA, TB, BM, BN, WGM, WGN, NS>;
   static bool attr_set = false;   // one attribute call per instantiation and process
   if (!attr_set) {
     DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -304,7 +317,7 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   if (g.splits < 1) g.splits = 1;
   const long blocks = (long)g.tiles_m * g.tiles_n * g.splits;
   if (blocks > 0x7fffffffL) return fail(DIPACO_ESHAPE, "gemm: too many tiles");
-  kern<<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(g);
+  kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) {
     size_t total = (size_t)a.M * a.N;
@@ -317,27 +330,65 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
 
 int g_forced_tile = 0;
 
-int pick_tile(int M, int N, int K) {
+// Measured on the training step's shapes: the eight-wave 256 x 256 tile is the fastest wherever its workgroups
+// can fill most of the chip's 256 compute units; below that the 128 x 128 tile (two workgroups per unit) wins.
+int pick_tile(int M, int N, int K, int splits) {
   if (g_forced_tile) return g_forced_tile;
-  // measured on the path's shapes: 256 x 256 tiles only pay once the K loop is long enough to amortise their
-  // prologue and epilogue and the problem still fills the chip with them
-  const long t3 = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (K >= 16384 && t3 >= 256) return 3;
-  return 1;
+  const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256) * (splits < 1 ? 1 : splits);
+  return (K >= 256 && t256 >= 160) ? 4 : 1;
 }
 
 template <typename T, typename TC, bool TA, bool TB>
 dipaco_status run_tiled(const GemmArgs& a, hipStream_t s) {
-  switch (pick_tile(a.M, a.N, a.K)) {
-    case 3: return run<T, TC, TA, TB, 256, 256, 1>(a, s);
-    case 2: return run<T, TC, TA, TB, 256, 128, 2>(a, s);
-    default: return run<T, TC, TA, TB, 128, 128, 2>(a, s);
+  switch (pick_tile(a.M, a.N, a.K, a.splits)) {
+    case 4: return run<T, TC, TA, TB, 256, 256, 2, 4, 1>(a, s);
+    case 3: return run<T, TC, TA, TB, 256, 256, 2, 2, 1>(a, s);
+    case 2: return run<T, TC, TA, TB, 256, 128, 2, 2, 2>(a, s);
+    default: return run<T, TC, TA, TB, 128, 128, 2, 2, 2>(a, s);
   }
 }
 
 }  // namespace
 
 void set_gemm_tile(int t) { g_forced_tile = t; }
+
+// Split count for a long-K product (a weight gradient: K = tokens).  With 256 x 256 tiles the cost of one
+// candidate, in units of one K step of one tile, is rounds * (K / s + fixed) + s * (traffic of one partial
+// plane), where rounds = workgroups / 256 rounded up; the constants are fitted to measured launches.
+static int splits_tile256(int M, int N, int K, int smax) {
+  const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (t256 * smax < 160) return 0;   // cannot fill the chip: not a 256 x 256 case
+  const double plane = (double)M * N * 6e-5;
+  double best = 0;
+  int best_s = 1;
+  for (int s = 1; s <= smax; ++s) {
+    const long rounds = (t256 * s + 255) / 256;
+    const double cost = rounds * ((double)K / s + 600.0) + (s > 1 ? s * plane : 0.0);
+    if (s == 1 || cost < best) { best = cost; best_s = s; }
+  }
+  return best_s;
+}
+
+static int splits_tile128(int M, int N, int smax) {
+  const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  const long s = std::min<long>((512 + t128 - 1) / t128, smax);
+  return (int)std::max<long>(s, 1);
+}
+
+int gemm_plan_splits(int M, int N, int K) {
+  const int smax = (int)std::min<long>(16, std::max(1, K / 256));
+  if (g_forced_tile == 0 || g_forced_tile == 4) {
+    const int s = splits_tile256(M, N, K, smax);
+    if (s) return s;
+  }
+  return splits_tile128(M, N, smax);
+}
+
+// Upper bound of gemm_plan_splits over every tile setting: sizes the partial-product workspace.
+int gemm_max_splits(int M, int N, int K) {
+  const int smax = (int)std::min<long>(16, std::max(1, K / 256));
+  return std::max(splits_tile256(M, N, K, smax), splits_tile128(M, N, smax));
+}
 
 template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s) {
   constexpr int VEC = MmaTraits<T>::VEC;

@@ -50,6 +50,8 @@ struct GemmArgs {
 template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s);
 // 0 = automatic; 1 = 128x128, 2 = 256x128, 3 = 256x256 workgroup tiles (tuning and tests)
 void set_gemm_tile(int t);
+int gemm_plan_splits(int M, int N, int K);   // split count the weight-gradient products are launched with
+int gemm_max_splits(int M, int N, int K);    // its upper bound over tile settings (workspace sizing)
 
 // ---- transformer.hip ---------------------------------------------------------------------------------
 template <typename T>

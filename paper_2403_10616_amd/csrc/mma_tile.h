@@ -70,17 +70,17 @@ __device__ __forceinline__ int acc_row(int e, int lane) { return 8 * (e >> 2) + 
 //   load_full(r, src_k, off)                  tile completely inside the K range; src_k = operand + k0 * k_step
 //   load_tail(r, src, ld, row0, rows_total, k0, k_end, tid)    any tile (K indices clamped to the last valid one)
 //   store(r, tile, tid, k0, k_end)            registers -> LDS (zeroing K >= k_end)
-template <typename T, int ROWS, bool TRANS> struct TileLoader;
+template <typename T, int ROWS, bool TRANS, int NT = GEMM_THREADS> struct TileLoader;   // NT threads fill a tile
 
 // K-contiguous source: element (row, k) at src[row * ld + k].
-template <typename T, int ROWS> struct TileLoader<T, ROWS, false> {
-  static constexpr int NLD = ROWS / 32;
+template <typename T, int ROWS, int NT> struct TileLoader<T, ROWS, false, NT> {
+  static constexpr int NLD = ROWS * 8 / NT;
   static constexpr int VEC = MmaTraits<T>::VEC;
   __device__ static __forceinline__ long k_step(long) { return 1; }
   __device__ static __forceinline__ void offsets(uint32_t (&off)[NLD], long ld, int row0, int rows_total, int tid) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + GEMM_THREADS * i;
+      const int idx = tid + NT * i;
       const int row = min(row0 + (idx >> 3), rows_total - 1);
       off[i] = (uint32_t)((long)row * ld + (idx & 7) * VEC);
     }
@@ -94,7 +94,7 @@ template <typename T, int ROWS> struct TileLoader<T, ROWS, false> {
                                                    int rows_total, int k0, int k_end, int tid) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + GEMM_THREADS * i;
+      const int idx = tid + NT * i;
       const int row = min(row0 + (idx >> 3), rows_total - 1);
       const int k = min(k0 + (idx & 7) * VEC, k_end - VEC);
       r[i] = *reinterpret_cast<const uint4*>(src + (long)row * ld + k);
@@ -103,7 +103,7 @@ template <typename T, int ROWS> struct TileLoader<T, ROWS, false> {
   __device__ static __forceinline__ void store_full(const uint4 (&r)[NLD], char* tile, int tid) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + GEMM_THREADS * i;
+      const int idx = tid + NT * i;
       *reinterpret_cast<uint4*>(tile_chunk(tile, idx >> 3, idx & 7)) = r[i];
     }
   }
@@ -114,7 +114,7 @@ template <typename T, int ROWS> struct TileLoader<T, ROWS, false> {
       const bool keep = k0 + (tid & 7) * VEC < k_end;
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int idx = tid + GEMM_THREADS * i;
+        const int idx = tid + NT * i;
         *reinterpret_cast<uint4*>(tile_chunk(tile, idx >> 3, idx & 7)) = keep_or_zero(r[i], keep);
       }
     }
@@ -126,14 +126,14 @@ template <typename T, int ROWS> struct TileLoader<T, ROWS, false> {
 // 4-K block kq = ((l>>1)&7) + 8*(w&1).  One load instruction then reads, per K row, 128 contiguous bytes; one
 // 8-byte LDS store instruction has each run of 16 consecutive lanes write 8 K-granules of two rows whose swizzles
 // differ by 4: sixteen different 8-byte slots.
-template <int ROWS> struct TileLoader<bf16, ROWS, true> {
-  static constexpr int NLD = ROWS / 32;
-  static constexpr int NSB = ROWS / 128;
+template <int ROWS, int NT> struct TileLoader<bf16, ROWS, true, NT> {
+  static constexpr int NLD = ROWS * 8 / NT;
+  static constexpr int NSB = NLD / 4;          // 4 x 8 blocks per thread; NT threads cover NT/2 rows per pass
   __device__ static __forceinline__ long k_step(long ld) { return ld; }
   __device__ static __forceinline__ void coords(int tid, int sb, int& kq, int& mq) {
     const int w = tid >> 6, l = tid & 63;
     kq = ((l >> 1) & 7) + 8 * (w & 1);
-    mq = (l & 1) + 2 * ((l >> 4) & 3) + 8 * (w >> 1) + 16 * sb;
+    mq = (l & 1) + 2 * ((l >> 4) & 3) + 8 * (w >> 1) + (NT / 16) * sb;
   }
   __device__ static __forceinline__ void offsets(uint32_t (&off)[NLD], long ld, int row0, int rows_total, int tid) {
 #pragma unroll
@@ -205,14 +205,14 @@ template <int ROWS> struct TileLoader<bf16, ROWS, true> {
 // Row-contiguous fp32 source: element (row, k) at src[k * ld + row].  rows_total % 4 == 0.
 // A thread owns 4 (K) x 4 (rows) blocks: lane l of wave w has 4-row block mq = (l&3) + 4*((l>>3)&7) and 4-K block
 // kq = ((l>>2)&1) + 2*w, so that 8 consecutive lanes write 8 different 16-byte slots.
-template <int ROWS> struct TileLoader<float, ROWS, true> {
-  static constexpr int NLD = ROWS / 32;
-  static constexpr int NSB = ROWS / 128;
+template <int ROWS, int NT> struct TileLoader<float, ROWS, true, NT> {
+  static constexpr int NLD = ROWS * 8 / NT;
+  static constexpr int NSB = NLD / 4;
   __device__ static __forceinline__ long k_step(long ld) { return ld; }
   __device__ static __forceinline__ void coords(int tid, int sb, int& kq, int& mq) {
     const int w = tid >> 6, l = tid & 63;
-    kq = ((l >> 2) & 1) + 2 * w;
-    mq = (l & 3) + 4 * ((l >> 3) & 7) + 32 * sb;
+    kq = ((l >> 2) & 1) + 2 * (w & 3);
+    mq = (l & 3) + 4 * ((l >> 3) & 7) + 32 * (w >> 2) + (NT / 8) * sb;
   }
   __device__ static __forceinline__ void offsets(uint32_t (&off)[NLD], long ld, int row0, int rows_total, int tid) {
 #pragma unroll

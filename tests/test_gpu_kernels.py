@@ -22,14 +22,22 @@ def _rand(shape, seed, dtype):
     return t.to(DEV), t.to(torch.float64).numpy()
 
 
+@pytest.fixture(params=[0, 1, 2, 3, 4], ids=lambda t: f"tile{t}")
+def gemm_tile(request):
+    """Every workgroup tile shape must reach the same parity; 0 is the library's own choice."""
+    dp.dipaco_k_set_gemm_tile(request.param)
+    yield request.param
+    dp.dipaco_k_set_gemm_tile(0)
+
+
 # (M, N, K): several tiles with ragged tails in every direction; K not a multiple of the K tile
 GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (1, 8, 8), (300, 264, 520), (64, 512, 1000)]
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
-def test_gemm_forward_layout_with_epilogues(dtype, M, N, K):
-    print(f"gemm fwd dtype={dtype} M={M} N={N} K={K}", flush=True)
+def test_gemm_forward_layout_with_epilogues(dtype, M, N, K, gemm_tile):
+    print(f"gemm fwd tile={gemm_tile} dtype={dtype} M={M} N={N} K={K}", flush=True)
     A, Ar = _rand((M, K), 1, dtype)
     B, Br = _rand((K, N), 2, dtype)
     bias, br = _rand((N,), 3, dtype)
@@ -57,8 +65,8 @@ def test_gemm_forward_layout_with_epilogues(dtype, M, N, K):
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
-def test_gemm_input_gradient_layout(dtype, M, N, K):
-    print(f"gemm dX dtype={dtype} M={M} N={N} K={K}", flush=True)
+def test_gemm_input_gradient_layout(dtype, M, N, K, gemm_tile):
+    print(f"gemm dX tile={gemm_tile} dtype={dtype} M={M} N={N} K={K}", flush=True)
     A, Ar = _rand((M, K), 5, dtype)
     Bt, Btr = _rand((N, K), 6, dtype)          # B stored [N, K]
     U, Ur = _rand((M, N), 7, dtype)
@@ -75,8 +83,8 @@ def test_gemm_input_gradient_layout(dtype, M, N, K):
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("M,N,K,splits", [(128, 128, 64, 1), (200, 136, 77, 1), (72, 264, 1000, 4), (8, 8, 5, 1),
                                           (136, 64, 4099, 16)])
-def test_gemm_weight_gradient_layout_and_split_k(dtype, M, N, K, splits):
-    print(f"gemm dW dtype={dtype} M={M} N={N} K={K} splits={splits}", flush=True)
+def test_gemm_weight_gradient_layout_and_split_k(dtype, M, N, K, splits, gemm_tile):
+    print(f"gemm dW tile={gemm_tile} dtype={dtype} M={M} N={N} K={K} splits={splits}", flush=True)
     At, Atr = _rand((K, M), 8, dtype)          # A stored [K, M]: contraction over rows (tokens)
     B, Br = _rand((K, N), 9, dtype)
     C = torch.empty((M, N), dtype=torch.float32, device=DEV)
