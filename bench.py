@@ -5,9 +5,11 @@ Default workload ("path_step"): one inner step of a 174M-parameter path -- forwa
 [32, 1024] batch of Zipf(1.1) tokens, bf16 compute with fp32 master weights and optimiser state -- through the
 C-ABI calls dipaco_path_fwd_bwd + dipaco_inner_adamw.  Prints ONE JSON line.
 
-Other workloads (for profiling the bandwidth / routing kernels; same JSON shape):
+Other workloads (for profiling single kernels; same JSON shape):
   --workload outer_step   16 deltas x 57,872,640 parameters, weighted mean + Nesterov
   --workload route        2^20 x 768 prefix embeddings against 256 centroids
+  --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
+  --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
 """
 from __future__ import annotations
 
@@ -246,19 +248,114 @@ def bench_route(args):
                          "hbm_gbs": (N * D * 4.0 + N * 8.0) / (ms * 1e-3) / 1e9}}
 
 
+def bench_gemm(args):
+    import torch
+    import paper_2403_10616_amd as dp
+    M, N, K = (int(x) for x in args.mnk.split(","))
+    dev = "cuda"
+    ta, tb = args.layout[0] == "t", args.layout[1] == "t"
+    out_f32 = args.layout == "tn"
+    a = torch.empty(M * K, dtype=torch.bfloat16, device=dev).normal_()
+    b = torch.empty(K * N, dtype=torch.bfloat16, device=dev).normal_(std=0.02)
+    c = torch.empty(M * N, dtype=torch.float32 if out_f32 else torch.bfloat16, device=dev)
+    ep = args.epilogue
+    bias = torch.zeros(N, dtype=torch.bfloat16, device=dev) if ep in ("bias", "gelu", "resid") else None
+    resid = torch.empty(M * N, dtype=torch.bfloat16, device=dev).normal_() if ep == "resid" else None
+    aux_out = torch.empty(M * N, dtype=torch.bfloat16, device=dev) if ep == "gelu" else None
+    aux_in = torch.empty(M * N, dtype=torch.bfloat16, device=dev).normal_() if ep == "dgelu" else None
+    act = {"gelu": 1, "dgelu": 2}.get(ep, 0)
+    splits, partial = 1, None
+    if out_f32 and args.splits > 1:
+        splits = args.splits
+        partial = torch.empty(splits * M * N, dtype=torch.float32, device=dev)
+
+    def step():
+        dp.dipaco_k_gemm(dp.BF16, ta, tb, out_f32, M, N, K, a, b, c, bias, resid, aux_out, aux_in, act, splits, partial)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * M * N * K
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"metric": "GEMM TFLOP/s on 1 MI355X", "value": ach, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"gemm {args.layout} M={M} N={N} K={K} epilogue={ep} splits={splits}"},
+            "roofline": {"bound": "mfma", "kernel": "gemm_kernel", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "flops_per_launch": flops}}
+
+
+def bench_attention(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[2]
+    B, S, H, dh = cfg["batch"], args.seq or cfg["seq"], cfg["n_heads"], cfg["d_head"]
+    if args.seq:
+        B = max(1, B * cfg["seq"] // S)
+    dev = "cuda"
+    A = H * dh
+    qkv = torch.empty(B * S * 3 * A, dtype=torch.bfloat16, device=dev).normal_()
+    o = torch.empty(B * S * A, dtype=torch.bfloat16, device=dev)
+    d_o = torch.empty(B * S * A, dtype=torch.bfloat16, device=dev).normal_()
+    dqkv = torch.empty(B * S * 3 * A, dtype=torch.bfloat16, device=dev)
+    lse = torch.empty(B * H * S, dtype=torch.float32, device=dev)
+    dsum = torch.empty(B * H * S, dtype=torch.float32, device=dev)
+    dp.dipaco_k_attention_fwd(dp.BF16, qkv, o, lse, B, S, H, dh)
+    bwd = getattr(args, "pass") == "bwd"
+
+    def step():
+        if bwd:
+            dp.dipaco_k_attention_bwd(dp.BF16, qkv, o, d_o, lse, dqkv, dsum, B, S, H, dh)
+        else:
+            dp.dipaco_k_attention_fwd(dp.BF16, qkv, o, lse, B, S, H, dh)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = B * H * (2 * 2 * S * S * dh) / 2 * (2.5 if bwd else 1.0)   # causal half; backward = five matmuls
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"metric": "causal attention TFLOP/s on 1 MI355X", "value": ach, "unit": "TFLOP/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"attention {'backward' if bwd else 'forward'} B={B} H={H} S={S} d_head={dh}"},
+            "roofline": {"bound": "mfma", "kernel": "attn_bwd_*_mfma" if bwd else "attn_fwd_mfma", "achieved": ach,
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                         "flops_per_launch": flops}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "route"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "route", "gemm", "attention"])
+    ap.add_argument("--mnk", default="32768,3584,896")
+    ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
+    ap.add_argument("--epilogue", default="none", choices=["none", "bias", "gelu", "dgelu", "resid"])
+    ap.add_argument("--splits", type=int, default=1)
+    ap.add_argument("--pass", default="fwd", choices=["fwd", "bwd"])
+    ap.add_argument("--seq", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs one path on ONE GPU (no collectives, no sharding); use --gpus 1")
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
-    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route}[args.workload]
+    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm,
+          "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 
 

@@ -452,7 +452,7 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
 }
 
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
-  if (tile < 0 || tile > 4) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..4");
+  if (tile < 0 || tile > 5) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..5");
   set_gemm_tile(tile);
   return DIPACO_OK;
 }

@@ -12,42 +12,13 @@
 #include <algorithm>
 #include <type_traits>
 
+#include "gemm_common.h"
 #include "kernels.h"
 #include "mma_tile.h"
 
 namespace dipaco {
 
 namespace {
-
-struct GemmDev {
-  const void* A; const void* B; void* C;
-  int M, N, K;
-  long lda, ldb, ldc;
-  const void* bias; const void* resid; void* aux_out; const void* aux_in;
-  int act;
-  int splits;
-  int k_per_split;   // multiple of BK
-  float* partial;
-  int tiles_m, tiles_n;
-};
-
-constexpr int N_XCD = 8;
-
-template <typename T> struct OutVec;   // 8 consecutive output elements
-template <> struct OutVec<float> {
-  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
-    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  }
-  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
-    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
-  }
-};
-template <> struct OutVec<bf16> {
-  static __device__ __forceinline__ void load(const bf16* p, float (&v)[8]) { load_vec16<bf16>(p, v); }
-  static __device__ __forceinline__ void store(bf16* p, const float (&v)[8]) { store_vec16<bf16>(p, v); }
-};
 
 // BM x BN tile, WGM x WGN waves, NS register sets of K tiles in flight
 template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int WGM, int WGN, int NS>
@@ -63,24 +34,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_kernel(const GemmDev g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // ---- which tile ----
-  const int tiles = g.tiles_m * g.tiles_n;
-  int bid = blockIdx.x;
-  const int split = bid / tiles;
-  bid -= split * tiles;
-  {  // XCD x gets the contiguous range of tile ids [x * per, ...): ids are dealt to XCDs round-robin
-    const int per = tiles / N_XCD, rem = tiles % N_XCD;
-    const int x = bid % N_XCD, i = bid / N_XCD;
-    bid = x * per + min(x, rem) + i;
-  }
-  const int group = 8;
-  const int per_group = group * g.tiles_n;
-  const int gidx = bid / per_group;
-  const int first_m = gidx * group;
-  const int gsize = min(group, g.tiles_m - first_m);
-  const int in_group = bid - gidx * per_group;
-  const int tile_m = first_m + in_group % gsize;
-  const int tile_n = in_group / gsize;
+  int split, tile_m, tile_n;
+  gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int k_begin = split * g.k_per_split;
@@ -191,90 +146,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_kernel(const GemmDev g) {
     if (t + 1 < nkt) step(R1{}, Any{}, t + 1);
   }
 
-  // ---- epilogue: accumulators -> LDS (this wave's private region) -> 8 consecutive columns per lane ----
-  float* stg = reinterpret_cast<float*>(smem) + wave * (32 * LDW);
-  const int col_l = lane & 31;
-  constexpr int GROUPS = WN / 8;                 // 8-column groups per row
-  constexpr int ITERS = 32 * GROUPS / WAVE;
-  const T* bias = static_cast<const T*>(g.bias);
-  const T* resid = static_cast<const T*>(g.resid);
-  const T* aux_in = static_cast<const T*>(g.aux_in);
-  T* aux_out = static_cast<T*>(g.aux_out);
-  const bool to_partial = g.splits > 1;
-  float* P = to_partial ? g.partial + (size_t)split * g.M * g.N : nullptr;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-      const int item = lane + WAVE * it;
-      const int rr = item / GROUPS, cg = item % GROUPS;
-      const int row = m0 + wm * (BM / WGM) + 32 * i + rr;
-      const int col = n0 + wn * WN + 8 * cg;
-      const float4 lo = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg);
-      const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
-      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      if (row >= g.M || col >= g.N) continue;
-      const bool full = col + 8 <= g.N;
-      if (to_partial) {
-        float* dst = P + (size_t)row * g.N + col;
-        if (full && (g.N & 3) == 0) OutVec<float>::store(dst, v);
-        else {
-#pragma unroll
-          for (int c = 0; c < 8; ++c)
-            if (col + c < g.N) dst[c] = v[c];
-        }
-        continue;
-      }
-      const size_t off = (size_t)row * g.ldc + col;
-      if (full) {
-        if (bias) {
-          float b[8];
-          OutVec<T>::load(bias + col, b);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] += b[c];
-        }
-        if (g.act == 1) {
-          // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
-          OutVec<T>::store(aux_out + off, v);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] = gelu_f(to_f32(from_f32<T>(v[c])));
-        } else if (g.act == 2) {
-          float u[8];
-          OutVec<T>::load(aux_in + off, u);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_f(u[c]);
-        }
-        if (resid) {
-          float rv[8];
-          OutVec<T>::load(resid + off, rv);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] += rv[c];
-        }
-        OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
-      } else {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          if (col + c >= g.N) break;
-          float x = v[c] + (bias ? to_f32(bias[col + c]) : 0.f);
-          if (g.act == 1) {
-            const T pre = from_f32<T>(x);
-            aux_out[off + c] = pre;
-            x = gelu_f(to_f32(pre));
-          } else if (g.act == 2) {
-            x *= gelu_grad_f(to_f32(aux_in[off + c]));
-          }
-          if (resid) x += to_f32(resid[off + c]);
-          static_cast<TC*>(g.C)[off + c] = from_f32<TC>(x);
-        }
-      }
-    }
-  }
+  gemm_epilogue<T, TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * LDW), lane,
+                                   m0 + wm * (BM / WGM), n0 + wn * WN, split, g);
 }
 
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ C,
@@ -288,6 +161,18 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
     C[row * ldc + col] = s;
   }
 }
+
+}  // namespace
+
+dipaco_status launch_splitk_reduce(const float* partial, float* C, int M, int N, long ldc, int splits, hipStream_t s) {
+  const size_t total = (size_t)M * N;
+  const int rb = (int)std::min<size_t>((total + 255) / 256, 256 * 32);
+  splitk_reduce_kernel<<<rb, 256, 0, s>>>(partial, C, M, N, ldc, splits);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+namespace {
 
 template <typename T, typename TC, bool TA, bool TB, int BM, int BN, int WGM, int WGN, int NS>
 dipaco_status run(const GemmArgs& a, hipStream_t s) {
@@ -319,12 +204,7 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   if (blocks > 0x7fffffffL) return fail(DIPACO_ESHAPE, "gemm: too many tiles");
   kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
   DIPACO_LAUNCH_CHECK();
-  if (g.splits > 1) {
-    size_t total = (size_t)a.M * a.N;
-    int rb = (int)std::min<size_t>((total + 255) / 256, 256 * 32);
-    splitk_reduce_kernel<<<rb, 256, 0, s>>>(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits);
-    DIPACO_LAUNCH_CHECK();
-  }
+  if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
   return DIPACO_OK;
 }
 
@@ -333,7 +213,7 @@ int g_forced_tile = 0;
 // Measured on the training step's shapes: the eight-wave 256 x 256 tile is the fastest wherever its workgroups
 // can fill most of the chip's 256 compute units; below that the 128 x 128 tile (two workgroups per unit) wins.
 int pick_tile(int M, int N, int K, int splits) {
-  if (g_forced_tile) return g_forced_tile;
+  if (g_forced_tile && g_forced_tile != 5) return g_forced_tile;
   const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256) * (splits < 1 ? 1 : splits);
   return (K >= 256 && t256 >= 160) ? 4 : 1;
 }
@@ -377,7 +257,7 @@ static int splits_tile128(int M, int N, int smax) {
 
 int gemm_plan_splits(int M, int N, int K) {
   const int smax = (int)std::min<long>(16, std::max(1, K / 256));
-  if (g_forced_tile == 0 || g_forced_tile == 4) {
+  if (g_forced_tile == 0 || g_forced_tile >= 4) {
     const int s = splits_tile256(M, N, K, smax);
     if (s) return s;
   }
@@ -405,6 +285,11 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s
     return fail(DIPACO_EALIGN, "gemm: operand not 16-byte aligned");
   if (a.splits > 1 && (!a.out_f32 || a.bias || a.resid || a.act || !a.partial))
     return fail(DIPACO_EINVAL, "gemm: split-K needs fp32 output, a partial buffer and no epilogue");
+  if constexpr (std::is_same<T, bf16>::value) {
+    // bf16 products that fill the chip with 256 x 256 tiles go to the direct-to-LDS kernel when their shape allows
+    const bool big = pick_tile(a.M, a.N, a.K, a.splits) == 4;
+    if ((g_forced_tile == 5 || (g_forced_tile == 0 && big)) && gemm_dlds_eligible(a)) return launch_gemm_dlds(a, s);
+  }
   if (a.out_f32) {
     if (a.trans_a && !a.trans_b) return run_tiled<T, float, true, false>(a, s);
     return fail(DIPACO_EUNSUPPORTED, "gemm: fp32 output only for A^T.B");

@@ -1,0 +1,152 @@
+// Pieces shared by the matrix-core GEMM kernels: the kernel argument block, the workgroup -> tile mapping and
+// the epilogue that turns a wave's accumulators into 16-byte row-contiguous stores.
+#pragma once
+#include "common.h"
+#include "mma_tile.h"
+
+namespace dipaco {
+
+struct GemmDev {
+  const void* A; const void* B; void* C;
+  int M, N, K;
+  long lda, ldb, ldc;
+  const void* bias; const void* resid; void* aux_out; const void* aux_in;
+  int act;
+  int splits;
+  int k_per_split;   // multiple of BK
+  float* partial;
+  int tiles_m, tiles_n;
+};
+
+constexpr int N_XCD = 8;
+
+template <typename T> struct OutVec;   // 8 consecutive output elements
+template <> struct OutVec<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct OutVec<bf16> {
+  static __device__ __forceinline__ void load(const bf16* p, float (&v)[8]) { load_vec16<bf16>(p, v); }
+  static __device__ __forceinline__ void store(bf16* p, const float (&v)[8]) { store_vec16<bf16>(p, v); }
+};
+
+
+// Workgroup ids are dealt to the 8 XCDs round-robin and every XCD owns a private L2: XCD x gets the contiguous
+// range of tile ids [x * per, ...), walked in groups of 8 tile rows that share their B panels.
+__device__ __forceinline__ void gemm_tile_of_block(const GemmDev& g, int bid, int& split, int& tile_m, int& tile_n) {
+  const int tiles = g.tiles_m * g.tiles_n;
+  split = bid / tiles;
+  bid -= split * tiles;
+  {
+    const int per = tiles / N_XCD, rem = tiles % N_XCD;
+    const int x = bid % N_XCD, i = bid / N_XCD;
+    bid = x * per + min(x, rem) + i;
+  }
+  const int group = 8;
+  const int per_group = group * g.tiles_n;
+  const int gidx = bid / per_group;
+  const int first_m = gidx * group;
+  const int gsize = min(group, g.tiles_m - first_m);
+  const int in_group = bid - gidx * per_group;
+  tile_m = first_m + in_group % gsize;
+  tile_n = in_group / gsize;
+}
+
+// Epilogue of one wave: its TM x TN accumulator tiles (32 x 32 each, rows from row0, columns from col0) go
+// through stg, a wave-private LDS region of 32 x (WN + 4) floats, 32 rows at a time, so that bias / GELU /
+// residual are applied on, and C is written with, 16-byte row-contiguous accesses.
+template <typename T, typename TC, int TM, int TN, int WN>
+__device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0, int col0,
+                                              int split, const GemmDev& g) {
+  constexpr int LDW = WN + 4;
+  const int col_l = lane & 31;
+  constexpr int GROUPS = WN / 8;                 // 8-column groups per row
+  constexpr int ITERS = 32 * GROUPS / WAVE;
+  const T* bias = static_cast<const T*>(g.bias);
+  const T* resid = static_cast<const T*>(g.resid);
+  const T* aux_in = static_cast<const T*>(g.aux_in);
+  T* aux_out = static_cast<T*>(g.aux_out);
+  const bool to_partial = g.splits > 1;
+  float* P = to_partial ? g.partial + (size_t)split * g.M * g.N : nullptr;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int item = lane + WAVE * it;
+      const int rr = item / GROUPS, cg = item % GROUPS;
+      const int row = row0 + 32 * i + rr;
+      const int col = col0 + 8 * cg;
+      const float4 lo = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg);
+      const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
+      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      if (row >= g.M || col >= g.N) continue;
+      const bool full = col + 8 <= g.N;
+      if (to_partial) {
+        float* dst = P + (size_t)row * g.N + col;
+        if (full && (g.N & 3) == 0) OutVec<float>::store(dst, v);
+        else {
+#pragma unroll
+          for (int c = 0; c < 8; ++c)
+            if (col + c < g.N) dst[c] = v[c];
+        }
+        continue;
+      }
+      const size_t off = (size_t)row * g.ldc + col;
+      if (full) {
+        if (bias) {
+          float b[8];
+          OutVec<T>::load(bias + col, b);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] += b[c];
+        }
+        if (g.act == 1) {
+          // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
+          OutVec<T>::store(aux_out + off, v);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] = gelu_f(to_f32(from_f32<T>(v[c])));
+        } else if (g.act == 2) {
+          float u[8];
+          OutVec<T>::load(aux_in + off, u);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_f(u[c]);
+        }
+        if (resid) {
+          float rv[8];
+          OutVec<T>::load(resid + off, rv);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] += rv[c];
+        }
+        OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          if (col + c >= g.N) break;
+          float x = v[c] + (bias ? to_f32(bias[col + c]) : 0.f);
+          if (g.act == 1) {
+            const T pre = from_f32<T>(x);
+            aux_out[off + c] = pre;
+            x = gelu_f(to_f32(pre));
+          } else if (g.act == 2) {
+            x *= gelu_grad_f(to_f32(aux_in[off + c]));
+          }
+          if (resid) x += to_f32(resid[off + c]);
+          static_cast<TC*>(g.C)[off + c] = from_f32<TC>(x);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace dipaco

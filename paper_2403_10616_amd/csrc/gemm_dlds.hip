@@ -1,0 +1,263 @@
+// bf16 matrix-core GEMM whose operand tiles go from global memory straight into LDS (gfx950's 16-byte
+// global_load_lds), for all three operand layouts of the path step.
+//
+// Tile 256 x 256, K tile 32, a ring of 4 LDS stages of 32 KB (A tile | B tile).  One wave-level load writes 1024
+// consecutive LDS bytes (lane l writes bytes [16 l, 16 l + 16)), so the LDS layout is linear in the lane and
+// every permutation is applied on the global side, by choosing which 16 bytes a lane fetches:
+//   * operand contiguous along K ([rows, K] in memory): tile row r is 64 bytes = 4 chunks; chunk c sits at chunk
+//     position c ^ ((r >> 2) & 3).  A fragment of v_mfma_f32_32x32x16_bf16 (lane l: row l%32, K half l/32) is one
+//     ds_read_b128, free of bank conflicts for the lane groups the LDS serves together.
+//   * operand contiguous along its rows ([K, rows] in memory: the forward weights, both operands of a weight
+//     gradient): tile K-row t is 512 bytes = 8 segments of 32 rows; segment s sits at segment position
+//     s ^ (t & 3).  Fragments are read with ds_read_b64_tr_b16, which transposes 4 x 4 halfword blocks across
+//     each group of 16 lanes: when lane 4e+q of a group points at rows 4q..4q+3 of K-row T(e), lane i receives
+//     row i of K-rows T(0..3).  Two such reads (K-rows 8h+0..3 and 8h+4..7 of the 16-deep step) build the same
+//     8-deep fragment a K-contiguous operand gives, so any mix of the two kinds multiplies correctly.
+// No operand passes through registers on its way to LDS, which leaves room for the 256 x 256 accumulator at two
+// waves per SIMD and lets loads run three K tiles ahead.
+//
+// Pipeline of one K tile (one barrier): [fragments of the tile's second half are read under the MFMAs of its
+// first half] -> own loads of the next tile have landed (s_waitcnt vmcnt) -> barrier (everybody's have, and
+// everybody is done reading this stage) -> [this stage is refilled with the tile four ahead and the next tile's
+// first fragments are read, both under the MFMAs of the second half].  The loads are inline assembly: written
+// with the builtin, the compiler puts a full vmcnt(0) in front of every later LDS read, which serialises the ring.
+#include <type_traits>
+
+#include "gemm_common.h"
+#include "kernels.h"
+
+namespace dipaco {
+
+namespace {
+
+constexpr int DL_BM = 256, DL_BN = 256, DL_BK = 32, DL_STAGES = 4;
+constexpr int DL_ROWB = DL_BK * 2;                          // bytes of a K-contiguous tile row
+constexpr int DL_TILE = DL_BM * DL_ROWB;                    // 16 KB per operand tile (either kind)
+constexpr int DL_STAGE = 2 * DL_TILE;
+constexpr int DL_KROW = 512;                                // bytes of a K-row of a row-contiguous tile
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+
+__device__ __forceinline__ void load16_to_lds(const bf16* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only: expcnt and lgkmcnt fields at maximum
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// A_KC: A is [M, K] (contiguous along K), else [K, M].  B_KC: B is [N, K], else [K, N].
+template <typename TC, bool A_KC, bool B_KC, int WGM, int WGN>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev g) {
+  constexpr int NW = WGM * WGN;
+  constexpr int LPS = 2 * DL_TILE / 1024 / NW;              // wave-level loads per wave and stage
+  constexpr int TM = DL_BM / (32 * WGM), TN = DL_BN / (32 * WGN);
+  constexpr int WN = DL_BN / WGN;
+  constexpr int NM = TM * TN, NR = TM + TN;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  int split, tile_m, tile_n;
+  gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
+  const int m0 = tile_m * DL_BM, n0 = tile_n * DL_BN;
+  const int k_begin = split * g.k_per_split;
+  const int k_end = min(g.K, k_begin + g.k_per_split);
+  const int nkt = (k_end - k_begin) / DL_BK;
+
+  // ---- loads: wave-level load j fills LDS bytes [1024 j, 1024 j + 1024) of a stage; j < 16: A tile, else B tile.
+  // Rows (columns) beyond the operand re-read its last ones: they only feed outputs that are never stored.
+  const bf16* gp[LPS];
+  long gstep[LPS];
+  uint32_t ldst[LPS];
+  const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+#pragma unroll
+  for (int i = 0; i < LPS; ++i) {
+    const int j = wave + NW * i;
+    const bool is_a = j < 16;
+    const int jj = is_a ? j : j - 16;
+    const bf16* base = static_cast<const bf16*>(is_a ? g.A : g.B);
+    const long ld = is_a ? g.lda : g.ldb;
+    const int r0 = is_a ? m0 : n0, rtot = is_a ? g.M : g.N;
+    if (is_a ? A_KC : B_KC) {
+      const int row = min(r0 + 16 * jj + (lane >> 2), rtot - 1);
+      const int chunk = (lane & 3) ^ ((lane >> 4) & 3);
+      gp[i] = base + (long)row * ld + k_begin + chunk * 8;
+      gstep[i] = DL_BK;
+    } else {
+      const int t = 2 * jj + (lane >> 5);
+      const int cp = lane & 31;
+      const int seg = (cp >> 2) ^ (t & 3);
+      const int col = min(r0 + (seg * 4 + (cp & 3)) * 8, rtot - 8);
+      gp[i] = base + (long)(k_begin + t) * ld + col;
+      gstep[i] = (long)DL_BK * ld;
+    }
+    ldst[i] = smem_base + j * 1024;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // ---- fragment addresses ----
+  const int r = lane & 31, h = lane >> 5;
+  const int sw = (r >> 2) & 3;
+  const int foff[2] = {r * DL_ROWB + ((0 + h) ^ sw) * 16, r * DL_ROWB + ((2 + h) ^ sw) * 16};
+  const int g4 = lane >> 4, ep = (lane & 15) >> 2, qp = lane & 3;
+  int toffa[TM], toffb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+    toffa[i] = (8 * (g4 >> 1) + ep) * DL_KROW + (((wm * (DL_BM / WGM) / 32 + i) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    toffb[j] = (8 * (g4 >> 1) + ep) * DL_KROW + (((wn * (DL_BN / WGN) / 32 + j) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+  const char* a_base = smem + (A_KC ? wm * (DL_BM / WGM) * DL_ROWB : 0);
+  const char* b_base = smem + DL_TILE + (B_KC ? wn * (DL_BN / WGN) * DL_ROWB : 0);
+  uint4 fa[2][TM], fb[2][TN];
+  auto tr_read = [&](const char* p) {
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)p);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)(p + 4 * DL_KROW));
+    uint4 o;
+    o.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+    o.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+    o.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+    o.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+    return o;
+  };
+  auto read_frag = [&](int set, int q, const char* as, const char* bs, int ks) {   // q-th of the NR fragments
+    if (q < TM) {
+      if (A_KC) fa[set][q] = *reinterpret_cast<const uint4*>(as + q * 32 * DL_ROWB + foff[ks]);
+      else fa[set][q] = tr_read(as + toffa[q] + ks * 16 * DL_KROW);
+    } else {
+      if (B_KC) fb[set][q - TM] = *reinterpret_cast<const uint4*>(bs + (q - TM) * 32 * DL_ROWB + foff[ks]);
+      else fb[set][q - TM] = tr_read(bs + toffb[q - TM] + ks * 16 * DL_KROW);
+    }
+  };
+  auto mfma = [&](int set, int m) {
+    const int i = m / TN, j = m % TN;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[set][i]),
+                                                        __builtin_bit_cast(bf16x8, fb[set][j]), acc[i][j], 0, 0, 0);
+  };
+  // own loads of every tile but the n newest have landed
+  auto wait_newer = [&](int n) {
+    if (n >= 3) wait_vmcnt<3 * LPS>();
+    else if (n == 2) wait_vmcnt<2 * LPS>();
+    else if (n == 1) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+  };
+  static_assert(DL_STAGES == 4, "wait_newer and the steady-state count below assume a ring of four");
+
+  // prologue: tiles 0..3 into stages 0..3
+#pragma unroll
+  for (int s = 0; s < DL_STAGES; ++s)
+    if (s < nkt) {
+#pragma unroll
+      for (int i = 0; i < LPS; ++i) load16_to_lds(gp[i] + s * gstep[i], ldst[i] + s * DL_STAGE);
+    }
+  wait_newer(min(nkt, DL_STAGES) - 1);
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < NR; ++q) read_frag(0, q, a_base, b_base, 0);
+
+  // One K tile.  FULL: tile kt + 4 exists (steady state: no conditions).
+  auto step = [&](auto FULL, int kt, int stage) {
+    constexpr bool full = decltype(FULL)::value;
+    const char* as = a_base + stage * DL_STAGE;
+    const char* bs = b_base + stage * DL_STAGE;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      if ((m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(1, (m * NR) / NM, as, bs, 1);
+      mfma(0, m);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (full) wait_vmcnt<2 * LPS>();
+    else wait_newer(max(nkt - 2 - kt, 0));
+    __syncthreads();
+    const int nst = stage + 1 == DL_STAGES ? 0 : stage + 1;
+    const char* as2 = a_base + nst * DL_STAGE;
+    const char* bs2 = b_base + nst * DL_STAGE;
+    const bool have_next = full || kt + 1 < nkt;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      if (full && (m * LPS) % NM < LPS && (m * LPS) / NM < LPS) {
+        const int q = (m * LPS) / NM;
+        load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+      }
+      if (have_next && (m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(0, (m * NR) / NM, as2, bs2, 0);
+      mfma(1, m);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  int stage = 0, kt = 0;
+  for (; kt + DL_STAGES < nkt; ++kt) {
+    step(std::true_type{}, kt, stage);
+    stage = stage + 1 == DL_STAGES ? 0 : stage + 1;
+  }
+  for (; kt < nkt; ++kt) {
+    step(std::false_type{}, kt, stage);
+    stage = stage + 1 == DL_STAGES ? 0 : stage + 1;
+  }
+
+  // every load has landed (the last steps waited for vmcnt 0); all waves are done with the ring before it is reused
+  wait_vmcnt<0>();
+  __syncthreads();
+  gemm_epilogue<bf16, TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4)), lane,
+                                      m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
+}
+
+template <typename TC, bool A_KC, bool B_KC>
+dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
+  constexpr int WGM = 2, WGN = 4;
+  constexpr size_t smem = (size_t)DL_STAGES * DL_STAGE;
+  static_assert((size_t)WGM * WGN * 32 * (DL_BN / WGN + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
+  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, WGM, WGN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)smem));
+    attr_set = true;
+  }
+  GemmDev g;
+  g.A = a.A; g.B = a.B; g.C = a.C; g.M = a.M; g.N = a.N; g.K = a.K;
+  g.lda = a.lda; g.ldb = a.ldb; g.ldc = a.ldc;
+  g.bias = a.bias; g.resid = a.resid; g.aux_out = a.aux_out; g.aux_in = a.aux_in; g.act = a.act;
+  g.partial = a.partial;
+  g.tiles_m = (a.M + DL_BM - 1) / DL_BM;
+  g.tiles_n = (a.N + DL_BN - 1) / DL_BN;
+  const int ktiles = a.K / DL_BK;
+  int splits = a.splits < 1 ? 1 : a.splits;
+  if (splits > ktiles) splits = ktiles;
+  g.k_per_split = ((ktiles + splits - 1) / splits) * DL_BK;
+  g.splits = (a.K + g.k_per_split - 1) / g.k_per_split;
+  const long blocks = (long)g.tiles_m * g.tiles_n * g.splits;
+  if (blocks > 0x7fffffffL) return fail(DIPACO_ESHAPE, "gemm: too many tiles");
+  kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
+  DIPACO_LAUNCH_CHECK();
+  if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
+  return DIPACO_OK;
+}
+
+}  // namespace
+
+// The shapes this kernel takes: whole K tiles of 32, 16-byte rows, and at least 8 rows (columns) where the
+// operand is read along them.
+bool gemm_dlds_eligible(const GemmArgs& a) {
+  if (a.K < DL_BK || a.K % DL_BK || a.lda % 8 || a.ldb % 8) return false;
+  if (a.trans_a && (a.M % 8 || a.M < 8)) return false;
+  if (!a.trans_b && (a.N % 8 || a.N < 8)) return false;
+  if (a.out_f32 ? !(a.trans_a && !a.trans_b) : a.trans_a) return false;
+  return true;
+}
+
+dipaco_status launch_gemm_dlds(const GemmArgs& a, hipStream_t s) {
+  if (!gemm_dlds_eligible(a)) return fail(DIPACO_EUNSUPPORTED, "gemm: shape not supported by the direct-to-LDS kernel");
+  if (a.out_f32) return run_dlds<float, false, false>(a, s);
+  if (!a.trans_b) return run_dlds<bf16, true, false>(a, s);
+  return run_dlds<bf16, true, true>(a, s);
+}
+
+}  // namespace dipaco

@@ -48,7 +48,14 @@ struct GemmArgs {
   float* partial;
 };
 template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s);
-// 0 = automatic; 1 = 128x128, 2 = 256x128, 3 = 256x256 workgroup tiles (tuning and tests)
+// gemm_dlds.hip: bf16, 256x256 tiles loaded from global memory straight into LDS; takes the shapes for which
+// gemm_dlds_eligible holds (whole K tiles of 32, 16-byte rows); launch_gemm routes to it by itself
+bool gemm_dlds_eligible(const GemmArgs& g);
+dipaco_status launch_gemm_dlds(const GemmArgs& g, hipStream_t s);
+// C[m, n] = sum over z < splits of partial[z, m, n], in index order
+dipaco_status launch_splitk_reduce(const float* partial, float* C, int M, int N, long ldc, int splits, hipStream_t s);
+// 0 = automatic; 1 = 128x128, 2 = 256x128, 3 / 4 = 256x256 workgroup tiles with four / eight waves, 5 = the
+// direct-to-LDS kernel wherever the shape allows (tuning and tests)
 void set_gemm_tile(int t);
 int gemm_plan_splits(int M, int N, int K);   // split count the weight-gradient products are launched with
 int gemm_max_splits(int M, int N, int K);    // its upper bound over tile settings (workspace sizing)

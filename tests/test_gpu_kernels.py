@@ -22,7 +22,7 @@ def _rand(shape, seed, dtype):
     return t.to(DEV), t.to(torch.float64).numpy()
 
 
-@pytest.fixture(params=[0, 1, 2, 3, 4], ids=lambda t: f"tile{t}")
+@pytest.fixture(params=[0, 1, 2, 3, 4, 5], ids=lambda t: f"tile{t}")
 def gemm_tile(request):
     """Every workgroup tile shape must reach the same parity; 0 is the library's own choice."""
     dp.dipaco_k_set_gemm_tile(request.param)
@@ -31,7 +31,8 @@ def gemm_tile(request):
 
 
 # (M, N, K): several tiles with ragged tails in every direction; K not a multiple of the K tile
-GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (1, 8, 8), (300, 264, 520), (64, 512, 1000)]
+GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (1, 8, 8), (300, 264, 520), (64, 512, 1000), (520, 776, 160),
+               (257, 8, 32)]
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
@@ -82,7 +83,7 @@ def test_gemm_input_gradient_layout(dtype, M, N, K, gemm_tile):
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("M,N,K,splits", [(128, 128, 64, 1), (200, 136, 77, 1), (72, 264, 1000, 4), (8, 8, 5, 1),
-                                          (136, 64, 4099, 16)])
+                                          (136, 64, 4099, 16), (264, 520, 1024, 5), (8, 776, 96, 1)])
 def test_gemm_weight_gradient_layout_and_split_k(dtype, M, N, K, splits, gemm_tile):
     print(f"gemm dW tile={gemm_tile} dtype={dtype} M={M} N={N} K={K} splits={splits}", flush=True)
     At, Atr = _rand((K, M), 8, dtype)          # A stored [K, M]: contraction over rows (tokens)
