@@ -65,6 +65,37 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
   return cdf + u * pdf;
 }
 
+// The same two functions for kernels whose result is rounded to bf16.  erf comes from the rational approximation
+// 7.1.26 of Abramowitz & Stegun, erfc(z) = (a1 t + ... + a5 t^5) exp(-z^2), t = 1 / (1 + p z), z >= 0, whose
+// absolute error is below 1.5e-7 (fp32 rounding of a value near 1, 1/10000 of a bf16 rounding step); it costs one
+// reciprocal and one exponential, and the exponential exp(-u^2 / 2) is the one the derivative's density term needs.
+// The lower tail is formed as 0.5 erfc(z) directly, without cancellation.
+__device__ __forceinline__ void normal_cdf_fast(float u, float& cdf, float& gauss) {
+  const float z = fabsf(u) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+  float poly = __builtin_fmaf(t, 1.061405429f, -1.453152027f);
+  poly = __builtin_fmaf(poly, t, 1.421413741f);
+  poly = __builtin_fmaf(poly, t, -0.284496736f);
+  poly = __builtin_fmaf(poly, t, 0.254829592f);
+  gauss = __builtin_amdgcn_exp2f(z * z * -1.4426950408889634f);   // exp(-u^2 / 2)
+  const float q = 0.5f * poly * t * gauss;                        // 0.5 erfc(|u| / sqrt 2)
+  cdf = u >= 0.f ? 1.0f - q : q;
+}
+template <typename T> __device__ __forceinline__ float gelu_t(float u);
+template <> __device__ __forceinline__ float gelu_t<float>(float u) { return gelu_f(u); }
+template <> __device__ __forceinline__ float gelu_t<bf16>(float u) {
+  float cdf, gauss;
+  normal_cdf_fast(u, cdf, gauss);
+  return u * cdf;
+}
+template <typename T> __device__ __forceinline__ float gelu_grad_t(float u);
+template <> __device__ __forceinline__ float gelu_grad_t<float>(float u) { return gelu_grad_f(u); }
+template <> __device__ __forceinline__ float gelu_grad_t<bf16>(float u) {
+  float cdf, gauss;
+  normal_cdf_fast(u, cdf, gauss);
+  return __builtin_fmaf(u * 0.39894228040143268f, gauss, cdf);
+}
+
 // ---- wave / block reductions -----------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -115,12 +115,12 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
           // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
           OutVec<T>::store(aux_out + off, v);
 #pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] = gelu_f(to_f32(from_f32<T>(v[c])));
+          for (int c = 0; c < 8; ++c) v[c] = gelu_t<T>(to_f32(from_f32<T>(v[c])));
         } else if (g.act == 2) {
           float u[8];
           OutVec<T>::load(aux_in + off, u);
 #pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_f(u[c]);
+          for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_t<T>(u[c]);
         }
         if (resid) {
           float rv[8];
@@ -137,9 +137,9 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
           if (g.act == 1) {
             const T pre = from_f32<T>(x);
             aux_out[off + c] = pre;
-            x = gelu_f(to_f32(pre));
+            x = gelu_t<T>(to_f32(pre));
           } else if (g.act == 2) {
-            x *= gelu_grad_f(to_f32(aux_in[off + c]));
+            x *= gelu_grad_t<T>(to_f32(aux_in[off + c]));
           }
           if (resid) x += to_f32(resid[off + c]);
           static_cast<TC*>(g.C)[off + c] = from_f32<TC>(x);

@@ -57,10 +57,15 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WGN, wn = wave % WGN;
+  // Waves w and w + 4 share a SIMD.  They are given different halves of the tile's rows AND of its columns, so
+  // that in a tile that sticks out of C by half (896 = 3.5 x 256 is the path's width) every SIMD keeps exactly
+  // one wave with work, which then has the matrix core to itself: such a tile costs half a tile.
+  static_assert(WGM == 2 && WGN == 4, "wave placement below is written for 2 x 4 waves");
+  const int wm = (wave & 1) ^ (wave >> 2), wn = 2 * (wave >> 2) + ((wave >> 1) & 1);
   int split, tile_m, tile_n;
   gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
   const int m0 = tile_m * DL_BM, n0 = tile_n * DL_BN;
+  const bool active = m0 + wm * (DL_BM / WGM) < g.M && n0 + wn * (DL_BN / WGN) < g.N;   // wave-uniform
   const int k_begin = split * g.k_per_split;
   const int k_end = min(g.K, k_begin + g.k_per_split);
   const int nkt = (k_end - k_begin) / DL_BK;
@@ -160,19 +165,23 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
     }
   wait_newer(min(nkt, DL_STAGES) - 1);
   __syncthreads();
+  if (active) {
 #pragma unroll
-  for (int q = 0; q < NR; ++q) read_frag(0, q, a_base, b_base, 0);
+    for (int q = 0; q < NR; ++q) read_frag(0, q, a_base, b_base, 0);
+  }
 
   // One K tile.  FULL: tile kt + 4 exists (steady state: no conditions).
   auto step = [&](auto FULL, int kt, int stage) {
     constexpr bool full = decltype(FULL)::value;
     const char* as = a_base + stage * DL_STAGE;
     const char* bs = b_base + stage * DL_STAGE;
+    if (active) {
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      if ((m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(1, (m * NR) / NM, as, bs, 1);
-      mfma(0, m);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int m = 0; m < NM; ++m) {
+        if ((m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(1, (m * NR) / NM, as, bs, 1);
+        mfma(0, m);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     if (full) wait_vmcnt<2 * LPS>();
     else wait_newer(max(nkt - 2 - kt, 0));
@@ -181,15 +190,20 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
     const char* as2 = a_base + nst * DL_STAGE;
     const char* bs2 = b_base + nst * DL_STAGE;
     const bool have_next = full || kt + 1 < nkt;
+    if (active) {
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      if (full && (m * LPS) % NM < LPS && (m * LPS) / NM < LPS) {
-        const int q = (m * LPS) / NM;
-        load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+      for (int m = 0; m < NM; ++m) {
+        if (full && (m * LPS) % NM < LPS && (m * LPS) / NM < LPS) {
+          const int q = (m * LPS) / NM;
+          load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+        }
+        if (have_next && (m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(0, (m * NR) / NM, as2, bs2, 0);
+        mfma(1, m);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      if (have_next && (m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(0, (m * NR) / NM, as2, bs2, 0);
-      mfma(1, m);
-      __builtin_amdgcn_sched_barrier(0);
+    } else if (full) {   // a wave without output still loads its share of the tiles
+#pragma unroll
+      for (int q = 0; q < LPS; ++q) load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
     }
   };
   int stage = 0, kt = 0;
@@ -205,7 +219,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
   // every load has landed (the last steps waited for vmcnt 0); all waves are done with the ring before it is reused
   wait_vmcnt<0>();
   __syncthreads();
-  gemm_epilogue<bf16, TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4)), lane,
+  if (active) gemm_epilogue<bf16, TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4)), lane,
                                       m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
 }
 
