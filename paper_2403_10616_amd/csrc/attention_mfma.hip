@@ -126,7 +126,7 @@ __device__ __forceinline__ void store_transposed_out(bf16* row_ptr, const f32x16
 }
 
 // ---- forward ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(AT_THREADS) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+__global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                             float* __restrict__ lse, int S, int H) {
   __shared__ __attribute__((aligned(16))) char smem[2][2][TILE_BYTES];   // [stage][K rows | V^T]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
@@ -229,7 +229,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_fwd_mfma(const bf16* __restri
 }
 
 // ---- backward, dQ (also writes D = rowsum(dO * O)) --------------------------------------------------------------
-__global__ void __launch_bounds__(AT_THREADS) attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+__global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                                const bf16* __restrict__ d_o,
                                                                const float* __restrict__ lse, bf16* __restrict__ dqkv,
                                                                float* __restrict__ dsum, int S, int H) {
@@ -334,7 +334,7 @@ __global__ void __launch_bounds__(AT_THREADS) attn_bwd_dq_mfma(const bf16* __res
 // ---- backward, dK and dV ------------------------------------------------------------------------------------------
 constexpr int DKV_STAGE = 4 * TILE_BYTES + 2 * 64 * (int)sizeof(float);   // Q rows | Q^T | dO rows | dO^T | -lse2 | D
 
-__global__ void __launch_bounds__(AT_THREADS) attn_bwd_dkv_mfma(const bf16* __restrict__ qkv,
+__global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* __restrict__ qkv,
                                                                 const bf16* __restrict__ d_o,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ dsum,
