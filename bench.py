@@ -27,6 +27,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # MI355X fp32 MFMA
 PEAK_HBM_GBS = 8000.0
+# Bytes that crossed the L2 / memory-fabric boundary per launch of the forward-layout GEMM, averaged over the 49
+# launches of one config-2 step: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two runs), each scaled by what the same
+# counter reads for the plain copy kernel of known size in the same run (fetch x 2.0, write x 1.0).  The summary is
+# profiles/gemm_fwd_config2_traffic.txt; the algorithmic figure beside it is 366.3 MB per launch.
+FWD_GEMM_TRAFFIC_BYTES = 339.4e6 + 201.0e6
 
 
 def _events(torch):
@@ -110,16 +115,23 @@ def bench_path_step(args):
     final_loss = float(loss.item())
 
     # ---- roofline of the dominant kernel: the forward-layout bf16 GEMM (projections, MLP, vocabulary head) ----
+    # Its 49 launches of one step are replayed with the step's own epilogues (bias, GELU + saved pre-activation,
+    # residual) on scratch operands and timed with events on the stream they are launched on.
     fwd, dx, dw = step_gemm_shapes(cfg, B, S)
     T = B * S
     big = max(max(M * N for M, N, K in fwd), max(M * K for M, N, K in fwd))
     a_buf = torch.empty(big, dtype=torch.bfloat16, device=dev).normal_()
     b_buf = torch.empty(max(K * N for M, N, K in fwd), dtype=torch.bfloat16, device=dev).normal_(std=0.02)
     c_buf = torch.empty(big, dtype=torch.bfloat16, device=dev)
+    r_buf = torch.empty(T * cfg["d_mlp"], dtype=torch.bfloat16, device=dev).normal_()
+    u_buf = torch.empty(T * cfg["d_mlp"], dtype=torch.bfloat16, device=dev)
+    bias = torch.zeros(max(N for M, N, K in fwd), dtype=torch.bfloat16, device=dev)
+    epilogues = [dict(bias=bias), dict(bias=bias, resid=r_buf), dict(bias=bias, aux_out=u_buf, act=1),
+                 dict(bias=bias, resid=r_buf)] * n_layers + [dict()]
 
     def replay():
-        for (M, N, K) in fwd:
-            dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, a_buf, b_buf, c_buf)
+        for (M, N, K), ep in zip(fwd, epilogues):
+            dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, a_buf, b_buf, c_buf, **ep)
     replay()
     torch.cuda.synchronize()
     reps = max(1, min(args.steps, 5))
@@ -142,9 +154,10 @@ def bench_path_step(args):
                    "params": n, "tokens_per_step": B * S, "final_loss": final_loss,
                    "model_tflops_per_step": step_flops / 1e12,
                    "model_flops_utilisation": step_flops / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<bf16,bf16,A row-major,B row-major,128,128>",
+        "roofline": {"bound": "mfma", "kernel": "gemm_dlds_kernel<bf16 out, A [M,K], B [K,N]> (forward layout)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": None, "launches_per_step": len(fwd), "flops_per_launch": fwd_flops / len(fwd),
+                     "traffic": FWD_GEMM_TRAFFIC_BYTES, "traffic_unit": "bytes per launch (fetch + write)",
+                     "launches_per_step": len(fwd), "flops_per_launch": fwd_flops / len(fwd),
                      "avg_launch_us": gemm_ms * 1e3 / len(fwd)},
     }
     if not args.no_cpu_baseline:

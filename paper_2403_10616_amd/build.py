@@ -31,8 +31,19 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+def _up_to_date(src: str, obj: str) -> bool:
+    """DIPACO_INCREMENTAL=1 (development): keep an object newer than its source, every header and this file."""
+    if os.environ.get("DIPACO_INCREMENTAL") != "1" or not os.path.exists(obj):
+        return False
+    deps = [src, __file__] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    deps += [os.path.join(HERE, "..", "include", f) for f in os.listdir(os.path.join(HERE, "..", "include"))]
+    return os.path.getmtime(obj) > max(os.path.getmtime(d) for d in deps)
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+    if _up_to_date(src, obj):
+        return obj
     cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(os.path.basename(src), []), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -261,13 +261,25 @@ __device__ __forceinline__ float block_reduce(float v, float* red, bool is_max) 
 }
 
 // one workgroup per row of logits
-template <typename T>
-__global__ void __launch_bounds__(ROW_THREADS) softmax_xent_kernel(T* __restrict__ logits,
-                                                                   const int* __restrict__ targets,
-                                                                   const int* __restrict__ n_valid,
-                                                                   float* __restrict__ nll, int V) {
+// One workgroup per row.  NV > 0: XENT_THREADS threads keep the whole row in registers (NV 16-byte vectors each,
+// V <= NV * XENT_THREADS * 16 / sizeof(T)), so the logits cross the memory interface once in each direction.
+// NV == 0: any V, three passes over memory.
+constexpr int XENT_THREADS = 1024;
+// exp for the softmax: logits held in bf16 carry 8 significant bits, so the hardware base-2 exponential (relative
+// error about 1e-6 over the range used here) is exact enough; fp32 runs keep the library routine
+template <typename T> __device__ __forceinline__ float softmax_exp(float x);
+template <> __device__ __forceinline__ float softmax_exp<float>(float x) { return expf(x); }
+template <> __device__ __forceinline__ float softmax_exp<bf16>(float x) {
+  return __builtin_amdgcn_exp2f(x * 1.4426950408889634f);
+}
+template <typename T, int NV>
+__global__ void __launch_bounds__(NV > 0 ? XENT_THREADS : ROW_THREADS)
+softmax_xent_kernel(T* __restrict__ logits, const int* __restrict__ targets, const int* __restrict__ n_valid,
+                    float* __restrict__ nll, int V) {
   constexpr int VEC = Vec16<T>::N;
-  __shared__ float red[ROWS_PER_BLOCK];
+  constexpr int NTH = NV > 0 ? XENT_THREADS : ROW_THREADS;
+  constexpr int NKEEP = NV > 0 ? NV : 1;
+  __shared__ float red[NTH / WAVE];
   const int row = blockIdx.x;
   T* lr = logits + (size_t)row * V;
   const int tgt = targets[row];
@@ -275,42 +287,64 @@ __global__ void __launch_bounds__(ROW_THREADS) softmax_xent_kernel(T* __restrict
     float zero[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) zero[i] = 0.f;
-    for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) store_vec16(lr + c, zero);
+    for (int c = threadIdx.x * VEC; c < V; c += NTH * VEC) store_vec16(lr + c, zero);
     if (threadIdx.x == 0) nll[row] = 0.f;
     return;
   }
+  uint4 keep[NKEEP];
+  auto vec_at = [&](int k, int c, float (&v)[VEC]) {   // k-th vector of this thread, at column c
+    if (NV > 0) {
+      const T* e = reinterpret_cast<const T*>(&keep[k]);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) v[i] = to_f32(e[i]);
+    } else {
+      load_vec16(lr + c, v);
+    }
+  };
+  auto for_each_vec = [&](auto&& f) {   // f(k, c): this thread's k-th vector, at column c
+    if constexpr (NV > 0) {
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int c = (threadIdx.x + k * NTH) * VEC;
+        if (c < V) f(k, c);
+      }
+    } else {
+      for (int c = threadIdx.x * VEC; c < V; c += NTH * VEC) f(0, c);
+    }
+  };
   float mx = -INFINITY;
-  for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) {
+  if constexpr (NV > 0) for_each_vec([&](int k, int c) { keep[k] = *reinterpret_cast<const uint4*>(lr + c); });
+  for_each_vec([&](int k, int c) {
     float v[VEC];
-    load_vec16(lr + c, v);
+    vec_at(k, c, v);
 #pragma unroll
     for (int i = 0; i < VEC; ++i) mx = fmaxf(mx, v[i]);
-  }
+  });
   mx = block_reduce(mx, red, true);
   float se = 0.f;
-  for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) {
+  for_each_vec([&](int k, int c) {
     float v[VEC];
-    load_vec16(lr + c, v);
+    vec_at(k, c, v);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) se += expf(v[i] - mx);
-  }
+    for (int i = 0; i < VEC; ++i) se += softmax_exp<T>(v[i] - mx);
+  });
   se = block_reduce(se, red, false);
   const int t = tgt >= V ? V - 1 : tgt;
   if (threadIdx.x == 0) nll[row] = logf(se) - (to_f32(lr[t]) - mx);
   __syncthreads();   // lr[t] is read before anyone overwrites it
   const float inv = 1.0f / se;
   const float scale = 1.0f / (float)n_valid[0];
-  for (int c = threadIdx.x * VEC; c < V; c += ROW_THREADS * VEC) {
+  for_each_vec([&](int k, int c) {
     float v[VEC];
-    load_vec16(lr + c, v);
+    vec_at(k, c, v);
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
-      float p = expf(v[i] - mx) * inv;
+      float p = softmax_exp<T>(v[i] - mx) * inv;
       if (c + i == t) p -= 1.0f;
       v[i] = p * scale;
     }
     store_vec16(lr + c, v);
-  }
+  });
 }
 
 // loss = (sum of nll in a fixed tree order) / n_valid; one workgroup
@@ -535,7 +569,10 @@ dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStr
 template <typename T>
 dipaco_status launch_softmax_xent(T* logits, const int* targets, const int* n_valid, float* nll, int rows, int V,
                                   hipStream_t s) {
-  softmax_xent_kernel<T><<<rows, ROW_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+  const size_t vectors = ((size_t)V * sizeof(T) + 15) / 16;
+  if (vectors <= 4 * (size_t)XENT_THREADS) softmax_xent_kernel<T, 4><<<rows, XENT_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+  else if (vectors <= 8 * (size_t)XENT_THREADS) softmax_xent_kernel<T, 8><<<rows, XENT_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+  else softmax_xent_kernel<T, 0><<<rows, ROW_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
