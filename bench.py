@@ -319,7 +319,7 @@ def bench_attention(args):
     d_o = torch.empty(B * S * A, dtype=torch.bfloat16, device=dev).normal_()
     dqkv = torch.empty(B * S * 3 * A, dtype=torch.bfloat16, device=dev)
     lse = torch.empty(B * H * S, dtype=torch.float32, device=dev)
-    dsum = torch.empty(B * H * S, dtype=torch.float32, device=dev)
+    dsum = torch.empty(2 * B * H * ((S + 127) // 128 * 128), dtype=torch.float32, device=dev)
     dp.dipaco_k_attention_fwd(dp.BF16, qkv, o, lse, B, S, H, dh)
     bwd = getattr(args, "pass") == "bwd"
 

@@ -41,7 +41,8 @@ dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,
                                      int32_t H, int32_t dh, void* stream);
 
-/* Gradient of the above: d_o [B*S, H*dh] -> dqkv [B*S, 3*H*dh].  dsum: fp32 [B, H, S] scratch. */
+/* Gradient of the above: d_o [B*S, H*dh] -> dqkv [B*S, 3*H*dh].  dsum: fp32 scratch of 2 * B * H * S128 floats,
+ * S128 = S rounded up to a multiple of 128 (per-query statistics passed between the two backward kernels). */
 dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* d_o, const float* lse,
                                      void* dqkv, float* dsum, int32_t B, int32_t S, int32_t H, int32_t dh,
                                      void* stream);

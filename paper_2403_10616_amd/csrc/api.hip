@@ -87,7 +87,7 @@ static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   p.x_final = take(T * d * es); p.meanf = take(T * 4); p.rstdf = take(T * 4); p.y = take(T * d * es);
   p.logits = take(T * V * es); p.nll = take(T * 4); p.n_valid = take(256);
   p.dxa = take(T * d * es); p.dxb = take(T * d * es); p.dh = take(T * d * es); p.du = take(T * F * es);
-  p.dqkv = take(T * 3 * A * es); p.d_o = take(T * A * es); p.dsum = take((size_t)B * a.n_heads * S * 4);
+  p.dqkv = take(T * 3 * A * es); p.d_o = take(T * A * es); p.dsum = take(2 * (size_t)B * a.n_heads * ((S + 127) / 128 * 128) * 4);
   p.ln_partial = take(ln_bwd_partial_floats((int)T, (int)d) * 4);
   const size_t widest = std::max(std::max(F, 3 * A), d);
   p.cs_partial = take(colsum_partial_floats((int)T, (int)widest) * 4);

@@ -6,14 +6,24 @@
 // ROW index of the score tile:
 //   forward, dQ:   S^T = K.Q^T  (rows = keys, columns = queries)  ->  O^T += V^T.P^T,   dQ^T += K^T.dS^T
 //   dK, dV:        S   = Q.K^T  (rows = queries, columns = keys)  ->  dV^T += dO^T.P,   dK^T += Q^T.dS
-// and the left operands V^T, K^T, dO^T, Q^T are written to LDS transposed, with their 8-byte granules (four
-// consecutive contraction indices) placed in the order in which the accumulator holds them.  Softmax state
-// (running max, sum, log-sum-exp, D = rowsum(dO*O)) is per query: per lane in the first family, per accumulator
-// row in the second.  Exponentials are base 2 with log2(e) folded into the score scale.
+// Softmax state (running max, sum, log-sum-exp, D = rowsum(dO*O)) is per query: per lane in the first family, per
+// accumulator row in the second.  Exponentials are base 2 with log2(e) folded into the score scale.
 //
-// One workgroup = 4 waves, each wave owns 32 queries (or 32 keys); K/V (or Q/dO) tiles of 64 rows are staged
-// in LDS, double-buffered, loaded by 128 threads each as 4x8 blocks that are stored row-major and/or transposed
-// from the same registers.  No atomics: every output element has exactly one writer and a fixed summation order.
+// One workgroup = 4 waves, each wave owns 32 queries (or 32 keys).  K / V (or Q / dO) tiles of 64 rows x 64
+// columns go from global memory straight into LDS (16-byte global_load_lds: lane l of a wave-level load writes
+// LDS bytes [16 l, 16 l + 16), so the swizzle is applied by choosing which 16 bytes a lane fetches) into a ring
+// of stages that runs two or three tiles ahead of the arithmetic, one barrier per tile.  A tile is stored once,
+// row-major, and read in both orientations:
+//   * rows as the MFMA row index, contraction along the 64 columns: one ds_read_b128 per fragment;
+//   * columns as the MFMA row index, contraction along the tile's rows (the V^T, K^T, dO^T, Q^T operands):
+//     ds_read_b64_tr_b16, which transposes 4x4 halfword blocks across each group of 16 lanes.  Lane 4e+q of a
+//     group points at columns 4q..4q+3 of tile row T(e); lane i then receives column i of rows T(0..3).  The
+//     rows T are chosen in the order in which an accumulator holds them (4h + 0..3, then 8 + 4h + 0..3 of each
+//     group of 16), so that accumulator elements 8g..8g+7, packed to bf16, are the matching B operand.
+// Chunk c (16 bytes) of tile row r sits at chunk position c ^ swz(r), swz(r) = 4*bit1(r) + bits3:2(r): both kinds
+// of read are then free of bank conflicts (rows two apart land in different 64-byte groups for the transposing
+// read; the lane groups that a ds_read_b128 serves together see eight different swizzles per row parity).
+// No atomics: every output element has exactly one writer and a fixed summation order.
 #include "kernels.h"
 #include "mma_tile.h"
 
@@ -26,6 +36,9 @@ constexpr int DH = 64;
 constexpr int TILE_BYTES = 64 * TILE_ROW_BYTES;   // 64 rows x 128 B
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
 
 __device__ __forceinline__ f32x16 mfma16(const uint4& a, const uint4& b, const f32x16& c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -41,75 +54,115 @@ template <int E0> __device__ __forceinline__ uint4 pack8(const f32x16& v) {
   return __builtin_bit_cast(uint4, o);
 }
 
-// ---- 64 x 64 bf16 tile, loaded by 128 threads as 4 (rows) x 8 (columns) blocks -----------------------------
-struct SubBlock { uint4 r[4]; };
-// lane l of loader wave w2: 8-column block mq = (l&1) + 2*((l>>4)&3), 4-row block kq = ((l>>1)&7) + 8*w2.  A load
-// instruction reads 128 contiguous bytes of 8 rows; 16 consecutive lanes of a transposed 8-byte store write 8
-// row-granules of two LDS rows whose swizzles differ by 4 (no bank conflicts, see mma_tile.h).
-__device__ __forceinline__ void sb_coords(int t128, int& kq, int& mq) {
-  const int l = t128 & 63;
-  mq = (l & 1) + 2 * ((l >> 4) & 3);
-  kq = ((l >> 1) & 7) + 8 * (t128 >> 6);
+__device__ __forceinline__ int swz64(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+
+// ---- global memory -> LDS -----------------------------------------------------------------------------------
+__device__ __forceinline__ void load16_to_lds(const bf16* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
 }
-// src points at the tile's first row and column; rows at or beyond rows_valid (>= 1) re-read the last valid row:
-// callers give such rows zero weight (masked probabilities), so any finite value will do, and no branch
-// surrounds the loads
-__device__ __forceinline__ void sb_load(SubBlock& s, const bf16* __restrict__ src, long ld, int rows_valid, int t128) {
-  int kq, mq;
-  sb_coords(t128, kq, mq);
+__device__ __forceinline__ void load4_to_lds(const float* gptr, uint32_t lds_addr) {   // lane l writes bytes [4 l, 4 l + 4)
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only: expcnt and lgkmcnt fields at maximum
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+// This wave's loads of every stage but the n newest have landed; LPW = loads per wave and stage.  (The loads are
+// invisible to the compiler, so the count is kept by hand; loads the compiler issues itself only ever make these
+// waits longer, never shorter, because the counter is decremented in issue order.)
+template <int LPW> __device__ __forceinline__ void wait_stages_but(int n) {
+  if (n >= 3) wait_vmcnt<3 * LPW>();
+  else if (n == 2) wait_vmcnt<2 * LPW>();
+  else if (n == 1) wait_vmcnt<LPW>();
+  else wait_vmcnt<0>();
+}
+
+// This wave's share of the loads of a stage made of two 64x64 tiles: 4 of the 16 wave-level loads (each fills 8
+// tile rows = 1024 LDS bytes).  Load i of wave w is number j = w + 4i: tile j / 8, rows 8 (j % 8) .. + 7.
+struct StageLoader {
+  const bf16* col[4];   // per lane: tile source + the 16-byte chunk this lane fetches (row 0 of the operand)
+  int row[4];           // per lane: row inside the tile
+  uint32_t dst[4];      // wave-uniform: byte offset of the load inside the stage
+};
+__device__ __forceinline__ StageLoader make_loader(const bf16* tile0, const bf16* tile1, int wave, int lane) {
+  StageLoader L;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = min(4 * kq + j, rows_valid - 1);
-    s.r[j] = *reinterpret_cast<const uint4*>(src + (long)row * ld + 8 * mq);
+  for (int i = 0; i < 4; ++i) {
+    const int j = wave + 4 * i;
+    const int rit = 8 * (j & 7) + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz64(rit);
+    L.col[i] = (j < 8 ? tile0 : tile1) + chunk * 8;
+    L.row[i] = rit;
+    L.dst[i] = (uint32_t)((j >> 3) * TILE_BYTES + (j & 7) * 1024);
   }
+  return L;
 }
-// LDS tile[row][column]: operand whose contraction index is the column
-__device__ __forceinline__ void sb_store_rows(const SubBlock& s, char* tile, int t128) {
-  int kq, mq;
-  sb_coords(t128, kq, mq);
+// Rows at or beyond rows_total re-read the last valid row: callers give such rows zero weight (masked
+// probabilities, -inf statistics), so any finite value will do, and no branch surrounds the loads.
+__device__ __forceinline__ void issue_stage(const StageLoader& L, int row0, int rows_total, long ld0, long ld1, int wave,
+                                            uint32_t stage_addr) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4*>(tile_chunk(tile, 4 * kq + j, mq)) = s.r[j];
-}
-// LDS tile[column][row], rows (the contraction index) in accumulator order: the granule of rows 4*kq..4*kq+3,
-// kq = (t, g2, gh, h) in bits 3..0, goes to chunk (t, g2, h), half gh; a lane of half h then finds, in chunk
-// 4t + 2*g2 + h, the eight rows that accumulator elements 8*g2..8*g2+7 of score tile t hold.
-__device__ __forceinline__ void sb_store_transposed(const SubBlock& s, char* tile, int t128) {
-  int kq, mq;
-  sb_coords(t128, kq, mq);
-  const int chunk = ((kq >> 2) << 1) | (kq & 1);
-  const int half = (kq >> 1) & 1;
-  const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&s.r[0]);
-  const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&s.r[1]);
-  const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&s.r[2]);
-  const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&s.r[3]);
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    const int j = c >> 1;
-    uint2 out;
-    if ((c & 1) == 0) {
-      out.x = (w0[j] & 0xffffu) | (w1[j] << 16);
-      out.y = (w2[j] & 0xffffu) | (w3[j] << 16);
-    } else {
-      out.x = (w0[j] >> 16) | (w1[j] & 0xffff0000u);
-      out.y = (w2[j] >> 16) | (w3[j] & 0xffff0000u);
-    }
-    *reinterpret_cast<uint2*>(tile_chunk(tile, 8 * mq + c, chunk) + (half << 3)) = out;
+  for (int i = 0; i < 4; ++i) {
+    const int r = min(row0 + L.row[i], rows_total - 1);
+    const long ld = (wave + 4 * i) < 8 ? ld0 : ld1;
+    load16_to_lds(L.col[i] + (long)r * ld, stage_addr + L.dst[i]);
   }
 }
 
-// Byte offsets of this lane's fragments inside a 64-row tile.  Lane l reads row 32*t + r (r = l%32) and chunk
-// c ^ swz(row); swz does not depend on t (32*t >> 1 is a multiple of 8) and every chunk index used here is an even
-// number plus h = l/32, so chunk ^ swz = even ^ (h ^ swz(r)): four values per lane, b[k] for even = 2k.  A fragment
-// read is then tile + b[k] + 4096*t with t a compile-time constant: no address arithmetic in the loops.
+// ---- fragment reads -----------------------------------------------------------------------------------------
+// Row-index reads.  Lane l reads row 32*t + r (r = l%32), chunk (2*ks + h) ^ swz(row), h = l/32; swz does not
+// depend on t (it uses bits 1..3 of the row).  b[ks]: byte offset for t = 0; add 4096*t.
 struct FragOff { int b[4]; };
 __device__ __forceinline__ FragOff frag_offsets(int lane) {
-  const int r = lane & 31, u = (lane >> 5) ^ swz(r);
+  const int r = lane & 31, h = lane >> 5, s = swz64(r);
   FragOff f;
 #pragma unroll
-  for (int k = 0; k < 4; ++k) f.b[k] = r * TILE_ROW_BYTES + ((u ^ (2 * k)) << 4);
+  for (int ks = 0; ks < 4; ++ks) f.b[ks] = r * TILE_ROW_BYTES + (((2 * ks + h) ^ s) << 4);
   return f;
 }
 __device__ __forceinline__ uint4 ld16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// Column-index (transposing) reads.  For output columns 32*dt .. + 31 and the 16 tile rows 32*t + 16*g2 .. + 15,
+// read p (0 / 1) of lane l = 16*g4 + 4*e + q fetches columns 32*dt + 16*(g4 & 1) + 4q .. + 3 of tile row
+// 32*t + 16*g2 + 8p + 4*(g4 >> 1) + e, and the two reads together give the lane its column's values in tile rows
+// 4h + 0..3, 8 + 4h + 0..3 of the group (h = l/32): the order of accumulator elements 8*g2 .. 8*g2 + 7.
+// b[dt][p]: byte offset for t = g2 = 0; add (32*t + 16*g2) * 128.
+struct TrOff { int b[2][2]; };
+__device__ __forceinline__ TrOff tr_offsets(int lane) {
+  const int g4 = lane >> 4, e = (lane & 15) >> 2, q = lane & 3, h = g4 >> 1;
+  TrOff t;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int row = 8 * p + 4 * h + e;
+      const int chunk = (4 * dt + 2 * (g4 & 1) + (q >> 1)) ^ swz64(row);
+      t.b[dt][p] = row * TILE_ROW_BYTES + (chunk << 4) + ((q & 1) << 3);
+    }
+  return t;
+}
+__device__ __forceinline__ uint4 tr_read(const char* tile, const TrOff& to, int dt, int rows16) {
+  const char* base = tile + rows16 * 16 * TILE_ROW_BYTES;
+  const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)(base + to.b[dt][0]));
+  const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)(base + to.b[dt][1]));
+  uint4 o;
+  o.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+  o.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+  o.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+  o.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+  return o;
+}
+// acc^T[dt] += (tile^T)[columns 32 dt.., rows 32 t..] . src[t]   for a 64-row tile and two accumulator tiles src
+__device__ __forceinline__ void mma_transposed(f32x16 (&acc)[2], const char* tile, const TrOff& to, const f32x16 (&src)[2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint4 p0 = pack8<0>(src[t]), p1 = pack8<8>(src[t]);
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+      acc[dt] = mfma16(tr_read(tile, to, dt, 2 * t), p0, acc[dt]);
+      acc[dt] = mfma16(tr_read(tile, to, dt, 2 * t + 1), p1, acc[dt]);
+    }
+  }
+}
 
 // store 4 consecutive head columns (accumulator elements 4g..4g+3 of a transposed-output tile) as bf16
 __device__ __forceinline__ void store4(bf16* dst, const f32x16& v, int g, float scale) {
@@ -126,17 +179,32 @@ __device__ __forceinline__ void store_transposed_out(bf16* row_ptr, const f32x16
 }
 
 // ---- forward ---------------------------------------------------------------------------------------------------
+constexpr int FWD_STAGES = 2, DQ_STAGES = 2, DKV_STAGES = 2;
+
 __global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                            float* __restrict__ lse, int S, int H) {
-  __shared__ __attribute__((aligned(16))) char smem[2][2][TILE_BYTES];   // [stage][K rows | V^T]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;   // long blocks first
+                                                               float* __restrict__ lse, int S, int H) {
+  constexpr int NS = FWD_STAGES;
+  __shared__ __attribute__((aligned(16))) char smem[NS][2][TILE_BYTES];   // [stage][K | V]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / H, hd = bh % H;
   const int A = H * DH;
   const long ld = 3L * A;
   const bf16* base = qkv + (long)b * S * ld + hd * DH;
-  const int q0 = qb * 128, qw0 = q0 + 32 * wave, q = qw0 + r;
   const FragOff fo = frag_offsets(lane);
+  const TrOff to = tr_offsets(lane);
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)&smem[0][0][0];
+  const StageLoader L = make_loader(base + A, base + 2 * A, wave, lane);
+  // A workgroup takes a long and a short query block (block x from the end, then block x from the start), so that
+  // every workgroup walks the same number of tiles whatever the causal triangle gives its blocks.
+  const int nqb = (S + 127) / 128;
+  for (int pass = 0; pass < 2; ++pass) {
+  const int qb = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (pass == 1) {
+    if (qb >= nqb - 1 - (int)blockIdx.x) break;   // the middle block of an odd count was done in the first pass
+    __syncthreads();                              // the stages are reused
+  }
+  const int q0 = qb * 128, qw0 = q0 + 32 * wave, q = qw0 + r;
 
   uint4 qf[4];
 #pragma unroll
@@ -150,33 +218,25 @@ __global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __res
   float m = -INFINITY, l = 0.f;
   const float sc = 0.125f * LOG2E;   // 1/sqrt(64), base-2 exponentials
 
-  const int t128 = tid & 127;
-  const bool load_v = tid >= 128;
-  SubBlock sb;
-  auto gload = [&](int kt) {
-    sb_load(sb, base + (load_v ? 2 * A : A) + (long)(kt * 64) * ld, ld, S - kt * 64, t128);
-  };
-  auto sstore = [&](int stage) {
-    if (load_v) sb_store_transposed(sb, smem[stage][1], t128);
-    else sb_store_rows(sb, smem[stage][0], t128);
-  };
-  gload(0);
-  sstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < ntiles; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < ntiles;
-    if (more) gload(kt + 1);
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < ntiles) issue_stage(L, s * 64, S, ld, ld, wave, smem_addr + s * 2 * TILE_BYTES);
+  int cur = 0;
+  for (int kt = 0; kt < ntiles; ++kt, cur = cur + 1 == NS ? 0 : cur + 1) {
+    wait_stages_but<4>(min(NS - 2, ntiles - 1 - kt));
+    __syncthreads();   // tile kt is in LDS; nobody still reads the stage of tile kt - 1, which is refilled now
+    if (kt + NS - 1 < ntiles)
+      issue_stage(L, (kt + NS - 1) * 64, S, ld, ld, wave, smem_addr + (cur == 0 ? NS - 1 : cur - 1) * 2 * TILE_BYTES);
     const int kv0 = kt * 64;
     if (kv0 <= qw0 + 31) {   // wave-uniform: at least one query of this wave sees this tile
-      const char* kt_ = smem[cur][0];
-      const char* vt_ = smem[cur][1];
+      const char* k_ = smem[cur][0];
+      const char* v_ = smem[cur][1];
       f32x16 st[2];
       zero(st[0]); zero(st[1]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) st[t] = mfma16(ld16(kt_ + fo.b[ks] + 4096 * t), qf[ks], st[t]);
+        for (int t = 0; t < 2; ++t) st[t] = mfma16(ld16(k_ + fo.b[ks] + 4096 * t), qf[ks], st[t]);
       if (kv0 + 63 > qw0) {   // wave-uniform: the tile crosses the diagonal of some query
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -209,39 +269,42 @@ __global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __res
         m = mn;
       }
       l += rs;
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const uint4 p0 = pack8<0>(st[t]), p1 = pack8<8>(st[t]);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          ot[dt] = mfma16(ld16(vt_ + fo.b[2 * t] + 4096 * dt), p0, ot[dt]);
-          ot[dt] = mfma16(ld16(vt_ + fo.b[2 * t + 1] + 4096 * dt), p1, ot[dt]);
-        }
-      }
+      mma_transposed(ot, v_, to, st);
     }
-    if (more) sstore(cur ^ 1);
-    __syncthreads();
   }
   if (q < S) {
     store_transposed_out(o + ((long)b * S + q) * A + hd * DH, ot, h, 1.0f / l);
     if (h == 0) lse[(long)bh * S + q] = (m + __builtin_amdgcn_logf(l)) * LN2;   // v_log_f32 is log2
   }
+  }
 }
 
 // ---- backward, dQ (also writes D = rowsum(dO * O)) --------------------------------------------------------------
 __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
-                                                               const bf16* __restrict__ d_o,
-                                                               const float* __restrict__ lse, bf16* __restrict__ dqkv,
-                                                               float* __restrict__ dsum, int S, int H) {
-  __shared__ __attribute__((aligned(16))) char smem[2][3][TILE_BYTES];   // [stage][K rows | V rows | K^T]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;
+                                                                  const bf16* __restrict__ d_o,
+                                                                  const float* __restrict__ lse, bf16* __restrict__ dqkv,
+                                                                  float* __restrict__ dsum, int S, int H) {
+  constexpr int NS = DQ_STAGES;
+  extern __shared__ __attribute__((aligned(16))) char dq_smem[];   // [stage][K | V]
+  char (*smem)[2][TILE_BYTES] = reinterpret_cast<char (*)[2][TILE_BYTES]>(dq_smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / H, hd = bh % H;
   const int A = H * DH;
   const long ld = 3L * A;
   const bf16* base = qkv + (long)b * S * ld + hd * DH;
-  const int q0 = qb * 128, qw0 = q0 + 32 * wave, q = qw0 + r;
   const FragOff fo = frag_offsets(lane);
+  const TrOff to = tr_offsets(lane);
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)dq_smem;
+  const StageLoader L = make_loader(base + A, base + 2 * A, wave, lane);
+  const int nqb = (S + 127) / 128;
+  for (int pass = 0; pass < 2; ++pass) {   // a long and a short query block per workgroup (see the forward kernel)
+  const int qb = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (pass == 1) {
+    if (qb >= nqb - 1 - (int)blockIdx.x) break;
+    __syncthreads();
+  }
+  const int q0 = qb * 128, qw0 = q0 + 32 * wave, q = qw0 + r;
 
   uint4 qf[4], gf[4];
   float D = 0.f;
@@ -262,8 +325,14 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
     }
   }
   D += __shfl_xor(D, 32, WAVE);
-  if (q < S && h == 0) dsum[(long)bh * S + q] = D;
   const float nlse2 = q < S ? -lse[(long)bh * S + q] * LOG2E : -INFINITY;
+  // per-query statistics for the dK / dV kernel, in rows padded to whole query blocks: D (0 beyond S) and
+  // -lse * log2(e) (-inf beyond S: probability 0), so that kernel needs neither a bounds check nor a rescale
+  if (h == 0) {
+    const long Sp = (long)nqb * 128;
+    dsum[bh * Sp + q] = q < S ? D : 0.f;
+    dsum[(long)gridDim.y * Sp + bh * Sp + q] = nlse2;
+  }
 
   const int kv_end = min(S, q0 + 128);
   const int ntiles = (kv_end + 63) / 64;
@@ -271,36 +340,27 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
   zero(dqt[0]); zero(dqt[1]);
   const float sc = 0.125f * LOG2E;
 
-  const int t128 = tid & 127;
-  const bool load_v = tid >= 128;
-  SubBlock sb;
-  auto gload = [&](int kt) {
-    sb_load(sb, base + (load_v ? 2 * A : A) + (long)(kt * 64) * ld, ld, S - kt * 64, t128);
-  };
-  auto sstore = [&](int stage) {
-    if (load_v) sb_store_rows(sb, smem[stage][1], t128);
-    else { sb_store_rows(sb, smem[stage][0], t128); sb_store_transposed(sb, smem[stage][2], t128); }
-  };
-  gload(0);
-  sstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < ntiles; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < ntiles;
-    if (more) gload(kt + 1);
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < ntiles) issue_stage(L, s * 64, S, ld, ld, wave, smem_addr + s * 2 * TILE_BYTES);
+  int cur = 0;
+  for (int kt = 0; kt < ntiles; ++kt, cur = cur + 1 == NS ? 0 : cur + 1) {
+    wait_stages_but<4>(min(NS - 2, ntiles - 1 - kt));
+    __syncthreads();   // tile kt is in LDS; nobody still reads the stage of tile kt - 1, which is refilled now
+    if (kt + NS - 1 < ntiles)
+      issue_stage(L, (kt + NS - 1) * 64, S, ld, ld, wave, smem_addr + (cur == 0 ? NS - 1 : cur - 1) * 2 * TILE_BYTES);
     const int kv0 = kt * 64;
     if (kv0 <= qw0 + 31) {
-      const char* k_rows = smem[cur][0];
-      const char* v_rows = smem[cur][1];
-      const char* k_t = smem[cur][2];
+      const char* k_ = smem[cur][0];
+      const char* v_ = smem[cur][1];
       f32x16 st[2], dp[2];
       zero(st[0]); zero(st[1]); zero(dp[0]); zero(dp[1]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          st[t] = mfma16(ld16(k_rows + fo.b[ks] + 4096 * t), qf[ks], st[t]);
-          dp[t] = mfma16(ld16(v_rows + fo.b[ks] + 4096 * t), gf[ks], dp[t]);
+          st[t] = mfma16(ld16(k_ + fo.b[ks] + 4096 * t), qf[ks], st[t]);
+          dp[t] = mfma16(ld16(v_ + fo.b[ks] + 4096 * t), gf[ks], dp[t]);
         }
       // dS^T without the 1/sqrt(d_head) factor (applied once when dQ is stored)
 #pragma unroll
@@ -315,40 +375,52 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
           for (int e = 0; e < 16; ++e)
             if (kv0 + 32 * t + acc_row(e, lane) > q) st[t][e] = 0.f;
       }
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const uint4 s0 = pack8<0>(st[t]), s1 = pack8<8>(st[t]);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          dqt[dt] = mfma16(ld16(k_t + fo.b[2 * t] + 4096 * dt), s0, dqt[dt]);
-          dqt[dt] = mfma16(ld16(k_t + fo.b[2 * t + 1] + 4096 * dt), s1, dqt[dt]);
-        }
-      }
+      mma_transposed(dqt, k_, to, st);
     }
-    if (more) sstore(cur ^ 1);
-    __syncthreads();
   }
   if (q < S) store_transposed_out(dqkv + ((long)b * S + q) * ld + hd * DH, dqt, h, 0.125f);
+  }
 }
 
 // ---- backward, dK and dV ------------------------------------------------------------------------------------------
-constexpr int DKV_STAGE = 4 * TILE_BYTES + 2 * 64 * (int)sizeof(float);   // Q rows | Q^T | dO rows | dO^T | -lse2 | D
+constexpr int DKV_STAGE = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);   // Q | dO | -lse2 | D
 
 __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* __restrict__ qkv,
-                                                                const bf16* __restrict__ d_o,
-                                                                const float* __restrict__ lse,
-                                                                const float* __restrict__ dsum,
-                                                                bf16* __restrict__ dqkv, int S, int H) {
-  extern __shared__ __attribute__((aligned(16))) char dsmem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
-  const int kb = blockIdx.x;
+                                                                   const bf16* __restrict__ d_o,
+                                                                   const float* __restrict__ dsum,
+                                                                   bf16* __restrict__ dqkv, int S, int H) {
+  constexpr int NS = DKV_STAGES;
+  extern __shared__ __attribute__((aligned(16))) char dkv_smem[];   // NS stages of DKV_STAGE bytes
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / H, hd = bh % H;
   const int A = H * DH;
   const long ld = 3L * A;
   const bf16* base = qkv + (long)b * S * ld + hd * DH;
   const bf16* gbase = d_o + (long)b * S * A + hd * DH;
-  const int k0 = kb * 128, kw0 = k0 + 32 * wave, key = kw0 + r;
   const FragOff fo = frag_offsets(lane);
+  const TrOff to = tr_offsets(lane);
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)dkv_smem;
+  const int nkb = (S + 127) / 128;
+  const int ntiles = (S + 63) / 64;
+  // Statistics of a tile's 64 queries (written by the dQ kernel into rows padded to whole query blocks): waves 0
+  // and 2 fetch -lse*log2(e), waves 1 and 3 fetch D, one float per lane; the duplicates keep every wave's count of
+  // outstanding loads the same.
+  const long Sp = (long)nkb * 128;
+  const float* stat_src = dsum + ((wave & 1) ? 0 : (long)gridDim.y * Sp) + bh * Sp + lane;
+  const uint32_t stat_dst = 2 * TILE_BYTES + ((wave & 1) ? 256 : 0);
+  const StageLoader L = make_loader(base, gbase, wave, lane);
+  auto issue = [&](int qt, int stage) {
+    issue_stage(L, qt * 64, S, ld, A, wave, smem_addr + stage * DKV_STAGE);
+    load4_to_lds(stat_src + qt * 64, smem_addr + stage * DKV_STAGE + stat_dst);
+  };
+  for (int pass = 0; pass < 2; ++pass) {   // an early (long) and a late (short) key block per workgroup
+  const int kb = pass == 0 ? (int)blockIdx.x : nkb - 1 - (int)blockIdx.x;
+  if (pass == 1) {
+    if (kb <= (int)blockIdx.x) break;
+    __syncthreads();
+  }
+  const int k0 = kb * 128, kw0 = k0 + 32 * wave, key = kw0 + r;
 
   uint4 kf[4], vf[4];
 #pragma unroll
@@ -362,49 +434,19 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
   const float sc = 0.125f * LOG2E;
 
   const int first = k0 / 64;               // first query tile that can see a key of this block
-  const int ntiles = (S + 63) / 64;
-  const int t128 = tid & 127;
-  const bool load_g = tid >= 128;
-  SubBlock sb;
-  float stat = 0.f;
-  // per-query statistics of the tile: threads 0-63 fetch -lse*log2(e) (-inf beyond S: probability 0), threads
-  // 64-127 fetch D (0 beyond S).  The index is clamped and the override is bitwise, so the load stays unconditional.
-  const float* stat_src = (tid & 64) ? dsum + (long)bh * S : lse + (long)bh * S;
-  const float stat_mul = (tid & 64) ? 1.0f : -LOG2E;
-  const uint32_t stat_fill = (tid & 64) ? 0u : 0xff800000u;
-  auto gload = [&](int qt) {
-    const int row0 = qt * 64;
-    if (load_g) sb_load(sb, gbase + (long)row0 * A, A, S - row0, t128);
-    else sb_load(sb, base + (long)row0 * ld, ld, S - row0, t128);
-    const int qi = row0 + (tid & 63);
-    const float v = stat_src[min(qi, S - 1)] * stat_mul;
-    const uint32_t keep = qi < S ? 0xffffffffu : 0u;
-    stat = __uint_as_float((__float_as_uint(v) & keep) | (stat_fill & ~keep));
-  };
-  auto sstore = [&](int stage) {
-    char* st = dsmem + stage * DKV_STAGE;
-    char* rows = st + (load_g ? 2 : 0) * TILE_BYTES;
-    sb_store_rows(sb, rows, t128);
-    sb_store_transposed(sb, rows + TILE_BYTES, t128);
-    if (tid < 128) reinterpret_cast<float*>(st + 4 * TILE_BYTES)[tid] = stat;
-  };
-  if (first < ntiles) {
-    gload(first);
-    sstore(0);
-  }
-  __syncthreads();
-  for (int qt = first; qt < ntiles; ++qt) {
-    const int cur = (qt - first) & 1;
-    const bool more = qt + 1 < ntiles;
-    if (more) gload(qt + 1);
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (first + s < ntiles) issue(first + s, s);
+  int cur = 0;
+  for (int qt = first; qt < ntiles; ++qt, cur = cur + 1 == NS ? 0 : cur + 1) {
+    wait_stages_but<5>(min(NS - 2, ntiles - 1 - qt));
+    __syncthreads();
+    if (qt + NS - 1 < ntiles) issue(qt + NS - 1, cur == 0 ? NS - 1 : cur - 1);
     const int q0 = qt * 64;
     if (q0 + 63 >= kw0) {   // wave-uniform: some query of this tile sees a key of this wave
-      const char* stg = dsmem + cur * DKV_STAGE;
-      const char* q_rows = stg;
-      const char* q_t = stg + TILE_BYTES;
-      const char* g_rows = stg + 2 * TILE_BYTES;
-      const char* g_t = stg + 3 * TILE_BYTES;
-      const float* nlse2s = reinterpret_cast<const float*>(stg + 4 * TILE_BYTES);
+      const char* q_ = dkv_smem + cur * DKV_STAGE;
+      const char* g_ = q_ + TILE_BYTES;
+      const float* nlse2s = reinterpret_cast<const float*>(q_ + 2 * TILE_BYTES);
       const float* Ds = nlse2s + 64;
       f32x16 st[2], dp[2];
       zero(st[0]); zero(st[1]); zero(dp[0]); zero(dp[1]);
@@ -412,17 +454,17 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          st[t] = mfma16(ld16(q_rows + fo.b[ks] + 4096 * t), kf[ks], st[t]);
-          dp[t] = mfma16(ld16(g_rows + fo.b[ks] + 4096 * t), vf[ks], dp[t]);
+          st[t] = mfma16(ld16(q_ + fo.b[ks] + 4096 * t), kf[ks], st[t]);
+          dp[t] = mfma16(ld16(g_ + fo.b[ks] + 4096 * t), vf[ks], dp[t]);
         }
       // accumulator elements 4g..4g+3 are queries 32t + 8g + 4h + (0..3): their statistics are 16 contiguous bytes
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const float4 L = *reinterpret_cast<const float4*>(nlse2s + 32 * t + 8 * g + 4 * h);
+          const float4 Lq = *reinterpret_cast<const float4*>(nlse2s + 32 * t + 8 * g + 4 * h);
           const float4 Dv = *reinterpret_cast<const float4*>(Ds + 32 * t + 8 * g + 4 * h);
-          const float Ls[4] = {L.x, L.y, L.z, L.w}, Dd[4] = {Dv.x, Dv.y, Dv.z, Dv.w};
+          const float Ls[4] = {Lq.x, Lq.y, Lq.z, Lq.w}, Dd[4] = {Dv.x, Dv.y, Dv.z, Dv.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int e = 4 * g + i;
@@ -438,33 +480,22 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
           for (int e = 0; e < 16; ++e)
             if (q0 + 32 * t + acc_row(e, lane) < key) { st[t][e] = 0.f; dp[t][e] = 0.f; }
       }
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const uint4 p0 = pack8<0>(st[t]), p1 = pack8<8>(st[t]);
-        const uint4 s0 = pack8<0>(dp[t]), s1 = pack8<8>(dp[t]);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          dvt[dt] = mfma16(ld16(g_t + fo.b[2 * t] + 4096 * dt), p0, dvt[dt]);
-          dvt[dt] = mfma16(ld16(g_t + fo.b[2 * t + 1] + 4096 * dt), p1, dvt[dt]);
-          dkt[dt] = mfma16(ld16(q_t + fo.b[2 * t] + 4096 * dt), s0, dkt[dt]);
-          dkt[dt] = mfma16(ld16(q_t + fo.b[2 * t + 1] + 4096 * dt), s1, dkt[dt]);
-        }
-      }
+      mma_transposed(dvt, g_, to, st);
+      mma_transposed(dkt, q_, to, dp);
     }
-    if (more) sstore(cur ^ 1);
-    __syncthreads();
   }
   if (key < S) {
     bf16* out = dqkv + ((long)b * S + key) * ld + hd * DH;
     store_transposed_out(out + A, dkt, h, 0.125f);
     store_transposed_out(out + 2 * A, dvt, h, 1.0f);
   }
+  }
 }
 
 }  // namespace
 
 dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, int B, int S, int H, hipStream_t s) {
-  dim3 grid((S + 127) / 128, B * H);
+  dim3 grid(((S + 127) / 128 + 1) / 2, B * H);   // two query blocks per workgroup
   attn_fwd_mfma<<<grid, AT_THREADS, 0, s>>>(qkv, o, lse, S, H);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
@@ -472,16 +503,18 @@ dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, in
 
 dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf16* d_o, const float* lse, bf16* dqkv,
                                         float* dsum, int B, int S, int H, hipStream_t s) {
-  dim3 grid((S + 127) / 128, B * H);
-  attn_bwd_dq_mfma<<<grid, AT_THREADS, 0, s>>>(qkv, o, d_o, lse, dqkv, dsum, S, H);
-  DIPACO_LAUNCH_CHECK();
+  dim3 grid(((S + 127) / 128 + 1) / 2, B * H);   // two query (key) blocks per workgroup
   static bool attr_set = false;
   if (!attr_set) {
+    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, DQ_STAGES * 2 * TILE_BYTES));
     DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, 2 * DKV_STAGE));
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, DKV_STAGES * DKV_STAGE));
     attr_set = true;
   }
-  attn_bwd_dkv_mfma<<<grid, AT_THREADS, 2 * DKV_STAGE, s>>>(qkv, d_o, lse, dsum, dqkv, S, H);
+  attn_bwd_dq_mfma<<<grid, AT_THREADS, DQ_STAGES * 2 * TILE_BYTES, s>>>(qkv, o, d_o, lse, dqkv, dsum, S, H);
+  DIPACO_LAUNCH_CHECK();
+  attn_bwd_dkv_mfma<<<grid, AT_THREADS, DKV_STAGES * DKV_STAGE, s>>>(qkv, d_o, dsum, dqkv, S, H);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

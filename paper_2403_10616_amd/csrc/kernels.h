@@ -95,7 +95,7 @@ size_t embed_bwd_scratch_ints(int rows, int vocab);
 // qkv: [B*S, 3A] (q | k | v, head h at columns h*dh), o: [B*S, A], lse: [B, H, S] fp32.
 template <typename T>
 dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S, int H, int dh, hipStream_t s);
-// dqkv: [B*S, 3A];  dscratch: [B, H, S] fp32 (rowsum(dO*O))
+// dqkv: [B*S, 3A];  dscratch: fp32 scratch of 2 * B * H * roundup(S, 128) floats (per-query statistics)
 template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv,
                                    float* dscratch, int B, int S, int H, int dh, hipStream_t s);

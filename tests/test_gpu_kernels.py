@@ -133,7 +133,7 @@ def test_attention_forward_backward(dtype, B, S, H, dh):
     assert rel_l2(host(o), o_ref) <= tol
     assert np.abs(host(lse) - lse_ref).max() <= (1e-5 if dtype == dp.F32 else 2e-2)
     dqkv = torch.empty_like(qkv)
-    dsum = torch.empty((B, H, S), dtype=torch.float32, device=DEV)
+    dsum = torch.empty(2 * B * H * ((S + 127) // 128 * 128), dtype=torch.float32, device=DEV)
     dp.dipaco_k_attention_bwd(dtype, qkv, o, d_o, lse, dqkv, dsum, B, S, H, dh)
     ref = np.empty((B * S, 3 * A))
     for b in range(B):
