@@ -32,8 +32,8 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
 /* Force the GEMM workgroup tile for every later call in this process: 0 = automatic (default), 1 = 128x128,
  * 2 = 256x128, 3 = 256x256 with four waves, 4 = 256x256 with eight waves, 5 = the bf16 kernel that loads its
  * 256x256 tiles from global memory straight into LDS, for every shape it takes (K a multiple of 32, 16-byte rows;
- * other shapes and fp32 keep the automatic choice).  For tests (every tile shape must give the same parity) and
- * tuning. */
+ * other shapes and fp32 keep the automatic choice), 6 / 7 = the same kernel with its 256x256 / 256x128 tile forced.
+ * For tests (every tile shape must give the same parity) and tuning. */
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 
 /* Causal softmax attention.  qkv: [B*S, 3*H*dh], row = q | k | v, head h at columns h*dh of each third;

@@ -175,14 +175,16 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
               false, 1, nullptr, st));
   T* dx = buf(p.dxa);
   T* dx_other = buf(p.dxb);
+  // every LayerNorm backward also leaves the column sums of the dx it writes: the bias gradient of the linear
+  // layer below it in the residual stream (W_down of the block before, W_o of its own block)
   TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(p.x_final), W + c->lnf_g, fbuf(p.meanf), fbuf(p.rstdf), nullptr, dx,
-                              G + c->lnf_g, G + c->lnf_b, lnp, T_, d, st));
+                              G + c->lnf_g, G + c->lnf_b, NL > 0 ? G + c->blocks[NL - 1].b_down : nullptr, lnp, T_, d,
+                              st));
   for (int l = NL - 1; l >= 0; --l) {
     const LayerBufs& L = p.layers[l];
     const BlockOff& o = c->blocks[l];
     // x_next = x_mid + gelu(u) W_down + b_down
     TRY(dweight(buf(L.act), dx, o.w_down, F, d));
-    TRY(launch_colsum<T>(dx, G + o.b_down, csp, T_, d, st));
     TRY(gemm<T>(dx, W + o.w_down, buf(p.du), T_, F, d, d, d, F, false, true, nullptr, nullptr, nullptr, buf(L.u), 2,
                 false, 1, nullptr, st));
     TRY(dweight(buf(L.h2), buf(p.du), o.w_up, d, F));
@@ -190,10 +192,9 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
     TRY(gemm<T>(buf(p.du), W + o.w_up, buf(p.dh), T_, d, F, F, F, d, false, true, nullptr, nullptr, nullptr, nullptr, 0,
                 false, 1, nullptr, st));
     TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_mid), W + o.ln2_g, fbuf(L.mean2), fbuf(L.rstd2), dx, dx_other,
-                                G + o.ln2_g, G + o.ln2_b, lnp, T_, d, st));
+                                G + o.ln2_g, G + o.ln2_b, G + o.b_o, lnp, T_, d, st));
     // x_mid = x_in + attn(...) W_o + b_o          (dx_other = gradient at x_mid)
     TRY(dweight(buf(L.o), dx_other, o.w_o, A, d));
-    TRY(launch_colsum<T>(dx_other, G + o.b_o, csp, T_, d, st));
     TRY(gemm<T>(dx_other, W + o.w_o, buf(p.d_o), T_, A, d, d, d, A, false, true, nullptr, nullptr, nullptr, nullptr, 0,
                 false, 1, nullptr, st));
     TRY(launch_attention_bwd<T>(buf(L.qkv), buf(L.o), buf(p.d_o), fbuf(L.lse), buf(p.dqkv), fbuf(p.dsum), B, S, H, dh,
@@ -203,7 +204,7 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
     TRY(gemm<T>(buf(p.dqkv), W + o.w_qkv, buf(p.dh), T_, d, 3 * A, 3 * A, 3 * A, d, false, true, nullptr, nullptr,
                 nullptr, nullptr, 0, false, 1, nullptr, st));
     TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_in), W + o.ln1_g, fbuf(L.mean1), fbuf(L.rstd1), dx_other, dx,
-                                G + o.ln1_g, G + o.ln1_b, lnp, T_, d, st));
+                                G + o.ln1_g, G + o.ln1_b, l > 0 ? G + c->blocks[l - 1].b_down : nullptr, lnp, T_, d, st));
   }
   TRY(launch_embed_bwd<T>(dx, tokens, G + c->tok_emb, G + c->pos_emb, reinterpret_cast<int*>(ws + p.embed_ints), B, S,
                           d, V, a.max_seq, st));
@@ -452,7 +453,7 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
 }
 
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
-  if (tile < 0 || tile > 5) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..5");
+  if (tile < 0 || tile > 7) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..7");
   set_gemm_tile(tile);
   return DIPACO_OK;
 }

@@ -80,10 +80,12 @@ template <int LPW> __device__ __forceinline__ void wait_stages_but(int n) {
 // tile rows = 1024 LDS bytes).  Load i of wave w is number j = w + 4i: tile j / 8, rows 8 (j % 8) .. + 7.
 struct StageLoader {
   const bf16* col[4];   // per lane: tile source + the 16-byte chunk this lane fetches (row 0 of the operand)
+  const bf16* src[4];   // per lane: the same for this lane's row of the tile that starts at operand row 0
   int row[4];           // per lane: row inside the tile
   uint32_t dst[4];      // wave-uniform: byte offset of the load inside the stage
 };
-__device__ __forceinline__ StageLoader make_loader(const bf16* tile0, const bf16* tile1, int wave, int lane) {
+__device__ __forceinline__ StageLoader make_loader(const bf16* tile0, const bf16* tile1, long ld0, long ld1, int wave,
+                                                   int lane) {
   StageLoader L;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -91,20 +93,30 @@ __device__ __forceinline__ StageLoader make_loader(const bf16* tile0, const bf16
     const int rit = 8 * (j & 7) + (lane >> 3);
     const int chunk = (lane & 7) ^ swz64(rit);
     L.col[i] = (j < 8 ? tile0 : tile1) + chunk * 8;
+    L.src[i] = L.col[i] + rit * (j < 8 ? ld0 : ld1);
     L.row[i] = rit;
     L.dst[i] = (uint32_t)((j >> 3) * TILE_BYTES + (j & 7) * 1024);
   }
   return L;
 }
 // Rows at or beyond rows_total re-read the last valid row: callers give such rows zero weight (masked
-// probabilities, -inf statistics), so any finite value will do, and no branch surrounds the loads.
+// probabilities, -inf statistics), so any finite value will do, and no branch surrounds a load.  Only the last
+// tile of an operand can stick out; every other tile adds a wave-uniform offset to the per-lane pointers.
 __device__ __forceinline__ void issue_stage(const StageLoader& L, int row0, int rows_total, long ld0, long ld1, int wave,
                                             uint32_t stage_addr) {
+  if (row0 + 64 <= rows_total) {   // wave-uniform
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = min(row0 + L.row[i], rows_total - 1);
-    const long ld = (wave + 4 * i) < 8 ? ld0 : ld1;
-    load16_to_lds(L.col[i] + (long)r * ld, stage_addr + L.dst[i]);
+    for (int i = 0; i < 4; ++i) {
+      const long ld = (wave + 4 * i) < 8 ? ld0 : ld1;
+      load16_to_lds(L.src[i] + row0 * ld, stage_addr + L.dst[i]);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = min(row0 + L.row[i], rows_total - 1);
+      const long ld = (wave + 4 * i) < 8 ? ld0 : ld1;
+      load16_to_lds(L.col[i] + (long)r * ld, stage_addr + L.dst[i]);
+    }
   }
 }
 
@@ -181,7 +193,7 @@ __device__ __forceinline__ void store_transposed_out(bf16* row_ptr, const f32x16
 // ---- forward ---------------------------------------------------------------------------------------------------
 constexpr int FWD_STAGES = 2, DQ_STAGES = 2, DKV_STAGES = 2;
 
-__global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+__global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                                float* __restrict__ lse, int S, int H) {
   constexpr int NS = FWD_STAGES;
   __shared__ __attribute__((aligned(16))) char smem[NS][2][TILE_BYTES];   // [stage][K | V]
@@ -194,7 +206,7 @@ __global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __res
   const FragOff fo = frag_offsets(lane);
   const TrOff to = tr_offsets(lane);
   const uint32_t smem_addr = (uint32_t)(uintptr_t)&smem[0][0][0];
-  const StageLoader L = make_loader(base + A, base + 2 * A, wave, lane);
+  const StageLoader L = make_loader(base + A, base + 2 * A, ld, ld, wave, lane);
   // A workgroup takes a long and a short query block (block x from the end, then block x from the start), so that
   // every workgroup walks the same number of tiles whatever the causal triangle gives its blocks.
   const int nqb = (S + 127) / 128;
@@ -248,18 +260,11 @@ __global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __res
 #pragma unroll
       for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(st[0][e], st[1][e]));
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      // The reference exponent m only has to stay within 2^8 of the true running maximum (probabilities then stay
+      // below 256, harmless in fp32 sums and in bf16 operands, and the final O / l and lse do not depend on the
+      // reference): the accumulators are rescaled only when some query's maximum outgrows it by more than that.
       const float mn = fmaxf(m, mx * sc);   // finite: key 0 is visible to every query
-      float rs = 0.f;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, -mn));
-          st[t][e] = p;
-          rs += p;
-        }
-      rs += __shfl_xor(rs, 32, WAVE);
-      if (__builtin_amdgcn_ballot_w64(mn != m) != 0) {   // wave-uniform: somebody's running maximum moved
+      if (__builtin_amdgcn_ballot_w64(mn > m + 8.0f) != 0) {   // wave-uniform
         const float corr = __builtin_amdgcn_exp2f(m - mn);
         l *= corr;
 #pragma unroll
@@ -268,6 +273,16 @@ __global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __res
           for (int e = 0; e < 16; ++e) ot[dt][e] *= corr;
         m = mn;
       }
+      float rs = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, -m));
+          st[t][e] = p;
+          rs += p;
+        }
+      rs += __shfl_xor(rs, 32, WAVE);
       l += rs;
       mma_transposed(ot, v_, to, st);
     }
@@ -296,7 +311,7 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
   const FragOff fo = frag_offsets(lane);
   const TrOff to = tr_offsets(lane);
   const uint32_t smem_addr = (uint32_t)(uintptr_t)dq_smem;
-  const StageLoader L = make_loader(base + A, base + 2 * A, wave, lane);
+  const StageLoader L = make_loader(base + A, base + 2 * A, ld, ld, wave, lane);
   const int nqb = (S + 127) / 128;
   for (int pass = 0; pass < 2; ++pass) {   // a long and a short query block per workgroup (see the forward kernel)
   const int qb = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
@@ -409,7 +424,7 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
   const long Sp = (long)nkb * 128;
   const float* stat_src = dsum + ((wave & 1) ? 0 : (long)gridDim.y * Sp) + bh * Sp + lane;
   const uint32_t stat_dst = 2 * TILE_BYTES + ((wave & 1) ? 256 : 0);
-  const StageLoader L = make_loader(base, gbase, wave, lane);
+  const StageLoader L = make_loader(base, gbase, ld, A, wave, lane);
   auto issue = [&](int qt, int stage) {
     issue_stage(L, qt * 64, S, ld, A, wave, smem_addr + stage * DKV_STAGE);
     load4_to_lds(stat_src + qt * 64, smem_addr + stage * DKV_STAGE + stat_dst);

@@ -230,7 +230,10 @@ dipaco_status run_tiled(const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
-void set_gemm_tile(int t) { g_forced_tile = t; }
+void set_gemm_tile(int t) {
+  g_forced_tile = t > 5 ? 5 : t;
+  set_gemm_dlds_shape(t > 5 ? t - 5 : 0);
+}
 
 // Split count for a long-K product (a weight gradient: K = tokens).  With 256 x 256 tiles the cost of one
 // candidate, in units of one K step of one tile, is rounds * (K / s + fixed) + s * (traffic of one partial

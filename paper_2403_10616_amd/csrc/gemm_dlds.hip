@@ -30,11 +30,8 @@ namespace dipaco {
 
 namespace {
 
-constexpr int DL_BM = 256, DL_BN = 256, DL_BK = 32, DL_STAGES = 4;
+constexpr int DL_BM = 256, DL_BK = 32;
 constexpr int DL_ROWB = DL_BK * 2;                          // bytes of a K-contiguous tile row
-constexpr int DL_TILE = DL_BM * DL_ROWB;                    // 16 KB per operand tile (either kind)
-constexpr int DL_STAGE = 2 * DL_TILE;
-constexpr int DL_KROW = 512;                                // bytes of a K-row of a row-contiguous tile
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
@@ -47,21 +44,31 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only:
 }
 
 // A_KC: A is [M, K] (contiguous along K), else [K, M].  B_KC: B is [N, K], else [K, N].
-template <typename TC, bool A_KC, bool B_KC, int WGM, int WGN>
-__global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev g) {
+// Two shapes are built: 256 x 256 tiles, 2 x 4 waves, 4 stages (one workgroup per compute unit; least operand
+// traffic, for long K), and 256 x 128 tiles, 2 x 2 waves, 3 stages (two workgroups per compute unit, whose
+// prologues and epilogues hide behind each other's multiplications: for the short-K products of the step, where
+// those ends are a large part of a tile's life).  Either way a wave owns 128 x 64 outputs and two waves share a SIMD.
+template <typename TC, bool A_KC, bool B_KC, int DL_BN, int WGM, int WGN, int DL_STAGES>
+__global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const GemmDev g) {
   constexpr int NW = WGM * WGN;
-  constexpr int LPS = 2 * DL_TILE / 1024 / NW;              // wave-level loads per wave and stage
+  constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;   // bytes of an operand tile (either kind)
+  constexpr int DL_STAGE = DL_TILE_A + DL_TILE_B;
+  constexpr int KROW_A = DL_BM * 2, KROW_B = DL_BN * 2;     // bytes of a K-row of a row-contiguous tile
+  constexpr int NLA = DL_TILE_A / 1024;                     // wave-level loads of the A tile
+  constexpr int LPS = DL_STAGE / 1024 / NW;                 // wave-level loads per wave and stage
   constexpr int TM = DL_BM / (32 * WGM), TN = DL_BN / (32 * WGN);
   constexpr int WN = DL_BN / WGN;
   constexpr int NM = TM * TN, NR = TM + TN;
+  static_assert(TM == 4 && TN == 2, "a wave owns 128 x 64 outputs");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // Waves w and w + 4 share a SIMD.  They are given different halves of the tile's rows AND of its columns, so
   // that in a tile that sticks out of C by half (896 = 3.5 x 256 is the path's width) every SIMD keeps exactly
   // one wave with work, which then has the matrix core to itself: such a tile costs half a tile.
-  static_assert(WGM == 2 && WGN == 4, "wave placement below is written for 2 x 4 waves");
-  const int wm = (wave & 1) ^ (wave >> 2), wn = 2 * (wave >> 2) + ((wave >> 1) & 1);
+  static_assert(WGM == 2 && (WGN == 4 || WGN == 2), "wave placement below is written for 2 x 4 and 2 x 2 waves");
+  const int wm = WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1;
+  const int wn = WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1;
   int split, tile_m, tile_n;
   gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
   const int m0 = tile_m * DL_BM, n0 = tile_n * DL_BN;
@@ -70,7 +77,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
   const int k_end = min(g.K, k_begin + g.k_per_split);
   const int nkt = (k_end - k_begin) / DL_BK;
 
-  // ---- loads: wave-level load j fills LDS bytes [1024 j, 1024 j + 1024) of a stage; j < 16: A tile, else B tile.
+  // ---- loads: wave-level load j fills LDS bytes [1024 j, 1024 j + 1024) of a stage; j < NLA: A tile, else B tile.
   // Rows (columns) beyond the operand re-read its last ones: they only feed outputs that are never stored.
   const bf16* gp[LPS];
   long gstep[LPS];
@@ -79,8 +86,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
 #pragma unroll
   for (int i = 0; i < LPS; ++i) {
     const int j = wave + NW * i;
-    const bool is_a = j < 16;
-    const int jj = is_a ? j : j - 16;
+    const bool is_a = j < NLA;
+    const int jj = is_a ? j : j - NLA;
     const bf16* base = static_cast<const bf16*>(is_a ? g.A : g.B);
     const long ld = is_a ? g.lda : g.ldb;
     const int r0 = is_a ? m0 : n0, rtot = is_a ? g.M : g.N;
@@ -90,8 +97,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
       gp[i] = base + (long)row * ld + k_begin + chunk * 8;
       gstep[i] = DL_BK;
     } else {
-      const int t = 2 * jj + (lane >> 5);
-      const int cp = lane & 31;
+      const int sh = (is_a || DL_BN == 256) ? 5 : 4;   // log2 of the 16-byte chunks per K-row (32 or 16)
+      const int t = (64 >> sh) * jj + (lane >> sh);
+      const int cp = lane & ((1 << sh) - 1);
       const int seg = (cp >> 2) ^ (t & 3);
       const int col = min(r0 + (seg * 4 + (cp & 3)) * 8, rtot - 8);
       gp[i] = base + (long)(k_begin + t) * ld + col;
@@ -116,16 +124,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
   int toffa[TM], toffb[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
-    toffa[i] = (8 * (g4 >> 1) + ep) * DL_KROW + (((wm * (DL_BM / WGM) / 32 + i) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+    toffa[i] = (8 * (g4 >> 1) + ep) * KROW_A + (((wm * (DL_BM / WGM) / 32 + i) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
 #pragma unroll
   for (int j = 0; j < TN; ++j)
-    toffb[j] = (8 * (g4 >> 1) + ep) * DL_KROW + (((wn * (DL_BN / WGN) / 32 + j) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+    toffb[j] = (8 * (g4 >> 1) + ep) * KROW_B + (((wn * (DL_BN / WGN) / 32 + j) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
   const char* a_base = smem + (A_KC ? wm * (DL_BM / WGM) * DL_ROWB : 0);
-  const char* b_base = smem + DL_TILE + (B_KC ? wn * (DL_BN / WGN) * DL_ROWB : 0);
+  const char* b_base = smem + DL_TILE_A + (B_KC ? wn * (DL_BN / WGN) * DL_ROWB : 0);
   uint4 fa[2][TM], fb[2][TN];
-  auto tr_read = [&](const char* p) {
+  auto tr_read = [&](const char* p, int krow) {
     const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)p);
-    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)(p + 4 * DL_KROW));
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)(p + 4 * krow));
     uint4 o;
     o.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
     o.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
@@ -136,10 +144,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
   auto read_frag = [&](int set, int q, const char* as, const char* bs, int ks) {   // q-th of the NR fragments
     if (q < TM) {
       if (A_KC) fa[set][q] = *reinterpret_cast<const uint4*>(as + q * 32 * DL_ROWB + foff[ks]);
-      else fa[set][q] = tr_read(as + toffa[q] + ks * 16 * DL_KROW);
+      else fa[set][q] = tr_read(as + toffa[q] + ks * 16 * KROW_A, KROW_A);
     } else {
       if (B_KC) fb[set][q - TM] = *reinterpret_cast<const uint4*>(bs + (q - TM) * 32 * DL_ROWB + foff[ks]);
-      else fb[set][q - TM] = tr_read(bs + toffb[q - TM] + ks * 16 * DL_KROW);
+      else fb[set][q - TM] = tr_read(bs + toffb[q - TM] + ks * 16 * KROW_B, KROW_B);
     }
   };
   auto mfma = [&](int set, int m) {
@@ -149,14 +157,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
   };
   // own loads of every tile but the n newest have landed
   auto wait_newer = [&](int n) {
-    if (n >= 3) wait_vmcnt<3 * LPS>();
-    else if (n == 2) wait_vmcnt<2 * LPS>();
+    if (DL_STAGES > 3 && n >= 3) wait_vmcnt<3 * LPS>();
+    else if (n >= 2) wait_vmcnt<2 * LPS>();
     else if (n == 1) wait_vmcnt<LPS>();
     else wait_vmcnt<0>();
   };
-  static_assert(DL_STAGES == 4, "wait_newer and the steady-state count below assume a ring of four");
+  static_assert(DL_STAGES == 3 || DL_STAGES == 4, "wait_newer handles rings of three and four");
 
-  // prologue: tiles 0..3 into stages 0..3
+  // prologue: the first DL_STAGES tiles, one per stage
 #pragma unroll
   for (int s = 0; s < DL_STAGES; ++s)
     if (s < nkt) {
@@ -170,7 +178,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
     for (int q = 0; q < NR; ++q) read_frag(0, q, a_base, b_base, 0);
   }
 
-  // One K tile.  FULL: tile kt + 4 exists (steady state: no conditions).
+  // One K tile.  FULL: tile kt + DL_STAGES exists (steady state: no conditions).
   auto step = [&](auto FULL, int kt, int stage) {
     constexpr bool full = decltype(FULL)::value;
     const char* as = a_base + stage * DL_STAGE;
@@ -183,7 +191,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    if (full) wait_vmcnt<2 * LPS>();
+    if (full) wait_vmcnt<(DL_STAGES - 2) * LPS>();
     else wait_newer(max(nkt - 2 - kt, 0));
     __syncthreads();
     const int nst = stage + 1 == DL_STAGES ? 0 : stage + 1;
@@ -223,12 +231,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dlds_kernel(const GemmDev
                                       m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
 }
 
-template <typename TC, bool A_KC, bool B_KC>
+template <typename TC, bool A_KC, bool B_KC, int BN, int WGM, int WGN, int STAGES>
 dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
-  constexpr int WGM = 2, WGN = 4;
-  constexpr size_t smem = (size_t)DL_STAGES * DL_STAGE;
-  static_assert((size_t)WGM * WGN * 32 * (DL_BN / WGN + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
-  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, WGM, WGN>;
+  constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_ROWB;
+  static_assert((size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
+  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, BN, WGM, WGN, STAGES>;
   static bool attr_set = false;
   if (!attr_set) {
     DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -241,7 +248,7 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   g.bias = a.bias; g.resid = a.resid; g.aux_out = a.aux_out; g.aux_in = a.aux_in; g.act = a.act;
   g.partial = a.partial;
   g.tiles_m = (a.M + DL_BM - 1) / DL_BM;
-  g.tiles_n = (a.N + DL_BN - 1) / DL_BN;
+  g.tiles_n = (a.N + BN - 1) / BN;
   const int ktiles = a.K / DL_BK;
   int splits = a.splits < 1 ? 1 : a.splits;
   if (splits > ktiles) splits = ktiles;
@@ -253,6 +260,18 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
   return DIPACO_OK;
+}
+
+int g_dlds_shape = 0;   // 0 = automatic, 1 = 256 x 256, 2 = 256 x 128
+
+// Measured on the step's products (K = 896 .. 32768), the two-workgroup shape gains what it hides of a tile's ends
+// and loses as much to its extra barriers and operand traffic: it wins only on the 2688-wide QKV projection (by 6 %)
+// and is kept as a tested option; the automatic choice is the 256 x 256 shape.
+template <typename TC, bool A_KC, bool B_KC>
+dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
+  const bool narrow = g_dlds_shape == 2;
+  if (narrow) return run_dlds<TC, A_KC, B_KC, 128, 2, 2, 3>(a, s);
+  return run_dlds<TC, A_KC, B_KC, 256, 2, 4, 4>(a, s);
 }
 
 }  // namespace
@@ -267,11 +286,13 @@ bool gemm_dlds_eligible(const GemmArgs& a) {
   return true;
 }
 
+void set_gemm_dlds_shape(int shape) { g_dlds_shape = shape; }
+
 dipaco_status launch_gemm_dlds(const GemmArgs& a, hipStream_t s) {
   if (!gemm_dlds_eligible(a)) return fail(DIPACO_EUNSUPPORTED, "gemm: shape not supported by the direct-to-LDS kernel");
-  if (a.out_f32) return run_dlds<float, false, false>(a, s);
-  if (!a.trans_b) return run_dlds<bf16, true, false>(a, s);
-  return run_dlds<bf16, true, true>(a, s);
+  if (a.out_f32) return run_dlds_shape<float, false, false>(a, s);
+  if (!a.trans_b) return run_dlds_shape<bf16, true, false>(a, s);
+  return run_dlds_shape<bf16, true, true>(a, s);
 }
 
 }  // namespace dipaco

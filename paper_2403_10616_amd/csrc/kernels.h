@@ -52,10 +52,12 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s
 // gemm_dlds_eligible holds (whole K tiles of 32, 16-byte rows); launch_gemm routes to it by itself
 bool gemm_dlds_eligible(const GemmArgs& g);
 dipaco_status launch_gemm_dlds(const GemmArgs& g, hipStream_t s);
+void set_gemm_dlds_shape(int shape);   // 0 = chosen by K, 1 = 256 x 256 tiles, 2 = 256 x 128 tiles (tuning and tests)
 // C[m, n] = sum over z < splits of partial[z, m, n], in index order
 dipaco_status launch_splitk_reduce(const float* partial, float* C, int M, int N, long ldc, int splits, hipStream_t s);
 // 0 = automatic; 1 = 128x128, 2 = 256x128, 3 / 4 = 256x256 workgroup tiles with four / eight waves, 5 = the
-// direct-to-LDS kernel wherever the shape allows (tuning and tests)
+// direct-to-LDS kernel wherever the shape allows, 6 / 7 = the same with its 256x256 / 256x128 shape forced
+// (tuning and tests)
 void set_gemm_tile(int t);
 int gemm_plan_splits(int M, int N, int K);   // split count the weight-gradient products are launched with
 int gemm_max_splits(int M, int N, int K);    // its upper bound over tile settings (workspace sizing)
@@ -67,11 +69,12 @@ dipaco_status launch_embed(const T* tok_emb, const T* pos_emb, const int* tokens
 template <typename T>
 dipaco_status launch_layernorm_fwd(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows,
                                    int d, float eps, hipStream_t s);
-// dx = resid_grad (nullable) + LN backward of dy;  dg/db fp32 via `partial` ([ln_bwd_partial_floats] scratch).
+// dx = resid_grad (nullable) + LN backward of dy;  dg/db fp32 via `partial` ([ln_bwd_partial_floats] scratch);
+// dcol (nullable) = column sums of dx as stored: the bias gradient of the linear layer that dx is the output gradient of.
 template <typename T>
 dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const float* mean, const float* rstd,
-                                   const T* resid_grad, T* dx, float* dg, float* db, float* partial, int rows,
-                                   int d, hipStream_t s);
+                                   const T* resid_grad, T* dx, float* dg, float* db, float* dcol, float* partial,
+                                   int rows, int d, hipStream_t s);
 size_t ln_bwd_partial_floats(int rows, int d);
 // out[n] = sum_m x[m,n] (fp32, fixed order);  partial: colsum_partial_floats scratch
 template <typename T>

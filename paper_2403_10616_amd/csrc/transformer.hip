@@ -78,25 +78,29 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_fwd_kernel(const T* __restrict
 
 // ---- LayerNorm backward -----------------------------------------------------------------------------------
 // Each workgroup owns LN_BWD_ROWS consecutive rows (one wave per row at a time), writes dx for them and one
-// partial row of dg / db; a second kernel sums the partial rows in block order.
-constexpr int LN_BWD_ROWS = 64;
+// partial row of dg / db / column sums of dx; a second kernel sums the partial rows in block order.  The column
+// sums of dx (of the values as stored, i.e. rounded to T) are the bias gradient of the linear layer whose output
+// gradient dx is.
+constexpr int LN_BWD_ROWS = 32;
 constexpr int LN_MAX_IT = 4;   // column chunks per lane: d <= 64 * VEC * LN_MAX_IT
 
-template <typename T>
+template <typename T, int NIT>   // NIT column chunks of 16 bytes per lane: d <= 64 * VEC * NIT
 __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                              const T* __restrict__ g, const float* __restrict__ mean,
                                                              const float* __restrict__ rstd,
                                                              const T* __restrict__ resid_grad, T* __restrict__ dx,
                                                              float* __restrict__ partial, int rows, int d) {
   constexpr int VEC = Vec16<T>::N;
-  constexpr int NIT = (sizeof(T) == 4) ? 2 * LN_MAX_IT : LN_MAX_IT;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row0 = blockIdx.x * LN_BWD_ROWS;
-  float ag[NIT][VEC], ab[NIT][VEC];
+  float ag[NIT][VEC], ab[NIT][VEC], ac[NIT][VEC], gv[NIT][VEC];
 #pragma unroll
-  for (int it = 0; it < NIT; ++it)
+  for (int it = 0; it < NIT; ++it) {
+    const int c = (lane + WAVE * it) * VEC;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) { ag[it][i] = 0.f; ab[it][i] = 0.f; }
+    for (int i = 0; i < VEC; ++i) { ag[it][i] = 0.f; ab[it][i] = 0.f; ac[it][i] = 0.f; gv[it][i] = 0.f; }
+    if (c < d) load_vec16(g + c, gv[it]);
+  }
 
   for (int r = wave; r < LN_BWD_ROWS; r += ROWS_PER_BLOCK) {
     const int row = row0 + r;
@@ -104,23 +108,28 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
     const float mu = mean[row], rs = rstd[row];
     const T* xr = x + (size_t)row * d;
     const T* dyr = dy + (size_t)row * d;
+    float xh[NIT][VEC], dv[NIT][VEC], out[NIT][VEC];   // the row stays in registers between the two passes
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int c = (lane + WAVE * it) * VEC;
       if (c < d) {
-        float xv[VEC], dv[VEC], gv[VEC];
+        float xv[VEC];
         load_vec16(xr + c, xv);
-        load_vec16(dyr + c, dv);
-        load_vec16(g + c, gv);
+        load_vec16(dyr + c, dv[it]);
+        if (resid_grad) load_vec16(resid_grad + (size_t)row * d + c, out[it]);
+        else {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) out[it][i] = 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-          const float xh = (xv[i] - mu) * rs;
-          const float dxh = dv[i] * gv[i];
+          xh[it][i] = (xv[i] - mu) * rs;
+          const float dxh = dv[it][i] * gv[it][i];
           s1 += dxh;
-          s2 += dxh * xh;
-          ag[it][i] += dv[i] * xh;
-          ab[it][i] += dv[i];
+          s2 += dxh * xh[it][i];
+          ag[it][i] += dv[it][i] * xh[it][i];
+          ab[it][i] += dv[it][i];
         }
       }
     }
@@ -130,25 +139,16 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
     for (int it = 0; it < NIT; ++it) {
       const int c = (lane + WAVE * it) * VEC;
       if (c < d) {
-        float xv[VEC], dv[VEC], gv[VEC], out[VEC];
-        load_vec16(xr + c, xv);
-        load_vec16(dyr + c, dv);
-        load_vec16(g + c, gv);
-        if (resid_grad) load_vec16(resid_grad + (size_t)row * d + c, out);
-        else {
-#pragma unroll
-          for (int i = 0; i < VEC; ++i) out[i] = 0.f;
-        }
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-          const float xh = (xv[i] - mu) * rs;
-          out[i] += rs * (dv[i] * gv[i] - c1 - xh * c2);
+          out[it][i] += rs * (dv[it][i] * gv[it][i] - c1 - xh[it][i] * c2);
+          ac[it][i] += to_f32(from_f32<T>(out[it][i]));
         }
-        store_vec16(dxr + c, out);
+        store_vec16(dxr + c, out[it]);
       }
     }
   }
-  // combine the four waves' column sums in wave order: each wave in turn adds into a [2][d] LDS row
+  // combine the four waves' column sums in wave order: each wave in turn adds into a [3][d] LDS row
   extern __shared__ float cols[];
   for (int w = 0; w < ROWS_PER_BLOCK; ++w) {
     if (wave == w) {
@@ -158,23 +158,24 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
         if (c < d) {
 #pragma unroll
           for (int i = 0; i < VEC; ++i) {
-            if (w == 0) { cols[c + i] = ag[it][i]; cols[d + c + i] = ab[it][i]; }
-            else { cols[c + i] += ag[it][i]; cols[d + c + i] += ab[it][i]; }
+            if (w == 0) { cols[c + i] = ag[it][i]; cols[d + c + i] = ab[it][i]; cols[2 * d + c + i] = ac[it][i]; }
+            else { cols[c + i] += ag[it][i]; cols[d + c + i] += ab[it][i]; cols[2 * d + c + i] += ac[it][i]; }
           }
         }
       }
     }
     __syncthreads();
   }
-  float* out = partial + (size_t)blockIdx.x * 2 * d;
-  for (int c = threadIdx.x; c < 2 * d; c += ROW_THREADS) out[c] = cols[c];
+  float* out = partial + (size_t)blockIdx.x * 3 * d;
+  for (int c = threadIdx.x; c < 3 * d; c += ROW_THREADS) out[c] = cols[c];
 }
 
 // out[c] = sum over p of partial[p * stride + c].  64 columns x 4 partial phases per workgroup: phase y adds
 // partials y, y+4, ... in order, then the four phase sums are added in phase order (a fixed tree).
+// Column c goes to out0 / out1 / out2 by c / d (a null output is skipped).
 __global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restrict__ partial, float* __restrict__ out0,
-                                                           float* __restrict__ out1, int n_partials, int stride,
-                                                           int d) {
+                                                           float* __restrict__ out1, float* __restrict__ out2,
+                                                           int n_partials, int stride, int d) {
   __shared__ float red[4][64];
   const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + x;
@@ -193,7 +194,8 @@ __global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restri
   if (y == 0 && c < stride) {
     const float t = ((red[0][x] + red[1][x]) + red[2][x]) + red[3][x];
     if (c < d) out0[c] = t;
-    else out1[c - d] = t;
+    else if (c < 2 * d) out1[c - d] = t;
+    else if (out2) out2[c - 2 * d] = t;
   }
 }
 
@@ -527,21 +529,29 @@ dipaco_status launch_layernorm_fwd(const T* x, const T* g, const T* b, T* y, flo
 }
 
 size_t ln_bwd_partial_floats(int rows, int d) {
-  return (size_t)((rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS) * 2 * d;
+  return (size_t)((rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS) * 3 * d;
 }
 
 template <typename T>
 dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const float* mean, const float* rstd,
-                                   const T* resid_grad, T* dx, float* dg, float* db, float* partial, int rows,
-                                   int d, hipStream_t s) {
+                                   const T* resid_grad, T* dx, float* dg, float* db, float* dcol, float* partial,
+                                   int rows, int d, hipStream_t s) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int NIT = (sizeof(T) == 4) ? 2 * LN_MAX_IT : LN_MAX_IT;
   if (d > WAVE * VEC * NIT) return fail(DIPACO_ESHAPE, "layernorm backward: d_model above 2048");
   const int blocks = (rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS;
-  ln_bwd_kernel<T><<<blocks, ROW_THREADS, 2 * d * sizeof(float), s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial,
-                                                                     rows, d);
+  const size_t lds = 3 * d * sizeof(float);
+  // the kernel keeps NIT chunks per lane of seven row-shaped quantities in registers: narrow models take the
+  // instantiation with half (a quarter) of them and twice (four times) the waves per SIMD
+  if (d <= WAVE * VEC * NIT / 4)
+    ln_bwd_kernel<T, NIT / 4><<<blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d);
+  else if (d <= WAVE * VEC * NIT / 2)
+    ln_bwd_kernel<T, NIT / 2><<<blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d);
+  else
+    ln_bwd_kernel<T, NIT><<<blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d);
   DIPACO_LAUNCH_CHECK();
-  sum_partials_kernel<<<(2 * d + 63) / 64, 256, 0, s>>>(partial, dg, db, blocks, 2 * d, d);
+  const int ncols = dcol ? 3 * d : 2 * d;
+  sum_partials_kernel<<<(ncols + 63) / 64, 256, 0, s>>>(partial, dg, db, dcol, blocks, 3 * d, d);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -555,7 +565,7 @@ dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, in
   dim3 grid((cols + WAVE * VEC - 1) / (WAVE * VEC), chunks);
   colsum_kernel<T><<<grid, ROW_THREADS, 0, s>>>(x, partial, rows, cols);
   DIPACO_LAUNCH_CHECK();
-  sum_partials_kernel<<<(cols + 63) / 64, 256, 0, s>>>(partial, out, out, chunks, cols, cols);
+  sum_partials_kernel<<<(cols + 63) / 64, 256, 0, s>>>(partial, out, out, nullptr, chunks, cols, cols);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -612,7 +622,7 @@ dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, flo
   template dipaco_status launch_layernorm_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float,  \
                                                  hipStream_t);                                                      \
   template dipaco_status launch_layernorm_bwd<T>(const T*, const T*, const T*, const float*, const float*, const T*, \
-                                                 T*, float*, float*, float*, int, int, hipStream_t);                \
+                                                 T*, float*, float*, float*, float*, int, int, hipStream_t);        \
   template dipaco_status launch_colsum<T>(const T*, float*, float*, int, int, hipStream_t);                          \
   template dipaco_status launch_softmax_xent<T>(T*, const int*, const int*, float*, int, int, hipStream_t);          \
   template dipaco_status launch_embed_bwd<T>(const T*, const int*, float*, float*, int*, int, int, int, int, int,    \
