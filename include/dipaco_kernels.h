@@ -20,7 +20,8 @@ extern "C" {
  *   trans_a = 0: A is [M,K] row-major; 1: A is [K,M] row-major.   trans_b = 0: B is [K,N]; 1: B is [N,K].
  *   Supported: (0,0) forward, (0,1) input gradient, (1,0) with out_f32 = 1 weight gradient.
  * Epilogue in this order, each optional: + bias[N];  act = 1: aux_out[M,N] = value, value = GELU(value);
- * act = 2: value *= GELU'(aux_in[M,N]);  + resid[M,N].  out_f32 = 1: C is fp32, else dtype.
+ * act = 2: value *= GELU'(aux_in[M,N]);  act = 3: aux_out[M,N] = GELU'(value), value = GELU(value);
+ * act = 4: value *= aux_in[M,N];  + resid[M,N].  out_f32 = 1: C is fp32, else dtype.
  * splits > 1 (needs out_f32, no epilogue): K is cut into ranges whose partial products are written to
  * partial ([splits, M, N] fp32) and summed in index order.  The contiguous extent of each operand must be a
  * multiple of 16 bytes. */

@@ -155,8 +155,9 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
                 nullptr, 0, false, 1, nullptr, st));
     TRY(launch_layernorm_fwd<T>(buf(L.x_mid), W + o.ln2_g, W + o.ln2_b, buf(L.h2), fbuf(L.mean2), fbuf(L.rstd2), T_, d,
                                 a.ln_eps, st));
+    // L.u receives GELU'(pre-activation), the only thing the backward pass needs of it
     TRY(gemm<T>(buf(L.h2), W + o.w_up, buf(L.act), T_, F, d, d, F, F, false, false, W + o.b_up, nullptr, buf(L.u),
-                nullptr, 1, false, 1, nullptr, st));
+                nullptr, 3, false, 1, nullptr, st));
     TRY(gemm<T>(buf(L.act), W + o.w_down, x_next, T_, d, F, F, d, d, false, false, W + o.b_down, buf(L.x_mid), nullptr,
                 nullptr, 0, false, 1, nullptr, st));
   }
@@ -185,7 +186,7 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
     const BlockOff& o = c->blocks[l];
     // x_next = x_mid + gelu(u) W_down + b_down
     TRY(dweight(buf(L.act), dx, o.w_down, F, d));
-    TRY(gemm<T>(dx, W + o.w_down, buf(p.du), T_, F, d, d, d, F, false, true, nullptr, nullptr, nullptr, buf(L.u), 2,
+    TRY(gemm<T>(dx, W + o.w_down, buf(p.du), T_, F, d, d, d, F, false, true, nullptr, nullptr, nullptr, buf(L.u), 4,
                 false, 1, nullptr, st));
     TRY(dweight(buf(L.h2), buf(p.du), o.w_up, d, F));
     TRY(launch_colsum<T>(buf(p.du), G + o.b_up, csp, T_, F, st));

@@ -88,6 +88,19 @@ template <> __device__ __forceinline__ float gelu_t<bf16>(float u) {
   normal_cdf_fast(u, cdf, gauss);
   return u * cdf;
 }
+// GELU(u) and GELU'(u) together (they share the normal distribution function and density)
+template <typename T> __device__ __forceinline__ float gelu_with_grad_t(float u, float& grad);
+template <> __device__ __forceinline__ float gelu_with_grad_t<float>(float u, float& grad) {
+  const float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
+  grad = cdf + u * 0.39894228040143268f * __expf(-0.5f * u * u);
+  return u * cdf;
+}
+template <> __device__ __forceinline__ float gelu_with_grad_t<bf16>(float u, float& grad) {
+  float cdf, gauss;
+  normal_cdf_fast(u, cdf, gauss);
+  grad = __builtin_fmaf(u * 0.39894228040143268f, gauss, cdf);
+  return u * cdf;
+}
 template <typename T> __device__ __forceinline__ float gelu_grad_t(float u);
 template <> __device__ __forceinline__ float gelu_grad_t<float>(float u) { return gelu_grad_f(u); }
 template <> __device__ __forceinline__ float gelu_grad_t<bf16>(float u) {

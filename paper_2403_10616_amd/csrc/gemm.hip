@@ -286,6 +286,10 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s
   if (!aligned16(a.A) || !aligned16(a.B) || !aligned16(a.C) || !aligned16(a.bias) || !aligned16(a.resid) ||
       !aligned16(a.aux_in) || !aligned16(a.aux_out) || !aligned16(a.partial))
     return fail(DIPACO_EALIGN, "gemm: operand not 16-byte aligned");
+  if (a.act < 0 || a.act > 4) return fail(DIPACO_EINVAL, "gemm: act must be 0..4");
+  if ((a.act == 1 || a.act == 3) && !a.aux_out) return fail(DIPACO_EINVAL, "gemm: act 1 / 3 need aux_out");
+  if ((a.act == 2 || a.act == 4) && !a.aux_in) return fail(DIPACO_EINVAL, "gemm: act 2 / 4 need aux_in");
+  if (a.out_f32 && (a.bias || a.resid || a.act)) return fail(DIPACO_EINVAL, "gemm: fp32 output takes no epilogue");
   if (a.splits > 1 && (!a.out_f32 || a.bias || a.resid || a.act || !a.partial))
     return fail(DIPACO_EINVAL, "gemm: split-K needs fp32 output, a partial buffer and no epilogue");
   if constexpr (std::is_same<T, bf16>::value) {

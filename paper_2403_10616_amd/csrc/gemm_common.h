@@ -82,7 +82,9 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
 #pragma unroll
       for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
+    // not unrolled on purpose: the body is long, and unrolled ITERS x TM times it outgrows the compiler's limit for
+    // honouring the unroll of the loop over i above, after which acc would be indexed at run time (scratch memory)
+#pragma unroll 1
     for (int it = 0; it < ITERS; ++it) {
       const int item = lane + WAVE * it;
       const int rr = item / GROUPS, cg = item % GROUPS;
@@ -121,6 +123,16 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
           OutVec<T>::load(aux_in + off, u);
 #pragma unroll
           for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_t<T>(u[c]);
+        } else if (g.act == 3) {
+          float dv[8];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] = gelu_with_grad_t<T>(v[c], dv[c]);
+          OutVec<T>::store(aux_out + off, dv);
+        } else if (g.act == 4) {
+          float u[8];
+          OutVec<T>::load(aux_in + off, u);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] *= u[c];
         }
         if (resid) {
           float rv[8];
@@ -140,6 +152,12 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
             x = gelu_t<T>(to_f32(pre));
           } else if (g.act == 2) {
             x *= gelu_grad_t<T>(to_f32(aux_in[off + c]));
+          } else if (g.act == 3) {
+            float dv;
+            x = gelu_with_grad_t<T>(x, dv);
+            aux_out[off + c] = from_f32<T>(dv);
+          } else if (g.act == 4) {
+            x *= to_f32(aux_in[off + c]);
           }
           if (resid) x += to_f32(resid[off + c]);
           static_cast<TC*>(g.C)[off + c] = from_f32<TC>(x);

@@ -29,7 +29,9 @@ dipaco_status launch_route(const float* z, const float* c, int64_t N, int D, int
 //   trans_a = 0: A is [M,K] row-major (lda);  1: A is [K,M] row-major (lda)
 //   trans_b = 0: B is [K,N] row-major (ldb);  1: B is [N,K] row-major (ldb)
 // Epilogue (all optional, applied in this order): + bias[n];  act = 1: aux_out = value, value = GELU(value);
-// act = 2: value *= GELU'(aux_in);  + resid[m,n].  aux and resid have row stride ldc.
+// act = 2: value *= GELU'(aux_in);  act = 3: aux_out = GELU'(value), value = GELU(value);  act = 4: value *= aux_in;
+// + resid[m,n].  aux and resid have row stride ldc.  (The path step uses the pair 3 / 4: the forward pass leaves the
+// derivative itself, which it gets almost for free beside GELU, and the backward epilogue is one multiplication.)
 // out_f32 = 1 writes fp32 (used for weight gradients), else T.
 // splits > 1 (only with out_f32 and no epilogue): K is cut into `splits` ranges whose partial products go to
 // `partial` ([splits, M, N] fp32) and are then summed in index order.

@@ -62,6 +62,13 @@ def test_gemm_forward_layout_with_epilogues(dtype, M, N, K, gemm_tile):
     u_seen = host(U).astype(np.float64)
     g_ref = 0.5 * u_seen * (1 + erf(u_seen / math.sqrt(2)))
     assert rel_l2(host(C), g_ref) <= tol
+    # bias + GELU, derivative saved (what the path step uses): both from the unrounded pre-activation
+    dp.dipaco_k_gemm(dtype, False, False, False, M, N, K, A, B, C, bias=bias, aux_out=U, act=3)
+    assert rel_l2(host(C), 0.5 * u_ref * (1 + erf(u_ref / math.sqrt(2)))) <= tol
+    d_ref = 0.5 * (1 + erf(u_ref / math.sqrt(2))) + u_ref * np.exp(-0.5 * u_ref * u_ref) / math.sqrt(2 * math.pi)
+    assert rel_l2(host(U), d_ref) <= tol
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_k_gemm(dtype, False, False, False, M, N, K, A, B, C, act=1)   # no aux_out: refused on the host
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
@@ -79,6 +86,8 @@ def test_gemm_input_gradient_layout(dtype, M, N, K, gemm_tile):
     dp.dipaco_k_gemm(dtype, False, True, False, M, N, K, A, Bt, C, aux_in=U, act=2)
     gp = 0.5 * (1 + erf(Ur / math.sqrt(2))) + Ur * np.exp(-0.5 * Ur * Ur) / math.sqrt(2 * math.pi)
     assert rel_l2(host(C), ref * gp) <= tol
+    dp.dipaco_k_gemm(dtype, False, True, False, M, N, K, A, Bt, C, aux_in=U, act=4)   # plain multiplication
+    assert rel_l2(host(C), ref * Ur) <= tol
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
