@@ -24,7 +24,7 @@ extern "C" {
  * act = 4: value *= aux_in[M,N];  + resid[M,N].  out_f32 = 1: C is fp32, else dtype.
  * splits > 1 (needs out_f32, no epilogue): K is cut into ranges whose partial products are written to
  * partial ([splits, M, N] fp32) and summed in index order.  The contiguous extent of each operand must be a
- * multiple of 16 bytes. */
+ * multiple of 16 bytes and N a multiple of 8. */
 dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t out_f32, int32_t M, int32_t N,
                             int32_t K, const void* A, const void* B, void* C, const void* bias, const void* resid,
                             void* aux_out, const void* aux_in, int32_t act, int32_t splits, float* partial,

@@ -279,7 +279,7 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s
   // 16-byte vectors run along the contiguous index of each operand and along the rows of C
   if ((a.trans_a ? a.M : a.K) % VEC || (a.trans_b ? a.K : a.N) % VEC || a.lda % VEC || a.ldb % VEC)
     return fail(DIPACO_ESHAPE, "gemm: contiguous extents and leading dimensions must be multiples of 16 bytes");
-  if (a.ldc % 8) return fail(DIPACO_ESHAPE, "gemm: ldc must be a multiple of 8");
+  if (a.ldc % 8 || a.N % 8) return fail(DIPACO_ESHAPE, "gemm: N and ldc must be multiples of 8");
   // per-thread element offsets are 32-bit
   const long ext_a = (a.trans_a ? 64 : (long)a.M) * a.lda + a.M, ext_b = (a.trans_b ? (long)a.N : 64) * a.ldb + a.N;
   if (ext_a >= (1L << 32) || ext_b >= (1L << 32)) return fail(DIPACO_ESHAPE, "gemm: operand above 2^32 elements");

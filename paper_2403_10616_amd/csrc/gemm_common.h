@@ -58,9 +58,26 @@ __device__ __forceinline__ void gemm_tile_of_block(const GemmDev& g, int bid, in
   tile_n = in_group / gsize;
 }
 
+// Eight consecutive elements of T as raw 16-byte vectors (loaded early, converted when used).
+template <typename T> struct Raw8 { uint4 v[sizeof(T) / 2]; };
+template <typename T> __device__ __forceinline__ Raw8<T> raw8_load(const T* p) {
+  Raw8<T> r;
+#pragma unroll
+  for (int k = 0; k < (int)sizeof(T) / 2; ++k) r.v[k] = reinterpret_cast<const uint4*>(p)[k];
+  return r;
+}
+template <typename T> __device__ __forceinline__ void raw8_unpack(const Raw8<T>& r, float (&out)[8]) {
+  const T* e = reinterpret_cast<const T*>(&r);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) out[c] = to_f32(e[c]);
+}
+
 // Epilogue of one wave: its TM x TN accumulator tiles (32 x 32 each, rows from row0, columns from col0) go
 // through stg, a wave-private LDS region of 32 x (WN + 4) floats, 32 rows at a time, so that bias / GELU /
-// residual are applied on, and C is written with, 16-byte row-contiguous accesses.
+// residual are applied on, and C is written with, 16-byte row-contiguous accesses.  N is a multiple of 8 (checked
+// on the host), so an 8-column group is either inside C or outside.  The residual / auxiliary input vectors of a
+// block of 32 rows are requested before its accumulators are staged, so that their latency is paid once per block
+// and mostly behind the staging, not once per vector.
 template <typename T, typename TC, int TM, int TN, int WN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0, int col0,
                                               int split, const GemmDev& g) {
@@ -74,17 +91,27 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
   T* aux_out = static_cast<T*>(g.aux_out);
   const bool to_partial = g.splits > 1;
   float* P = to_partial ? g.partial + (size_t)split * g.M * g.N : nullptr;
+  const bool want_aux = g.act == 2 || g.act == 4;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    Raw8<T> rres[ITERS], raux[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int item = lane + WAVE * it;
+      const int row = row0 + 32 * i + item / GROUPS, col = col0 + 8 * (item % GROUPS);
+      if (row < g.M && col < g.N) {
+        const size_t off = (size_t)row * g.ldc + col;
+        if (resid) rres[it] = raw8_load(resid + off);
+        if (want_aux) raux[it] = raw8_load(aux_in + off);
+      }
+    }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
     __builtin_amdgcn_wave_barrier();
-    // not unrolled on purpose: the body is long, and unrolled ITERS x TM times it outgrows the compiler's limit for
-    // honouring the unroll of the loop over i above, after which acc would be indexed at run time (scratch memory)
-#pragma unroll 1
+#pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       const int item = lane + WAVE * it;
       const int rr = item / GROUPS, cg = item % GROUPS;
@@ -94,75 +121,40 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
       const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
       float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       if (row >= g.M || col >= g.N) continue;
-      const bool full = col + 8 <= g.N;
       if (to_partial) {
-        float* dst = P + (size_t)row * g.N + col;
-        if (full && (g.N & 3) == 0) OutVec<float>::store(dst, v);
-        else {
-#pragma unroll
-          for (int c = 0; c < 8; ++c)
-            if (col + c < g.N) dst[c] = v[c];
-        }
+        OutVec<float>::store(P + (size_t)row * g.N + col, v);
         continue;
       }
       const size_t off = (size_t)row * g.ldc + col;
-      if (full) {
-        if (bias) {
-          float b[8];
-          OutVec<T>::load(bias + col, b);
+      if (bias) {
+        float b[8];
+        OutVec<T>::load(bias + col, b);
 #pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] += b[c];
-        }
-        if (g.act == 1) {
-          // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
-          OutVec<T>::store(aux_out + off, v);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] = gelu_t<T>(to_f32(from_f32<T>(v[c])));
-        } else if (g.act == 2) {
-          float u[8];
-          OutVec<T>::load(aux_in + off, u);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] *= gelu_grad_t<T>(u[c]);
-        } else if (g.act == 3) {
-          float dv[8];
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] = gelu_with_grad_t<T>(v[c], dv[c]);
-          OutVec<T>::store(aux_out + off, dv);
-        } else if (g.act == 4) {
-          float u[8];
-          OutVec<T>::load(aux_in + off, u);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] *= u[c];
-        }
-        if (resid) {
-          float rv[8];
-          OutVec<T>::load(resid + off, rv);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] += rv[c];
-        }
-        OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
-      } else {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          if (col + c >= g.N) break;
-          float x = v[c] + (bias ? to_f32(bias[col + c]) : 0.f);
-          if (g.act == 1) {
-            const T pre = from_f32<T>(x);
-            aux_out[off + c] = pre;
-            x = gelu_t<T>(to_f32(pre));
-          } else if (g.act == 2) {
-            x *= gelu_grad_t<T>(to_f32(aux_in[off + c]));
-          } else if (g.act == 3) {
-            float dv;
-            x = gelu_with_grad_t<T>(x, dv);
-            aux_out[off + c] = from_f32<T>(dv);
-          } else if (g.act == 4) {
-            x *= to_f32(aux_in[off + c]);
-          }
-          if (resid) x += to_f32(resid[off + c]);
-          static_cast<TC*>(g.C)[off + c] = from_f32<TC>(x);
-        }
+        for (int c = 0; c < 8; ++c) v[c] += b[c];
       }
+      if (g.act == 1) {
+        // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
+        OutVec<T>::store(aux_out + off, v);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] = gelu_t<T>(to_f32(from_f32<T>(v[c])));
+      } else if (g.act == 3) {
+        float dv[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] = gelu_with_grad_t<T>(v[c], dv[c]);
+        OutVec<T>::store(aux_out + off, dv);
+      } else if (want_aux) {
+        float u[8];
+        raw8_unpack(raux[it], u);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] *= g.act == 2 ? gelu_grad_t<T>(u[c]) : u[c];
+      }
+      if (resid) {
+        float rv[8];
+        raw8_unpack(rres[it], rv);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] += rv[c];
+      }
+      OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
     }
   }
 }
