@@ -142,6 +142,31 @@ dipaco_status dipaco_module_outer_step(float* theta, float* momentum, const floa
 dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_t N, int32_t D, int32_t K,
                                   int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream);
 
+/* The same assignment with a row stride and, optionally, the two closest centroids.
+ *   z          device fp32, row n at z + n * ldz (ldz >= D, multiple of 4): a column block of a wider feature matrix
+ *              can be routed in place, which is all that product k-means needs (appendix on product k-means: route
+ *              the first and the second half of the features against their own centroid sets; the pair of indices
+ *              is the path's module tuple, see dipaco_path_index).
+ *   n_best = 1: idx_out int32 [N] as above.
+ *   n_best = 2: idx_out int32 [N, 2] = the closest and the second closest centroid (the top-2 overlapping shards of
+ *              Section 2.4.4; second entry -1 when K = 1), ties to the lower index; hist_out[k] counts the documents
+ *              that have k as either choice, i.e. the sizes of the overlapping shards.
+ *   margin_out as above (second-best minus best score) in both modes. */
+dipaco_status dipaco_route_prefix_top(const float* z, int64_t ldz, const float* centroids, int64_t N, int32_t D,
+                                      int32_t K, int32_t n_best, int32_t* idx_out, int64_t* hist_out, float* margin_out,
+                                      void* stream);
+
+/* One k-means update ("we perform k-Means on the features z", Section 2.4.1; with dipaco_route_prefix as the
+ * assignment step this is one Lloyd iteration): centroids[k] <- mean of the rows z_n with idx[n] = k, in place; a
+ * centroid without rows keeps its value.  idx values are clamped to [0, K).  counts_out: device int64 [K] or NULL.
+ * The sums are formed in a fixed order (stable counting sort by cluster, partial sums of 512 rows added in order):
+ * results are bit-reproducible.  workspace: device, >= dipaco_kmeans_workspace_bytes(N, D, K) bytes.
+ * D multiple of 4, 1 <= K <= 4096. */
+size_t dipaco_kmeans_workspace_bytes(int64_t N, int32_t D, int32_t K);
+dipaco_status dipaco_kmeans_update(const float* z, int64_t ldz, const int32_t* idx, int64_t N, int32_t D, int32_t K,
+                                   float* centroids, int64_t* counts_out, void* workspace, size_t workspace_bytes,
+                                   void* stream);
+
 #ifdef __cplusplus
 }
 #endif

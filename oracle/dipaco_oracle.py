@@ -434,3 +434,51 @@ def route_prefix(z, centroids):
             margin[n] = np.inf
     hist = np.bincount(idx, minlength=K).astype(np.int64)
     return idx, hist, margin
+
+
+def route_prefix_top2(z, centroids):
+    """The two closest centroids of every row (overlapping shards, Section 2.4.4: "we use the top-2 choices").
+
+    idx2[n] = (closest, second closest) under the order (squared distance, index): exact ties go to the lower
+    index; the second entry is -1 when there is only one centroid.  hist[k] = number of rows that have k as either
+    choice (the sizes of the overlapping shards)."""
+    z = np.asarray(z, dtype=F64)
+    c = np.asarray(centroids, dtype=F64)
+    N, K = z.shape[0], c.shape[0]
+    idx2 = np.full((N, 2), -1, dtype=np.int32)
+    for n in range(N):
+        diff = z[n][None, :] - c
+        d = (diff * diff).sum(axis=1)
+        first = int(np.argmin(d))                 # the first minimiser
+        idx2[n, 0] = first
+        if K > 1:
+            d2 = d.copy()
+            d2[first] = np.inf
+            idx2[n, 1] = int(np.argmin(d2))       # the first minimiser among the others
+    hist = np.bincount(idx2[idx2 >= 0], minlength=K).astype(np.int64)
+    return idx2, hist
+
+
+def kmeans_update(z, idx, centroids_prev):
+    """The update half of a k-means (Lloyd) iteration (Section 2.4.1 fits the prototypes c_1..c_k by k-means):
+    every centroid becomes the mean of the rows assigned to it; one without rows keeps its value.
+    Returns (centroids, counts)."""
+    z = np.asarray(z, dtype=F64)
+    idx = np.asarray(idx)
+    c = np.array(centroids_prev, dtype=F64, copy=True)
+    K = c.shape[0]
+    counts = np.zeros(K, dtype=np.int64)
+    for k in range(K):
+        rows = z[idx == k]
+        counts[k] = rows.shape[0]
+        if rows.shape[0] > 0:
+            c[k] = rows.sum(axis=0) / rows.shape[0]
+    return c, counts
+
+
+def kmeans_objective(z, idx, centroids):
+    """sum_n ||z_n - c_idx[n]||^2: what both halves of a Lloyd iteration can only lower."""
+    z = np.asarray(z, dtype=F64)
+    c = np.asarray(centroids, dtype=F64)
+    diff = z - c[np.asarray(idx)]
+    return float((diff * diff).sum())

@@ -52,6 +52,11 @@ _SIGS = {
                                            C.c_int32, C.c_size_t, C.c_int32, C.c_float, C.c_float, C.c_void_p]),
     "dipaco_route_prefix": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
+    "dipaco_route_prefix_top": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dipaco_kmeans_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int32, C.c_int32]),
+    "dipaco_kmeans_update": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "dipaco_k_gemm": (C.c_int, [C.c_int32] * 7 + [C.c_void_p] * 7 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dipaco_k_set_gemm_tile": (C.c_int, [C.c_int32]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
@@ -203,6 +208,32 @@ def dipaco_module_outer_step(theta, momentum, inputs, weights, n_elems: int, is_
 def dipaco_route_prefix(z, centroids, N: int, D: int, K: int, idx_out, hist_out, margin_out=None, stream=None):
     _check(load().dipaco_route_prefix(_ptr(z), _ptr(centroids), N, D, K, _ptr(idx_out), _ptr(hist_out),
                                       _ptr(margin_out), _stream(stream)))
+
+
+def _ptr_at(t, offset_elems: int = 0) -> Optional[int]:
+    """data pointer of a device tensor plus an element offset (a view's storage need not be contiguous)"""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise DipacoError("expected a device tensor")
+    return t.data_ptr() + offset_elems * t.element_size()
+
+
+def dipaco_route_prefix_top(z, ldz: int, centroids, N: int, D: int, K: int, n_best: int, idx_out, hist_out,
+                            margin_out=None, stream=None, z_offset: int = 0):
+    """z: device tensor holding the feature matrix; row n starts z_offset + n * ldz elements into it"""
+    _check(load().dipaco_route_prefix_top(_ptr_at(z, z_offset), ldz, _ptr(centroids), N, D, K, n_best, _ptr(idx_out),
+                                          _ptr(hist_out), _ptr(margin_out), _stream(stream)))
+
+
+def dipaco_kmeans_workspace_bytes(N: int, D: int, K: int) -> int:
+    return load().dipaco_kmeans_workspace_bytes(N, D, K)
+
+
+def dipaco_kmeans_update(z, ldz: int, idx, N: int, D: int, K: int, centroids, counts_out, workspace, stream=None,
+                         z_offset: int = 0):
+    _check(load().dipaco_kmeans_update(_ptr_at(z, z_offset), ldz, _ptr(idx), N, D, K, _ptr(centroids), _ptr(counts_out),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 # ---- kernel-level entry points ---------------------------------------------------------------------------

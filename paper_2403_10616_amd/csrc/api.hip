@@ -434,8 +434,49 @@ dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_
     TRY(check_ptr(z, "z"));
     TRY(check_ptr(idx_out, "idx_out"));
   }
-  return launch_route(z, centroids, N, D, K, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
+  return launch_route(z, D, centroids, N, D, K, 1, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
                       static_cast<hipStream_t>(stream));
+}
+
+dipaco_status dipaco_route_prefix_top(const float* z, int64_t ldz, const float* centroids, int64_t N, int32_t D,
+                                      int32_t K, int32_t n_best, int32_t* idx_out, int64_t* hist_out, float* margin_out,
+                                      void* stream) {
+  if (N < 0) return fail(DIPACO_EINVAL, "N must be >= 0");
+  if (D < 4 || D % 4) return fail(DIPACO_ESHAPE, "D must be a positive multiple of 4");
+  if (ldz < D || ldz % 4) return fail(DIPACO_ESHAPE, "ldz must be a multiple of 4, at least D");
+  if (K < 1 || K > 4096) return fail(DIPACO_ESHAPE, "K must be in [1, 4096]");
+  if (n_best != 1 && n_best != 2) return fail(DIPACO_EINVAL, "n_best must be 1 or 2");
+  TRY(check_ptr(centroids, "centroids"));
+  TRY(check_ptr(hist_out, "hist_out"));
+  if (N > 0) {
+    TRY(check_ptr(z, "z"));
+    TRY(check_ptr(idx_out, "idx_out"));
+  }
+  return launch_route(z, ldz, centroids, N, D, K, n_best, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
+                      static_cast<hipStream_t>(stream));
+}
+
+size_t dipaco_kmeans_workspace_bytes(int64_t N, int32_t D, int32_t K) {
+  if (N < 0 || D < 1 || K < 1) return 0;
+  return kmeans_workspace_bytes((long)N, D, K);
+}
+
+dipaco_status dipaco_kmeans_update(const float* z, int64_t ldz, const int32_t* idx, int64_t N, int32_t D, int32_t K,
+                                   float* centroids, int64_t* counts_out, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  if (N < 0 || N > 0x7fff0000LL) return fail(DIPACO_EINVAL, "N must be in [0, 2^31 - 65536]");
+  if (D < 4 || D % 4) return fail(DIPACO_ESHAPE, "D must be a positive multiple of 4");
+  if (ldz < D || ldz % 4) return fail(DIPACO_ESHAPE, "ldz must be a multiple of 4, at least D");
+  if (K < 1 || K > 4096) return fail(DIPACO_ESHAPE, "K must be in [1, 4096]");
+  TRY(check_ptr(centroids, "centroids"));
+  TRY(check_ptr(workspace, "workspace"));
+  if (workspace_bytes < kmeans_workspace_bytes((long)N, D, K)) return fail(DIPACO_EWORKSPACE, "workspace too small");
+  if (N > 0) {
+    TRY(check_ptr(z, "z"));
+    TRY(check_ptr(idx, "idx"));
+  }
+  return launch_kmeans_update(z, (long)ldz, idx, (long)N, D, K, centroids, reinterpret_cast<long long*>(counts_out),
+                              workspace, static_cast<hipStream_t>(stream));
 }
 
 // ---- kernel-level entry points (include/dipaco_kernels.h) -------------------------------------------------

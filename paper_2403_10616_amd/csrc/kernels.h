@@ -21,8 +21,24 @@ dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s);
 dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s);
 
 // ---- route.hip ---------------------------------------------------------------------------------------
-dipaco_status launch_route(const float* z, const float* c, int64_t N, int D, int K, int* idx, long long* hist,
-                           float* margin, hipStream_t s);
+// z row n at z + n * ldz;  n_best = 1: idx [N];  n_best = 2: idx [N, 2] (best, second best; -1 if K = 1), hist
+// counts both memberships
+dipaco_status launch_route(const float* z, int64_t ldz, const float* c, int64_t N, int D, int K, int n_best, int* idx,
+                           long long* hist, float* margin, hipStream_t s);
+
+// ---- kmeans.hip --------------------------------------------------------------------------------------
+// order[0..n) = the indices 0..n-1 stably sorted by keys[i] (clamped to [0, n_keys), n_keys <= 65536);
+// scratch: sort_scratch_ints(n, n_keys) ints
+size_t sort_scratch_ints(long n, int n_keys);
+dipaco_status launch_stable_sort_indices(const int* keys, long n, int n_keys, int* order, int* scratch, hipStream_t s);
+// start[k] = number of keys below k, k = 0..n_keys (count: [n_keys] scratch; chunk_start: nullable, [n_keys + 1])
+dipaco_status launch_key_offsets(const int* keys, long n, int n_keys, int* count, int* start, int* chunk_start,
+                                 hipStream_t s);
+// centroids[k] <- mean of the rows z[n] (row stride ldz) with idx[n] = k, in a fixed summation order; clusters
+// without rows keep their centroid.  counts (nullable): rows per cluster.
+size_t kmeans_workspace_bytes(long N, int D, int K);
+dipaco_status launch_kmeans_update(const float* z, long ldz, const int* idx, long N, int D, int K, float* centroids,
+                                   long long* counts, void* workspace, hipStream_t s);
 
 // ---- gemm.hip ----------------------------------------------------------------------------------------
 // C[M,N] = opA(A) . opB(B)  (+ epilogue), fp32 accumulation on the matrix cores.

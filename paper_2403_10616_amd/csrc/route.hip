@@ -19,34 +19,46 @@ constexpr int RBK = 32;    // fp32 K tile
 constexpr int R_STAGE = (RBM + RBN) * TILE_ROW_BYTES;
 constexpr int R_MAX_K_LDS_HIST = 4096;
 
+// Best and second-best (score, index) of a row, ordered lexicographically: exact ties go to the lower index.
+// TOP2 = false: the second index is not tracked (only its score, for the margin).
 struct Best {
-  float s1; int i1; float s2;
+  float s1; int i1; float s2; int i2;
 };
+constexpr int NO_INDEX = 0x7fffffff;
 
-__device__ __forceinline__ void best_insert(Best& b, float s, int i) {
-  if (s < b.s1 || (s == b.s1 && i < b.i1)) { b.s2 = b.s1; b.s1 = s; b.i1 = i; }
-  else if (s < b.s2) b.s2 = s;
+template <bool TOP2> __device__ __forceinline__ void best_insert(Best& b, float s, int i) {
+  if (s < b.s1 || (s == b.s1 && i < b.i1)) {
+    b.s2 = b.s1; b.s1 = s;
+    if (TOP2) b.i2 = b.i1;
+    b.i1 = i;
+  } else if (TOP2 ? (s < b.s2 || (s == b.s2 && i < b.i2)) : s < b.s2) {
+    b.s2 = s;
+    if (TOP2) b.i2 = i;
+  }
 }
-__device__ __forceinline__ void best_merge(Best& a, float s1, int i1, float s2) {
-  if (s1 < a.s1 || (s1 == a.s1 && i1 < a.i1)) { a.s2 = fminf(a.s1, s2); a.s1 = s1; a.i1 = i1; }
-  else a.s2 = fminf(a.s2, s1);
+template <bool TOP2> __device__ __forceinline__ void best_merge(Best& a, float s1, int i1, float s2, int i2) {
+  best_insert<TOP2>(a, s1, i1);
+  best_insert<TOP2>(a, s2, i2);
 }
 
-__global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __restrict__ z, const float* __restrict__ c,
-                                                             long N, int D, int K, int* __restrict__ idx,
+// z: row n at z + n * ldz.  TOP2: idx is [N, 2] (second entry -1 when K = 1) and hist counts both memberships.
+template <bool TOP2>
+__global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __restrict__ z, long ldz,
+                                                             const float* __restrict__ c, long N, int D, int K,
+                                                             int* __restrict__ idx,
                                                              unsigned long long* __restrict__ hist,
                                                              float* __restrict__ margin) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ float cnorm[RBN];
   __shared__ float red_s1[2][RBM], red_s2[2][RBM];
-  __shared__ int red_i1[2][RBM];
+  __shared__ int red_i1[2][RBM], red_i2[TOP2 ? 2 : 1][TOP2 ? RBM : 1];
   __shared__ unsigned int lhist[R_MAX_K_LDS_HIST];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const long m0 = (long)blockIdx.x * RBM;
   const int rows_left = (int)min((long)RBM, N - m0);
-  const float* zb = z + m0 * D;
+  const float* zb = z + m0 * ldz;
   const bool use_lhist = K <= R_MAX_K_LDS_HIST;
   if (use_lhist) for (int k = tid; k < K; k += GEMM_THREADS) lhist[k] = 0;
 
@@ -59,7 +71,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { best[i][e].s1 = INFINITY; best[i][e].i1 = 0x7fffffff; best[i][e].s2 = INFINITY; }
+    for (int e = 0; e < 16; ++e) { best[i][e].s1 = INFINITY; best[i][e].i1 = NO_INDEX; best[i][e].s2 = INFINITY; best[i][e].i2 = NO_INDEX; }
 
   for (int n0 = 0; n0 < K; n0 += RBN) {
     f32x16 acc[2][4];
@@ -76,7 +88,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
     uint4 rz[LZ::NLD], rc[LC::NLD];
     const float* cb = c + (long)n0 * D;
     const int crow_left = min(RBN, K - n0);
-    LZ::load_tail(rz, zb, D, 0, rows_left, 0, D, tid);
+    LZ::load_tail(rz, zb, ldz, 0, rows_left, 0, D, tid);
     LC::load_tail(rc, cb, D, 0, crow_left, 0, D, tid);
     __syncthreads();   // previous centroid tile's readers of LDS and of cnorm are done
     LZ::store(rz, smem, tid, 0, D);
@@ -93,7 +105,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       char* nxt = smem + ((kt + 1) & 1) * R_STAGE;
       const bool more = kt + 1 < nkt;
       if (more) {
-        LZ::load_tail(rz, zb, D, 0, rows_left, (kt + 1) * RBK, D, tid);
+        LZ::load_tail(rz, zb, ldz, 0, rows_left, (kt + 1) * RBK, D, tid);
         LC::load_tail(rc, cb, D, 0, crow_left, (kt + 1) * RBK, D, tid);
       }
       mma_ktile<float, 2, 4>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 128, lane);
@@ -131,7 +143,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           float s = (k < K) ? cn - 2.0f * acc[i][j][e] : INFINITY;
-          best_insert(best[i][e], s, k < K ? k : 0x7fffffff);
+          best_insert<TOP2>(best[i][e], s, k < K ? k : NO_INDEX);
         }
     }
   }
@@ -144,21 +156,34 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       Best b = best[i][e];
 #pragma unroll
       for (int o = 1; o < 32; o <<= 1) {
-        float s1 = __shfl_xor(b.s1, o, WAVE);
-        int i1 = __shfl_xor(b.i1, o, WAVE);
-        float s2 = __shfl_xor(b.s2, o, WAVE);
-        best_merge(b, s1, i1, s2);
+        const float s1 = __shfl_xor(b.s1, o, WAVE);
+        const int i1 = __shfl_xor(b.i1, o, WAVE);
+        const float s2 = __shfl_xor(b.s2, o, WAVE);
+        const int i2 = TOP2 ? __shfl_xor(b.i2, o, WAVE) : NO_INDEX;
+        best_merge<TOP2>(b, s1, i1, s2, i2);
       }
       if ((lane & 31) == 0) {
         const int row = wm * 64 + 32 * i + acc_row(e, lane);
         red_s1[wn][row] = b.s1; red_i1[wn][row] = b.i1; red_s2[wn][row] = b.s2;
+        if (TOP2) red_i2[wn][row] = b.i2;
       }
     }
   __syncthreads();
   if (tid < RBM && tid < rows_left) {
     Best b; b.s1 = red_s1[0][tid]; b.i1 = red_i1[0][tid]; b.s2 = red_s2[0][tid];
-    best_merge(b, red_s1[1][tid], red_i1[1][tid], red_s2[1][tid]);
-    idx[m0 + tid] = b.i1;
+    b.i2 = TOP2 ? red_i2[0][tid] : NO_INDEX;
+    best_merge<TOP2>(b, red_s1[1][tid], red_i1[1][tid], red_s2[1][tid], TOP2 ? red_i2[1][tid] : NO_INDEX);
+    if (TOP2) {
+      const bool has2 = b.i2 != NO_INDEX;
+      idx[2 * (m0 + tid)] = b.i1;
+      idx[2 * (m0 + tid) + 1] = has2 ? b.i2 : -1;
+      if (has2) {
+        if (use_lhist) atomicAdd(&lhist[b.i2], 1u);
+        else atomicAdd(&hist[b.i2], 1ull);
+      }
+    } else {
+      idx[m0 + tid] = b.i1;
+    }
     if (margin) margin[m0 + tid] = b.s2 - b.s1;
     if (use_lhist) atomicAdd(&lhist[b.i1], 1u);
     else atomicAdd(&hist[b.i1], 1ull);
@@ -174,22 +199,25 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
 
 }  // namespace
 
-dipaco_status launch_route(const float* z, const float* c, int64_t N, int D, int K, int* idx, long long* hist,
-                           float* margin, hipStream_t s) {
+dipaco_status launch_route(const float* z, int64_t ldz, const float* c, int64_t N, int D, int K, int n_best, int* idx,
+                           long long* hist, float* margin, hipStream_t s) {
   dipaco_status st = launch_fill_i64(hist, 0, (size_t)K, s);
   if (st != DIPACO_OK) return st;
   if (N == 0) return DIPACO_OK;
   constexpr size_t smem = 2 * (size_t)R_STAGE;
   static bool attr_set = false;
   if (!attr_set) {
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel),
+    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
   const int64_t blocks = (N + RBM - 1) / RBM;
   if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "route: N too large");
-  route_kernel<<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, c, (long)N, D, K, idx,
-                                                           reinterpret_cast<unsigned long long*>(hist), margin);
+  auto* h = reinterpret_cast<unsigned long long*>(hist);
+  if (n_best == 2) route_kernel<true><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, (long)N, D, K, idx, h, margin);
+  else route_kernel<false><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, (long)N, D, K, idx, h, margin);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

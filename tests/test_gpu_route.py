@@ -6,7 +6,7 @@ import torch
 import dipaco_inputs as gen
 import paper_2403_10616_amd as dp
 from oracle import dipaco_oracle as orc
-from gpu_util import DEV, dev, host
+from gpu_util import DEV, dev, host, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -62,3 +62,118 @@ def test_route_exact_ties_pick_lowest_index_and_empty_input():
     assert idx[11] == 4 and hist[11] == 0
     idx, hist, _ = _run(np.zeros((0, 8), np.float32), c)
     assert len(idx) == 0 and np.array_equal(hist, np.zeros(16, np.int64))
+
+
+# ---- top-2 assignment, strided rows (product k-means), k-means update ----------------------------------------------
+def _run_top(z_full, ldz, off, D, c, n_best):
+    N = z_full.shape[0]
+    K = c.shape[0]
+    idx = torch.full((max(N, 1) * n_best,), -9, dtype=torch.int32, device=DEV)
+    hist = torch.full((K,), -7, dtype=torch.int64, device=DEV)
+    margin = torch.zeros(max(N, 1), dtype=torch.float32, device=DEV)
+    dp.dipaco_route_prefix_top(dev(z_full), ldz, dev(c), N, D, K, n_best, idx, hist, margin, z_offset=off)
+    out = host(idx)[:N * n_best]
+    return (out.reshape(N, 2) if n_best == 2 else out), host(hist), host(margin)[:N]
+
+
+@pytest.mark.parametrize("N,D,K", [(1000, 768, 256), (129, 64, 8), (777, 100, 1), (5, 4, 3), (2500, 64, 600)])
+def test_route_top2_matches_oracle(N, D, K):
+    print(f"route top2 N={N} D={D} K={K}", flush=True)
+    z, c, _ = gen.gaussian_mixture(N, D, K, 0.3, seed=14)
+    idx2, hist, margin = _run_top(z, D, 0, D, c, 2)
+    o_idx2, o_hist = orc.route_prefix_top2(z, c)
+    d = ((z.astype(np.float64)[:, None, :] - c.astype(np.float64)[None, :, :]) ** 2).sum(-1) if N * K <= 2_000_000 else None
+    moved = 0
+    for n in range(N):
+        if np.array_equal(idx2[n], o_idx2[n]):
+            continue
+        moved += 1                                  # only near-ties may differ: compare distances, not indices
+        dn = ((z[n].astype(np.float64) - c.astype(np.float64)) ** 2).sum(1) if d is None else d[n]
+        assert idx2[n, 0] != idx2[n, 1]
+        for j in range(2):
+            assert abs(dn[idx2[n, j]] - dn[o_idx2[n, j]]) <= TIE, (n, j)
+    assert moved <= max(2, N // 100)
+    assert np.array_equal(hist, np.bincount(idx2[idx2 >= 0], minlength=K))
+    assert np.abs(hist - o_hist).sum() <= 4 * moved
+    if K > 1:
+        o_margin = orc.route_prefix(z, c)[2]
+        assert np.abs(margin - o_margin).max() <= 2e-4
+    else:
+        assert np.all(idx2[:, 1] == -1) and np.all(np.isinf(margin))
+
+
+def test_route_top2_exact_ties_and_single_best_mode():
+    rng = np.random.default_rng(1)
+    c = rng.integers(-3, 4, size=(16, 8)).astype(np.float32)
+    c[11] = c[4]
+    z = rng.integers(-3, 4, size=(300, 8)).astype(np.float32)
+    idx2, hist, _ = _run_top(z, 8, 0, 8, c, 2)          # small integers: fp32 scores are exact
+    o_idx2, o_hist = orc.route_prefix_top2(z, c)
+    assert np.array_equal(idx2, o_idx2) and np.array_equal(hist, o_hist)
+    idx1, hist1, _ = _run_top(z, 8, 0, 8, c, 1)
+    assert np.array_equal(idx1, o_idx2[:, 0]) and hist1.sum() == 300
+
+
+def test_route_strided_halves_give_product_kmeans_pairs():
+    """Product k-means: the two halves of the features are routed in place against their own centroid sets."""
+    N, D, K = 700, 64, 12
+    z, _, _ = gen.gaussian_mixture(N, D, K, 0.3, seed=15)
+    c1 = gen.gaussian_mixture(1, D // 2, K, 0.3, seed=16)[1]
+    c2 = gen.gaussian_mixture(1, D // 2, K, 0.3, seed=17)[1]
+    i1, _, _ = _run_top(z, D, 0, D // 2, c1, 1)
+    i2, _, _ = _run_top(z, D, D // 2, D // 2, c2, 1)
+    o1, _, m1 = orc.route_prefix(z[:, :D // 2], c1)
+    o2, _, m2 = orc.route_prefix(z[:, D // 2:], c2)
+    assert np.array_equal(i1[m1 > TIE], o1[m1 > TIE]) and np.array_equal(i2[m2 > TIE], o2[m2 > TIE])
+    pair = [dp.dipaco_path_index([int(a), int(b)], [K, K]) for a, b in zip(i1[:5], i2[:5])]
+    assert pair == [int(a) * K + int(b) for a, b in zip(i1[:5], i2[:5])]
+
+
+def _kmeans_gpu(z_full, ldz, off, D, idx, c_prev):
+    N, K = z_full.shape[0], c_prev.shape[0]
+    cd = dev(c_prev.copy())
+    counts = torch.full((K,), -3, dtype=torch.int64, device=DEV)
+    ws = torch.empty(dp.dipaco_kmeans_workspace_bytes(N, D, K), dtype=torch.uint8, device=DEV)
+    zd = dev(z_full) if N else torch.zeros((1, max(ldz, 4)), dtype=torch.float32, device=DEV)
+    idd = dev(idx.astype(np.int32)) if N else torch.zeros(1, dtype=torch.int32, device=DEV)
+    dp.dipaco_kmeans_update(zd, ldz, idd, N, D, K, cd, counts, ws, z_offset=off)
+    return host(cd), host(counts)
+
+
+@pytest.mark.parametrize("N,D,K", [(5000, 768, 256), (3, 4, 2), (2049, 100, 7), (40000, 32, 300), (0, 8, 5),
+                                   (9000, 1028, 3)])
+def test_kmeans_update_matches_oracle(N, D, K):
+    print(f"kmeans update N={N} D={D} K={K}", flush=True)
+    z, c, _ = gen.gaussian_mixture(max(N, 1), D, K, 0.3, seed=24)
+    z = z[:N]
+    rng = np.random.default_rng(25)
+    idx = rng.integers(0, K, size=N)
+    if K > 2 and N > 0:
+        idx[idx == 1] = 0                           # an empty cluster
+    got, counts = _kmeans_gpu(z, D, 0, D, idx, c)
+    want, o_counts = orc.kmeans_update(z, idx, c)
+    assert np.array_equal(counts, o_counts)
+    assert rel_l2(got, want) <= 1e-6
+    assert np.abs(got - want).max() <= 1e-5
+    empty = o_counts == 0
+    assert np.array_equal(got[empty], c[empty])     # untouched, bit for bit
+    again, _ = _kmeans_gpu(z, D, 0, D, idx, c)
+    assert np.array_equal(got, again)               # fixed summation order
+
+
+def test_kmeans_update_strided_rows_and_lloyd_iteration_lowers_objective():
+    N, D, K = 6000, 48, 10
+    z, c_true, _ = gen.gaussian_mixture(N, D, K, 0.3, seed=26)
+    wide = np.zeros((N, 80), dtype=np.float32)
+    wide[:, 16:16 + D] = z
+    wide[:, :16] = 99.0                             # must not be read
+    c = (c_true + 0.3 * np.random.default_rng(27).standard_normal(c_true.shape)).astype(np.float32)
+    prev = np.inf
+    for _ in range(3):
+        idx, _, _ = _run_top(wide, 80, 16, D, c, 1)
+        c, counts = _kmeans_gpu(wide, 80, 16, D, idx, c)
+        obj = orc.kmeans_objective(z, idx, c)
+        assert obj < prev
+        prev = obj
+        want, o_counts = orc.kmeans_update(z, idx, c)   # a fixed point of the update for this assignment
+        assert rel_l2(c, want) <= 1e-6 and np.array_equal(counts, o_counts)

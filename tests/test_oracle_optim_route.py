@@ -201,3 +201,78 @@ def test_route_matches_expanded_square_form_away_from_ties():
     alt = score.argmin(1)
     far = margin > 1e-9
     assert far.sum() > 400 and np.array_equal(idx[far], alt[far])
+
+
+# ---- top-2 assignment and the k-means update ------------------------------------------------------------------
+def test_top2_brute_force_ties_and_relation_to_argmin():
+    rng = np.random.default_rng(5)
+    c = rng.integers(-2, 3, size=(6, 3)).astype(np.float64)
+    c[4] = c[1]                                   # an exact duplicate: ties everywhere it matters
+    z = rng.integers(-2, 3, size=(40, 3)).astype(np.float64)
+    idx2, hist = orc.route_prefix_top2(z, c)
+    for n in range(len(z)):                       # plain loops, (distance, index) pairs sorted as tuples
+        pairs = sorted((sum((z[n][j] - c[k][j]) ** 2 for j in range(3)), k) for k in range(6))
+        assert (idx2[n, 0], idx2[n, 1]) == (pairs[0][1], pairs[1][1])
+    first, _, _ = orc.route_prefix(z, c)
+    assert np.array_equal(idx2[:, 0], first)
+    assert np.all(idx2[:, 0] != idx2[:, 1])
+    assert hist.sum() == 2 * len(z)
+    assert np.array_equal(hist, np.bincount(idx2.ravel(), minlength=6))
+    # the duplicate pair: whenever centroid 1 is closest, the second choice is as close (its copy 4, or another
+    # centroid at that very distance with a lower index)
+    for n in np.nonzero(idx2[:, 0] == 1)[0]:
+        d = ((z[n] - c) ** 2).sum(1)
+        assert d[idx2[n, 1]] == d[1] and idx2[n, 1] <= 4
+
+
+def test_top2_single_centroid_and_point_on_centroid():
+    idx2, hist = orc.route_prefix_top2(np.ones((3, 2)), np.zeros((1, 2)))
+    assert np.array_equal(idx2, [[0, -1]] * 3) and np.array_equal(hist, [3])
+    c = np.array([[0.0, 0.0], [10.0, 0.0], [0.0, 1.0]])
+    idx2, _ = orc.route_prefix_top2(c, c)         # a point on a centroid: itself first, then its nearest neighbour
+    assert np.array_equal(idx2, [[0, 2], [1, 0], [2, 0]])
+
+
+def test_kmeans_update_by_hand_and_empty_cluster():
+    z = np.array([[0.0, 0.0], [2.0, 0.0], [0.0, 4.0], [10.0, 10.0], [1.0, 1.0]])
+    idx = np.array([0, 0, 0, 2, 2])
+    prev = np.array([[9.0, 9.0], [7.0, -7.0], [5.0, 5.0]])
+    c, counts = orc.kmeans_update(z, idx, prev)
+    assert np.array_equal(c[0], [2.0 / 3.0, 4.0 / 3.0])
+    assert np.array_equal(c[1], [7.0, -7.0])       # no rows: keeps its value
+    assert np.array_equal(c[2], [5.5, 5.5])
+    assert np.array_equal(counts, [3, 0, 2])
+    c1, _ = orc.kmeans_update(z[:1], idx[:1], prev)
+    assert np.array_equal(c1[0], z[0])             # one member: the member itself
+
+
+def test_kmeans_update_invariants():
+    rng = np.random.default_rng(6)
+    z = rng.standard_normal((200, 5))
+    idx = rng.integers(0, 7, size=200)
+    prev = rng.standard_normal((7, 5))
+    c, counts = orc.kmeans_update(z, idx, prev)
+    for k in range(7):                             # residuals of a cluster sum to zero (definition of the mean)
+        assert np.abs((z[idx == k] - c[k]).sum(axis=0)).max() < 1e-12
+    assert counts.sum() == 200
+    perm = rng.permutation(200)                    # order of the points is irrelevant
+    c_p, _ = orc.kmeans_update(z[perm], idx[perm], prev)
+    assert np.abs(c_p - c).max() < 1e-13
+    shift = rng.standard_normal(5)                 # translation equivariance
+    c_s, _ = orc.kmeans_update(z + shift, idx, prev + shift)
+    assert np.abs(c_s - (c + shift)).max() < 1e-12
+    # the mean minimises the within-cluster squared error: any other centre is worse
+    assert orc.kmeans_objective(z, idx, c) <= orc.kmeans_objective(z, idx, c + 1e-3 * rng.standard_normal(c.shape))
+
+
+def test_lloyd_iterations_never_raise_the_objective():
+    z, c0, _ = gen.gaussian_mixture(600, 16, 12, 0.3, seed=7, dtype=np.float64)
+    c = c0 + 0.2 * np.random.default_rng(8).standard_normal(c0.shape)
+    prev = np.inf
+    for _ in range(5):
+        idx, _, _ = orc.route_prefix(z, c)
+        after_assign = orc.kmeans_objective(z, idx, c)
+        assert after_assign <= prev + 1e-9
+        c, _ = orc.kmeans_update(z, idx, c)
+        prev = orc.kmeans_objective(z, idx, c)
+        assert prev <= after_assign + 1e-9
