@@ -8,6 +8,7 @@ C-ABI calls dipaco_path_fwd_bwd + dipaco_inner_adamw.  Prints ONE JSON line.
 Other workloads (for profiling single kernels; same JSON shape):
   --workload outer_step   16 deltas x 57,872,640 parameters, weighted mean + Nesterov
   --workload route        2^20 x 768 prefix embeddings against 256 centroids
+  --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
   --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
   --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
 """
@@ -261,6 +262,54 @@ def bench_route(args):
                          "hbm_gbs": (N * D * 4.0 + N * 8.0) / (ms * 1e-3) / 1e9}}
 
 
+def bench_kmeans(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[4]
+    N, D, K = cfg["N"], cfg["D"], cfg["K"]
+    dev = "cuda"
+    z, c, _ = gen.gaussian_mixture(N, D, K, cfg["noise_std"], cfg["seed"])
+    zd, cd = torch.from_numpy(z).to(dev), torch.from_numpy(c).to(dev)
+    nb = args.n_best
+    idx = torch.empty(N * nb, dtype=torch.int32, device=dev)
+    hist = torch.empty(K, dtype=torch.int64, device=dev)
+    counts = torch.empty(K, dtype=torch.int64, device=dev)
+    ws = torch.empty(dp.dipaco_kmeans_workspace_bytes(N, D, K), dtype=torch.uint8, device=dev)
+    idx1 = torch.empty(N, dtype=torch.int32, device=dev)
+    dp.dipaco_route_prefix(zd, cd, N, D, K, idx1, hist, None)
+
+    def assign():
+        dp.dipaco_route_prefix_top(zd, D, cd, N, D, K, nb, idx, hist, None)
+
+    def update():
+        dp.dipaco_kmeans_update(zd, D, idx1, N, D, K, cd, counts, ws)
+    times = {}
+    for name, fn in (("assign", assign), ("update", update)):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        times[name] = e0.elapsed_time(e1) / args.steps
+    ms = times["assign"] + times["update"]
+    upd_bytes = N * D * 4.0 + N * 4.0 * 4 + K * D * 4.0   # the points once; cluster ids read three times, order written
+    ach = upd_bytes / (times["update"] * 1e-3) / 1e9
+    return {"metric": "k-means iteration documents/sec on 1 MI355X", "value": N / (ms * 1e-3), "unit": "documents/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"config 4 data: 1,048,576 x 768 embeddings, 256 centroids; top-{nb} assignment "
+                                   "+ centroid update", "assign_ms": times["assign"], "update_ms": times["update"],
+                       "assign_tflops": 2.0 * N * D * K / (times["assign"] * 1e-3) / 1e12},
+            "roofline": {"bound": "hbm", "kernel": "kmeans_partial_kernel (+ stable sort, finish)", "achieved": ach,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                         "bytes_per_launch": upd_bytes}}
+
+
 def bench_gemm(args):
     import torch
     import paper_2403_10616_amd as dp
@@ -354,7 +403,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "route", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "route", "kmeans", "gemm", "attention"])
+    ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
     ap.add_argument("--epilogue", default="none", choices=["none", "bias", "gelu", "dgelu", "resid"])
@@ -367,7 +417,7 @@ def main():
         sys.exit("bench.py: this build runs one path on ONE GPU (no collectives, no sharding); use --gpus 1")
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
-    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm,
+    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 

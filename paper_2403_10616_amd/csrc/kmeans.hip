@@ -37,16 +37,22 @@ __global__ void __launch_bounds__(256) sort_scan_kernel(int* __restrict__ block_
   __shared__ int total[256];
   const int d = threadIdx.x;
   int run = 0;
-  for (int b = 0; b < nblocks; ++b) {
-    const int t = block_hist[b * 256 + d];
-    block_hist[b * 256 + d] = run;
-    run += t;
+  for (int b0 = 0; b0 < nblocks; b0 += 16) {   // 16 independent loads in flight, then the running sum
+    int t[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t[i] = b0 + i < nblocks ? block_hist[(b0 + i) * 256 + d] : 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (b0 + i < nblocks) block_hist[(b0 + i) * 256 + d] = run;
+      run += t[i];
+    }
   }
   total[d] = run;
   __syncthreads();
   int start = 0;
   for (int e = 0; e < d; ++e) start += total[e];
-  for (int b = 0; b < nblocks; ++b) block_hist[b * 256 + d] += start;
+  if (start)
+    for (int b = 0; b < nblocks; ++b) block_hist[b * 256 + d] += start;
 }
 
 // One wave per block walks its keys 64 at a time, in order.  Lanes holding the same digit find each other with eight
@@ -83,26 +89,61 @@ __global__ void __launch_bounds__(64) sort_scatter_kernel(const int* __restrict_
 }
 
 // count[k] = number of keys equal to k (integer atomics: the result does not depend on their order)
+// LDS: a workgroup counts KC_BLOCK keys in LDS first (n_keys <= KC_MAX_LDS) and adds only its non-zero bins.
+constexpr int KC_BLOCK = 8192, KC_MAX_LDS = 4096;
+template <bool LDS>
 __global__ void __launch_bounds__(256) key_count_kernel(const int* __restrict__ keys, long n, int n_keys,
                                                         int* __restrict__ count) {
-  const long i = (long)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) atomicAdd(&count[clamp_key(keys[i], n_keys)], 1);
+  __shared__ int h[LDS ? KC_MAX_LDS : 1];
+  if (LDS) {
+    for (int k = threadIdx.x; k < n_keys; k += 256) h[k] = 0;
+    __syncthreads();
+  }
+  const long base = (long)blockIdx.x * KC_BLOCK;
+  for (int i = threadIdx.x; i < KC_BLOCK; i += 256) {
+    const long j = base + i;
+    if (j < n) atomicAdd(LDS ? &h[clamp_key(keys[j], n_keys)] : &count[clamp_key(keys[j], n_keys)], 1);
+  }
+  if (LDS) {
+    __syncthreads();
+    for (int k = threadIdx.x; k < n_keys; k += 256)
+      if (h[k]) atomicAdd(&count[k], h[k]);
+  }
 }
 
-// start[k] = sum of count[0..k), k = 0..n_keys; chunk_start[k] = sum over k' < k of ceil(count[k'] / KM_CHUNK)
-__global__ void __launch_bounds__(64) key_scan_kernel(const int* __restrict__ count, int n_keys, int* __restrict__ start,
-                                                      int* __restrict__ chunk_start) {
-  if (threadIdx.x != 0) return;
-  int run = 0, chunks = 0;
-  for (int k = 0; k < n_keys; ++k) {
-    start[k] = run;
-    if (chunk_start) chunk_start[k] = chunks;
-    const int c = count[k];
-    run += c;
-    chunks += (c + KM_CHUNK - 1) / KM_CHUNK;
+// start[k] = sum of count[0..k), k = 0..n_keys; chunk_start[k] = sum over k' < k of ceil(count[k'] / KM_CHUNK).
+// One workgroup: every thread sums a run of consecutive keys, the 1024 run totals are scanned in LDS, then every
+// thread walks its run again.
+__global__ void __launch_bounds__(1024) key_scan_kernel(const int* __restrict__ count, int n_keys, int* __restrict__ start,
+                                                        int* __restrict__ chunk_start) {
+  __shared__ int run_sum[1024], run_chunks[1024];
+  const int per = (n_keys + 1023) / 1024;
+  const int k0 = min(threadIdx.x * per, n_keys), k1 = min(k0 + per, n_keys);
+  int s = 0, ch = 0;
+  for (int k = k0; k < k1; ++k) { const int c = count[k]; s += c; ch += (c + KM_CHUNK - 1) / KM_CHUNK; }
+  run_sum[threadIdx.x] = s;
+  run_chunks[threadIdx.x] = ch;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int a = 0, b = 0;
+    for (int t = 0; t < 1024; ++t) {
+      const int x = run_sum[t], y = run_chunks[t];
+      run_sum[t] = a; run_chunks[t] = b;
+      a += x; b += y;
+    }
+    start[n_keys] = a;
+    if (chunk_start) chunk_start[n_keys] = b;
   }
-  start[n_keys] = run;
-  if (chunk_start) chunk_start[n_keys] = chunks;
+  __syncthreads();
+  s = run_sum[threadIdx.x];
+  ch = run_chunks[threadIdx.x];
+  for (int k = k0; k < k1; ++k) {
+    start[k] = s;
+    if (chunk_start) chunk_start[k] = ch;
+    const int c = count[k];
+    s += c;
+    ch += (c + KM_CHUNK - 1) / KM_CHUNK;
+  }
 }
 
 __global__ void __launch_bounds__(256) fill_int_kernel2(int* p, int v, long n) {
@@ -208,10 +249,12 @@ dipaco_status launch_key_offsets(const int* keys, long n, int n_keys, int* count
   fill_int_kernel2<<<(n_keys + 255) / 256, 256, 0, s>>>(count, 0, n_keys);
   DIPACO_LAUNCH_CHECK();
   if (n > 0) {
-    key_count_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(keys, n, n_keys, count);
+    const unsigned blocks = (unsigned)((n + KC_BLOCK - 1) / KC_BLOCK);
+    if (n_keys <= KC_MAX_LDS) key_count_kernel<true><<<blocks, 256, 0, s>>>(keys, n, n_keys, count);
+    else key_count_kernel<false><<<blocks, 256, 0, s>>>(keys, n, n_keys, count);
     DIPACO_LAUNCH_CHECK();
   }
-  key_scan_kernel<<<1, 64, 0, s>>>(count, n_keys, start, chunk_start);
+  key_scan_kernel<<<1, 1024, 0, s>>>(count, n_keys, start, chunk_start);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

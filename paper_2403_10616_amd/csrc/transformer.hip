@@ -366,58 +366,8 @@ __global__ void __launch_bounds__(1024) mean_loss_kernel(const float* __restrict
 }
 
 // ---- embedding gradient ----------------------------------------------------------------------------------
-// d_tok[v] = sum of dx rows whose token is v, added in increasing position order (no float atomics):
-//   count tokens -> exclusive scan -> stable slot of every position -> one workgroup per vocabulary row.
-__global__ void __launch_bounds__(256) tok_count_kernel(const int* __restrict__ tok, int rows, int vocab,
-                                                        int* __restrict__ count) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= rows) return;
-  int t = tok[i];
-  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
-  atomicAdd(&count[t], 1);
-}
-
-// offsets[v] = sum_{u<v} count[u], offsets[vocab] = total; single workgroup
-__global__ void __launch_bounds__(1024) exclusive_scan_kernel(const int* __restrict__ count, int* __restrict__ offsets,
-                                                              int vocab) {
-  __shared__ int sums[1024];
-  const int per = (vocab + 1023) / 1024;
-  const int lo = min(vocab, (int)threadIdx.x * per), hi = min(vocab, lo + per);
-  int s = 0;
-  for (int i = lo; i < hi; ++i) s += count[i];
-  sums[threadIdx.x] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int i = 0; i < 1024; ++i) { int t = sums[i]; sums[i] = run; run += t; }
-    offsets[vocab] = run;
-  }
-  __syncthreads();
-  int run = sums[threadIdx.x];
-  for (int i = lo; i < hi; ++i) { offsets[i] = run; run += count[i]; }
-}
-
-// order[offsets[tok[i]] + #{j < i : tok[j] == tok[i]}] = i
-__global__ void __launch_bounds__(256) tok_slot_kernel(const int* __restrict__ tok, const int* __restrict__ offsets,
-                                                       int rows, int vocab, int* __restrict__ order) {
-  __shared__ int tile[256];
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  int mine = -1;
-  if (i < rows) { mine = tok[i]; mine = mine < 0 ? 0 : (mine >= vocab ? vocab - 1 : mine); }
-  int rank = 0;
-  for (int base = 0; base <= (int)blockIdx.x * 256; base += 256) {
-    const int j = base + threadIdx.x;
-    int t = -2;
-    if (j < rows) { t = tok[j]; t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t); }
-    __syncthreads();
-    tile[threadIdx.x] = t;
-    __syncthreads();
-    const int lim = min(256, i - base);   // only positions before i
-    for (int k = 0; k < lim; ++k) rank += tile[k] == mine;
-  }
-  if (i < rows) order[offsets[mine] + rank] = i;
-}
-
+// d_tok[v] = sum of dx rows whose token is v, added in increasing position order (no float atomics): positions are
+// grouped by token with a stable sort (kmeans.hip), then one workgroup per vocabulary row adds its positions.
 // One workgroup (8 waves) per vocabulary row.  Wave w adds the row's positions w, w+8, ... in order (lanes over
 // 16-byte column chunks), then the eight wave sums are added in wave order: a fixed tree, so the frequent tokens
 // of a Zipf batch (thousands of positions) are spread over the workgroup without any atomics.
@@ -500,11 +450,6 @@ __global__ void __launch_bounds__(128) pos_grad_kernel(const T* __restrict__ dx,
 #pragma unroll
     for (int i = 0; i < VEC; ++i) o[i] = acc[i];
   }
-}
-
-__global__ void __launch_bounds__(256) fill_int_kernel(int* p, int v, int n) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) p[i] = v;
 }
 
 inline int row_blocks(int rows) { return (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK; }
@@ -593,7 +538,9 @@ dipaco_status launch_mean_loss(const float* nll, const int* n_valid, float* loss
   return DIPACO_OK;
 }
 
-size_t embed_bwd_scratch_ints(int rows, int vocab) { return (size_t)vocab + (size_t)vocab + 1 + (size_t)rows; }
+size_t embed_bwd_scratch_ints(int rows, int vocab) {
+  return (size_t)vocab + (size_t)vocab + 1 + (size_t)rows + sort_scratch_ints(rows, vocab);
+}
 
 template <typename T>
 dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, float* d_pos, int* scratch, int B,
@@ -602,14 +549,13 @@ dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, flo
   int* count = scratch;
   int* offsets = scratch + vocab;
   int* order = offsets + vocab + 1;
-  fill_int_kernel<<<(vocab + 255) / 256, 256, 0, s>>>(count, 0, vocab);
-  DIPACO_LAUNCH_CHECK();
-  tok_count_kernel<<<(rows + 255) / 256, 256, 0, s>>>(tokens, rows, vocab, count);
-  DIPACO_LAUNCH_CHECK();
-  exclusive_scan_kernel<<<1, 1024, 0, s>>>(count, offsets, vocab);
-  DIPACO_LAUNCH_CHECK();
-  tok_slot_kernel<<<(rows + 255) / 256, 256, 0, s>>>(tokens, offsets, rows, vocab, order);
-  DIPACO_LAUNCH_CHECK();
+  int* sort_scratch = order + rows;
+  // positions grouped by token id, earlier positions first (stable sort: integer work only), so that every
+  // vocabulary row is summed in a fixed order
+  dipaco_status st = launch_key_offsets(tokens, rows, vocab, count, offsets, nullptr, s);
+  if (st != DIPACO_OK) return st;
+  st = launch_stable_sort_indices(tokens, rows, vocab, order, sort_scratch, s);
+  if (st != DIPACO_OK) return st;
   tok_grad_kernel<T><<<vocab, TG_WAVES * WAVE, TG_WAVES * d * sizeof(float), s>>>(dx, offsets, order, d_tok, d);
   DIPACO_LAUNCH_CHECK();
   pos_grad_kernel<T><<<max_seq, 128, 0, s>>>(dx, d_pos, B, S, d);
