@@ -133,6 +133,24 @@ dipaco_status dipaco_module_outer_step(float* theta, float* momentum, const floa
                                        const float* weights, int32_t n_paths, size_t n_elems, int32_t is_delta,
                                        float outer_lr, float outer_momentum, void* stream);
 
+/* The same outer step one path at a time (Section 5, "Online Parameter Gradient Averaging": a path's result is added
+ * to the partial sum as soon as it is available), with the optional norm rescaling of Section 3.3:
+ *   dipaco_module_delta_accumulate:  delta_sum <- (first ? 0 : delta_sum) + weight * (theta_prev - input)   (is_delta = 0)
+ *                                                                         + weight * input                  (is_delta = 1)
+ *       weight: the path's un-normalised shard weight (1 for the uniform mean); theta_prev may be NULL when is_delta.
+ *   dipaco_module_outer_apply:       Delta = norm_scale * delta_sum / weight_sum;
+ *       momentum <- mu * momentum + Delta;   theta <- theta - outer_lr * (Delta + mu * momentum)
+ *       weight_sum: the sum of the weights accumulated; norm_scale: 1, or sqrt(number of paths through the module)
+ *       for "outer gradient norm rescaling" (read as a multiplication: averaging over more paths acts like a larger
+ *       batch, so the averaged step is made longer).
+ * All buffers device fp32 [n_elems], 16-byte aligned; delta_sum is caller-owned scratch that lives across the calls.
+ * With norm_scale = 1 the result equals dipaco_module_outer_step up to the order of the additions. */
+dipaco_status dipaco_module_delta_accumulate(float* delta_sum, const float* theta_prev, const float* input, float weight,
+                                             size_t n_elems, int32_t is_delta, int32_t first, void* stream);
+dipaco_status dipaco_module_outer_apply(float* theta, float* momentum, const float* delta_sum, double weight_sum,
+                                        float norm_scale, size_t n_elems, float outer_lr, float outer_momentum,
+                                        void* stream);
+
 /* Generative routing (Section 2.4.1, eq. 1): idx[n] = argmin_k ||z_n - c_k||^2, lowest k on exact ties of the
  * computed scores; hist[k] = number of n routed to k.  The kernel minimises ||c_k||^2 - 2 z_n.c_k (same
  * argmin) in fp32.

@@ -482,3 +482,25 @@ def kmeans_objective(z, idx, centroids):
     c = np.asarray(centroids, dtype=F64)
     diff = z - c[np.asarray(idx)]
     return float((diff * diff).sum())
+
+
+def outer_step_streaming(theta_prev, momentum, inputs: Sequence[np.ndarray], weights, is_delta: bool,
+                         outer_lr: float, outer_momentum: float, norm_scale: float = 1.0):
+    """The outer update with the paths' results added one at a time, in arrival order, to a running weighted sum
+    (Section 5, online averaging), and the optional rescaling of the averaged outer gradient (Section 3.3):
+    Delta = norm_scale * (sum_i w_i d_i) / (sum_i w_i), d_i = theta_prev - theta_i (or the ready-made delta);
+    then Nesterov as in outer_step.  norm_scale = sqrt(P_le) is the paper's rescaling read as a multiplication."""
+    theta_prev = np.asarray(theta_prev, dtype=F64)
+    buf = np.asarray(momentum, dtype=F64)
+    n = len(inputs)
+    w = np.ones(n, dtype=F64) if weights is None else np.asarray(weights, dtype=F64)
+    acc = np.zeros_like(theta_prev)
+    wsum = 0.0
+    for i in range(n):
+        x = np.asarray(inputs[i], dtype=F64)
+        acc = acc + w[i] * (x if is_delta else (theta_prev - x))
+        wsum += w[i]
+    delta = norm_scale * acc / wsum
+    buf = outer_momentum * buf + delta
+    theta = theta_prev - outer_lr * (delta + outer_momentum * buf)
+    return theta, buf

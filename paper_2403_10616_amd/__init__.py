@@ -50,6 +50,10 @@ _SIGS = {
                                      C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
     "dipaco_module_outer_step": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_float),
                                            C.c_int32, C.c_size_t, C.c_int32, C.c_float, C.c_float, C.c_void_p]),
+    "dipaco_module_delta_accumulate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_size_t, C.c_int32,
+                                                 C.c_int32, C.c_void_p]),
+    "dipaco_module_outer_apply": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_float, C.c_size_t,
+                                            C.c_float, C.c_float, C.c_void_p]),
     "dipaco_route_prefix": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
     "dipaco_route_prefix_top": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
@@ -203,6 +207,18 @@ def dipaco_module_outer_step(theta, momentum, inputs, weights, n_elems: int, is_
     w = None if weights is None else (C.c_float * n)(*[float(x) for x in weights])
     _check(load().dipaco_module_outer_step(_ptr(theta), _ptr(momentum), ptrs, w, n, n_elems, int(bool(is_delta)),
                                            outer_lr, outer_momentum, _stream(stream)))
+
+
+def dipaco_module_delta_accumulate(delta_sum, theta_prev, inp, weight: float, n_elems: int, is_delta: bool, first: bool,
+                                   stream=None):
+    _check(load().dipaco_module_delta_accumulate(_ptr(delta_sum), _ptr(theta_prev), _ptr(inp), weight, n_elems,
+                                                 int(bool(is_delta)), int(bool(first)), _stream(stream)))
+
+
+def dipaco_module_outer_apply(theta, momentum, delta_sum, weight_sum: float, norm_scale: float, n_elems: int,
+                              outer_lr: float, outer_momentum: float, stream=None):
+    _check(load().dipaco_module_outer_apply(_ptr(theta), _ptr(momentum), _ptr(delta_sum), weight_sum, norm_scale, n_elems,
+                                            outer_lr, outer_momentum, _stream(stream)))
 
 
 def dipaco_route_prefix(z, centroids, N: int, D: int, K: int, idx_out, hist_out, margin_out=None, stream=None):

@@ -423,6 +423,28 @@ dipaco_status dipaco_module_outer_step(float* theta, float* momentum, const floa
                       static_cast<hipStream_t>(stream));
 }
 
+dipaco_status dipaco_module_delta_accumulate(float* delta_sum, const float* theta_prev, const float* input, float weight,
+                                             size_t n_elems, int32_t is_delta, int32_t first, void* stream) {
+  if (!(weight > 0.0f) || !std::isfinite(weight)) return fail(DIPACO_EINVAL, "weight must be positive and finite");
+  TRY(check_ptr(delta_sum, "delta_sum"));
+  TRY(check_ptr(input, "input"));
+  if (!is_delta) TRY(check_ptr(theta_prev, "theta_prev"));
+  return launch_delta_accumulate(delta_sum, theta_prev, input, weight, n_elems, is_delta ? 1 : 0, first ? 1 : 0,
+                                 static_cast<hipStream_t>(stream));
+}
+
+dipaco_status dipaco_module_outer_apply(float* theta, float* momentum, const float* delta_sum, double weight_sum,
+                                        float norm_scale, size_t n_elems, float outer_lr, float outer_momentum,
+                                        void* stream) {
+  if (!(weight_sum > 0.0) || !std::isfinite(weight_sum)) return fail(DIPACO_EINVAL, "weight_sum must be positive and finite");
+  if (!(norm_scale > 0.0f) || !std::isfinite(norm_scale)) return fail(DIPACO_EINVAL, "norm_scale must be positive and finite");
+  TRY(check_ptr(theta, "theta"));
+  TRY(check_ptr(momentum, "momentum"));
+  TRY(check_ptr(delta_sum, "delta_sum"));
+  return launch_outer_apply(theta, momentum, delta_sum, (float)((double)norm_scale / weight_sum), n_elems, outer_lr,
+                            outer_momentum, static_cast<hipStream_t>(stream));
+}
+
 dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_t N, int32_t D, int32_t K,
                                   int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream) {
   if (N < 0) return fail(DIPACO_EINVAL, "N must be >= 0");

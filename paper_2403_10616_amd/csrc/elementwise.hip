@@ -156,6 +156,54 @@ __global__ void __launch_bounds__(EW_THREADS) outer_kernel(const OuterArgs a) {
   }
 }
 
+// Streaming form of the outer step: sum <- (first ? 0 : sum) + w * (is_delta ? in : theta_prev - in), one path at a
+// time as its result arrives; then the Nesterov update from the finished sum.
+__global__ void __launch_bounds__(EW_THREADS) delta_accumulate_kernel(float* __restrict__ sum,
+                                                                      const float* __restrict__ theta_prev,
+                                                                      const float* __restrict__ in, float w, size_t n,
+                                                                      int is_delta, int first) {
+  const size_t nv = n >> 2;
+  const size_t stride = (size_t)gridDim.x * EW_THREADS;
+  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
+    float4 x = reinterpret_cast<const float4*>(in)[i];
+    if (!is_delta) {
+      const float4 t = reinterpret_cast<const float4*>(theta_prev)[i];
+      x = make_float4(t.x - x.x, t.y - x.y, t.z - x.z, t.w - x.w);
+    }
+    float4 a = first ? make_float4(0.f, 0.f, 0.f, 0.f) : reinterpret_cast<const float4*>(sum)[i];
+    a.x += w * x.x; a.y += w * x.y; a.z += w * x.z; a.w += w * x.w;
+    reinterpret_cast<float4*>(sum)[i] = a;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    const size_t i = (nv << 2) + threadIdx.x;
+    const float x = is_delta ? in[i] : theta_prev[i] - in[i];
+    sum[i] = (first ? 0.f : sum[i]) + w * x;
+  }
+}
+
+// Delta = scale * sum;  buf <- mu buf + Delta;  theta <- theta - lr (Delta + mu buf)
+__global__ void __launch_bounds__(EW_THREADS) outer_apply_kernel(float* __restrict__ theta, float* __restrict__ buf,
+                                                                 const float* __restrict__ sum, float scale, size_t n,
+                                                                 float lr, float mu) {
+  const size_t nv = n >> 2;
+  const size_t stride = (size_t)gridDim.x * EW_THREADS;
+  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
+    float4 d = reinterpret_cast<const float4*>(sum)[i];
+    d.x *= scale; d.y *= scale; d.z *= scale; d.w *= scale;
+    float4 b = reinterpret_cast<const float4*>(buf)[i];
+    const float4 th = outer_one(reinterpret_cast<const float4*>(theta)[i], d, b, lr, mu);
+    reinterpret_cast<float4*>(theta)[i] = th;
+    reinterpret_cast<float4*>(buf)[i] = b;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    const size_t i = (nv << 2) + threadIdx.x;
+    const float d = scale * sum[i];
+    const float b = mu * buf[i] + d;
+    theta[i] = theta[i] - lr * (d + mu * b);
+    buf[i] = b;
+  }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(EW_THREADS) fill_kernel(T* p, T value, size_t n) {
   size_t stride = (size_t)gridDim.x * EW_THREADS;
@@ -204,6 +252,22 @@ dipaco_status launch_outer(float* theta, float* momentum, const float* const* in
     case 16: outer_kernel<16><<<blocks, EW_THREADS, 0, s>>>(a); break;
     default: outer_kernel<0><<<blocks, EW_THREADS, 0, s>>>(a); break;
   }
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_delta_accumulate(float* sum, const float* theta_prev, const float* in, float w, size_t n,
+                                      int is_delta, int first, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  delta_accumulate_kernel<<<ew_blocks((n >> 2) + 1), EW_THREADS, 0, s>>>(sum, theta_prev, in, w, n, is_delta, first);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_outer_apply(float* theta, float* momentum, const float* sum, float scale, size_t n, float lr,
+                                 float mu, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  outer_apply_kernel<<<ew_blocks((n >> 2) + 1), EW_THREADS, 0, s>>>(theta, momentum, sum, scale, n, lr, mu);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

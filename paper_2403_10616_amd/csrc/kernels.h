@@ -17,6 +17,12 @@ dipaco_status launch_adamw(float* theta, const float* grad, float* m, float* v, 
                            hipStream_t s);
 dipaco_status launch_outer(float* theta, float* momentum, const float* const* inputs, const float* alpha,
                            int n_paths, size_t n, int is_delta, float lr, float mu, hipStream_t s);
+// streaming outer step: sum <- (first ? 0 : sum) + w * (is_delta ? in : theta_prev - in);  then
+// Delta = scale * sum, momentum <- mu momentum + Delta, theta <- theta - lr (Delta + mu momentum)
+dipaco_status launch_delta_accumulate(float* sum, const float* theta_prev, const float* in, float w, size_t n,
+                                      int is_delta, int first, hipStream_t s);
+dipaco_status launch_outer_apply(float* theta, float* momentum, const float* sum, float scale, size_t n, float lr,
+                                 float mu, hipStream_t s);
 dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s);
 dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s);
 

@@ -103,3 +103,42 @@ def test_outer_step_special_cases():
     # rejected inputs
     with pytest.raises(dp.DipacoError):
         dp.dipaco_module_outer_step(th_d, buf_d, [dev(ins[0])], [0.0], n, False, 0.7, 0.9)
+
+
+@pytest.mark.parametrize("n_paths,n_elems,weighted,is_delta,scale", [
+    (1, 1000, False, False, 1.0), (3, 4096 + 3, True, False, 1.0), (16, 70_001, True, True, 4.0),
+    (16, 1 << 20, True, False, 4.0), (5, 2, False, True, 2.0)])
+def test_streaming_outer_step_matches_oracle_and_one_shot_form(n_paths, n_elems, weighted, is_delta, scale):
+    rng = np.random.default_rng(40 + n_paths)
+    theta = (rng.standard_normal(n_elems) * 0.02).astype(np.float32)
+    buf0 = (rng.standard_normal(n_elems) * 1e-3).astype(np.float32)
+    w = gen.shard_weights(n_paths, 3) if weighted else np.ones(n_paths)
+    eps = [gen.perturbation(n_elems, 1e-3, 700 + i) for i in range(n_paths)]
+    ins = [np.asarray(-e if is_delta else theta + e, dtype=np.float32) for e in eps]
+    th_d, buf_d = dev(theta), dev(buf0)
+    prev_d = dev(theta)                                          # theta_prev stays untouched while paths arrive
+    acc = torch.full((n_elems,), 123.0, dtype=torch.float32, device=DEV)   # garbage: the first call overwrites
+    for i, x in enumerate(ins):
+        dp.dipaco_module_delta_accumulate(acc, None if is_delta else prev_d, dev(x), float(w[i]), n_elems, is_delta,
+                                          i == 0)
+    dp.dipaco_module_outer_apply(th_d, buf_d, acc, float(np.sum(w.astype(np.float64))), scale, n_elems, 0.7, 0.9)
+    th_o, buf_o = orc.outer_step_streaming(theta, buf0, ins, w, is_delta, 0.7, 0.9, norm_scale=scale)
+    assert rel_l2(host(th_d), th_o) <= 1e-6
+    assert rel_l2(host(buf_d), buf_o) <= 2e-5
+    if scale == 1.0:                                              # same numbers as the one-shot entry point
+        th1, buf1 = dev(theta), dev(buf0)
+        dp.dipaco_module_outer_step(th1, buf1, [dev(x) for x in ins], w if weighted else None, n_elems, is_delta, 0.7,
+                                    0.9)
+        assert np.abs(host(th1) - host(th_d)).max() <= 1e-6
+
+
+def test_streaming_outer_step_rejects_bad_arguments():
+    t = torch.zeros(16, dtype=torch.float32, device=DEV)
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_module_delta_accumulate(t, t, t, 0.0, 16, False, True)
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_module_delta_accumulate(t, None, t, 1.0, 16, False, True)    # theta_prev needed for local copies
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_module_outer_apply(t, t, t, 0.0, 1.0, 16, 0.7, 0.9)
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_module_outer_apply(t, t, t, 1.0, float("nan"), 16, 0.7, 0.9)

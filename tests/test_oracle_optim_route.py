@@ -276,3 +276,35 @@ def test_lloyd_iterations_never_raise_the_objective():
         c, _ = orc.kmeans_update(z, idx, c)
         prev = orc.kmeans_objective(z, idx, c)
         assert prev <= after_assign + 1e-9
+
+
+# ---- streaming outer step and norm rescaling ------------------------------------------------------------------------
+def test_streaming_outer_equals_batch_form_in_any_arrival_order():
+    rng = np.random.default_rng(9)
+    theta, buf = rng.standard_normal(50), rng.standard_normal(50)
+    locals_ = [theta + 1e-2 * rng.standard_normal(50) for _ in range(5)]
+    w = rng.uniform(0.5, 1.5, size=5)
+    want = orc.outer_step(theta, buf, locals_, w, False, 0.7, 0.9)
+    got = orc.outer_step_streaming(theta, buf, locals_, w, False, 0.7, 0.9)
+    assert np.abs(got[0] - want[0]).max() < 1e-14 and np.abs(got[1] - want[1]).max() < 1e-14
+    perm = [3, 0, 4, 2, 1]
+    got_p = orc.outer_step_streaming(theta, buf, [locals_[i] for i in perm], w[perm], False, 0.7, 0.9)
+    assert np.abs(got_p[0] - want[0]).max() < 1e-14
+    deltas = [theta - x for x in locals_]
+    got_d = orc.outer_step_streaming(theta, buf, deltas, w, True, 0.7, 0.9)
+    assert np.abs(got_d[0] - want[0]).max() < 1e-14
+
+
+def test_norm_rescaling_closed_forms():
+    theta, buf0 = np.array([1.0, -2.0, 0.5]), np.zeros(3)
+    d = np.array([0.1, 0.2, -0.4])
+    P = 16
+    th, buf = orc.outer_step_streaming(theta, buf0, [d] * P, None, True, 0.5, 0.0, norm_scale=np.sqrt(P))
+    assert np.allclose(th, theta - 0.5 * 4.0 * d, atol=1e-15)      # P equal deltas: mean d, times sqrt(16) = 4
+    assert np.allclose(buf, 4.0 * d, atol=1e-15)
+    # without momentum the step is linear in the scale; with it, theta - theta_prev = -lr (1 + mu) s d on the first step
+    th2, _ = orc.outer_step_streaming(theta, buf0, [d], None, True, 0.7, 0.9, norm_scale=3.0)
+    assert np.allclose(th2, theta - 0.7 * 1.9 * 3.0 * d, atol=1e-15)
+    th1, b1 = orc.outer_step_streaming(theta, buf0, [d], None, True, 0.7, 0.9, norm_scale=1.0)
+    ref = orc.outer_step(theta, buf0, [d], None, True, 0.7, 0.9)
+    assert np.array_equal(th1, ref[0]) and np.array_equal(b1, ref[1])
