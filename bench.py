@@ -8,6 +8,7 @@ C-ABI calls dipaco_path_fwd_bwd + dipaco_inner_adamw.  Prints ONE JSON line.
 Other workloads (for profiling single kernels; same JSON shape):
   --workload outer_step   16 deltas x 57,872,640 parameters, weighted mean + Nesterov
   --workload route        2^20 x 768 prefix embeddings against 256 centroids
+  --workload outer_stream the same module, the 16 deltas accumulated one at a time, then the Nesterov update
   --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
   --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
   --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
@@ -224,6 +225,45 @@ def bench_outer_step(args):
                          "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_}}
 
 
+def bench_outer_stream(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[3]
+    n, P = cfg["n_elems"], cfg["n_paths"]
+    dev = "cuda"
+    theta = torch.randn(n, device=dev) * 0.02
+    buf = torch.zeros(n, device=dev)
+    acc = torch.empty(n, device=dev)
+    deltas = [torch.randn(n, device=dev) * cfg["delta_std"] for _ in range(P)]
+    w = gen.shard_weights(P, cfg["seed"])
+
+    def step():
+        for i in range(P):
+            dp.dipaco_module_delta_accumulate(acc, None, deltas[i], float(w[i]), n, True, i == 0)
+        dp.dipaco_module_outer_apply(theta, buf, acc, float(w.sum()), float(P) ** 0.5, n, cfg["outer_lr"],
+                                     cfg["outer_momentum"])
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    bytes_ = (8.0 + (P - 1) * 12.0 + 20.0) * n     # first delta: read + write; others: 2 reads + write; apply: 3 reads + 2 writes
+    ach = bytes_ / (ms * 1e-3) / 1e9
+    return {"metric": "streaming module outer-step parameters/sec on 1 MI355X", "value": n / (ms * 1e-3),
+            "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "config 3 module, 16 weighted deltas accumulated one by one, sqrt(16) rescaling, Nesterov"},
+            "roofline": {"bound": "hbm", "kernel": "delta_accumulate_kernel x16 + outer_apply_kernel", "achieved": ach,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                         "bytes_per_launch": bytes_ / (P + 1)}}
+
+
 def bench_route(args):
     import torch
     import dipaco_inputs as gen
@@ -403,7 +443,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "route", "kmeans", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "route", "kmeans", "gemm", "attention"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
@@ -417,7 +457,7 @@ def main():
         sys.exit("bench.py: this build runs one path on ONE GPU (no collectives, no sharding); use --gpus 1")
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
-    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans,
+    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "outer_stream": bench_outer_stream,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 

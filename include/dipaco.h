@@ -111,6 +111,17 @@ dipaco_status dipaco_path_fwd_bwd(dipaco_ctx* ctx, const float* path_master, con
                                   float* loss_out, float* token_nll_out, float* grads, void* workspace,
                                   size_t workspace_bytes, void* stream);
 
+/* Router features g(document) (appendix on routing: "the average of the hidden state from the last transformer block
+ * ... over the first 32 tokens of a document"): the path's blocks are run forward on tokens [batch, seq] (seq = 32
+ * in the paper) and features_out[b, :] = mean over the seq positions of the residual stream that leaves the last
+ * block (before the final LayerNorm; the head is not evaluated).  features_out: device fp32 [batch, d_model]; these
+ * are the z of dipaco_route_prefix.  path_master / path_lowp as in dipaco_path_fwd_bwd.
+ * workspace: device, >= dipaco_features_workspace_bytes(ctx, batch, seq) (one block's activations, reused). */
+size_t dipaco_features_workspace_bytes(const dipaco_ctx* ctx, int32_t batch, int32_t seq);
+dipaco_status dipaco_path_prefix_features(dipaco_ctx* ctx, const float* path_master, const void* path_lowp,
+                                          const int32_t* tokens, int32_t batch, int32_t seq, float* features_out,
+                                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* InnerOpt = AdamW (Algorithm 1, inner loop; Section 2.5), over the whole flat path buffer, in place:
  *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
  *   theta <- theta - lr * ( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + weight_decay * theta ),

@@ -504,3 +504,28 @@ def outer_step_streaming(theta_prev, momentum, inputs: Sequence[np.ndarray], wei
     buf = outer_momentum * buf + delta
     theta = theta_prev - outer_lr * (delta + outer_momentum * buf)
     return theta, buf
+
+
+def prefix_features(params, a: Arch, tokens) -> np.ndarray:
+    """Router features (appendix on routing): for every row of tokens [B, S] (S = 32 in the paper), the mean over
+    the S positions of the hidden state that leaves the last transformer block.  Read as the residual stream after
+    the last block, before the final LayerNorm.  Returns [B, d_model]."""
+    P = np.asarray(params, dtype=F64)
+    lay = param_layout(a)
+    tokens = np.asarray(tokens)
+    A = a.d_attn
+    out = np.empty((tokens.shape[0], a.d_model), dtype=F64)
+    for b in range(tokens.shape[0]):
+        tok = tokens[b]
+        S = tok.shape[0]
+        x = view(P, lay, "tok_emb")[tok] + view(P, lay, "pos_emb")[:S]
+        for layer in range(a.n_layers):
+            w = lambda n: view(P, lay, f"blk{layer}.{n}")
+            h1, _ = _layer_norm(x, w("ln1_g"), w("ln1_b"), a.ln_eps)
+            qkv = h1 @ w("w_qkv") + w("b_qkv")
+            o, _ = _attention(qkv[:, :A], qkv[:, A:2 * A], qkv[:, 2 * A:], a)
+            x = x + o @ w("w_o") + w("b_o")
+            h2, _ = _layer_norm(x, w("ln2_g"), w("ln2_b"), a.ln_eps)
+            x = x + _gelu(h2 @ w("w_up") + w("b_up")) @ w("w_down") + w("b_down")
+        out[b] = x.sum(axis=0) / S
+    return out

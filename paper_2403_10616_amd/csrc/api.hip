@@ -212,6 +212,54 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
   return DIPACO_OK;
 }
 
+// ---- prefix features: forward through the blocks only, one set of layer buffers reused by every block -------
+struct FeaturePlan {
+  size_t x_a, x_b, h, mean, rstd, qkv, o, lse, x_mid, u, act, total;
+};
+static FeaturePlan make_feature_plan(const dipaco_ctx* c, int B, int S) {
+  const dipaco_arch& a = c->arch;
+  const size_t T = (size_t)B * S, d = a.d_model, A = c->A, F = a.d_mlp;
+  const size_t es = a.compute == DIPACO_BF16 ? 2 : 4;
+  size_t pos = 0;
+  auto take = [&](size_t bytes) { size_t at = pos; pos += (bytes + 255) & ~(size_t)255; return at; };
+  FeaturePlan p;
+  p.x_a = take(T * d * es); p.x_b = take(T * d * es); p.h = take(T * d * es); p.mean = take(T * 4); p.rstd = take(T * 4);
+  p.qkv = take(T * 3 * A * es); p.o = take(T * A * es); p.lse = take((size_t)B * a.n_heads * S * 4);
+  p.x_mid = take(T * d * es); p.u = take(T * F * es); p.act = take(T * F * es);
+  p.total = pos;
+  return p;
+}
+
+template <typename T>
+static dipaco_status run_features(const dipaco_ctx* c, const T* W, const int* tokens, int B, int S, float* out, char* ws,
+                                  hipStream_t st) {
+  const dipaco_arch& a = c->arch;
+  const int T_ = B * S, d = a.d_model, A = c->A, F = a.d_mlp, V = a.vocab, H = a.n_heads, dh = a.d_head;
+  const FeaturePlan p = make_feature_plan(c, B, S);
+  auto buf = [&](size_t off) { return reinterpret_cast<T*>(ws + off); };
+  auto fbuf = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  T* x = buf(p.x_a);
+  T* x_other = buf(p.x_b);
+  TRY(launch_embed<T>(W + c->tok_emb, W + c->pos_emb, tokens, x, B, S, d, V, st));
+  for (int l = 0; l < c->n_layers; ++l) {
+    const BlockOff& o = c->blocks[l];
+    TRY(launch_layernorm_fwd<T>(x, W + o.ln1_g, W + o.ln1_b, buf(p.h), fbuf(p.mean), fbuf(p.rstd), T_, d, a.ln_eps, st));
+    TRY(gemm<T>(buf(p.h), W + o.w_qkv, buf(p.qkv), T_, 3 * A, d, d, 3 * A, 3 * A, false, false, W + o.b_qkv, nullptr,
+                nullptr, nullptr, 0, false, 1, nullptr, st));
+    TRY(launch_attention_fwd<T>(buf(p.qkv), buf(p.o), fbuf(p.lse), B, S, H, dh, st));
+    TRY(gemm<T>(buf(p.o), W + o.w_o, buf(p.x_mid), T_, d, A, A, d, d, false, false, W + o.b_o, x, nullptr, nullptr, 0,
+                false, 1, nullptr, st));
+    TRY(launch_layernorm_fwd<T>(buf(p.x_mid), W + o.ln2_g, W + o.ln2_b, buf(p.h), fbuf(p.mean), fbuf(p.rstd), T_, d,
+                                a.ln_eps, st));
+    TRY(gemm<T>(buf(p.h), W + o.w_up, buf(p.act), T_, F, d, d, F, F, false, false, W + o.b_up, nullptr, buf(p.u), nullptr,
+                3, false, 1, nullptr, st));
+    TRY(gemm<T>(buf(p.act), W + o.w_down, x_other, T_, d, F, F, d, d, false, false, W + o.b_down, buf(p.x_mid), nullptr,
+                nullptr, 0, false, 1, nullptr, st));
+    std::swap(x, x_other);
+  }
+  return launch_mean_pool<T>(x, out, B, S, d, st);
+}
+
 static dipaco_status check_ptr(const void* p, const char* name) {
   if (!p) return fail(DIPACO_EINVAL, std::string(name) + " is NULL");
   if (!aligned16(p)) return fail(DIPACO_EALIGN, std::string(name) + " is not 16-byte aligned");
@@ -387,6 +435,28 @@ dipaco_status dipaco_path_fwd_bwd(dipaco_ctx* c, const float* master, const void
     return run_fwd_bwd<bf16>(c, static_cast<const bf16*>(lowp), tokens, targets, B, S, loss_out, nll_out, grads,
                              static_cast<char*>(ws), st);
   return run_fwd_bwd<float>(c, master, tokens, targets, B, S, loss_out, nll_out, grads, static_cast<char*>(ws), st);
+}
+
+size_t dipaco_features_workspace_bytes(const dipaco_ctx* c, int32_t batch, int32_t seq) {
+  if (!c || batch < 1 || seq < 1) return 0;
+  return make_feature_plan(c, batch, seq).total;
+}
+
+dipaco_status dipaco_path_prefix_features(dipaco_ctx* c, const float* master, const void* lowp, const int32_t* tokens,
+                                          int32_t B, int32_t S, float* features_out, void* ws, size_t ws_bytes,
+                                          void* stream) {
+  if (!c) return fail(DIPACO_EINVAL, "dipaco_path_prefix_features: NULL context");
+  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
+  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  const bool lowprec = c->arch.compute == DIPACO_BF16;
+  TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
+  TRY(check_ptr(tokens, "tokens"));
+  TRY(check_ptr(features_out, "features_out"));
+  TRY(check_ptr(ws, "workspace"));
+  if (ws_bytes < make_feature_plan(c, B, S).total) return fail(DIPACO_EWORKSPACE, "workspace too small");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (lowprec) return run_features<bf16>(c, static_cast<const bf16*>(lowp), tokens, B, S, features_out, static_cast<char*>(ws), st);
+  return run_features<float>(c, master, tokens, B, S, features_out, static_cast<char*>(ws), st);
 }
 
 dipaco_status dipaco_inner_adamw(dipaco_ctx* c, float* master, const float* grads, float* m, float* v, void* lowp,

@@ -563,6 +563,24 @@ dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, flo
   return DIPACO_OK;
 }
 
+// out[b, :] = mean over the S positions of x[b*S + p, :]  (fp32, positions added in order)
+template <typename T>
+__global__ void __launch_bounds__(256) mean_pool_kernel(const T* __restrict__ x, float* __restrict__ out, int S, int d) {
+  const int b = blockIdx.x;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float s = 0.f;
+    for (int p = 0; p < S; ++p) s += to_f32(x[((size_t)b * S + p) * d + c]);
+    out[(size_t)b * d + c] = s / (float)S;
+  }
+}
+
+template <typename T>
+dipaco_status launch_mean_pool(const T* x, float* out, int B, int S, int d, hipStream_t s) {
+  mean_pool_kernel<T><<<B, 256, 0, s>>>(x, out, S, d);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
 #define INSTANTIATE(T)                                                                                              \
   template dipaco_status launch_embed<T>(const T*, const T*, const int*, T*, int, int, int, int, hipStream_t);       \
   template dipaco_status launch_layernorm_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float,  \
@@ -570,6 +588,7 @@ dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, flo
   template dipaco_status launch_layernorm_bwd<T>(const T*, const T*, const T*, const float*, const float*, const T*, \
                                                  T*, float*, float*, float*, float*, int, int, hipStream_t);        \
   template dipaco_status launch_colsum<T>(const T*, float*, float*, int, int, hipStream_t);                          \
+  template dipaco_status launch_mean_pool<T>(const T*, float*, int, int, int, hipStream_t);                          \
   template dipaco_status launch_softmax_xent<T>(T*, const int*, const int*, float*, int, int, hipStream_t);          \
   template dipaco_status launch_embed_bwd<T>(const T*, const int*, float*, float*, int*, int, int, int, int, int,    \
                                              hipStream_t);

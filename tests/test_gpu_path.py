@@ -163,3 +163,45 @@ def test_bf16_loss_and_gradients_close_to_oracle(name, B, S, mask):
     assert worst <= 6e-2, (where, worst)
     g0 = host(st.grads).copy()
     assert st.fwd_bwd(tok, tgt) == loss and np.array_equal(g0, host(st.grads))
+
+
+# ---- router features: forward through the blocks, mean over the prefix ------------------------------------------
+def _features_gpu(ctx, theta, tok):
+    B, S = tok.shape
+    n = dp.dipaco_path_param_count(ctx)
+    master = dev(theta.astype(np.float32))
+    lowp = master.to(torch.bfloat16) if ctx.compute == dp.BF16 else None
+    out = torch.full((B, ctx_d(ctx)), 7.0, dtype=torch.float32, device=DEV)
+    ws = torch.empty(dp.dipaco_features_workspace_bytes(ctx, B, S), dtype=torch.uint8, device=DEV)
+    dp.dipaco_path_prefix_features(ctx, master, lowp, dev(tok.astype(np.int32)), B, S, out, ws)
+    return host(out)
+
+
+def ctx_d(ctx):
+    return next(cols for name, _, rows, cols, _ in (dp.dipaco_tensor_info(ctx, i) for i in range(dp.dipaco_tensor_count(ctx)))
+                if name == "tok_emb")
+
+
+@pytest.mark.parametrize("name,B,S,compute,tol", [("ragged", 5, 32, dp.F32, 1e-5), ("wide", 130, 32, dp.F32, 1e-5),
+                                                  ("one_level", 3, 1, dp.F32, 1e-5), ("wide", 130, 32, dp.BF16, 2e-2),
+                                                  ("ragged", 7, 56, dp.BF16, 2e-2)])
+def test_prefix_features_match_oracle(name, B, S, compute, tol):
+    print(f"features {name} B={B} S={S} compute={compute}", flush=True)
+    cfg = SHAPES[name]
+    a, ctx = make_arch(cfg, compute)
+    lay = orc.param_layout(a)
+    theta = gen.random_params(orc.param_count(a), seed=31, scale=0.08)
+    for n_, (off, shape, _) in lay.items():
+        if n_.endswith("_g"):
+            theta[off:off + shape[0]] += 1.0
+    tok = gen.uniform_tokens((B, S), cfg["vocab"], 32)
+    ref_theta = theta if compute == dp.F32 else torch.from_numpy(theta.astype(np.float32)).to(torch.bfloat16).float().numpy()
+    want = orc.prefix_features(ref_theta, a, tok)
+    got = _features_gpu(ctx, theta, tok)
+    assert got.shape == want.shape
+    assert rel_l2(got, want) <= tol
+    assert np.abs(got - want).max() <= tol * 10 * np.abs(want).max()
+    with pytest.raises(dp.DipacoError):      # workspace too small is refused on the host
+        dp.dipaco_path_prefix_features(ctx, dev(theta.astype(np.float32)), None if compute == dp.F32 else dev(theta).to(torch.bfloat16),
+                                       dev(tok.astype(np.int32)), B, S, torch.zeros((B, a.d_model), device=DEV),
+                                       torch.empty(16, dtype=torch.uint8, device=DEV))

@@ -32,6 +32,23 @@ def _data(a, B, S, seed, mask_prefix=0):
     return tok, tgt
 
 
+def _torch_hidden(p, a, tok):
+    """residual stream after the last block, [B, S, d], built from torch's library routines"""
+    B, S = tok.shape
+    x = p["tok_emb"][tok] + p["pos_emb"][:S]
+    A, H, dh = a.d_attn, a.n_heads, a.d_head
+    for l in range(a.n_layers):
+        w = lambda n: p[f"blk{l}.{n}"]
+        h = F.layer_norm(x, (a.d_model,), w("ln1_g"), w("ln1_b"), a.ln_eps)
+        qkv = h @ w("w_qkv") + w("b_qkv")
+        q, k, v = [t.reshape(B, S, H, dh).transpose(1, 2) for t in qkv.split(A, dim=-1)]
+        o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B, S, A)
+        x = x + o @ w("w_o") + w("b_o")
+        h = F.layer_norm(x, (a.d_model,), w("ln2_g"), w("ln2_b"), a.ln_eps)
+        x = x + F.gelu(h @ w("w_up") + w("b_up")) @ w("w_down") + w("b_down")
+    return x
+
+
 def _torch_loss(flat, a, tok, tgt):
     lay = orc.param_layout(a)
     p = {n: flat[o:o + int(np.prod(s))].reshape(s) for n, (o, s, _) in lay.items()}
@@ -164,3 +181,38 @@ def test_param_counts_of_the_benchmark_architectures():
     c = gen.CONFIGS[1]
     a = orc.Arch(c["layers_per_level"], c["d_model"], c["n_heads"], c["d_head"], c["d_mlp"], c["vocab"], c["max_seq"])
     assert orc.param_count(a) == 136_960
+
+
+# ---- router features --------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("a,B,S", [(TINY, 3, 5), (WIDE, 2, 8)])
+def test_prefix_features_match_library_build(a, B, S):
+    theta = gen.random_params(orc.param_count(a), seed=17, scale=0.3, dtype=np.float64)
+    tok = gen.uniform_tokens((B, S), a.vocab, 18)
+    lay = orc.param_layout(a)
+    t = torch.tensor(theta, dtype=torch.float64)
+    p = {n: t[o:o + int(np.prod(s))].reshape(s) for n, (o, s, _) in lay.items()}
+    want = _torch_hidden(p, a, torch.as_tensor(tok, dtype=torch.long)).mean(dim=1).numpy()
+    got = orc.prefix_features(theta, a, tok)
+    assert got.shape == (B, a.d_model)
+    assert np.abs(got - want).max() <= 1e-12
+
+
+def test_prefix_features_closed_forms():
+    # no blocks: the feature is the mean of token + position embeddings
+    a0 = orc.Arch(layers_per_level=(0,), d_model=8, n_heads=2, d_head=4, d_mlp=16, vocab=11, max_seq=6)
+    theta = gen.random_params(orc.param_count(a0), seed=19, scale=0.3, dtype=np.float64)
+    lay = orc.param_layout(a0)
+    tok = gen.uniform_tokens((2, 4), a0.vocab, 20)
+    E, Ppos = orc.view(theta, lay, "tok_emb"), orc.view(theta, lay, "pos_emb")
+    want = np.stack([(E[tok[b]] + Ppos[:4]).mean(axis=0) for b in range(2)])
+    assert np.abs(orc.prefix_features(theta, a0, tok) - want).max() <= 1e-15
+    # rows are independent and a one-token prefix is that token's own hidden state: the final LayerNorm of it,
+    # times the head, gives the logits of path_logits
+    theta = gen.random_params(orc.param_count(TINY), seed=21, scale=0.3, dtype=np.float64)
+    tok = gen.uniform_tokens((3, 1), TINY.vocab, 22)
+    f = orc.prefix_features(theta, TINY, tok)
+    lay = orc.param_layout(TINY)
+    y, _ = orc._layer_norm(f, orc.view(theta, lay, "lnf_g"), orc.view(theta, lay, "lnf_b"), TINY.ln_eps)
+    logits = y @ orc.view(theta, lay, "w_head")
+    assert np.abs(logits - orc.path_logits(theta, TINY, tok)[:, 0, :]).max() <= 1e-12
+    assert np.array_equal(orc.prefix_features(theta, TINY, tok[[2, 0]]), f[[2, 0]])
