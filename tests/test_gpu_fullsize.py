@@ -167,3 +167,70 @@ def test_config5_full_round_sampled():
         assert rel_l2(host(buf_d)[pick], buf_o) <= 2e-5, level
         del ins
         _say(f"config 5: outer step of level {level} done")
+
+
+def test_config3_full_size_streaming_outer_step_on_sampled_elements():
+    """The one-path-at-a-time form with sqrt(P) rescaling at the bench's size, against the oracle on a sample."""
+    cfg = gen.CONFIGS[3]
+    n, P = cfg["n_elems"], cfg["n_paths"]
+    _say("config 3 (streaming): building inputs")
+    theta = (gen.perturbation(n, 0.02, 31)).astype(np.float32)
+    buf0 = (gen.perturbation(n, 1e-3, 32)).astype(np.float32)
+    w = gen.shard_weights(P, cfg["seed"])
+    deltas = [(-gen.perturbation(n, cfg["delta_std"], 800 + i)).astype(np.float32) for i in range(P)]
+    th_d, buf_d = dev(theta), dev(buf0)
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    for i in range(P):
+        dp.dipaco_module_delta_accumulate(acc, None, dev(deltas[i]), float(w[i]), n, True, i == 0)
+    dp.dipaco_module_outer_apply(th_d, buf_d, acc, float(np.sum(w.astype(np.float64))), math.sqrt(P), n,
+                                 cfg["outer_lr"], cfg["outer_momentum"])
+    sel = np.random.default_rng(5).choice(n, size=200_000, replace=False)
+    sel = np.concatenate([sel, [0, 1, 2, 3, n - 4, n - 3, n - 2, n - 1]])
+    th_o, buf_o = orc.outer_step_streaming(theta[sel], buf0[sel], [d[sel] for d in deltas], w, True, cfg["outer_lr"],
+                                           cfg["outer_momentum"], norm_scale=math.sqrt(P))
+    assert rel_l2(host(th_d)[sel], th_o) <= 1e-6
+    assert rel_l2(host(buf_d)[sel], buf_o) <= 2e-5
+
+
+def test_config4_full_size_top2_and_kmeans_update():
+    """Top-2 assignment and the centroid update at the bench's size: sampled points against the oracle, identities
+    that hold at any size, and every centroid against the oracle's mean over the GPU's own assignment."""
+    cfg = gen.CONFIGS[4]
+    N, D, K = cfg["N"], cfg["D"], cfg["K"]
+    _say("config 4 (top-2, update): generating the mixture")
+    z, c, _ = gen.gaussian_mixture(N, D, K, cfg["noise_std"], cfg["seed"])
+    zd, cd = dev(z), dev(c)
+    idx2 = torch.empty(N * 2, dtype=torch.int32, device=DEV)
+    hist = torch.empty(K, dtype=torch.int64, device=DEV)
+    margin = torch.empty(N, dtype=torch.float32, device=DEV)
+    dp.dipaco_route_prefix_top(zd, D, cd, N, D, K, 2, idx2, hist, margin)
+    i2 = host(idx2).reshape(N, 2)
+    h = host(hist)
+    assert h.sum() == 2 * N and np.array_equal(h, np.bincount(i2.ravel(), minlength=K))
+    assert np.all(i2[:, 0] != i2[:, 1]) and i2.min() >= 0 and i2.max() < K
+    sel = np.random.default_rng(6).choice(N, size=3000, replace=False)
+    o2, _ = orc.route_prefix_top2(z[sel], c)
+    c64 = c.astype(np.float64)
+    bad = 0
+    for j, n_ in enumerate(sel):
+        if np.array_equal(i2[n_], o2[j]):
+            continue
+        bad += 1
+        d = ((z[n_].astype(np.float64) - c64) ** 2).sum(1)
+        for t in range(2):                      # a different pick must be as close (a near-tie in fp32)
+            assert abs(d[i2[n_, t]] - d[o2[j, t]]) <= 1e-4
+    assert bad <= 30
+    _say("config 4 (update): centroid means")
+    idx1 = dev(np.ascontiguousarray(i2[:, 0]))
+    counts = torch.empty(K, dtype=torch.int64, device=DEV)
+    ws = torch.empty(dp.dipaco_kmeans_workspace_bytes(N, D, K), dtype=torch.uint8, device=DEV)
+    c_new = dev(c.copy())
+    dp.dipaco_kmeans_update(zd, D, idx1, N, D, K, c_new, counts, ws)
+    want, o_counts = orc.kmeans_update(z, i2[:, 0], c)
+    assert np.array_equal(host(counts), o_counts)
+    got = host(c_new)
+    assert rel_l2(got, want) <= 1e-6 and np.abs(got - want).max() <= 1e-5
+    # one Lloyd iteration lowers the objective
+    before = orc.kmeans_objective(z[sel], i2[sel, 0], c)
+    after = orc.kmeans_objective(z[sel], i2[sel, 0], got)
+    assert after < before
