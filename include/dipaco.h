@@ -122,6 +122,18 @@ dipaco_status dipaco_path_prefix_features(dipaco_ctx* ctx, const float* path_mas
                                           const int32_t* tokens, int32_t batch, int32_t seq, float* features_out,
                                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* Path scores for discriminative routing (Section 2.4.2; appendix on routing: the summed auto-regressive
+ * log-likelihood of each document under each path, whose argmax over paths is the router's training label):
+ * forward pass only.  doc_loglik_out[b] = sum over positions with target >= 0 of log p(target | prefix), natural log
+ * (device fp32 [batch]); token_nll_out: device fp32 [batch, seq] or NULL, the per-position negative log-likelihoods
+ * (0 at ignored positions).  Call once per path on the same documents and take the argmax on the host; the same call
+ * at seq = 2048 is the forward-only evaluation of Section 4.  tokens / targets / parameters as in
+ * dipaco_path_fwd_bwd; workspace >= dipaco_score_workspace_bytes(ctx, batch, seq). */
+size_t dipaco_score_workspace_bytes(const dipaco_ctx* ctx, int32_t batch, int32_t seq);
+dipaco_status dipaco_path_score(dipaco_ctx* ctx, const float* path_master, const void* path_lowp, const int32_t* tokens,
+                                const int32_t* targets, int32_t batch, int32_t seq, float* doc_loglik_out,
+                                float* token_nll_out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* InnerOpt = AdamW (Algorithm 1, inner loop; Section 2.5), over the whole flat path buffer, in place:
  *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
  *   theta <- theta - lr * ( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + weight_decay * theta ),

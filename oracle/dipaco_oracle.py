@@ -529,3 +529,15 @@ def prefix_features(params, a: Arch, tokens) -> np.ndarray:
             x = x + _gelu(h2 @ w("w_up") + w("b_up")) @ w("w_down") + w("b_down")
         out[b] = x.sum(axis=0) / S
     return out
+
+
+def path_doc_scores(params, a: Arch, tokens, targets) -> np.ndarray:
+    """Scores for discriminative routing (appendix on routing): for every document (row), the summed
+    auto-regressive log-likelihood sum_j log p(t_j | t_<j) under this path, over positions with target >= 0."""
+    return -path_token_nll(params, a, tokens, targets).sum(axis=1)
+
+
+def route_labels_from_scores(scores) -> np.ndarray:
+    """Router training labels: argmax over paths of the documents' scores; scores [n_paths, n_docs]; the first
+    path wins exact ties."""
+    return np.argmax(np.asarray(scores, dtype=F64), axis=0).astype(np.int32)

@@ -49,6 +49,9 @@ _SIGS = {
     "dipaco_features_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
     "dipaco_path_prefix_features": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                               C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dipaco_score_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
+    "dipaco_path_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "dipaco_inner_adamw": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                      C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
     "dipaco_module_outer_step": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_float),
@@ -206,6 +209,17 @@ def dipaco_path_prefix_features(ctx: Context, path_master, path_lowp, tokens, ba
     _check(load().dipaco_path_prefix_features(ctx.handle, _ptr(path_master), _ptr(path_lowp), _ptr(tokens), batch, seq,
                                               _ptr(features_out), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def dipaco_score_workspace_bytes(ctx: Context, batch: int, seq: int) -> int:
+    return load().dipaco_score_workspace_bytes(ctx.handle, batch, seq)
+
+
+def dipaco_path_score(ctx: Context, path_master, path_lowp, tokens, targets, batch: int, seq: int, doc_loglik_out,
+                      token_nll_out, workspace, stream=None):
+    _check(load().dipaco_path_score(ctx.handle, _ptr(path_master), _ptr(path_lowp), _ptr(tokens), _ptr(targets), batch,
+                                    seq, _ptr(doc_loglik_out), _ptr(token_nll_out), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def dipaco_inner_adamw(ctx: Context, path_master, grads, m, v, path_lowp, step: int, lr: float, beta1: float,

@@ -214,9 +214,9 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
 
 // ---- prefix features: forward through the blocks only, one set of layer buffers reused by every block -------
 struct FeaturePlan {
-  size_t x_a, x_b, h, mean, rstd, qkv, o, lse, x_mid, u, act, total;
+  size_t x_a, x_b, h, mean, rstd, qkv, o, lse, x_mid, u, act, logits, nll, n_valid, total;
 };
-static FeaturePlan make_feature_plan(const dipaco_ctx* c, int B, int S) {
+static FeaturePlan make_feature_plan(const dipaco_ctx* c, int B, int S, bool with_head = false) {
   const dipaco_arch& a = c->arch;
   const size_t T = (size_t)B * S, d = a.d_model, A = c->A, F = a.d_mlp;
   const size_t es = a.compute == DIPACO_BF16 ? 2 : 4;
@@ -226,16 +226,19 @@ static FeaturePlan make_feature_plan(const dipaco_ctx* c, int B, int S) {
   p.x_a = take(T * d * es); p.x_b = take(T * d * es); p.h = take(T * d * es); p.mean = take(T * 4); p.rstd = take(T * 4);
   p.qkv = take(T * 3 * A * es); p.o = take(T * A * es); p.lse = take((size_t)B * a.n_heads * S * 4);
   p.x_mid = take(T * d * es); p.u = take(T * F * es); p.act = take(T * F * es);
+  p.logits = p.nll = p.n_valid = 0;
+  if (with_head) { p.logits = take(T * (size_t)a.vocab * es); p.nll = take(T * 4); p.n_valid = take(256); }
   p.total = pos;
   return p;
 }
 
+// out: router features [B, d] (targets == nullptr), or per-document log-likelihood [B] (+ nll_out [B, S], nullable)
 template <typename T>
-static dipaco_status run_features(const dipaco_ctx* c, const T* W, const int* tokens, int B, int S, float* out, char* ws,
-                                  hipStream_t st) {
+static dipaco_status run_features(const dipaco_ctx* c, const T* W, const int* tokens, const int* targets, int B, int S,
+                                  float* out, float* nll_out, char* ws, hipStream_t st) {
   const dipaco_arch& a = c->arch;
   const int T_ = B * S, d = a.d_model, A = c->A, F = a.d_mlp, V = a.vocab, H = a.n_heads, dh = a.d_head;
-  const FeaturePlan p = make_feature_plan(c, B, S);
+  const FeaturePlan p = make_feature_plan(c, B, S, targets != nullptr);
   auto buf = [&](size_t off) { return reinterpret_cast<T*>(ws + off); };
   auto fbuf = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
   T* x = buf(p.x_a);
@@ -257,7 +260,16 @@ static dipaco_status run_features(const dipaco_ctx* c, const T* W, const int* to
                 nullptr, 0, false, 1, nullptr, st));
     std::swap(x, x_other);
   }
-  return launch_mean_pool<T>(x, out, B, S, d, st);
+  if (!targets) return launch_mean_pool<T>(x, out, B, S, d, st);
+  // scoring: final LayerNorm, head, per-token negative log-likelihood, summed per document
+  TRY(launch_layernorm_fwd<T>(x, W + c->lnf_g, W + c->lnf_b, buf(p.h), fbuf(p.mean), fbuf(p.rstd), T_, d, a.ln_eps, st));
+  TRY(gemm<T>(buf(p.h), W + c->w_head, buf(p.logits), T_, V, d, d, V, V, false, false, nullptr, nullptr, nullptr, nullptr,
+              0, false, 1, nullptr, st));
+  int* n_valid = reinterpret_cast<int*>(ws + p.n_valid);
+  float* nll = nll_out ? nll_out : fbuf(p.nll);
+  TRY(launch_count_valid(targets, T_, n_valid, st));
+  TRY(launch_softmax_xent<T>(buf(p.logits), targets, n_valid, nll, T_, V, st));
+  return launch_doc_score(nll, out, B, S, st);
 }
 
 static dipaco_status check_ptr(const void* p, const char* name) {
@@ -455,8 +467,31 @@ dipaco_status dipaco_path_prefix_features(dipaco_ctx* c, const float* master, co
   TRY(check_ptr(ws, "workspace"));
   if (ws_bytes < make_feature_plan(c, B, S).total) return fail(DIPACO_EWORKSPACE, "workspace too small");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (lowprec) return run_features<bf16>(c, static_cast<const bf16*>(lowp), tokens, B, S, features_out, static_cast<char*>(ws), st);
-  return run_features<float>(c, master, tokens, B, S, features_out, static_cast<char*>(ws), st);
+  if (lowprec) return run_features<bf16>(c, static_cast<const bf16*>(lowp), tokens, nullptr, B, S, features_out, nullptr, static_cast<char*>(ws), st);
+  return run_features<float>(c, master, tokens, nullptr, B, S, features_out, nullptr, static_cast<char*>(ws), st);
+}
+
+size_t dipaco_score_workspace_bytes(const dipaco_ctx* c, int32_t batch, int32_t seq) {
+  if (!c || batch < 1 || seq < 1) return 0;
+  return make_feature_plan(c, batch, seq, true).total;
+}
+
+dipaco_status dipaco_path_score(dipaco_ctx* c, const float* master, const void* lowp, const int32_t* tokens,
+                                const int32_t* targets, int32_t B, int32_t S, float* doc_loglik_out, float* nll_out,
+                                void* ws, size_t ws_bytes, void* stream) {
+  if (!c) return fail(DIPACO_EINVAL, "dipaco_path_score: NULL context");
+  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
+  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  const bool lowprec = c->arch.compute == DIPACO_BF16;
+  TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
+  TRY(check_ptr(tokens, "tokens"));
+  TRY(check_ptr(targets, "targets"));
+  TRY(check_ptr(doc_loglik_out, "doc_loglik_out"));
+  TRY(check_ptr(ws, "workspace"));
+  if (ws_bytes < make_feature_plan(c, B, S, true).total) return fail(DIPACO_EWORKSPACE, "workspace too small");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (lowprec) return run_features<bf16>(c, static_cast<const bf16*>(lowp), tokens, targets, B, S, doc_loglik_out, nll_out, static_cast<char*>(ws), st);
+  return run_features<float>(c, master, tokens, targets, B, S, doc_loglik_out, nll_out, static_cast<char*>(ws), st);
 }
 
 dipaco_status dipaco_inner_adamw(dipaco_ctx* c, float* master, const float* grads, float* m, float* v, void* lowp,

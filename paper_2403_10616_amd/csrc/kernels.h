@@ -106,6 +106,8 @@ dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, in
 size_t colsum_partial_floats(int rows, int cols);
 // out[b, :] (fp32) = mean over positions of x[b*S + p, :]
 template <typename T> dipaco_status launch_mean_pool(const T* x, float* out, int B, int S, int d, hipStream_t s);
+// out[b] = -sum_p nll[b*S + p]
+dipaco_status launch_doc_score(const float* nll, float* out, int B, int S, hipStream_t s);
 // n_valid[0] = #targets >= 0
 dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStream_t s);
 // logits [rows, V] (T) -> nll[rows] fp32 and, in place, dlogits = (softmax - onehot)/n_valid (0 on ignored rows)

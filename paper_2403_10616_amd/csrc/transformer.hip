@@ -574,6 +574,24 @@ __global__ void __launch_bounds__(256) mean_pool_kernel(const T* __restrict__ x,
   }
 }
 
+// out[b] = -(sum over the S positions of nll[b*S + p]), positions added in a fixed tree order
+__global__ void __launch_bounds__(256) doc_score_kernel(const float* __restrict__ nll, float* __restrict__ out, int S) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  float s = 0.f;
+  for (int p = threadIdx.x; p < S; p += 256) s += nll[(size_t)b * S + p];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) out[b] = -(((red[0] + red[1]) + red[2]) + red[3]);
+}
+
+dipaco_status launch_doc_score(const float* nll, float* out, int B, int S, hipStream_t s) {
+  doc_score_kernel<<<B, 256, 0, s>>>(nll, out, S);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
 template <typename T>
 dipaco_status launch_mean_pool(const T* x, float* out, int B, int S, int d, hipStream_t s) {
   mean_pool_kernel<T><<<B, 256, 0, s>>>(x, out, S, d);

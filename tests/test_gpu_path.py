@@ -205,3 +205,32 @@ def test_prefix_features_match_oracle(name, B, S, compute, tol):
         dp.dipaco_path_prefix_features(ctx, dev(theta.astype(np.float32)), None if compute == dp.F32 else dev(theta).to(torch.bfloat16),
                                        dev(tok.astype(np.int32)), B, S, torch.zeros((B, a.d_model), device=DEV),
                                        torch.empty(16, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("name,B,S,compute,mask", [("ragged", 3, 50, dp.F32, 5), ("wide", 4, 160, dp.F32, 32),
+                                                   ("wide", 4, 160, dp.BF16, 32), ("one_level", 2, 16, dp.F32, 0)])
+def test_path_scores_match_oracle_and_training_loss(name, B, S, compute, mask):
+    print(f"scores {name} B={B} S={S} compute={compute}", flush=True)
+    cfg = SHAPES[name]
+    a, ctx = make_arch(cfg, compute)
+    lay = orc.param_layout(a)
+    theta = gen.random_params(orc.param_count(a), seed=41, scale=0.08)
+    for n_, (off, shape, _) in lay.items():
+        if n_.endswith("_g"):
+            theta[off:off + shape[0]] += 1.0
+    tok, tgt = _batch(cfg, B, S, seed=42, mask_prefix=mask)
+    master = dev(theta.astype(np.float32))
+    lowp = master.to(torch.bfloat16) if compute == dp.BF16 else None
+    score = torch.zeros(B, dtype=torch.float32, device=DEV)
+    nll = torch.zeros(B * S, dtype=torch.float32, device=DEV)
+    ws = torch.empty(dp.dipaco_score_workspace_bytes(ctx, B, S), dtype=torch.uint8, device=DEV)
+    dp.dipaco_path_score(ctx, master, lowp, dev(tok.astype(np.int32)), dev(tgt.astype(np.int32)), B, S, score, nll, ws)
+    ref_theta = theta if compute == dp.F32 else master.to(torch.bfloat16).float().cpu().numpy()
+    want = orc.path_doc_scores(ref_theta, a, tok, tgt)
+    tol = 1e-5 if compute == dp.F32 else 2e-2
+    assert np.abs(host(score) - want).max() <= tol * np.abs(want).max()
+    assert np.abs(host(nll).reshape(B, S).sum(1) + host(score)).max() <= 1e-3 * np.abs(want).max()
+    # the forward pass of the training step gives the same per-token values
+    st = PathState(ctx, theta, B, S)
+    st.fwd_bwd(tok, tgt)
+    assert np.abs(host(st.nll) - host(nll)).max() <= (1e-5 if compute == dp.F32 else 5e-2)

@@ -216,3 +216,25 @@ def test_prefix_features_closed_forms():
     logits = y @ orc.view(theta, lay, "w_head")
     assert np.abs(logits - orc.path_logits(theta, TINY, tok)[:, 0, :]).max() <= 1e-12
     assert np.array_equal(orc.prefix_features(theta, TINY, tok[[2, 0]]), f[[2, 0]])
+
+
+# ---- path scores for discriminative routing ------------------------------------------------------------------------
+def test_doc_scores_relation_to_loss_and_closed_form():
+    a = WIDE
+    theta = gen.random_params(orc.param_count(a), seed=23, scale=0.3, dtype=np.float64)
+    tok, tgt = _data(a, 4, 7, seed=24, mask_prefix=2)
+    sc = orc.path_doc_scores(theta, a, tok, tgt)
+    n_t = int((tgt >= 0).sum())
+    assert abs(-sc.sum() / n_t - orc.path_loss(theta, a, tok, tgt)) <= 1e-12       # the loss is their mean
+    t = torch.tensor(theta, dtype=torch.float64)
+    for b in range(4):                                                           # per document, from the torch build
+        lb = _torch_loss(t, a, tok[b:b + 1], tgt[b:b + 1]).item() * int((tgt[b] >= 0).sum())
+        assert abs(sc[b] + lb) <= 1e-10
+    lay = orc.param_layout(a)
+    off, shape, _ = lay["w_head"]
+    flat = theta.copy()
+    flat[off:off + int(np.prod(shape))] = 0.0                                    # zero head: uniform prediction
+    sc0 = orc.path_doc_scores(flat, a, tok, tgt)
+    assert np.allclose(sc0, -(tgt >= 0).sum(axis=1) * math.log(a.vocab), atol=1e-12)
+    labels = orc.route_labels_from_scores(np.array([[1.0, 5.0, 2.0], [1.0, 4.0, 3.0]]))
+    assert np.array_equal(labels, [0, 0, 1])                                     # ties to the first path
