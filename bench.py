@@ -10,6 +10,7 @@ Other workloads (for profiling single kernels; same JSON shape):
   --workload route        2^20 x 768 prefix embeddings against 256 centroids
   --workload outer_stream the same module, the 16 deltas accumulated one at a time, then the Nesterov update
   --workload features     router features of 8192 documents (32-token prefixes) through the config-2 path's blocks
+  --workload score        forward-only log-likelihood of 16 documents x 2048 tokens under the config-5 path
   --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
   --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
   --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
@@ -342,6 +343,46 @@ def bench_features(args):
                          "flops_per_launch": flops}}
 
 
+def bench_score(args):
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[5]
+    B, S = cfg["batch"], cfg["seq"]
+    ctx = dp.Context(**_arch_kwargs(cfg, dp.BF16))
+    n = dp.dipaco_path_param_count(ctx)
+    dev = "cuda"
+    lowp = (torch.randn(n, device=dev) * 0.02).to(torch.bfloat16)
+    seqs = gen.zipf_tokens((B, S + 1), cfg["vocab"], cfg["zipf_s"], cfg["seed"])
+    tok = torch.from_numpy(np.ascontiguousarray(seqs[:, :-1]).astype(np.int32)).to(dev)
+    tgt = torch.from_numpy(np.ascontiguousarray(seqs[:, 1:]).astype(np.int32)).to(dev)
+    out = torch.empty(B, dtype=torch.float32, device=dev)
+    ws = torch.empty(dp.dipaco_score_workspace_bytes(ctx, B, S), dtype=torch.uint8, device=dev)
+
+    def step():
+        dp.dipaco_path_score(ctx, None, lowp, tok, tgt, B, S, out, None, ws)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    fwd, _, _ = step_gemm_shapes(cfg, B, S)
+    flops = sum(2.0 * M * N * K for M, N, K in fwd) + attention_flops(cfg, B, S)[0]
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"metric": "path-scoring tokens/sec on 1 MI355X (forward only)", "value": B * S / (ms * 1e-3), "unit": "tokens/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "config-5 path (174.9M parameters), 16 documents x 2048 Zipf(1.1) tokens, forward + per-document log-likelihood"},
+            "roofline": {"bound": "mfma", "kernel": "gemm_dlds_kernel (forward layout) + attn_fwd_mfma", "achieved": ach,
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                         "flops_per_launch": flops}}
+
+
 def bench_kmeans(args):
     import torch
     import dipaco_inputs as gen
@@ -483,7 +524,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "route", "kmeans", "features", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "route", "kmeans", "features", "score", "gemm", "attention"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
@@ -497,7 +538,7 @@ def main():
         sys.exit("bench.py: this build runs one path on ONE GPU (no collectives, no sharding); use --gpus 1")
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
-    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "outer_stream": bench_outer_stream,
+    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 
