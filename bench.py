@@ -165,7 +165,7 @@ def bench_path_step(args):
                      "avg_launch_us": gemm_ms * 1e3 / len(fwd)},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline_path_step(cfg, theta, seqs[0, :1], layout)
+        out["cpu_baseline"] = cpu_baseline_path_step(cfg, theta, seqs[0, :3], layout)
     return out
 
 
@@ -187,7 +187,8 @@ def cpu_baseline_path_step(cfg, theta, seqs, layout):
     except Exception:
         cores = os.cpu_count()
     return {"value": tok.size / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 of the 32 sequences (1024 tokens) of the same batch, fwd+bwd+AdamW in fp64 numpy, {dt:.1f} s",
+            "sample": f"{tok.shape[0]} of the 32 sequences ({tok.size} tokens) of the same batch, fwd+bwd+AdamW in fp64 numpy, "
+                      f"{dt:.1f} s",
             "loss": loss}
 
 

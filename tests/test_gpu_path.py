@@ -23,6 +23,8 @@ SHAPES = {
     "ragged": dict(layers_per_level=(1, 2), d_model=72, n_heads=3, d_head=32, d_mlp=200, vocab=264, max_seq=56),
     "wide": dict(layers_per_level=(1, 1), d_model=256, n_heads=2, d_head=64, d_mlp=520, vocab=1000, max_seq=160),
     "one_level": dict(layers_per_level=(2,), d_model=64, n_heads=1, d_head=128, d_mlp=64, vocab=64, max_seq=16),
+    # a vocabulary row too long for the register-resident cross-entropy kernel: the three-pass kernel runs
+    "big_vocab": dict(layers_per_level=(1,), d_model=64, n_heads=2, d_head=32, d_mlp=64, vocab=40000, max_seq=8),
 }
 
 
@@ -39,7 +41,7 @@ def _batch(cfg, B, S, seed, mask_prefix=0, zipf=False):
 
 
 @pytest.mark.parametrize("name,B,S,mask", [("ragged", 3, 50, 0), ("ragged", 2, 56, 5), ("wide", 2, 160, 32),
-                                           ("one_level", 5, 16, 0), ("one_level", 1, 1, 0)])
+                                           ("one_level", 5, 16, 0), ("one_level", 1, 1, 0), ("big_vocab", 2, 8, 1)])
 def test_fp32_loss_and_gradients_match_oracle(name, B, S, mask):
     print(f"fp32 path {name} B={B} S={S} mask={mask}", flush=True)
     cfg = SHAPES[name]
