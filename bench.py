@@ -447,7 +447,7 @@ def bench_gemm(args):
     resid = torch.empty(M * N, dtype=torch.bfloat16, device=dev).normal_() if ep == "resid" else None
     aux_out = torch.empty(M * N, dtype=torch.bfloat16, device=dev) if ep == "gelu" else None
     aux_in = torch.empty(M * N, dtype=torch.bfloat16, device=dev).normal_() if ep == "dgelu" else None
-    act = {"gelu": 1, "dgelu": 2}.get(ep, 0)
+    act = {"gelu": 3, "dgelu": 4}.get(ep, 0)   # the pair the path step uses: GELU' saved in forward, multiplied in backward
     splits, partial = 1, None
     if out_f32 and args.splits > 1:
         splits = args.splits

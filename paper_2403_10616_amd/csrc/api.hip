@@ -64,7 +64,7 @@ struct Plan {
   size_t total;
 };
 
-static int dw_splits(int M, int N, int K) { return gemm_plan_splits(M, N, K); }
+template <typename T> static int dw_splits(int M, int N, int K) { return gemm_plan_splits(M, N, K, sizeof(T) == 2); }
 
 static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   const dipaco_arch& a = c->arch;
@@ -136,7 +136,7 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
   // weight gradient dW[K_in, N_out] = X^T . dY (contraction over the tokens), fp32 into the gradient buffer
   auto dweight = [&](const T* X, const T* dY, size_t w_off, int K_in, int N_out) {
     return gemm<T>(X, dY, G + w_off, K_in, N_out, T_, K_in, N_out, N_out, true, false, nullptr, nullptr, nullptr, nullptr,
-                   0, true, dw_splits(K_in, N_out, T_), skp, st);
+                   0, true, dw_splits<T>(K_in, N_out, T_), skp, st);
   };
 
   // ---------------- forward ----------------

@@ -164,6 +164,41 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
 
 }  // namespace
 
+namespace {
+// As splitk_reduce_kernel, for partial planes in which the number of K slices depends on where the element lies:
+// n_slices[(row >= row_edge) + 2 * (col >= col_edge)]
+__global__ void __launch_bounds__(256) splitk_reduce_classes_kernel(const float* __restrict__ partial,
+                                                                    float* __restrict__ C, int M, int N, long ldc,
+                                                                    int row_edge, int col_edge, int s0, int s1, int s2,
+                                                                    int s3) {
+  const size_t total = (size_t)M * N, quads = total / 4;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < quads; q += stride) {
+    const size_t i = 4 * q;
+    const size_t row = i / N, col = i - row * N;   // N is a multiple of 8: the four elements share a row
+    const bool er = (int)row >= row_edge, ec = (int)col >= col_edge;
+    const int n = er ? (ec ? s3 : s1) : (ec ? s2 : s0);
+    float4 acc = *reinterpret_cast<const float4*>(partial + i);
+    for (int z = 1; z < n; ++z) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)z * total + i);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(C + row * ldc + col) = acc;
+  }
+}
+}  // namespace
+
+dipaco_status launch_splitk_reduce_classes(const float* partial, float* C, int M, int N, long ldc, int row_edge,
+                                           int col_edge, const int (&n_slices)[4], hipStream_t s) {
+  if (N % 8 || ldc % 4 || col_edge % 4) return fail(DIPACO_ESHAPE, "split-K reduce: N, ldc, col_edge must be multiples of 8, 4, 4");
+  const size_t quads = (size_t)M * N / 4;
+  const int rb = (int)std::min<size_t>((quads + 255) / 256, 256 * 32);
+  splitk_reduce_classes_kernel<<<rb, 256, 0, s>>>(partial, C, M, N, ldc, row_edge, col_edge, n_slices[0], n_slices[1],
+                                                  n_slices[2], n_slices[3]);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
 dipaco_status launch_splitk_reduce(const float* partial, float* C, int M, int N, long ldc, int splits, hipStream_t s) {
   const size_t total = (size_t)M * N;
   const int rb = (int)std::min<size_t>((total + 255) / 256, 256 * 32);
@@ -258,8 +293,13 @@ static int splits_tile128(int M, int N, int smax) {
   return (int)std::max<long>(s, 1);
 }
 
-int gemm_plan_splits(int M, int N, int K) {
+int gemm_plan_splits(int M, int N, int K, bool bf16_operands) {
   const int smax = (int)std::min<long>(16, std::max(1, K / 256));
+  if (bf16_operands && (g_forced_tile == 0 || g_forced_tile >= 5)) {
+    // direct-to-LDS kernel, one workgroup per compute unit, fewer slices for tiles that stick out of C
+    const int s = gemm_dlds_plan_slices(M, N, K, (int)std::min<long>(GEMM_SLICE_CAP, std::max(1, K / 256)), false);
+    if (s) return s;
+  }
   if (g_forced_tile == 0 || g_forced_tile >= 4) {
     const int s = splits_tile256(M, N, K, smax);
     if (s) return s;
@@ -270,7 +310,9 @@ int gemm_plan_splits(int M, int N, int K) {
 // Upper bound of gemm_plan_splits over every tile setting: sizes the partial-product workspace.
 int gemm_max_splits(int M, int N, int K) {
   const int smax = (int)std::min<long>(16, std::max(1, K / 256));
-  return std::max(splits_tile256(M, N, K, smax), splits_tile128(M, N, smax));
+  const int cap = (int)std::min<long>(GEMM_SLICE_CAP, std::max(1, K / 256));
+  return std::max(std::max(splits_tile256(M, N, K, smax), splits_tile128(M, N, smax)),
+                  gemm_dlds_plan_slices(M, N, K, cap, true));
 }
 
 template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s) {

@@ -16,6 +16,14 @@ struct GemmDev {
   int k_per_split;   // multiple of BK
   float* partial;
   int tiles_m, tiles_n;
+  // Uneven split-K (weight gradients, one workgroup per compute unit): tiles fall into four classes -- inside C,
+  // sticking out over its last rows, over its last columns, over both -- and a class whose tiles cost less per K
+  // step is cut into fewer K slices, so that all workgroups of the launch end together.  Class c owns workgroup
+  // ids [cls_base[c], cls_base[c + 1]), slice-major; full_m / full_n = tile rows / columns of the first class.
+  int uneven = 0;
+  int cls_s[4];
+  int cls_base[5];
+  int full_m, full_n;
 };
 
 constexpr int N_XCD = 8;
@@ -58,6 +66,29 @@ __device__ __forceinline__ void gemm_tile_of_block(const GemmDev& g, int bid, in
   tile_n = in_group / gsize;
 }
 
+// XCD x gets the contiguous range [x * per, ...) of `total` work items
+__device__ __forceinline__ int xcd_contiguous(int bid, int total) {
+  const int per = total / N_XCD, rem = total % N_XCD;
+  const int x = bid % N_XCD, i = bid / N_XCD;
+  return x * per + min(x, rem) + i;
+}
+
+// Uneven split-K: workgroup id -> tile, K slice and the number of slices its tile is cut into.
+__device__ __forceinline__ void gemm_uneven_of_block(const GemmDev& g, int bid, int& split, int& nsplit, int& tile_m,
+                                                     int& tile_n) {
+  const int v = xcd_contiguous(bid, g.cls_base[4]);
+  const int c = (v >= g.cls_base[1]) + (v >= g.cls_base[2]) + (v >= g.cls_base[3]);
+  const int local = v - g.cls_base[c];
+  nsplit = g.cls_s[c];
+  const int n_tiles = (g.cls_base[c + 1] - g.cls_base[c]) / nsplit;
+  split = local / n_tiles;
+  const int t = local - split * n_tiles;
+  if (c == 0) { tile_m = t % g.full_m; tile_n = t / g.full_m; }
+  else if (c == 1) { tile_m = g.full_m; tile_n = t; }
+  else if (c == 2) { tile_m = t; tile_n = g.full_n; }
+  else { tile_m = g.full_m; tile_n = g.full_n; }
+}
+
 // Eight consecutive elements of T as raw 16-byte vectors (loaded early, converted when used).
 template <typename T> struct Raw8 { uint4 v[sizeof(T) / 2]; };
 template <typename T> __device__ __forceinline__ Raw8<T> raw8_load(const T* p) {
@@ -76,8 +107,8 @@ template <typename T> __device__ __forceinline__ void raw8_unpack(const Raw8<T>&
 // through stg, a wave-private LDS region of 32 x (WN + 4) floats, 32 rows at a time, so that bias / GELU /
 // residual are applied on, and C is written with, 16-byte row-contiguous accesses.  N is a multiple of 8 (checked
 // on the host), so an 8-column group is either inside C or outside.  The residual / auxiliary input vectors of a
-// block of 32 rows are requested before its accumulators are staged, so that their latency is paid once per block
-// and mostly behind the staging, not once per vector.
+// block of 32 rows are requested one block ahead (two register buffers), so that their latency hides behind the
+// staging, arithmetic and stores of the block before.
 template <typename T, typename TC, int TM, int TN, int WN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0, int col0,
                                               int split, const GemmDev& g) {
@@ -92,19 +123,24 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
   const bool to_partial = g.splits > 1;
   float* P = to_partial ? g.partial + (size_t)split * g.M * g.N : nullptr;
   const bool want_aux = g.act == 2 || g.act == 4;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    Raw8<T> rres[ITERS], raux[ITERS];
+  // one operand stream is requested ahead: the saved operand if there is one, else the residual (a product that
+  // takes both loads its residual where it is used)
+  const T* ahead = want_aux ? aux_in : resid;
+  const bool resid_late = want_aux && resid;
+  Raw8<T> rin[2][ITERS];
+  // requests the vectors of 32-row block i into buffer i & 1
+  auto prefetch = [&](int i) {
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       const int item = lane + WAVE * it;
       const int row = row0 + 32 * i + item / GROUPS, col = col0 + 8 * (item % GROUPS);
-      if (row < g.M && col < g.N) {
-        const size_t off = (size_t)row * g.ldc + col;
-        if (resid) rres[it] = raw8_load(resid + off);
-        if (want_aux) raux[it] = raw8_load(aux_in + off);
-      }
+      if (ahead && row < g.M && col < g.N) rin[i & 1][it] = raw8_load(ahead + (size_t)row * g.ldc + col);
     }
+  };
+  prefetch(0);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    if (i + 1 < TM) prefetch(i + 1);   // in flight while block i is staged, combined and stored
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -144,13 +180,13 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
         OutVec<T>::store(aux_out + off, dv);
       } else if (want_aux) {
         float u[8];
-        raw8_unpack(raux[it], u);
+        raw8_unpack(rin[i & 1][it], u);
 #pragma unroll
         for (int c = 0; c < 8; ++c) v[c] *= g.act == 2 ? gelu_grad_t<T>(u[c]) : u[c];
       }
       if (resid) {
         float rv[8];
-        raw8_unpack(rres[it], rv);
+        raw8_unpack(resid_late ? raw8_load(resid + off) : rin[i & 1][it], rv);
 #pragma unroll
         for (int c = 0; c < 8; ++c) v[c] += rv[c];
       }

@@ -21,6 +21,8 @@
 // everybody is done reading this stage) -> [this stage is refilled with the tile four ahead and the next tile's
 // first fragments are read, both under the MFMAs of the second half].  The loads are inline assembly: written
 // with the builtin, the compiler puts a full vmcnt(0) in front of every later LDS read, which serialises the ring.
+#include <algorithm>
+#include <cmath>
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -65,17 +67,26 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // Waves w and w + 4 share a SIMD.  They are given different halves of the tile's rows AND of its columns, so
   // that in a tile that sticks out of C by half (896 = 3.5 x 256 is the path's width) every SIMD keeps exactly
-  // one wave with work, which then has the matrix core to itself: such a tile costs half a tile.
+  // one wave with work, which then has the matrix core to itself.  (Letting the idle wave of the SIMD take half of
+  // every K tile of its partner's outputs was measured: no gain, the launch is not bound by that wave's latencies.)
   static_assert(WGM == 2 && (WGN == 4 || WGN == 2), "wave placement below is written for 2 x 4 and 2 x 2 waves");
   const int wm = WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1;
   const int wn = WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1;
-  int split, tile_m, tile_n;
-  gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
+  int split, tile_m, tile_n, k_begin, nkt;
+  if (g.uneven) {
+    int nsplit;
+    gemm_uneven_of_block(g, blockIdx.x, split, nsplit, tile_m, tile_n);
+    const long ktiles = g.K / DL_BK;
+    const int kt0 = (int)(split * ktiles / nsplit), kt1 = (int)((split + 1) * ktiles / nsplit);
+    k_begin = kt0 * DL_BK;
+    nkt = kt1 - kt0;
+  } else {
+    gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
+    k_begin = split * g.k_per_split;
+    nkt = (min(g.K, k_begin + g.k_per_split) - k_begin) / DL_BK;
+  }
   const int m0 = tile_m * DL_BM, n0 = tile_n * DL_BN;
   const bool active = m0 + wm * (DL_BM / WGM) < g.M && n0 + wn * (DL_BN / WGN) < g.N;   // wave-uniform
-  const int k_begin = split * g.k_per_split;
-  const int k_end = min(g.K, k_begin + g.k_per_split);
-  const int nkt = (k_end - k_begin) / DL_BK;
 
   // ---- loads: wave-level load j fills LDS bytes [1024 j, 1024 j + 1024) of a stage; j < NLA: A tile, else B tile.
   // Rows (columns) beyond the operand re-read its last ones: they only feed outputs that are never stored.
@@ -231,6 +242,45 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
                                       m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
 }
 
+// ---- uneven split-K ----------------------------------------------------------------------------------------
+// Cost of one K step of a tile in which only the fraction `frac` of the waves has work, relative to a full tile
+// (measured: 0.73 for half a tile -- the operand loads are the same, the matrix-core work halves).
+double partial_tile_cost(double frac) { return 0.5 + 0.5 * frac; }
+
+struct UnevenPlan {
+  int s[4];          // K slices per class; s[0] = the largest
+  int n[4];          // tiles per class
+  int full_m, full_n;
+};
+
+// The largest slice count <= max_slices such that every tile class c, cut into ceil(cost_c * s) slices, still
+// gives at most one workgroup per compute unit.  False if there is no such plan with at least two slices.
+bool plan_uneven(int M, int N, int K, int BN, int WGN, int max_slices, UnevenPlan& p) {
+  constexpr int CUS = 256;
+  const int tiles_m = (M + DL_BM - 1) / DL_BM, tiles_n = (N + BN - 1) / BN;
+  if ((long)tiles_m * tiles_n > CUS / 2) return false;
+  const int rm = M - (tiles_m - 1) * DL_BM, rn = N - (tiles_n - 1) * BN;
+  const int WM = DL_BM / 2, WN = BN / WGN;
+  const double am = (double)((rm + WM - 1) / WM) / 2, an = (double)((rn + WN - 1) / WN) / WGN;
+  p.full_m = tiles_m - (am < 1.0 ? 1 : 0);
+  p.full_n = tiles_n - (an < 1.0 ? 1 : 0);
+  p.n[0] = p.full_m * p.full_n;
+  p.n[1] = (tiles_m - p.full_m) * p.full_n;
+  p.n[2] = p.full_m * (tiles_n - p.full_n);
+  p.n[3] = (tiles_m - p.full_m) * (tiles_n - p.full_n);
+  const double w[4] = {1.0, partial_tile_cost(am), partial_tile_cost(an), partial_tile_cost(am * an)};
+  const int ktiles = K / DL_BK;
+  for (int sf = std::min(max_slices, ktiles); sf >= 2; --sf) {
+    long total = 0;
+    for (int c = 0; c < 4; ++c) {
+      p.s[c] = std::min(sf, std::max(1, (int)std::ceil(w[c] * sf - 1e-9)));
+      total += (long)p.n[c] * p.s[c];
+    }
+    if (total <= CUS) return true;
+  }
+  return false;
+}
+
 template <typename TC, bool A_KC, bool B_KC, int BN, int WGM, int WGN, int STAGES>
 dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_ROWB;
@@ -250,6 +300,19 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   g.tiles_m = (a.M + DL_BM - 1) / DL_BM;
   g.tiles_n = (a.N + BN - 1) / BN;
   const int ktiles = a.K / DL_BK;
+  UnevenPlan up;
+  if (a.splits > 1 && plan_uneven(a.M, a.N, a.K, BN, WGN, a.splits, up)) {
+    g.uneven = 1;
+    g.splits = up.s[0];
+    g.k_per_split = 0;
+    g.full_m = up.full_m; g.full_n = up.full_n;
+    g.cls_base[0] = 0;
+    for (int c = 0; c < 4; ++c) { g.cls_s[c] = up.s[c]; g.cls_base[c + 1] = g.cls_base[c] + up.n[c] * up.s[c]; }
+    kern<<<(unsigned)g.cls_base[4], 64 * WGM * WGN, smem, s>>>(g);
+    DIPACO_LAUNCH_CHECK();
+    return launch_splitk_reduce_classes(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, up.full_m * DL_BM,
+                                        up.full_n * BN, up.s, s);
+  }
   int splits = a.splits < 1 ? 1 : a.splits;
   if (splits > ktiles) splits = ktiles;
   g.k_per_split = ((ktiles + splits - 1) / splits) * DL_BK;
@@ -287,6 +350,14 @@ bool gemm_dlds_eligible(const GemmArgs& a) {
 }
 
 void set_gemm_dlds_shape(int shape) { g_dlds_shape = shape; }
+
+int gemm_dlds_plan_slices(int M, int N, int K, int max_slices, bool any_shape) {
+  UnevenPlan up;
+  const int wide = plan_uneven(M, N, K, 256, 4, max_slices, up) ? up.s[0] : 0;
+  const int narrow = plan_uneven(M, N, K, 128, 2, max_slices, up) ? up.s[0] : 0;
+  if (any_shape) return std::max(wide, narrow);
+  return g_dlds_shape == 2 ? narrow : wide;
+}
 
 dipaco_status launch_gemm_dlds(const GemmArgs& a, hipStream_t s) {
   if (!gemm_dlds_eligible(a)) return fail(DIPACO_EUNSUPPORTED, "gemm: shape not supported by the direct-to-LDS kernel");

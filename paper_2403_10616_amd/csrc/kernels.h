@@ -83,7 +83,16 @@ dipaco_status launch_splitk_reduce(const float* partial, float* C, int M, int N,
 // direct-to-LDS kernel wherever the shape allows, 6 / 7 = the same with its 256x256 / 256x128 shape forced
 // (tuning and tests)
 void set_gemm_tile(int t);
-int gemm_plan_splits(int M, int N, int K);   // split count the weight-gradient products are launched with
+// the same where the number of slices depends on the tile class of the element:
+// n_slices[(row >= row_edge) + 2 * (col >= col_edge)]
+dipaco_status launch_splitk_reduce_classes(const float* partial, float* C, int M, int N, long ldc, int row_edge,
+                                           int col_edge, const int (&n_slices)[4], hipStream_t s);
+// direct-to-LDS kernel: slices of a full tile in its uneven split-K plan with at most max_slices, 0 if it has none
+// (for the tile shape in force, or the larger count over both shapes)
+int gemm_dlds_plan_slices(int M, int N, int K, int max_slices, bool any_shape);
+constexpr int GEMM_SLICE_CAP = 32;
+// split count the weight-gradient products are launched with
+int gemm_plan_splits(int M, int N, int K, bool bf16_operands);
 int gemm_max_splits(int M, int N, int K);    // its upper bound over tile settings (workspace sizing)
 
 // ---- transformer.hip ---------------------------------------------------------------------------------
