@@ -90,7 +90,7 @@ static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   p.dqkv = take(T * 3 * A * es); p.d_o = take(T * A * es); p.dsum = take(2 * (size_t)B * a.n_heads * ((S + 127) / 128 * 128) * 4);
   p.ln_partial = take(ln_bwd_partial_floats((int)T, (int)d) * 4);
   const size_t widest = std::max(std::max(F, 3 * A), d);
-  p.cs_partial = take(colsum_partial_floats((int)T, (int)widest) * 4);
+  p.cs_partial = take(std::max(colsum_partial_floats((int)T, (int)widest), gemm_colsum_partial_floats((int)T, (int)F)) * 4);
   size_t sk = 0;
   auto need = [&](size_t M, size_t N) { sk = std::max(sk, (size_t)gemm_max_splits((int)M, (int)N, (int)T) * M * N); };
   need(d, 3 * A); need(A, d); need(d, F); need(F, d); need(d, V);
@@ -104,8 +104,10 @@ static Plan make_plan(const dipaco_ctx* c, int B, int S) {
 template <typename T>
 static dipaco_status gemm(const T* A, const T* B, void* C, int M, int N, int K, long lda, long ldb, long ldc,
                           bool ta, bool tb, const T* bias, const T* resid, T* aux_out, const T* aux_in, int act,
-                          bool out_f32, int splits, float* partial, hipStream_t s) {
+                          bool out_f32, int splits, float* partial, hipStream_t s, float* colsum = nullptr,
+                          float* colsum_partial = nullptr) {
   GemmArgs g;
+  g.colsum = colsum; g.colsum_partial = colsum_partial;
   g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.bias = bias; g.resid = resid; g.aux_out = aux_out; g.aux_in = aux_in; g.act = act;
   g.trans_a = ta; g.trans_b = tb; g.out_f32 = out_f32; g.splits = splits; g.partial = partial;
@@ -186,10 +188,10 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
     const BlockOff& o = c->blocks[l];
     // x_next = x_mid + gelu(u) W_down + b_down
     TRY(dweight(buf(L.act), dx, o.w_down, F, d));
+    // du = (dx W_down^T) * GELU'(u); its column sums, the gradient of b_up, come out of the same product
     TRY(gemm<T>(dx, W + o.w_down, buf(p.du), T_, F, d, d, d, F, false, true, nullptr, nullptr, nullptr, buf(L.u), 4,
-                false, 1, nullptr, st));
+                false, 1, nullptr, st, G + o.b_up, csp));
     TRY(dweight(buf(L.h2), buf(p.du), o.w_up, d, F));
-    TRY(launch_colsum<T>(buf(p.du), G + o.b_up, csp, T_, F, st));
     TRY(gemm<T>(buf(p.du), W + o.w_up, buf(p.dh), T_, d, F, F, F, d, false, true, nullptr, nullptr, nullptr, nullptr, 0,
                 false, 1, nullptr, st));
     TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_mid), W + o.ln2_g, fbuf(L.mean2), fbuf(L.rstd2), dx, dx_other,

@@ -237,9 +237,12 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   if (g.splits < 1) g.splits = 1;
   const long blocks = (long)g.tiles_m * g.tiles_n * g.splits;
   if (blocks > 0x7fffffffL) return fail(DIPACO_ESHAPE, "gemm: too many tiles");
+  g.colsum_partial = a.colsum ? a.colsum_partial : nullptr;
   kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
+  constexpr int WAVE_ROWS = BM / WGM;
+  if (a.colsum) return launch_sum_rows(a.colsum_partial, a.colsum, (a.M + WAVE_ROWS - 1) / WAVE_ROWS, a.N, s);
   return DIPACO_OK;
 }
 
@@ -293,6 +296,8 @@ static int splits_tile128(int M, int N, int smax) {
   return (int)std::max<long>(s, 1);
 }
 
+size_t gemm_colsum_partial_floats(int M, int N) { return (size_t)((M + 31) / 32) * N; }
+
 int gemm_plan_splits(int M, int N, int K, bool bf16_operands) {
   const int smax = (int)std::min<long>(16, std::max(1, K / 256));
   if (bf16_operands && (g_forced_tile == 0 || g_forced_tile >= 5)) {
@@ -332,6 +337,8 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s
   if ((a.act == 1 || a.act == 3) && !a.aux_out) return fail(DIPACO_EINVAL, "gemm: act 1 / 3 need aux_out");
   if ((a.act == 2 || a.act == 4) && !a.aux_in) return fail(DIPACO_EINVAL, "gemm: act 2 / 4 need aux_in");
   if (a.out_f32 && (a.bias || a.resid || a.act)) return fail(DIPACO_EINVAL, "gemm: fp32 output takes no epilogue");
+  if (a.colsum && (!a.colsum_partial || a.splits > 1 || !aligned16(a.colsum_partial)))
+    return fail(DIPACO_EINVAL, "gemm: column sums need their scratch and no split-K");
   if (a.splits > 1 && (!a.out_f32 || a.bias || a.resid || a.act || !a.partial))
     return fail(DIPACO_EINVAL, "gemm: split-K needs fp32 output, a partial buffer and no epilogue");
   if constexpr (std::is_same<T, bf16>::value) {

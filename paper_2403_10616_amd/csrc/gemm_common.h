@@ -15,6 +15,7 @@ struct GemmDev {
   int splits;
   int k_per_split;   // multiple of BK
   float* partial;
+  float* colsum_partial = nullptr;   // [ceil(M / rows of a wave)][N]: column sums of each wave's rows of C
   int tiles_m, tiles_n;
   // Uneven split-K (weight gradients, one workgroup per compute unit): tiles fall into four classes -- inside C,
   // sticking out over its last rows, over its last columns, over both -- and a class whose tiles cost less per K
@@ -138,6 +139,8 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
     }
   };
   prefetch(0);
+  static_assert(WAVE % GROUPS == 0, "a lane keeps its column group over the items");
+  float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // column sums over this lane's rows
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     if (i + 1 < TM) prefetch(i + 1);   // in flight while block i is staged, combined and stored
@@ -191,7 +194,21 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
         for (int c = 0; c < 8; ++c) v[c] += rv[c];
       }
       OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
+      if (g.colsum_partial) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) cs[c] += v[c];
+      }
     }
+  }
+  if (g.colsum_partial && !to_partial) {
+    // lanes l, l + GROUPS, ... hold the same columns: fixed butterfly, then one row of partial sums per wave
+#pragma unroll
+    for (int m = GROUPS; m < WAVE; m <<= 1)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) cs[c] += __shfl_xor(cs[c], m, WAVE);
+    const int col = col0 + 8 * lane;
+    if (lane < GROUPS && col < g.N && row0 < g.M)
+      OutVec<float>::store(g.colsum_partial + (size_t)(row0 / (32 * TM)) * g.N + col, cs);
   }
 }
 

@@ -319,9 +319,12 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   g.splits = (a.K + g.k_per_split - 1) / g.k_per_split;
   const long blocks = (long)g.tiles_m * g.tiles_n * g.splits;
   if (blocks > 0x7fffffffL) return fail(DIPACO_ESHAPE, "gemm: too many tiles");
+  g.colsum_partial = a.colsum ? a.colsum_partial : nullptr;
   kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
+  constexpr int WAVE_ROWS = DL_BM / WGM;
+  if (a.colsum) return launch_sum_rows(a.colsum_partial, a.colsum, (a.M + WAVE_ROWS - 1) / WAVE_ROWS, a.N, s);
   return DIPACO_OK;
 }
 

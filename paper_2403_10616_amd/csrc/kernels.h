@@ -70,7 +70,12 @@ struct GemmArgs {
   int out_f32;
   int splits;
   float* partial;
+  // optional: colsum[n] = sum over m of the values written to C (before rounding to C's type), fp32, fixed order;
+  // colsum_partial = gemm_colsum_partial_floats(M, N) floats of scratch.  Not with split-K.
+  float* colsum = nullptr;
+  float* colsum_partial = nullptr;
 };
+size_t gemm_colsum_partial_floats(int M, int N);
 template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s);
 // gemm_dlds.hip: bf16, 256x256 tiles loaded from global memory straight into LDS; takes the shapes for which
 // gemm_dlds_eligible holds (whole K tiles of 32, 16-byte rows); launch_gemm routes to it by itself
@@ -109,6 +114,8 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
                                    const T* resid_grad, T* dx, float* dg, float* db, float* dcol, float* partial,
                                    int rows, int d, hipStream_t s);
 size_t ln_bwd_partial_floats(int rows, int d);
+// out[c] = sum over p < n_partials of partial[p * cols + c], fixed order
+dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s);
 // out[n] = sum_m x[m,n] (fp32, fixed order);  partial: colsum_partial_floats scratch
 template <typename T>
 dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, int cols, hipStream_t s);

@@ -515,6 +515,12 @@ dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, in
   return DIPACO_OK;
 }
 
+dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s) {
+  sum_partials_kernel<<<(cols + 63) / 64, 256, 0, s>>>(partial, out, out, nullptr, n_partials, cols, cols);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
 dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStream_t s) {
   count_valid_kernel<<<1, 1024, 0, s>>>(targets, n, n_valid);
   DIPACO_LAUNCH_CHECK();
