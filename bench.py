@@ -9,6 +9,7 @@ Other workloads (for profiling single kernels; same JSON shape):
   --workload outer_step   16 deltas x 57,872,640 parameters, weighted mean + Nesterov
   --workload route        2^20 x 768 prefix embeddings against 256 centroids
   --workload outer_stream the same module, the 16 deltas accumulated one at a time, then the Nesterov update
+  --workload outer_table  two shared modules (16 deltas each) and 32 path-specific blocks updated by one launch
   --workload features     router features of 8192 documents (32-token prefixes) through the config-2 path's blocks
   --workload score        forward-only log-likelihood of 16 documents x 2048 tokens under the config-5 path
   --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
@@ -267,6 +268,53 @@ def bench_outer_stream(args):
                          "bytes_per_launch": bytes_ / (P + 1)}}
 
 
+def bench_outer_table(args):
+    """Outer step of a phase's modules in one launch: two shared level modules (config-3 size, 16 weighted deltas
+    each, sqrt(16) rescaling) and 32 path-specific blocks (one path each, no averaging)."""
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[3]
+    n_shared, P = cfg["n_elems"], cfg["n_paths"]
+    n_own = 9_645_440          # one transformer block at d_model 896 (4 d^2 + 2 d d_mlp + biases and gains)
+    dev = "cuda"
+    mods = []
+    for m in range(2):
+        mods.append(dict(theta=torch.randn(n_shared, device=dev) * 0.02, momentum=torch.zeros(n_shared, device=dev),
+                         inputs=[torch.randn(n_shared, device=dev) * cfg["delta_std"] for _ in range(P)],
+                         weights=gen.shard_weights(P, cfg["seed"] + m), n_elems=n_shared, is_delta=True,
+                         norm_scale=float(P) ** 0.5))
+    for m in range(32):
+        th = torch.randn(n_own, device=dev) * 0.02
+        mods.append(dict(theta=th, momentum=torch.zeros(n_own, device=dev), inputs=[th + 1e-3 * torch.randn(n_own, device=dev)],
+                         weights=None, n_elems=n_own, is_delta=False, norm_scale=1.0))
+    image = dp.dipaco_outer_table_pack(mods)
+    table = torch.frombuffer(bytearray(image), dtype=torch.uint8).to(dev)
+
+    def step():
+        dp.dipaco_outer_step_table(image, table, cfg["outer_lr"], cfg["outer_momentum"])
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    n_total = 2 * n_shared + 32 * n_own
+    bytes_ = 2 * n_shared * 4.0 * (P + 4) + 32 * n_own * 4.0 * (1 + 4)   # inputs + theta, momentum read and written
+    ach = bytes_ / (ms * 1e-3) / 1e9
+    return {"metric": "table-driven outer-step parameters/sec on 1 MI355X", "value": n_total / (ms * 1e-3),
+            "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "2 shared modules (58M, 16 weighted deltas, sqrt(16) rescaling) + 32 path-specific blocks "
+                                   "(9.6M, one path) in one launch"},
+            "roofline": {"bound": "hbm", "kernel": "outer_table_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_}}
+
+
 def bench_route(args):
     import torch
     import dipaco_inputs as gen
@@ -441,6 +489,9 @@ def bench_gemm(args):
     out_f32 = args.layout == "tn"
     a = torch.empty(M * K, dtype=torch.bfloat16, device=dev).normal_()
     b = torch.empty(K * N, dtype=torch.bfloat16, device=dev).normal_(std=0.02)
+    if args.operands == "zeros":   # no bit toggles in the matrix cores: the clock the chip holds is higher
+        a.zero_()
+        b.zero_()
     c = torch.empty(M * N, dtype=torch.float32 if out_f32 else torch.bfloat16, device=dev)
     ep = args.epilogue
     bias = torch.zeros(N, dtype=torch.bfloat16, device=dev) if ep in ("bias", "gelu", "resid") else None
@@ -470,7 +521,7 @@ def bench_gemm(args):
     return {"metric": "GEMM TFLOP/s on 1 MI355X", "value": ach, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"gemm {args.layout} M={M} N={N} K={K} epilogue={ep} splits={splits}"},
+            "config": {"workload": f"gemm {args.layout} M={M} N={N} K={K} epilogue={ep} splits={splits} operands={args.operands}"},
             "roofline": {"bound": "mfma", "kernel": "gemm_kernel", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                          "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "flops_per_launch": flops}}
 
@@ -525,11 +576,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "route", "kmeans", "features", "score", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "outer_table", "route", "kmeans", "features", "score", "gemm", "attention"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
     ap.add_argument("--epilogue", default="none", choices=["none", "bias", "gelu", "dgelu", "resid"])
+    ap.add_argument("--operands", default="normal", choices=["normal", "zeros"])
     ap.add_argument("--splits", type=int, default=1)
     ap.add_argument("--pass", default="fwd", choices=["fwd", "bwd"])
     ap.add_argument("--seq", type=int, default=0)
@@ -540,6 +592,7 @@ def main():
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
     fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
+          "outer_table": bench_outer_table,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 

@@ -174,6 +174,37 @@ dipaco_status dipaco_module_outer_apply(float* theta, float* momentum, const flo
                                         float norm_scale, size_t n_elems, float outer_lr, float outer_momentum,
                                         void* stream);
 
+/* Outer step of many modules in one launch.  Algorithm 1 runs the outer update for every module (l, e) of the grid;
+ * Section 2.6 keeps it for path-specific modules too (one path, no averaging, same outer optimiser), so a phase ends
+ * with many updates of very different sizes and path counts.  A table that lives in device memory describes them all;
+ * it is built once and reused for as long as the buffers it names stay where they are.
+ *   dipaco_module_desc: one module, as in dipaco_module_outer_step: theta / momentum device fp32 [n_elems], 16-byte
+ *     aligned; inputs = HOST array of n_paths device pointers (fp32 [n_elems], 16-byte aligned); weights = HOST
+ *     [n_paths] positive, or NULL for the plain mean; norm_scale multiplies the averaged Delta (1, or sqrt(paths
+ *     through the module) for the rescaling of Section 3.3); n_elems may be 0.
+ *   dipaco_outer_table_bytes: size of the table image for these modules (0 on invalid arguments).
+ *   dipaco_outer_table_pack:  host-only; validates the descriptions and writes the image (normalised weights
+ *     alpha_i = norm_scale * w_i / sum w in fp32, pointers, chunk offsets) into HOST memory `image`.  The caller copies
+ *     the image to device memory (8-byte aligned) and passes both copies to the step.
+ *   dipaco_outer_step_table:  momentum <- mu * momentum + Delta; theta <- theta - outer_lr * (Delta + mu * momentum)
+ *     for every module of the table, Delta summed over its inputs in index order (reproducible).  Modules must not
+ *     overlap in memory. */
+typedef struct dipaco_module_desc {
+  float* theta;
+  float* momentum;
+  const float* const* inputs;
+  const float* weights;
+  uint64_t n_elems;
+  int32_t n_paths;
+  int32_t is_delta;
+  float norm_scale;
+} dipaco_module_desc;
+size_t dipaco_outer_table_bytes(const dipaco_module_desc* modules, int32_t n_modules);
+dipaco_status dipaco_outer_table_pack(const dipaco_module_desc* modules, int32_t n_modules, void* image,
+                                      size_t image_bytes);
+dipaco_status dipaco_outer_step_table(const void* table_host, const void* table_device, size_t table_bytes,
+                                      float outer_lr, float outer_momentum, void* stream);
+
 /* Generative routing (Section 2.4.1, eq. 1): idx[n] = argmin_k ||z_n - c_k||^2, lowest k on exact ties of the
  * computed scores; hist[k] = number of n routed to k.  The kernel minimises ||c_k||^2 - 2 z_n.c_k (same
  * argmin) in fp32.

@@ -506,6 +506,28 @@ def outer_step_streaming(theta_prev, momentum, inputs: Sequence[np.ndarray], wei
     return theta, buf
 
 
+def outer_step_modules(modules, outer_lr: float, outer_momentum: float):
+    """Outer update of every module of a grid (Algorithm 1: the loop over levels and experts; Section 2.6: a
+    path-specific module has a single path and is updated by the same rule).  `modules` is a sequence of dicts with
+    theta, momentum, inputs, weights (or None), is_delta and optionally norm_scale (Section 3.3, read as a
+    multiplication of the averaged Delta).  Returns a list of (theta, momentum), one per module; modules do not
+    interact."""
+    out = []
+    for m in modules:
+        theta_prev = np.asarray(m["theta"], dtype=F64)
+        buf = np.asarray(m["momentum"], dtype=F64)
+        n = len(m["inputs"])
+        w = np.ones(n, dtype=F64) if m.get("weights") is None else np.asarray(m["weights"], dtype=F64)
+        delta = np.zeros_like(theta_prev)
+        for i in range(n):
+            x = np.asarray(m["inputs"][i], dtype=F64)
+            delta += (w[i] / w.sum()) * (x if m["is_delta"] else (theta_prev - x))
+        delta = float(m.get("norm_scale", 1.0)) * delta
+        buf = outer_momentum * buf + delta
+        out.append((theta_prev - outer_lr * (delta + outer_momentum * buf), buf))
+    return out
+
+
 def prefix_features(params, a: Arch, tokens) -> np.ndarray:
     """Router features (appendix on routing): for every row of tokens [B, S] (S = 32 in the paper), the mean over
     the S positions of the hidden state that leaves the last transformer block.  Read as the residual stream after

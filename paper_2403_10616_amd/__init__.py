@@ -29,6 +29,12 @@ class _Arch(C.Structure):
                 ("vocab", C.c_int32), ("max_seq", C.c_int32), ("ln_eps", C.c_float), ("compute", C.c_int32)]
 
 
+class _ModuleDesc(C.Structure):
+    _fields_ = [("theta", C.c_void_p), ("momentum", C.c_void_p), ("inputs", C.POINTER(C.c_void_p)),
+                ("weights", C.POINTER(C.c_float)), ("n_elems", C.c_uint64), ("n_paths", C.c_int32),
+                ("is_delta", C.c_int32), ("norm_scale", C.c_float)]
+
+
 _SIGS = {
     "dipaco_create": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(_Arch)]),
     "dipaco_destroy": (None, [C.c_void_p]),
@@ -60,6 +66,9 @@ _SIGS = {
                                                  C.c_int32, C.c_void_p]),
     "dipaco_module_outer_apply": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_float, C.c_size_t,
                                             C.c_float, C.c_float, C.c_void_p]),
+    "dipaco_outer_table_bytes": (C.c_size_t, [C.POINTER(_ModuleDesc), C.c_int32]),
+    "dipaco_outer_table_pack": (C.c_int, [C.POINTER(_ModuleDesc), C.c_int32, C.c_void_p, C.c_size_t]),
+    "dipaco_outer_step_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_float, C.c_float, C.c_void_p]),
     "dipaco_route_prefix": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
     "dipaco_route_prefix_top": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
@@ -102,6 +111,8 @@ def _check(status: int):
 def _ptr(t) -> Optional[int]:
     if t is None:
         return None
+    if isinstance(t, int):   # a raw device address
+        return t
     if not t.is_cuda or not t.is_contiguous():
         raise DipacoError("expected a contiguous device tensor")
     return t.data_ptr()
@@ -247,6 +258,43 @@ def dipaco_module_outer_apply(theta, momentum, delta_sum, weight_sum: float, nor
                               outer_lr: float, outer_momentum: float, stream=None):
     _check(load().dipaco_module_outer_apply(_ptr(theta), _ptr(momentum), _ptr(delta_sum), weight_sum, norm_scale, n_elems,
                                             outer_lr, outer_momentum, _stream(stream)))
+
+
+def _module_descs(modules):
+    """ctypes array of dipaco_module_desc from dicts with keys theta, momentum, inputs (device tensors or integer
+    addresses), weights (floats or None), n_elems, is_delta, norm_scale; also returns the objects it points into"""
+    descs = (_ModuleDesc * len(modules))()
+    keep = []
+    for d, m in zip(descs, modules):
+        n = len(m["inputs"])
+        ptrs = (C.c_void_p * n)(*[_ptr(t) for t in m["inputs"]])
+        w = None if m.get("weights") is None else (C.c_float * len(m["weights"]))(*[float(x) for x in m["weights"]])
+        keep += [ptrs, w]
+        d.theta, d.momentum = _ptr(m["theta"]), _ptr(m["momentum"])
+        d.inputs = C.cast(ptrs, C.POINTER(C.c_void_p))
+        d.weights = C.cast(w, C.POINTER(C.c_float)) if w is not None else None
+        d.n_elems, d.n_paths = int(m["n_elems"]), n
+        d.is_delta, d.norm_scale = int(bool(m["is_delta"])), float(m.get("norm_scale", 1.0))
+    return descs, keep
+
+
+def dipaco_outer_table_bytes(modules) -> int:
+    descs, _keep = _module_descs(modules)
+    return int(load().dipaco_outer_table_bytes(descs, len(modules)))
+
+
+def dipaco_outer_table_pack(modules) -> bytes:
+    """the table image, in host memory; copy it to the device and pass both to dipaco_outer_step_table"""
+    descs, _keep = _module_descs(modules)
+    need = int(load().dipaco_outer_table_bytes(descs, len(modules)))
+    image = C.create_string_buffer(max(need, 1))
+    _check(load().dipaco_outer_table_pack(descs, len(modules), image, need))
+    return image.raw[:need]
+
+
+def dipaco_outer_step_table(table_host: bytes, table_device, outer_lr: float, outer_momentum: float, stream=None):
+    _check(load().dipaco_outer_step_table(table_host, _ptr(table_device), len(table_host), outer_lr, outer_momentum,
+                                          _stream(stream)))
 
 
 def dipaco_route_prefix(z, centroids, N: int, D: int, K: int, idx_out, hist_out, margin_out=None, stream=None):

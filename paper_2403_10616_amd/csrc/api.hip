@@ -552,6 +552,97 @@ dipaco_status dipaco_module_outer_apply(float* theta, float* momentum, const flo
                             outer_momentum, static_cast<hipStream_t>(stream));
 }
 
+// ---- table-driven outer step: image = header | entries | input pointers | alpha ----------------------------
+namespace {
+struct OuterTableHeader {
+  unsigned long long magic, n_modules, total_chunks, total_paths;
+};
+constexpr unsigned long long OUTER_TABLE_MAGIC = 0x64697061636f5442ull;
+
+size_t outer_table_layout(unsigned long long n_modules, unsigned long long total_paths, size_t& off_inputs,
+                          size_t& off_alpha) {
+  off_inputs = sizeof(OuterTableHeader) + n_modules * sizeof(dipaco::OuterTableEntry);
+  off_alpha = off_inputs + total_paths * sizeof(const float*);
+  return (off_alpha + total_paths * sizeof(float) + 15) & ~(size_t)15;
+}
+}  // namespace
+
+size_t dipaco_outer_table_bytes(const dipaco_module_desc* modules, int32_t n_modules) {
+  if (!modules || n_modules < 1) return 0;
+  unsigned long long paths = 0;
+  for (int m = 0; m < n_modules; ++m) {
+    if (modules[m].n_paths < 1 || modules[m].n_paths > DIPACO_MAX_PATHS_PER_MODULE) return 0;
+    paths += (unsigned long long)modules[m].n_paths;
+  }
+  size_t a, b;
+  return outer_table_layout((unsigned long long)n_modules, paths, a, b);
+}
+
+dipaco_status dipaco_outer_table_pack(const dipaco_module_desc* modules, int32_t n_modules, void* image,
+                                      size_t image_bytes) {
+  using namespace dipaco;
+  if (!modules || !image) return fail(DIPACO_EINVAL, "modules / image is NULL");
+  if (n_modules < 1) return fail(DIPACO_EINVAL, "n_modules must be >= 1");
+  const size_t need = dipaco_outer_table_bytes(modules, n_modules);
+  if (need == 0) return fail(DIPACO_ESHAPE, "n_paths must be in [1, DIPACO_MAX_PATHS_PER_MODULE]");
+  if (image_bytes < need) return fail(DIPACO_EWORKSPACE, "table image too small");
+  unsigned long long paths = 0;
+  for (int m = 0; m < n_modules; ++m) paths += (unsigned long long)modules[m].n_paths;
+  size_t off_inputs, off_alpha;
+  outer_table_layout((unsigned long long)n_modules, paths, off_inputs, off_alpha);
+  char* base = static_cast<char*>(image);
+  std::memset(base, 0, need);
+  OuterTableEntry* entries = reinterpret_cast<OuterTableEntry*>(base + sizeof(OuterTableHeader));
+  const float** inputs = reinterpret_cast<const float**>(base + off_inputs);
+  float* alpha = reinterpret_cast<float*>(base + off_alpha);
+  unsigned long long chunk = 0, pb = 0;
+  for (int m = 0; m < n_modules; ++m) {
+    const dipaco_module_desc& d = modules[m];
+    if (!d.inputs) return fail(DIPACO_EINVAL, "inputs is NULL");
+    TRY(check_ptr(d.theta, "theta"));
+    TRY(check_ptr(d.momentum, "momentum"));
+    if (!(d.norm_scale > 0.0f) || !std::isfinite(d.norm_scale))
+      return fail(DIPACO_EINVAL, "norm_scale must be positive and finite");
+    double sum = 0.0;
+    for (int i = 0; i < d.n_paths; ++i) {
+      TRY(check_ptr(d.inputs[i], "input pointer"));
+      const double w = d.weights ? (double)d.weights[i] : 1.0;
+      if (!(w > 0.0) || !std::isfinite(w)) return fail(DIPACO_EINVAL, "weights must be positive and finite");
+      sum += w;
+    }
+    for (int i = 0; i < d.n_paths; ++i) {
+      inputs[pb + i] = d.inputs[i];
+      alpha[pb + i] = (float)((double)d.norm_scale * (d.weights ? (double)d.weights[i] : 1.0) / sum);
+    }
+    OuterTableEntry& e = entries[m];
+    e.theta = d.theta; e.momentum = d.momentum; e.n_elems = d.n_elems; e.first_chunk = chunk; e.path_begin = pb;
+    e.n_paths = d.n_paths; e.is_delta = d.is_delta ? 1 : 0;
+    chunk += (d.n_elems + OUTER_CHUNK - 1) / OUTER_CHUNK;
+    pb += (unsigned long long)d.n_paths;
+  }
+  OuterTableHeader* h = reinterpret_cast<OuterTableHeader*>(base);
+  h->magic = OUTER_TABLE_MAGIC; h->n_modules = (unsigned long long)n_modules; h->total_chunks = chunk; h->total_paths = paths;
+  return DIPACO_OK;
+}
+
+dipaco_status dipaco_outer_step_table(const void* table_host, const void* table_device, size_t table_bytes,
+                                      float outer_lr, float outer_momentum, void* stream) {
+  using namespace dipaco;
+  if (!table_host || !table_device) return fail(DIPACO_EINVAL, "table is NULL");
+  if ((uintptr_t)table_device % 8) return fail(DIPACO_EALIGN, "device table is not 8-byte aligned");
+  if (table_bytes < sizeof(OuterTableHeader)) return fail(DIPACO_EINVAL, "table image too small");
+  const OuterTableHeader* h = static_cast<const OuterTableHeader*>(table_host);
+  if (h->magic != OUTER_TABLE_MAGIC) return fail(DIPACO_EINVAL, "not a table image written by dipaco_outer_table_pack");
+  size_t off_inputs, off_alpha;
+  if (h->n_modules > 0x7fffffffull || outer_table_layout(h->n_modules, h->total_paths, off_inputs, off_alpha) > table_bytes)
+    return fail(DIPACO_EINVAL, "table image does not match its size");
+  const char* dev = static_cast<const char*>(table_device);
+  return launch_outer_table(reinterpret_cast<const OuterTableEntry*>(dev + sizeof(OuterTableHeader)),
+                            reinterpret_cast<const float* const*>(dev + off_inputs),
+                            reinterpret_cast<const float*>(dev + off_alpha), (int)h->n_modules, h->total_chunks, outer_lr,
+                            outer_momentum, static_cast<hipStream_t>(stream));
+}
+
 dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_t N, int32_t D, int32_t K,
                                   int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream) {
   if (N < 0) return fail(DIPACO_EINVAL, "N must be >= 0");

@@ -156,6 +156,77 @@ __global__ void __launch_bounds__(EW_THREADS) outer_kernel(const OuterArgs a) {
   }
 }
 
+// ---- outer step of a table of modules ---------------------------------------------------------------------
+// One workgroup takes chunks of OUTER_CHUNK elements; the module a chunk belongs to is found by bisection over
+// the entries' first_chunk (workgroup-uniform).  Per thread four 16-byte vectors are in flight per input.
+__global__ void __launch_bounds__(EW_THREADS) outer_table_kernel(const OuterTableEntry* __restrict__ entries,
+                                                                 const float* const* __restrict__ inputs,
+                                                                 const float* __restrict__ alpha, int n_modules,
+                                                                 unsigned long long total_chunks, float lr, float mu) {
+  constexpr int IT = OUTER_CHUNK / 4 / EW_THREADS;
+  for (unsigned long long chunk = blockIdx.x; chunk < total_chunks; chunk += gridDim.x) {
+    int lo = 0, hi = n_modules - 1;   // largest m with first_chunk[m] <= chunk
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (entries[mid].first_chunk <= chunk) lo = mid; else hi = mid - 1;
+    }
+    const OuterTableEntry e = entries[lo];
+    const size_t local = chunk - e.first_chunk;
+    const size_t nv = e.n_elems >> 2;
+    const size_t i0 = local * (OUTER_CHUNK / 4) + threadIdx.x;
+    const float* const* in = inputs + e.path_begin;
+    const float* al = alpha + e.path_begin;
+    float4 th[IT], b[IT], d[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const size_t i = i0 + (size_t)it * EW_THREADS;
+      d[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < nv) {
+        th[it] = reinterpret_cast<const float4*>(e.theta)[i];
+        b[it] = reinterpret_cast<const float4*>(e.momentum)[i];
+      }
+    }
+    for (int p = 0; p < e.n_paths; ++p) {
+      const float4* src = reinterpret_cast<const float4*>(in[p]);
+      const float a = al[p];
+      float4 x[IT];
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const size_t i = i0 + (size_t)it * EW_THREADS;
+        x[it] = i < nv ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        if (e.is_delta) {
+          d[it].x += a * x[it].x; d[it].y += a * x[it].y; d[it].z += a * x[it].z; d[it].w += a * x[it].w;
+        } else {
+          d[it].x += a * (th[it].x - x[it].x); d[it].y += a * (th[it].y - x[it].y);
+          d[it].z += a * (th[it].z - x[it].z); d[it].w += a * (th[it].w - x[it].w);
+        }
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const size_t i = i0 + (size_t)it * EW_THREADS;
+      if (i < nv) {
+        reinterpret_cast<float4*>(e.theta)[i] = outer_one(th[it], d[it], b[it], lr, mu);
+        reinterpret_cast<float4*>(e.momentum)[i] = b[it];
+      }
+    }
+    // the up to three elements after the last whole vector belong to the module's last chunk
+    const size_t last_chunk = (e.n_elems + OUTER_CHUNK - 1) / OUTER_CHUNK - 1;
+    if (local == last_chunk && threadIdx.x < (e.n_elems & 3)) {
+      const size_t i = (nv << 2) + threadIdx.x;
+      const float t = e.theta[i];
+      float bb = e.momentum[i], dd = 0.f;
+      for (int p = 0; p < e.n_paths; ++p) dd += al[p] * (e.is_delta ? in[p][i] : (t - in[p][i]));
+      bb = mu * bb + dd;
+      e.theta[i] = t - lr * (dd + mu * bb);
+      e.momentum[i] = bb;
+    }
+  }
+}
+
 // Streaming form of the outer step: sum <- (first ? 0 : sum) + w * (is_delta ? in : theta_prev - in), one path at a
 // time as its result arrives; then the Nesterov update from the finished sum.
 __global__ void __launch_bounds__(EW_THREADS) delta_accumulate_kernel(float* __restrict__ sum,
@@ -252,6 +323,15 @@ dipaco_status launch_outer(float* theta, float* momentum, const float* const* in
     case 16: outer_kernel<16><<<blocks, EW_THREADS, 0, s>>>(a); break;
     default: outer_kernel<0><<<blocks, EW_THREADS, 0, s>>>(a); break;
   }
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_outer_table(const OuterTableEntry* entries, const float* const* inputs, const float* alpha,
+                                 int n_modules, unsigned long long total_chunks, float lr, float mu, hipStream_t s) {
+  if (n_modules <= 0 || total_chunks == 0) return DIPACO_OK;
+  const unsigned blocks = (unsigned)std::min<unsigned long long>(total_chunks, 256ull * 16);
+  outer_table_kernel<<<blocks, EW_THREADS, 0, s>>>(entries, inputs, alpha, n_modules, total_chunks, lr, mu);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

@@ -23,6 +23,20 @@ dipaco_status launch_delta_accumulate(float* sum, const float* theta_prev, const
                                       int is_delta, int first, hipStream_t s);
 dipaco_status launch_outer_apply(float* theta, float* momentum, const float* sum, float scale, size_t n, float lr,
                                  float mu, hipStream_t s);
+// One entry of the device-resident module table of the table-driven outer step; chunks of OUTER_CHUNK elements
+// are the unit of work, first_chunk the running sum of the chunk counts of the entries before.
+constexpr size_t OUTER_CHUNK = 4096;
+struct OuterTableEntry {
+  float* theta;
+  float* momentum;
+  unsigned long long n_elems;
+  unsigned long long first_chunk;
+  unsigned long long path_begin;   // index of the module's first input pointer / weight in the table's flat arrays
+  int n_paths;
+  int is_delta;
+};
+dipaco_status launch_outer_table(const OuterTableEntry* entries, const float* const* inputs, const float* alpha,
+                                 int n_modules, unsigned long long total_chunks, float lr, float mu, hipStream_t s);
 dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s);
 dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s);
 

@@ -92,3 +92,37 @@ def test_stateless_calls_validate_before_touching_the_gpu():
     st = lib.dipaco_route_prefix(ctypes.c_void_p(16), ctypes.c_void_p(16), 8, 8, 5000, ctypes.c_void_p(16),
                                  ctypes.c_void_p(16), None, None)
     assert st == -2
+
+
+def test_outer_table_pack_is_host_only_and_validates():
+    """The table image of the table-driven outer step is built on the host: sizes, chunk offsets and normalised
+    weights can be checked without a GPU (the addresses are never dereferenced by the packer)."""
+    import struct
+    mods = [dict(theta=0x1000, momentum=0x2000, inputs=[0x3000, 0x4000, 0x5000], weights=[1.0, 2.0, 1.0],
+                 n_elems=4096 * 2 + 5, is_delta=False),
+            dict(theta=0x6000, momentum=0x7000, inputs=[0x8000], weights=None, n_elems=0, is_delta=True),
+            dict(theta=0x9000, momentum=0xa000, inputs=[0xb000], weights=None, n_elems=10, is_delta=True,
+                 norm_scale=4.0)]
+    need = dp.dipaco_outer_table_bytes(mods)
+    image = dp.dipaco_outer_table_pack(mods)
+    assert len(image) == need and need % 16 == 0
+    magic, n_modules, total_chunks, total_paths = struct.unpack_from("<4Q", image, 0)
+    assert (n_modules, total_chunks, total_paths) == (3, 3 + 0 + 1, 5)
+    entry = struct.Struct("<QQQQQii")                       # theta, momentum, n_elems, first_chunk, path_begin, ...
+    ents = [entry.unpack_from(image, 32 + i * entry.size) for i in range(3)]
+    assert [e[3] for e in ents] == [0, 3, 3] and [e[4] for e in ents] == [0, 3, 4]
+    assert [e[0] for e in ents] == [0x1000, 0x6000, 0x9000] and [e[6] for e in ents] == [0, 1, 1]
+    off_inputs = 32 + 3 * entry.size
+    assert struct.unpack_from("<5Q", image, off_inputs) == (0x3000, 0x4000, 0x5000, 0x8000, 0xb000)
+    alpha = struct.unpack_from("<5f", image, off_inputs + 5 * 8)
+    assert np.allclose(alpha, [0.25, 0.5, 0.25, 1.0, 4.0], rtol=1e-7)
+    for bad in (dict(mods[0], theta=0x1004), dict(mods[0], weights=[1.0, -1.0, 1.0]), dict(mods[0], inputs=[]),
+                dict(mods[0], norm_scale=0.0), dict(mods[0], inputs=[0x3000, 0, 0x5000])):
+        with pytest.raises(dp.DipacoError):
+            dp.dipaco_outer_table_pack([bad])
+    with pytest.raises(dp.DipacoError):                     # an image that the packer did not write
+        dp.dipaco_outer_step_table(bytes(len(image)), 0x1000, 0.7, 0.9, stream=_NoStream())
+
+
+class _NoStream:
+    cuda_stream = 0

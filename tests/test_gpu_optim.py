@@ -142,3 +142,66 @@ def test_streaming_outer_step_rejects_bad_arguments():
         dp.dipaco_module_outer_apply(t, t, t, 0.0, 1.0, 16, 0.7, 0.9)
     with pytest.raises(dp.DipacoError):
         dp.dipaco_module_outer_apply(t, t, t, 1.0, float("nan"), 16, 0.7, 0.9)
+
+
+def _grid_modules(seed, sizes, path_counts, weighted, is_delta, scales):
+    """host arrays of a table of modules: sizes / path counts / norm scales per module"""
+    rng = np.random.default_rng(seed)
+    mods = []
+    for m, (n, P) in enumerate(zip(sizes, path_counts)):
+        theta = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        buf = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        eps = [gen.perturbation(n, 1e-3, 900 + 17 * m + i) for i in range(P)]
+        ins = [np.asarray(-e if is_delta[m] else theta + e, dtype=np.float32) for e in eps]
+        w = gen.shard_weights(P, 5 + m) if weighted[m] else None
+        mods.append(dict(theta=theta, momentum=buf, inputs=ins, weights=w, is_delta=is_delta[m], norm_scale=scales[m],
+                         n_elems=n))
+    return mods
+
+
+@pytest.mark.parametrize("case", ["mixed", "many_small", "single"])
+def test_table_outer_step_matches_oracle_and_per_module_calls(case):
+    """Shared modules of different sizes and path counts and path-specific modules (one path) in one launch."""
+    if case == "mixed":
+        sizes = [70_001, 4096, 0, 3, 1 << 20, 4097, 12_288]
+        paths = [16, 1, 2, 5, 4, 1, 256]
+    elif case == "many_small":
+        sizes = [1 + (37 * i) % 9000 for i in range(300)]
+        paths = [1 + i % 3 for i in range(300)]
+    else:
+        sizes, paths = [123_457], [16]
+    M = len(sizes)
+    weighted = [i % 2 == 0 for i in range(M)]
+    is_delta = [i % 3 == 0 for i in range(M)]
+    scales = [1.0 if i % 4 else float(np.sqrt(paths[i])) for i in range(M)]
+    mods = _grid_modules(77, sizes, paths, weighted, is_delta, scales)
+    # every buffer is a view into one arena at a 16-byte aligned offset (n_elems = 3 leaves odd sizes behind)
+    dmods = []
+    for m in mods:
+        dmods.append(dict(m, theta=dev(m["theta"]) if m["n_elems"] else torch.zeros(4, device=DEV),
+                          momentum=dev(m["momentum"]) if m["n_elems"] else torch.zeros(4, device=DEV),
+                          inputs=[dev(x) if m["n_elems"] else torch.zeros(4, device=DEV) for x in m["inputs"]]))
+    image = dp.dipaco_outer_table_pack(dmods)
+    table = torch.frombuffer(bytearray(image), dtype=torch.uint8).to(DEV)
+    dp.dipaco_outer_step_table(image, table, 0.7, 0.9)
+    want = orc.outer_step_modules(mods, 0.7, 0.9)
+    for m, d, (th_o, buf_o) in zip(mods, dmods, want):
+        n = m["n_elems"]
+        if n == 0:
+            continue
+        assert rel_l2(host(d["theta"]), th_o) <= 1e-6
+        assert rel_l2(host(d["momentum"]), buf_o) <= 2e-5
+        if m["norm_scale"] == 1.0:        # the single-module entry point gives the same numbers
+            th1, buf1 = dev(m["theta"]), dev(m["momentum"])
+            dp.dipaco_module_outer_step(th1, buf1, [dev(x) for x in m["inputs"]], m["weights"], n, m["is_delta"], 0.7,
+                                        0.9)
+            assert np.abs(host(th1) - host(d["theta"])).max() <= 1e-6
+    # a second step with the same table (momentum carried over) still follows the oracle
+    dp.dipaco_outer_step_table(image, table, 0.7, 0.9)
+    mods2 = [dict(m, theta=th, momentum=buf) for m, (th, buf) in zip(mods, want)]
+    for m in mods2:                       # inputs that were local copies keep their values; deltas too
+        pass
+    want2 = orc.outer_step_modules(mods2, 0.7, 0.9)
+    for m, d, (th_o, _b) in zip(mods, dmods, want2):
+        if m["n_elems"]:
+            assert rel_l2(host(d["theta"]), th_o) <= 2e-6

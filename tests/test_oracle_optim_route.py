@@ -308,3 +308,34 @@ def test_norm_rescaling_closed_forms():
     th1, b1 = orc.outer_step_streaming(theta, buf0, [d], None, True, 0.7, 0.9, norm_scale=1.0)
     ref = orc.outer_step(theta, buf0, [d], None, True, 0.7, 0.9)
     assert np.array_equal(th1, ref[0]) and np.array_equal(b1, ref[1])
+
+
+def test_module_table_path_specific_module_and_independence():
+    """Section 2.6: a path-specific module (one path, no averaging) still takes the outer optimiser.  First step
+    from zero momentum in closed form; shared modules equal the single-module rule; modules do not interact."""
+    rng = np.random.default_rng(21)
+    th_a, th_b = rng.standard_normal(7), rng.standard_normal(11)
+    local_a = th_a + 0.01 * rng.standard_normal(7)
+    locals_b = [th_b + 0.01 * rng.standard_normal(11) for _ in range(4)]
+    w_b = rng.uniform(0.5, 1.5, size=4)
+    mods = [dict(theta=th_a, momentum=np.zeros(7), inputs=[local_a], weights=None, is_delta=False),
+            dict(theta=th_b, momentum=rng.standard_normal(11), inputs=locals_b, weights=w_b, is_delta=False)]
+    out = orc.outer_step_modules(mods, 0.7, 0.9)
+    # one path, zero momentum: theta - lr (1 + mu) (theta - theta_local); momentum = the delta itself
+    assert np.allclose(out[0][0], th_a - 0.7 * 1.9 * (th_a - local_a), atol=1e-15)
+    assert np.allclose(out[0][1], th_a - local_a, atol=1e-15)
+    # hand-expanded weighted mean for the shared module
+    alpha = w_b / w_b.sum()
+    delta = sum(alpha[i] * (th_b - locals_b[i]) for i in range(4))
+    buf = 0.9 * mods[1]["momentum"] + delta
+    assert np.allclose(out[1][1], buf, atol=1e-15)
+    assert np.allclose(out[1][0], th_b - 0.7 * (delta + 0.9 * buf), atol=1e-15)
+    # independence: changing module a leaves module b's result bit-identical
+    mods2 = [dict(mods[0], inputs=[local_a + 1.0]), mods[1]]
+    out2 = orc.outer_step_modules(mods2, 0.7, 0.9)
+    assert np.array_equal(out2[1][0], out[1][0]) and not np.array_equal(out2[0][0], out[0][0])
+    # norm rescaling multiplies the averaged delta: with zero momentum coefficient the step is linear in it
+    m3 = [dict(mods[1], momentum=np.zeros(11), norm_scale=2.0)]
+    m1 = [dict(mods[1], momentum=np.zeros(11))]
+    s3, s1 = orc.outer_step_modules(m3, 0.5, 0.0), orc.outer_step_modules(m1, 0.5, 0.0)
+    assert np.allclose(th_b - s3[0][0], 2.0 * (th_b - s1[0][0]), atol=1e-15)
