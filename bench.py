@@ -12,6 +12,7 @@ Other workloads (for profiling single kernels; same JSON shape):
   --workload outer_table  two shared modules (16 deltas each) and 32 path-specific blocks updated by one launch
   --workload features     router features of 8192 documents (32-token prefixes) through the config-2 path's blocks
   --workload score        forward-only log-likelihood of 16 documents x 2048 tokens under the config-5 path
+  --workload router       discriminative router on the config-4 data: logistic loss + gradients, and linear routing
   --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
   --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
   --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
@@ -480,6 +481,60 @@ def bench_kmeans(args):
                          "bytes_per_launch": upd_bytes}}
 
 
+def bench_router(args):
+    """Discriminative router on the config-4 data: one evaluation of the K-class logistic loss with its gradients
+    (what one optimiser step costs), and the trained router used for routing."""
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[4]
+    N, D, K = cfg["N"], cfg["D"], cfg["K"]
+    dev = "cuda"
+    z, c, comp = gen.gaussian_mixture(N, D, K, cfg["noise_std"], cfg["seed"])
+    zd = torch.from_numpy(z).to(dev)
+    W = torch.from_numpy(c).to(dev).contiguous()             # a router near the generating centres
+    b = torch.zeros(K, dtype=torch.float32, device=dev)
+    labels = torch.from_numpy(comp.astype("int32")).to(dev)
+    nbytes = dp.dipaco_router_workspace_bytes(N, D, K)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    loss = torch.zeros(4, dtype=torch.float32, device=dev)
+    dW = torch.empty((K, D), dtype=torch.float32, device=dev)
+    db = torch.empty(K, dtype=torch.float32, device=dev)
+    idx = torch.empty(N, dtype=torch.int32, device=dev)
+    hist = torch.empty(K, dtype=torch.int64, device=dev)
+
+    def grad():
+        dp.dipaco_router_logistic_grad(zd, labels, W, b, N, D, K, loss, dW, db, ws, nbytes)
+
+    def route():
+        dp.dipaco_route_linear(zd, D, W, b, N, D, K, idx, hist, None)
+    times = {}
+    for name, fn in (("grad", grad), ("route", route)):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        times[name] = e0.elapsed_time(e1) / args.steps
+    ms = times["grad"]
+    flops = 4.0 * N * D * K                                  # logits and weight gradient
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"metric": "router logistic loss+gradient documents/sec on 1 MI355X", "value": N / (ms * 1e-3),
+            "unit": "documents/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "config 4 data: 1,048,576 x 768 features, 256 paths; logistic loss + dW + db",
+                       "route_linear_ms": times["route"],
+                       "route_linear_tflops": 2.0 * N * D * K / (times["route"] * 1e-3) / 1e12,
+                       "loss": float(loss[0].item())},
+            "roofline": {"bound": "mfma", "kernel": "gemm_kernel<float> (logits, weight gradient) + logistic_rows_kernel",
+                         "achieved": ach, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_F32_TFLOPS,
+                         "traffic": None}}
+
+
 def bench_gemm(args):
     import torch
     import paper_2403_10616_amd as dp
@@ -576,7 +631,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "outer_table", "route", "kmeans", "features", "score", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "outer_table", "route", "router", "kmeans", "features", "score", "gemm", "attention"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
@@ -592,7 +647,7 @@ def main():
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
     fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
-          "outer_table": bench_outer_table,
+          "outer_table": bench_outer_table, "router": bench_router,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 

@@ -228,6 +228,26 @@ dipaco_status dipaco_route_prefix_top(const float* z, int64_t ldz, const float* 
                                       int32_t K, int32_t n_best, int32_t* idx_out, int64_t* hist_out, float* margin_out,
                                       void* stream);
 
+/* Discriminative router (Section 2.4.2; appendix on routing): a K-class linear logistic classifier on the features z,
+ * trained on the labels argmax_p sum_j S_ijp that dipaco_path_score provides, then used as r(z).
+ *   dipaco_route_linear: idx[n] = argmax_k (weights_k . z_n + bias_k), lowest k on exact ties; hist_out as in
+ *     dipaco_route_prefix; margin_out (or NULL) = best minus second-best logit (+inf when K = 1).  weights device
+ *     fp32 [K, D]; bias device fp32 [K]; z row n at z + n * ldz.  D multiple of 4, 1 <= K <= 4096.
+ *   dipaco_router_logistic_grad: loss = mean over the N documents of -log softmax(z_n W^T + b)[label_n] and its
+ *     gradients dweights_out [K, D] (NULL: not computed), dbias_out [K], all fp32 on the device; the caller applies
+ *     them with the optimiser it likes (dipaco_module_outer_step with one ready-made delta is plain / Nesterov SGD).
+ *     Since dbias = mean softmax - label frequencies, descending on the bias alone (dweights_out = NULL) is the
+ *     "bias term trained to match the target document-to-path distribution": it stops where the mean predicted
+ *     distribution equals the labels'.  labels device int32 [N]; a label outside [0, K) drops its document from loss
+ *     and gradients (the mean stays over N).  z device fp32 [N, D] contiguous.  D and K multiples of 8, K <= 4096,
+ *     N * max(D, K) < 2^32.  workspace: device, >= dipaco_router_workspace_bytes(N, D, K) bytes (0 = invalid shape). */
+dipaco_status dipaco_route_linear(const float* z, int64_t ldz, const float* weights, const float* bias, int64_t N, int32_t D,
+                                  int32_t K, int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream);
+size_t dipaco_router_workspace_bytes(int64_t N, int32_t D, int32_t K);
+dipaco_status dipaco_router_logistic_grad(const float* z, const int32_t* labels, const float* weights, const float* bias,
+                                          int64_t N, int32_t D, int32_t K, float* loss_out, float* dweights_out,
+                                          float* dbias_out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* One k-means update ("we perform k-Means on the features z", Section 2.4.1; with dipaco_route_prefix as the
  * assignment step this is one Lloyd iteration): centroids[k] <- mean of the rows z_n with idx[n] = k, in place; a
  * centroid without rows keeps its value.  idx values are clamped to [0, K).  counts_out: device int64 [K] or NULL.

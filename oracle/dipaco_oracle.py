@@ -506,6 +506,51 @@ def outer_step_streaming(theta_prev, momentum, inputs: Sequence[np.ndarray], wei
     return theta, buf
 
 
+def route_linear(z, weights, bias):
+    """The trained discriminative router used as r(z) (Section 2.4.2): idx[n] = argmax_k (w_k . z_n + b_k), lowest k
+    on ties; hist[k] = #{n : idx[n] = k}; margin[n] = largest minus second-largest logit (inf when K = 1)."""
+    z = np.asarray(z, dtype=F64)
+    W = np.asarray(weights, dtype=F64)
+    b = np.asarray(bias, dtype=F64)
+    N, K = z.shape[0], W.shape[0]
+    idx = np.empty(N, dtype=np.int32)
+    margin = np.empty(N, dtype=F64)
+    for n in range(N):
+        logit = W @ z[n] + b
+        k = int(np.argmax(logit))                   # numpy returns the first maximiser
+        idx[n] = k
+        margin[n] = logit[k] - np.delete(logit, k).max() if K > 1 else np.inf
+    return idx, np.bincount(idx, minlength=K).astype(np.int64), margin
+
+
+def logistic_loss_grad(z, labels, weights, bias):
+    """K-class linear logistic classifier on router features (appendix on routing: target argmax_p sum_j S_ijp,
+    feature g(document)): mean cross-entropy over the N documents and its gradients.
+        p_n = softmax(W z_n + b);  loss = -(1/N) sum_n log p_n[y_n]
+        dW = (1/N) sum_n (p_n - e_{y_n}) z_n^T;  db = (1/N) sum_n (p_n - e_{y_n})
+    A label outside [0, K) drops its document (the mean stays over N).  Returns (loss, dW [K, D], db [K])."""
+    z = np.asarray(z, dtype=F64)
+    W = np.asarray(weights, dtype=F64)
+    b = np.asarray(bias, dtype=F64)
+    y = np.asarray(labels)
+    N, K = z.shape[0], W.shape[0]
+    loss = 0.0
+    dW = np.zeros_like(W)
+    db = np.zeros_like(b)
+    for n in range(N):
+        if y[n] < 0 or y[n] >= K:
+            continue
+        logit = W @ z[n] + b
+        m = logit.max()
+        lse = m + np.log(np.exp(logit - m).sum())
+        p = np.exp(logit - lse)
+        loss -= (logit[y[n]] - lse)
+        p[y[n]] -= 1.0
+        dW += np.outer(p, z[n])
+        db += p
+    return loss / N, dW / N, db / N
+
+
 def outer_step_modules(modules, outer_lr: float, outer_momentum: float):
     """Outer update of every module of a grid (Algorithm 1: the loop over levels and experts; Section 2.6: a
     path-specific module has a single path and is updated by the same rule).  `modules` is a sequence of dicts with

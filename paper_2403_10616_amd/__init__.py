@@ -73,6 +73,12 @@ _SIGS = {
                                       C.c_void_p, C.c_void_p]),
     "dipaco_route_prefix_top": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dipaco_route_linear": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dipaco_router_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int32, C.c_int32]),
+    "dipaco_router_logistic_grad": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                              C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                              C.c_void_p]),
     "dipaco_kmeans_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int32, C.c_int32]),
     "dipaco_kmeans_update": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -258,6 +264,23 @@ def dipaco_module_outer_apply(theta, momentum, delta_sum, weight_sum: float, nor
                               outer_lr: float, outer_momentum: float, stream=None):
     _check(load().dipaco_module_outer_apply(_ptr(theta), _ptr(momentum), _ptr(delta_sum), weight_sum, norm_scale, n_elems,
                                             outer_lr, outer_momentum, _stream(stream)))
+
+
+def dipaco_route_linear(z, ldz: int, weights, bias, N: int, D: int, K: int, idx_out, hist_out, margin_out=None,
+                        stream=None, z_offset: int = 0):
+    _check(load().dipaco_route_linear(_ptr_at(z, z_offset), ldz, _ptr(weights), _ptr(bias), N, D, K, _ptr(idx_out),
+                                      _ptr(hist_out), _ptr(margin_out), _stream(stream)))
+
+
+def dipaco_router_workspace_bytes(N: int, D: int, K: int) -> int:
+    return int(load().dipaco_router_workspace_bytes(N, D, K))
+
+
+def dipaco_router_logistic_grad(z, labels, weights, bias, N: int, D: int, K: int, loss_out, dweights_out, dbias_out,
+                                workspace, workspace_bytes: int, stream=None):
+    _check(load().dipaco_router_logistic_grad(_ptr(z), _ptr(labels), _ptr(weights), _ptr(bias), N, D, K, _ptr(loss_out),
+                                              _ptr(dweights_out), _ptr(dbias_out), _ptr(workspace), workspace_bytes,
+                                              _stream(stream)))
 
 
 def _module_descs(modules):

@@ -654,7 +654,7 @@ dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_
     TRY(check_ptr(z, "z"));
     TRY(check_ptr(idx_out, "idx_out"));
   }
-  return launch_route(z, D, centroids, N, D, K, 1, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
+  return launch_route(z, D, centroids, nullptr, N, D, K, 1, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -672,8 +672,88 @@ dipaco_status dipaco_route_prefix_top(const float* z, int64_t ldz, const float* 
     TRY(check_ptr(z, "z"));
     TRY(check_ptr(idx_out, "idx_out"));
   }
-  return launch_route(z, ldz, centroids, N, D, K, n_best, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
+  return launch_route(z, ldz, centroids, nullptr, N, D, K, n_best, idx_out, reinterpret_cast<long long*>(hist_out),
+                      margin_out, static_cast<hipStream_t>(stream));
+}
+
+dipaco_status dipaco_route_linear(const float* z, int64_t ldz, const float* weights, const float* bias, int64_t N, int32_t D,
+                                  int32_t K, int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream) {
+  if (N < 0) return fail(DIPACO_EINVAL, "N must be >= 0");
+  if (D < 4 || D % 4) return fail(DIPACO_ESHAPE, "D must be a positive multiple of 4");
+  if (ldz < D || ldz % 4) return fail(DIPACO_ESHAPE, "ldz must be a multiple of 4, at least D");
+  if (K < 1 || K > 4096) return fail(DIPACO_ESHAPE, "K must be in [1, 4096]");
+  TRY(check_ptr(weights, "weights"));
+  TRY(check_ptr(bias, "bias"));
+  TRY(check_ptr(hist_out, "hist_out"));
+  if (N > 0) {
+    TRY(check_ptr(z, "z"));
+    TRY(check_ptr(idx_out, "idx_out"));
+  }
+  return launch_route(z, ldz, weights, bias, N, D, K, 1, idx_out, reinterpret_cast<long long*>(hist_out), margin_out,
                       static_cast<hipStream_t>(stream));
+}
+
+namespace {
+struct RouterPlan { size_t logits, nll, n_valid, cs_partial, sk_partial, total; };
+RouterPlan make_router_plan(int64_t N, int D, int K) {
+  RouterPlan p;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
+  p.logits = take((size_t)N * K * 4);
+  p.nll = take((size_t)N * 4);
+  p.n_valid = take(256);
+  p.cs_partial = take(dipaco::colsum_partial_floats((int)N, K) * 4);
+  p.sk_partial = take((size_t)dipaco::gemm_max_splits(K, D, (int)N) * K * D * 4);
+  p.total = off;
+  return p;
+}
+dipaco_status check_router_shape(int64_t N, int D, int K) {
+  using namespace dipaco;
+  if (N < 1 || N > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "N must be in [1, 2^31)");
+  if (D < 8 || D % 8) return fail(DIPACO_ESHAPE, "D must be a positive multiple of 8");
+  if (K < 8 || K % 8 || K > 4096) return fail(DIPACO_ESHAPE, "K must be a multiple of 8 in [8, 4096]");
+  if ((int64_t)N * std::max(D, K) >= (1LL << 32)) return fail(DIPACO_ESHAPE, "N * max(D, K) must stay below 2^32");
+  return DIPACO_OK;
+}
+}  // namespace
+
+size_t dipaco_router_workspace_bytes(int64_t N, int32_t D, int32_t K) {
+  if (check_router_shape(N, D, K) != DIPACO_OK) return 0;
+  return make_router_plan(N, D, K).total;
+}
+
+dipaco_status dipaco_router_logistic_grad(const float* z, const int32_t* labels, const float* weights, const float* bias,
+                                          int64_t N, int32_t D, int32_t K, float* loss_out, float* dweights_out,
+                                          float* dbias_out, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace dipaco;
+  TRY(check_router_shape(N, D, K));
+  TRY(check_ptr(z, "z"));
+  TRY(check_ptr(labels, "labels"));
+  TRY(check_ptr(weights, "weights"));
+  TRY(check_ptr(bias, "bias"));
+  TRY(check_ptr(loss_out, "loss_out"));
+  TRY(check_ptr(dbias_out, "dbias_out"));
+  if (dweights_out) TRY(check_ptr(dweights_out, "dweights_out"));
+  TRY(check_ptr(workspace, "workspace"));
+  const RouterPlan p = make_router_plan(N, D, K);
+  if (workspace_bytes < p.total) return fail(DIPACO_EWORKSPACE, "workspace smaller than dipaco_router_workspace_bytes");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* logits = reinterpret_cast<float*>(ws + p.logits);
+  float* nll = reinterpret_cast<float*>(ws + p.nll);
+  int* n_valid = reinterpret_cast<int*>(ws + p.n_valid);
+  // logits = z W^T + b;  then per row the loss and (softmax - onehot) / N in place
+  TRY(gemm<float>(z, weights, logits, (int)N, K, D, D, D, K, false, true, bias, nullptr, nullptr, nullptr, 0, false, 1,
+                  nullptr, st));
+  TRY(launch_logistic_rows(logits, labels, N, K, (float)(1.0 / (double)N), nll, st));
+  TRY(launch_fill_i32(n_valid, (int)N, 1, st));
+  TRY(launch_mean_loss(nll, n_valid, loss_out, (int)N, st));
+  // db = column sums;  dW = dlogits^T z (contraction over the documents)
+  TRY(launch_colsum<float>(logits, dbias_out, reinterpret_cast<float*>(ws + p.cs_partial), (int)N, K, st));
+  if (dweights_out)
+    TRY(gemm<float>(logits, z, dweights_out, K, D, (int)N, K, D, D, true, false, nullptr, nullptr, nullptr, nullptr, 0,
+                    true, gemm_plan_splits(K, D, (int)N, false), reinterpret_cast<float*>(ws + p.sk_partial), st));
+  return DIPACO_OK;
 }
 
 size_t dipaco_kmeans_workspace_bytes(int64_t N, int32_t D, int32_t K) {

@@ -359,6 +359,13 @@ dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s) {
   return DIPACO_OK;
 }
 
+dipaco_status launch_fill_i32(int* p, int value, size_t n, hipStream_t s) {
+  if (n == 0) return DIPACO_OK;
+  fill_kernel<int><<<ew_blocks(n), EW_THREADS, 0, s>>>(p, value, n);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
 dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s) {
   if (n == 0) return DIPACO_OK;
   fill_kernel<long long><<<ew_blocks(n), EW_THREADS, 0, s>>>(p, value, n);

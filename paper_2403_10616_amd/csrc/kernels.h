@@ -38,13 +38,18 @@ struct OuterTableEntry {
 dipaco_status launch_outer_table(const OuterTableEntry* entries, const float* const* inputs, const float* alpha,
                                  int n_modules, unsigned long long total_chunks, float lr, float mu, hipStream_t s);
 dipaco_status launch_fill_f32(float* p, float value, size_t n, hipStream_t s);
+dipaco_status launch_fill_i32(int* p, int value, size_t n, hipStream_t s);
 dipaco_status launch_fill_i64(long long* p, long long value, size_t n, hipStream_t s);
 
 // ---- route.hip ---------------------------------------------------------------------------------------
 // z row n at z + n * ldz;  n_best = 1: idx [N];  n_best = 2: idx [N, 2] (best, second best; -1 if K = 1), hist
 // counts both memberships
-dipaco_status launch_route(const float* z, int64_t ldz, const float* c, int64_t N, int D, int K, int n_best, int* idx,
-                           long long* hist, float* margin, hipStream_t s);
+// lin_bias (nullable): linear router -- c holds the K weight rows and the score minimised is -(c_k.z_n + lin_bias[k])
+dipaco_status launch_route(const float* z, int64_t ldz, const float* c, const float* lin_bias, int64_t N, int D, int K,
+                           int n_best, int* idx, long long* hist, float* margin, hipStream_t s);
+// logits [rows, K] fp32 -> nll[rows] and, in place, (softmax - onehot(label)) * inv_n; labels outside [0, K): zeros
+dipaco_status launch_logistic_rows(float* logits, const int* labels, int64_t rows, int K, float inv_n, float* nll,
+                                   hipStream_t s);
 
 // ---- kmeans.hip --------------------------------------------------------------------------------------
 // order[0..n) = the indices 0..n-1 stably sorted by keys[i] (clamped to [0, n_keys), n_keys <= 65536);

@@ -44,7 +44,8 @@ template <bool TOP2> __device__ __forceinline__ void best_merge(Best& a, float s
 // z: row n at z + n * ldz.  TOP2: idx is [N, 2] (second entry -1 when K = 1) and hist counts both memberships.
 template <bool TOP2>
 __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __restrict__ z, long ldz,
-                                                             const float* __restrict__ c, long N, int D, int K,
+                                                             const float* __restrict__ c,
+                                                             const float* __restrict__ lin_bias, long N, int D, int K,
                                                              int* __restrict__ idx,
                                                              unsigned long long* __restrict__ hist,
                                                              float* __restrict__ margin) {
@@ -60,6 +61,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   const int rows_left = (int)min((long)RBM, N - m0);
   const float* zb = z + m0 * ldz;
   const bool use_lhist = K <= R_MAX_K_LDS_HIST;
+  const float dot_mul = lin_bias ? 1.0f : 2.0f;
   if (use_lhist) for (int k = tid; k < K; k += GEMM_THREADS) lhist[k] = 0;
 
   using LZ = TileLoader<float, RBM, false>;
@@ -129,7 +131,11 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       v += __shfl_xor(v, 1, WAVE);
       v += __shfl_xor(v, 2, WAVE);
       v += __shfl_xor(v, 4, WAVE);
-      if ((tid & 7) == 0) cnorm[(tid >> 3) + 32 * i] = v;
+      if ((tid & 7) == 0) {
+        const int col = (tid >> 3) + 32 * i;
+        // linear router: the score to minimise is -(w_k.z + b_k), so -b_k takes the place of ||c_k||^2
+        cnorm[col] = lin_bias ? (n0 + col < K ? -lin_bias[n0 + col] : 0.f) : v;
+      }
     }
     __syncthreads();
     // fold this centroid tile into the running best of every row this lane sees
@@ -142,7 +148,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          float s = (k < K) ? cn - 2.0f * acc[i][j][e] : INFINITY;
+          float s = (k < K) ? cn - dot_mul * acc[i][j][e] : INFINITY;
           best_insert<TOP2>(best[i][e], s, k < K ? k : NO_INDEX);
         }
     }
@@ -197,10 +203,79 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   }
 }
 
+// ---- K-class logistic regression: per-row softmax cross-entropy --------------------------------------------------
+// One wave per row of logits [rows, K] (K a multiple of 4, at most LOGIT_MAX_K): nll[row] = logsumexp - logit[label],
+// and in place logits <- (softmax - onehot(label)) * inv_n.  A row whose label is outside [0, K) gives 0 and zeros.
+constexpr int LOGIT_MAX_VEC = 16;                 // float4 per lane
+constexpr int LOGIT_MAX_K = 64 * 4 * LOGIT_MAX_VEC;
+__global__ void __launch_bounds__(256) logistic_rows_kernel(float* __restrict__ logits, const int* __restrict__ labels,
+                                                            long rows, int K, float inv_n, float* __restrict__ nll) {
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int nvec = K >> 2;
+  float4* lr = reinterpret_cast<float4*>(logits + row * K);
+  float4 v[LOGIT_MAX_VEC];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < LOGIT_MAX_VEC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nvec) {
+      v[i] = lr[c];
+      mx = fmaxf(mx, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  const int label = labels[row];
+  const bool valid = label >= 0 && label < K;
+  float sum = 0.f, at_label = 0.f;   // at_label: logit[label] - max, held by one lane
+#pragma unroll
+  for (int i = 0; i < LOGIT_MAX_VEC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nvec) {
+      float x[4] = {v[i].x - mx, v[i].y - mx, v[i].z - mx, v[i].w - mx};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (valid && 4 * c + q == label) at_label = x[q];
+      v[i].x = expf(x[0]); v[i].y = expf(x[1]); v[i].z = expf(x[2]); v[i].w = expf(x[3]);
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) sum += __shfl_xor(sum, o, 64);
+  const float scale = valid ? inv_n / sum : 0.f;
+#pragma unroll
+  for (int i = 0; i < LOGIT_MAX_VEC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nvec) {
+      float e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+      float o[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = e[q] * scale - ((valid && 4 * c + q == label) ? inv_n : 0.f);
+      lr[c] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) at_label += __shfl_xor(at_label, o, 64);
+  if (lane == 0) nll[row] = valid ? logf(sum) - at_label : 0.f;
+}
+
 }  // namespace
 
-dipaco_status launch_route(const float* z, int64_t ldz, const float* c, int64_t N, int D, int K, int n_best, int* idx,
-                           long long* hist, float* margin, hipStream_t s) {
+dipaco_status launch_logistic_rows(float* logits, const int* labels, int64_t rows, int K, float inv_n, float* nll,
+                                   hipStream_t s) {
+  if (K < 4 || K % 4 || K > LOGIT_MAX_K) return fail(DIPACO_ESHAPE, "logistic rows: K must be a multiple of 4 in [4, 4096]");
+  if (rows == 0) return DIPACO_OK;
+  const int64_t blocks = (rows + 3) / 4;
+  if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "logistic rows: too many rows");
+  logistic_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(logits, labels, (long)rows, K, inv_n, nll);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status launch_route(const float* z, int64_t ldz, const float* c, const float* lin_bias, int64_t N, int D, int K,
+                           int n_best, int* idx, long long* hist, float* margin, hipStream_t s) {
   dipaco_status st = launch_fill_i64(hist, 0, (size_t)K, s);
   if (st != DIPACO_OK) return st;
   if (N == 0) return DIPACO_OK;
@@ -216,8 +291,8 @@ dipaco_status launch_route(const float* z, int64_t ldz, const float* c, int64_t 
   const int64_t blocks = (N + RBM - 1) / RBM;
   if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "route: N too large");
   auto* h = reinterpret_cast<unsigned long long*>(hist);
-  if (n_best == 2) route_kernel<true><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, (long)N, D, K, idx, h, margin);
-  else route_kernel<false><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, (long)N, D, K, idx, h, margin);
+  if (n_best == 2) route_kernel<true><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, lin_bias, (long)N, D, K, idx, h, margin);
+  else route_kernel<false><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, lin_bias, (long)N, D, K, idx, h, margin);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

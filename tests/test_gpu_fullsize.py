@@ -234,3 +234,51 @@ def test_config4_full_size_top2_and_kmeans_update():
     before = orc.kmeans_objective(z[sel], i2[sel, 0], c)
     after = orc.kmeans_objective(z[sel], i2[sel, 0], got)
     assert after < before
+
+
+def test_config4_full_size_linear_router_and_logistic_gradients():
+    """The discriminative router at the bench's size: routing on sampled points against the oracle plus the
+    histogram identities; loss and gradients through the identity that the mean over all documents is the mean of the
+    means over its two halves, and against the oracle on a slice."""
+    cfg = gen.CONFIGS[4]
+    N, D, K = cfg["N"], cfg["D"], cfg["K"]
+    _say("config 4 (router): generating the mixture")
+    z, c, comp = gen.gaussian_mixture(N, D, K, cfg["noise_std"], cfg["seed"])
+    rng = np.random.default_rng(12)
+    W = (c + 0.05 * rng.standard_normal(c.shape)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    y = comp.astype(np.int32)
+    zd, Wd, bd, yd = dev(z), dev(W), dev(b), dev(y)
+    idx = torch.empty(N, dtype=torch.int32, device=DEV)
+    hist = torch.empty(K, dtype=torch.int64, device=DEV)
+    margin = torch.empty(N, dtype=torch.float32, device=DEV)
+    dp.dipaco_route_linear(zd, D, Wd, bd, N, D, K, idx, hist, margin)
+    gi, gh, gm = host(idx), host(hist), host(margin)
+    assert gh.sum() == N and np.array_equal(gh, np.bincount(gi, minlength=K)) and np.all(gm >= 0)
+    pick = np.random.default_rng(3).choice(N, size=3000, replace=False)
+    o_idx, _, o_margin = orc.route_linear(z[pick], W, b)
+    clear = o_margin > 1e-4
+    assert clear.mean() > 0.99 and np.array_equal(gi[pick][clear], o_idx[clear])
+    assert np.abs(gm[pick][clear] - o_margin[clear]).max() <= 2e-4
+
+    def grads(lo, hi):
+        n = hi - lo
+        nbytes = dp.dipaco_router_workspace_bytes(n, D, K)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        loss = torch.zeros(4, dtype=torch.float32, device=DEV)
+        dW = torch.empty((K, D), dtype=torch.float32, device=DEV)
+        db = torch.empty(K, dtype=torch.float32, device=DEV)
+        dp.dipaco_router_logistic_grad(zd[lo:hi], yd[lo:hi], Wd, bd, n, D, K, loss, dW, db, ws, nbytes)
+        return float(host(loss)[0]), host(dW).astype(np.float64), host(db).astype(np.float64)
+    _say("config 4 (router): loss and gradients, whole set and halves")
+    l, dW, db = grads(0, N)
+    l1, dW1, db1 = grads(0, N // 2)
+    l2, dW2, db2 = grads(N // 2, N)
+    assert abs(l - 0.5 * (l1 + l2)) <= 2e-6 * max(1.0, abs(l))
+    assert rel_l2(dW, 0.5 * (dW1 + dW2)) <= 1e-5 and np.abs(db - 0.5 * (db1 + db2)).max() <= 1e-6
+    assert abs(db.sum()) <= 1e-5                       # rows of softmax - onehot sum to zero
+    _say("config 4 (router): oracle on a slice of 4096 documents")
+    ls, dWs, dbs = grads(1000, 1000 + 4096)
+    o_l, o_dW, o_db = orc.logistic_loss_grad(z[1000:1000 + 4096], y[1000:1000 + 4096], W, b)
+    assert abs(ls - o_l) <= 1e-5 * max(1.0, abs(o_l)) and rel_l2(dWs, o_dW) <= 1e-5
+    assert np.abs(dbs - o_db).max() <= 1e-6

@@ -177,3 +177,122 @@ def test_kmeans_update_strided_rows_and_lloyd_iteration_lowers_objective():
         prev = obj
         want, o_counts = orc.kmeans_update(z, idx, c)   # a fixed point of the update for this assignment
         assert rel_l2(c, want) <= 1e-6 and np.array_equal(counts, o_counts)
+
+
+# ---- discriminative router: linear logistic classifier --------------------------------------------------------------
+def _labelled_mixture(N, D, K, seed):
+    z, c, comp = gen.gaussian_mixture(N, D, K, 0.3, seed=seed)
+    return z, c, comp.astype(np.int32)
+
+
+@pytest.mark.parametrize("N,D,K", [(1000, 768, 256), (130, 64, 8), (4100, 32, 304), (777, 104, 1), (5, 4, 3)])
+def test_route_linear_matches_oracle(N, D, K):
+    print(f"route_linear N={N} D={D} K={K}", flush=True)
+    rng = np.random.default_rng(50 + K)
+    z, c, _ = _labelled_mixture(N, D, K, 6)
+    W = (2.0 * c + 0.05 * rng.standard_normal(c.shape)).astype(np.float32)
+    b = (-(c.astype(np.float64) ** 2).sum(1) + 0.1 * rng.standard_normal(K)).astype(np.float32)
+    idx = torch.full((N,), -1, dtype=torch.int32, device=DEV)
+    hist = torch.full((K,), -7, dtype=torch.int64, device=DEV)
+    margin = torch.zeros(N, dtype=torch.float32, device=DEV)
+    dp.dipaco_route_linear(dev(z), D, dev(W), dev(b), N, D, K, idx, hist, margin)
+    idx, hist, margin = host(idx), host(hist), host(margin)
+    o_idx, o_hist, o_margin = orc.route_linear(z, W, b)
+    clear = o_margin > TIE
+    assert np.array_equal(idx[clear], o_idx[clear])
+    for n in np.nonzero(~clear)[0]:           # near-ties: the GPU's pick must be one of the oracle's two best
+        logit = W.astype(np.float64) @ z[n].astype(np.float64) + b
+        assert idx[n] in np.argsort(-logit, kind="stable")[:2]
+    assert hist.sum() == N and np.array_equal(hist, np.bincount(idx, minlength=K))
+    fin = clear & np.isfinite(o_margin)
+    assert np.abs(margin[fin] - o_margin[fin]).max(initial=0.0) <= 2e-4
+    assert np.array_equal(np.isinf(margin), np.isinf(o_margin))
+
+
+def test_route_linear_exact_ties_pick_lowest_index():
+    rng = np.random.default_rng(1)
+    W = rng.integers(-2, 3, size=(16, 8)).astype(np.float32)
+    b = rng.integers(-2, 3, size=16).astype(np.float32)
+    W[11], b[11] = W[4], b[4]
+    z = rng.integers(-3, 4, size=(300, 8)).astype(np.float32)
+    idx = torch.empty(300, dtype=torch.int32, device=DEV)
+    hist = torch.empty(16, dtype=torch.int64, device=DEV)
+    margin = torch.empty(300, dtype=torch.float32, device=DEV)
+    dp.dipaco_route_linear(dev(z), 8, dev(W), dev(b), 300, 8, 16, idx, hist, margin)   # small integers: exact in fp32
+    o_idx, o_hist, o_margin = orc.route_linear(z, W, b)
+    assert np.array_equal(host(idx), o_idx) and np.array_equal(host(hist), o_hist)
+    assert np.array_equal(host(margin).astype(np.float64), o_margin) and host(hist)[11] == 0
+
+
+def _logistic(z, y, W, b, want_dw=True):
+    N, D = z.shape
+    K = W.shape[0]
+    nbytes = dp.dipaco_router_workspace_bytes(N, D, K)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    loss = torch.zeros(4, dtype=torch.float32, device=DEV)
+    dW = torch.full((K, D), 9.0, dtype=torch.float32, device=DEV) if want_dw else None
+    db = torch.full((K,), 9.0, dtype=torch.float32, device=DEV)
+    dp.dipaco_router_logistic_grad(dev(z), dev(y), dev(W), dev(b), N, D, K, loss, dW, db, ws, nbytes)
+    return float(host(loss)[0]), (host(dW) if want_dw else None), host(db)
+
+
+@pytest.mark.parametrize("N,D,K", [(1000, 768, 256), (129, 64, 8), (3000, 32, 304), (7, 8, 8), (2500, 104, 1000)])
+def test_logistic_loss_and_gradients_match_oracle(N, D, K):
+    print(f"logistic N={N} D={D} K={K}", flush=True)
+    rng = np.random.default_rng(60 + K)
+    z, c, y = _labelled_mixture(N, D, K, 8)
+    y = y.copy()
+    if N > 100:
+        y[::97] = -1                                            # dropped documents
+        y[5] = K
+    W = (c + 0.1 * rng.standard_normal(c.shape)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    loss, dW, db = _logistic(z, y, W, b)
+    o_loss, o_dW, o_db = orc.logistic_loss_grad(z, y, W, b)
+    assert abs(loss - o_loss) <= 1e-5 * max(1.0, abs(o_loss))
+    assert rel_l2(dW, o_dW) <= 1e-5
+    assert np.abs(db - o_db).max() <= 1e-6
+    _, none_dW, db2 = _logistic(z, y, W, b, want_dw=False)        # bias-only mode
+    assert none_dW is None and np.array_equal(db2, db)
+
+
+def test_bias_fit_on_gpu_gradients_matches_label_distribution_and_refills_empty_paths():
+    """Weights frozen, bias descended with the GPU's dbias: the mean predicted distribution reaches the labels',
+    and classes the unfitted classifier never picked get documents again."""
+    rng = np.random.default_rng(70)
+    N, D, K = 4000, 16, 8
+    z = rng.standard_normal((N, D)).astype(np.float32)
+    W = (0.3 * rng.standard_normal((K, D))).astype(np.float32)
+    b0 = np.zeros(K, dtype=np.float32)
+    b0[6:] = -3.0                                                 # classes 6, 7 start out nearly unreachable
+    logits = z @ W.T
+    y = np.argmax(logits + rng.gumbel(size=logits.shape), axis=1).astype(np.int32)   # labels spread over all classes
+    q = np.bincount(y, minlength=K) / N
+    b = b0.copy()
+    for _ in range(400):
+        _, _, db = _logistic(z, y, W, b, want_dw=False)
+        b = (b - 4.0 * db).astype(np.float32)
+    _, _, db = _logistic(z, y, W, b, want_dw=False)
+    assert np.abs(db).max() < 2e-4                                # mean softmax - q
+    o_db = orc.logistic_loss_grad(z, y, W, b)[2]
+    assert np.abs(db - o_db).max() <= 1e-6
+    h0 = orc.route_linear(z, W, b0)[1]
+    idx = torch.empty(N, dtype=torch.int32, device=DEV)
+    hist = torch.empty(K, dtype=torch.int64, device=DEV)
+    dp.dipaco_route_linear(dev(z), D, dev(W), dev(b), N, D, K, idx, hist, None)
+    h1 = host(hist)
+    assert h0[6:].sum() < 0.2 * N * q[6:].sum() and h1[6:].sum() > 0.5 * N * q[6:].sum()
+
+
+def test_router_entry_points_reject_bad_arguments():
+    t = torch.zeros(64, dtype=torch.float32, device=DEV)
+    i = torch.zeros(64, dtype=torch.int32, device=DEV)
+    h = torch.zeros(8, dtype=torch.int64, device=DEV)
+    assert dp.dipaco_router_workspace_bytes(8, 12, 8) == 0 and dp.dipaco_router_workspace_bytes(8, 8, 12) == 0
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_router_logistic_grad(t, i, t, t, 8, 8, 8, t, t, t, t, 16)         # workspace too small
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_route_linear(t, 6, t, t, 8, 8, 8, i, h, None)                     # ldz < D
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_route_linear(t, 8, t, None, 8, 8, 8, i, h, None)                  # bias missing

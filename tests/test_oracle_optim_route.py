@@ -339,3 +339,101 @@ def test_module_table_path_specific_module_and_independence():
     m1 = [dict(mods[1], momentum=np.zeros(11))]
     s3, s1 = orc.outer_step_modules(m3, 0.5, 0.0), orc.outer_step_modules(m1, 0.5, 0.0)
     assert np.allclose(th_b - s3[0][0], 2.0 * (th_b - s1[0][0]), atol=1e-15)
+
+
+# ---- discriminative router: linear logistic classifier --------------------------------------------------------------
+def test_logistic_closed_forms_at_zero_weights_and_two_classes():
+    rng = np.random.default_rng(31)
+    N, D, K = 40, 6, 5
+    z = rng.standard_normal((N, D))
+    y = rng.integers(0, K, size=N)
+    loss, dW, db = orc.logistic_loss_grad(z, y, np.zeros((K, D)), np.zeros(K))
+    q = np.bincount(y, minlength=K) / N
+    assert abs(loss - math.log(K)) < 1e-14                       # uniform prediction
+    assert np.allclose(db, 1.0 / K - q, atol=1e-15)              # mean softmax minus label frequencies
+    want = np.full((K, D), 1.0 / K) * z.mean(0)[None, :]
+    for k in range(K):
+        want[k] -= z[y == k].sum(0) / N
+    assert np.allclose(dW, want, atol=1e-14)
+    # two classes: softmax over (a, -a) is the logistic sigmoid of 2a -- the textbook binary model
+    w, b0 = rng.standard_normal(D), 0.3
+    W2, b2 = np.stack([w, -w]), np.array([b0, -b0])
+    y2 = rng.integers(0, 2, size=N)
+    loss2, dW2, db2 = orc.logistic_loss_grad(z, y2, W2, b2)
+    s = 1.0 / (1.0 + np.exp(-2.0 * (z @ w + b0)))                # P(class 0)
+    assert abs(loss2 + np.mean(np.where(y2 == 0, np.log(s), np.log1p(-s)))) < 1e-13
+    assert np.allclose(db2, [np.mean(s - (y2 == 0)), -np.mean(s - (y2 == 0))], atol=1e-14)
+    assert np.allclose(dW2[0], ((s - (y2 == 0))[:, None] * z).mean(0), atol=1e-14)
+    assert np.allclose(dW2.sum(0), 0.0, atol=1e-14) and abs(db2.sum()) < 1e-15   # rows of p - e sum to zero
+
+
+def test_logistic_gradients_match_finite_differences_and_ignore_bad_labels():
+    rng = np.random.default_rng(32)
+    N, D, K = 25, 4, 3
+    z = rng.standard_normal((N, D))
+    y = rng.integers(0, K, size=N)
+    W, b = 0.5 * rng.standard_normal((K, D)), 0.2 * rng.standard_normal(K)
+    loss, dW, db = orc.logistic_loss_grad(z, y, W, b)
+    h = 1e-6
+    for (k, d) in [(0, 0), (2, 3), (1, 2)]:
+        Wp, Wm = W.copy(), W.copy()
+        Wp[k, d] += h
+        Wm[k, d] -= h
+        fd = (orc.logistic_loss_grad(z, y, Wp, b)[0] - orc.logistic_loss_grad(z, y, Wm, b)[0]) / (2 * h)
+        assert abs(fd - dW[k, d]) < 1e-8
+    for k in range(K):
+        bp, bm = b.copy(), b.copy()
+        bp[k] += h
+        bm[k] -= h
+        fd = (orc.logistic_loss_grad(z, y, W, bp)[0] - orc.logistic_loss_grad(z, y, W, bm)[0]) / (2 * h)
+        assert abs(fd - db[k]) < 1e-8
+    y_bad = y.copy()
+    y_bad[:5] = [-1, K, 7, -3, K + 1]
+    l2, dW2, db2 = orc.logistic_loss_grad(z, y_bad, W, b)
+    l3, dW3, db3 = orc.logistic_loss_grad(z[5:], y[5:], W, b)
+    assert abs(l2 * N - l3 * (N - 5)) < 1e-12 and np.allclose(dW2 * N, dW3 * (N - 5), atol=1e-12)
+
+
+def test_bias_only_descent_matches_the_label_distribution():
+    """The appendix's remedy for under-represented paths: a bias trained (weights frozen) until the router's mean
+    predicted distribution equals the labels' -- the stationary point of the cross-entropy in the bias."""
+    rng = np.random.default_rng(33)
+    N, D, K = 400, 5, 4
+    z = rng.standard_normal((N, D))
+    W = rng.standard_normal((K, D))
+    y = rng.choice(K, size=N, p=[0.55, 0.3, 0.1, 0.05])          # an unbalanced target
+    q = np.bincount(y, minlength=K) / N
+    b = np.zeros(K)
+    for _ in range(3000):
+        _, _, db = orc.logistic_loss_grad(z, y, W, b)
+        b -= 2.0 * db
+    _, _, db = orc.logistic_loss_grad(z, y, W, b)
+    assert np.abs(db).max() < 1e-9                               # mean softmax = q
+    logit = z @ W.T + b
+    p = np.exp(logit - logit.max(1, keepdims=True))
+    p /= p.sum(1, keepdims=True)
+    assert np.allclose(p.mean(0), q, atol=1e-8)
+
+
+def test_route_linear_brute_force_and_relation_to_kmeans():
+    rng = np.random.default_rng(34)
+    W = rng.integers(-2, 3, size=(6, 4)).astype(np.float64)
+    W[4] = W[1]
+    b = rng.integers(-1, 2, size=6).astype(np.float64)
+    b[4] = b[1]                                                   # class 4 duplicates class 1: ties go to 1
+    z = rng.integers(-3, 4, size=(50, 4)).astype(np.float64)
+    idx, hist, margin = orc.route_linear(z, W, b)
+    for n in range(50):
+        logits = [sum(W[k][d] * z[n][d] for d in range(4)) + b[k] for k in range(6)]
+        best = max(logits)
+        assert idx[n] == logits.index(best)
+        assert margin[n] == best - sorted(logits)[-2]
+    assert hist[4] == 0 and hist.sum() == 50
+    # with w_k = 2 c_k and b_k = -||c_k||^2 the linear router is the k-means router of eq. 1
+    c = rng.standard_normal((7, 5))
+    x = rng.standard_normal((60, 5))
+    i_lin, h_lin, _ = orc.route_linear(x, 2.0 * c, -(c * c).sum(1))
+    i_km, h_km, _ = orc.route_prefix(x, c)
+    assert np.array_equal(i_lin, i_km) and np.array_equal(h_lin, h_km)
+    i1, h1, m1 = orc.route_linear(x, c[:1], np.zeros(1))
+    assert np.all(i1 == 0) and np.all(np.isinf(m1))
