@@ -13,6 +13,7 @@ Other workloads (for profiling single kernels; same JSON shape):
   --workload features     router features of 8192 documents (32-token prefixes) through the config-2 path's blocks
   --workload score        forward-only log-likelihood of 16 documents x 2048 tokens under the config-5 path
   --workload router       discriminative router on the config-4 data: logistic loss + gradients, and linear routing
+  --workload reroute      evaluation at seq 2048 under 4 paths with the path re-chosen every 128 tokens
   --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
   --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
   --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
@@ -433,6 +434,63 @@ def bench_score(args):
                          "flops_per_launch": flops}}
 
 
+def bench_reroute(args):
+    """Forward-only evaluation at seq 2048 with the path re-chosen every 128 tokens (Section 2.4.3): every document
+    is scored under each of 4 paths, the window labels of the token-level router are formed, and the chunk-routed
+    log-likelihood is read off with the labels standing in for the trained router's decisions."""
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+    cfg = gen.CONFIGS[5]
+    B, S, P, W = cfg["batch"], cfg["seq"], 4, 128
+    ctx = dp.Context(**_arch_kwargs(cfg, dp.BF16))
+    n = dp.dipaco_path_param_count(ctx)
+    dev = "cuda"
+    paths = [(torch.randn(n, device=dev) * 0.02).to(torch.bfloat16) for _ in range(P)]
+    seqs = gen.zipf_tokens((B, S + 1), cfg["vocab"], cfg["zipf_s"], cfg["seed"])
+    tok = torch.from_numpy(np.ascontiguousarray(seqs[:, :-1]).astype(np.int32)).to(dev)
+    tgt = torch.from_numpy(np.ascontiguousarray(seqs[:, 1:]).astype(np.int32)).to(dev)
+    doc = torch.empty(B, dtype=torch.float32, device=dev)
+    nll = torch.empty((P, B, S), dtype=torch.float32, device=dev)
+    labels = torch.empty((B, S), dtype=torch.int32, device=dev)
+    n_chunks = (S + W - 1) // W
+    routed = torch.empty(B, dtype=torch.float32, device=dev)
+    ws = torch.empty(dp.dipaco_score_workspace_bytes(ctx, B, S), dtype=torch.uint8, device=dev)
+    rbytes = dp.dipaco_reroute_workspace_bytes(P, B, S)
+    rws = torch.empty(rbytes, dtype=torch.uint8, device=dev)
+
+    def step():
+        for p in range(P):
+            dp.dipaco_path_score(ctx, None, paths[p], tok, tgt, B, S, doc, nll[p], ws)
+        dp.dipaco_window_targets(nll, P, B, S, S, labels, rws, rbytes)
+        # chunk c + 1 takes the path decided at the last token of chunk c; the first chunk takes the document's label
+        choice = torch.cat([labels[:, :1], labels[:, W - 1:S - 1:W]], dim=1).contiguous()
+        dp.dipaco_chunk_routed_score(nll, choice, P, B, S, W, routed, rws, rbytes)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    fwd, _, _ = step_gemm_shapes(cfg, B, S)
+    flops = P * (sum(2.0 * M * N * K for M, N, K in fwd) + attention_flops(cfg, B, S)[0])
+    ach = flops / (ms * 1e-3) / 1e12
+    single = max(float(-nll[p].sum().item()) for p in range(P))
+    return {"metric": "re-routed evaluation tokens/sec on 1 MI355X (forward only, 4 paths)", "value": B * S / (ms * 1e-3),
+            "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "config-5 architecture, 4 random-init paths, 16 documents x 2048 tokens, path re-chosen "
+                                   "every 128 tokens from the window labels (L = rest of the document)",
+                       "n_chunks": n_chunks, "routed_loglik": float(routed.sum().item()), "best_single_path_loglik": single},
+            "roofline": {"bound": "mfma", "kernel": "gemm_dlds_kernel (forward layout) + attn_fwd_mfma", "achieved": ach,
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                         "flops_per_launch": flops}}
+
+
 def bench_kmeans(args):
     import torch
     import dipaco_inputs as gen
@@ -631,7 +689,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "outer_table", "route", "router", "kmeans", "features", "score", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "outer_table", "route", "router", "reroute", "kmeans", "features", "score", "gemm", "attention"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
@@ -647,7 +705,7 @@ def main():
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
     fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
-          "outer_table": bench_outer_table, "router": bench_router,
+          "outer_table": bench_outer_table, "router": bench_router, "reroute": bench_reroute,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
 

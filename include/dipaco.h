@@ -134,6 +134,24 @@ dipaco_status dipaco_path_score(dipaco_ctx* ctx, const float* path_master, const
                                 const int32_t* targets, int32_t batch, int32_t seq, float* doc_loglik_out,
                                 float* token_nll_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Routing more often than once per document at evaluation (Section 2.4.3; appendix, "More frequent routing during
+ * evaluation").  token_nll: device fp32 [n_paths, batch, seq], the per-position negative log-likelihoods that
+ * dipaco_path_score writes (token_nll_out) for each path on the same documents, i.e. -S_ijp.
+ *   dipaco_window_targets: targets_out[b, j] (device int32 [batch, seq]) = argmax_p sum_{j' = j}^{min(seq, j + window) - 1}
+ *     S_{b j' p}: the labels T_ij the token-level router is trained to transduce; lowest p on exact ties.  The window
+ *     sums are differences of fp64 running sums.
+ *   dipaco_chunk_routed_score: doc_loglik_out[b] (device fp32 [batch]) = log-likelihood of document b when its c-th chunk
+ *     of `chunk` consecutive positions is scored by path chunk_path[b, c] (device int32 [batch, ceil(seq / chunk)],
+ *     values clamped to [0, n_paths)); every path conditions on the whole preceding text, as its scoring pass did.
+ *     chunk = seq with one path per document is that path's dipaco_path_score.
+ * workspace: device, >= dipaco_reroute_workspace_bytes(n_paths, batch, seq) bytes (0 = invalid shape). */
+size_t dipaco_reroute_workspace_bytes(int32_t n_paths, int32_t batch, int32_t seq);
+dipaco_status dipaco_window_targets(const float* token_nll, int32_t n_paths, int32_t batch, int32_t seq, int32_t window,
+                                    int32_t* targets_out, void* workspace, size_t workspace_bytes, void* stream);
+dipaco_status dipaco_chunk_routed_score(const float* token_nll, const int32_t* chunk_path, int32_t n_paths, int32_t batch,
+                                        int32_t seq, int32_t chunk, float* doc_loglik_out, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
 /* InnerOpt = AdamW (Algorithm 1, inner loop; Section 2.5), over the whole flat path buffer, in place:
  *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
  *   theta <- theta - lr * ( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + weight_decay * theta ),

@@ -506,6 +506,33 @@ def outer_step_streaming(theta_prev, momentum, inputs: Sequence[np.ndarray], wei
     return theta, buf
 
 
+def window_targets(token_scores, window: int) -> np.ndarray:
+    """Labels for the token-level router (appendix, more frequent routing during evaluation):
+    T[i, j] = argmax_p sum_{j' = j}^{min(len, j + L - 1)} S[i, j', p], lowest p on ties.
+    token_scores: S as an array [P, n_docs, len] of per-token log-likelihoods."""
+    S = np.asarray(token_scores, dtype=F64)
+    P, n, length = S.shape
+    T = np.empty((n, length), dtype=np.int32)
+    for i in range(n):
+        for j in range(length):
+            hi = min(length, j + window)
+            sums = [S[p, i, j:hi].sum() for p in range(P)]
+            T[i, j] = int(np.argmax(sums))
+    return T
+
+
+def chunk_routed_scores(token_scores, chunk_path, chunk: int) -> np.ndarray:
+    """Section 2.4.3: a document is cut into chunks of W consecutive tokens and chunk c is scored by the path
+    chunk_path[i, c] (each path sees the whole preceding text).  Returns the documents' log-likelihoods."""
+    S = np.asarray(token_scores, dtype=F64)
+    _P, n, length = S.shape
+    out = np.zeros(n, dtype=F64)
+    for i in range(n):
+        for c, lo in enumerate(range(0, length, chunk)):
+            out[i] += S[chunk_path[i][c], i, lo:min(length, lo + chunk)].sum()
+    return out
+
+
 def route_linear(z, weights, bias):
     """The trained discriminative router used as r(z) (Section 2.4.2): idx[n] = argmax_k (w_k . z_n + b_k), lowest k
     on ties; hist[k] = #{n : idx[n] = k}; margin[n] = largest minus second-largest logit (inf when K = 1)."""

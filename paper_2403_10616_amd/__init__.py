@@ -73,6 +73,11 @@ _SIGS = {
                                       C.c_void_p, C.c_void_p]),
     "dipaco_route_prefix_top": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dipaco_reroute_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32]),
+    "dipaco_window_targets": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]),
+    "dipaco_chunk_routed_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "dipaco_route_linear": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dipaco_router_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int32, C.c_int32]),
@@ -264,6 +269,22 @@ def dipaco_module_outer_apply(theta, momentum, delta_sum, weight_sum: float, nor
                               outer_lr: float, outer_momentum: float, stream=None):
     _check(load().dipaco_module_outer_apply(_ptr(theta), _ptr(momentum), _ptr(delta_sum), weight_sum, norm_scale, n_elems,
                                             outer_lr, outer_momentum, _stream(stream)))
+
+
+def dipaco_reroute_workspace_bytes(n_paths: int, batch: int, seq: int) -> int:
+    return int(load().dipaco_reroute_workspace_bytes(n_paths, batch, seq))
+
+
+def dipaco_window_targets(token_nll, n_paths: int, batch: int, seq: int, window: int, targets_out, workspace,
+                          workspace_bytes: int, stream=None):
+    _check(load().dipaco_window_targets(_ptr(token_nll), n_paths, batch, seq, window, _ptr(targets_out), _ptr(workspace),
+                                        workspace_bytes, _stream(stream)))
+
+
+def dipaco_chunk_routed_score(token_nll, chunk_path, n_paths: int, batch: int, seq: int, chunk: int, doc_loglik_out,
+                              workspace, workspace_bytes: int, stream=None):
+    _check(load().dipaco_chunk_routed_score(_ptr(token_nll), _ptr(chunk_path), n_paths, batch, seq, chunk,
+                                            _ptr(doc_loglik_out), _ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def dipaco_route_linear(z, ldz: int, weights, bias, N: int, D: int, K: int, idx_out, hist_out, margin_out=None,

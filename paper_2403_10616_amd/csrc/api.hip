@@ -756,6 +756,52 @@ dipaco_status dipaco_router_logistic_grad(const float* z, const int32_t* labels,
   return DIPACO_OK;
 }
 
+namespace {
+dipaco_status check_reroute_shape(int32_t P, int32_t B, int32_t S) {
+  using namespace dipaco;
+  if (P < 1 || P > 4096) return fail(DIPACO_ESHAPE, "n_paths must be in [1, 4096]");
+  if (B < 1 || S < 1) return fail(DIPACO_ESHAPE, "batch and seq must be positive");
+  if ((int64_t)P * B > 0x7fffffffLL || (int64_t)B * S > 0x7fffffffLL * 128)
+    return fail(DIPACO_ESHAPE, "n_paths * batch and batch * seq are too large");
+  return DIPACO_OK;
+}
+}  // namespace
+
+size_t dipaco_reroute_workspace_bytes(int32_t n_paths, int32_t batch, int32_t seq) {
+  if (check_reroute_shape(n_paths, batch, seq) != DIPACO_OK) return 0;
+  return dipaco::reroute_prefix_doubles(n_paths, batch, seq) * sizeof(double);
+}
+
+dipaco_status dipaco_window_targets(const float* token_nll, int32_t n_paths, int32_t batch, int32_t seq, int32_t window,
+                                    int32_t* targets_out, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace dipaco;
+  TRY(check_reroute_shape(n_paths, batch, seq));
+  if (window < 1) return fail(DIPACO_EINVAL, "window must be >= 1");
+  TRY(check_ptr(token_nll, "token_nll"));
+  TRY(check_ptr(targets_out, "targets_out"));
+  TRY(check_ptr(workspace, "workspace"));
+  if (workspace_bytes < dipaco_reroute_workspace_bytes(n_paths, batch, seq))
+    return fail(DIPACO_EWORKSPACE, "workspace smaller than dipaco_reroute_workspace_bytes");
+  return launch_window_targets(token_nll, n_paths, batch, seq, window, targets_out, static_cast<double*>(workspace),
+                               static_cast<hipStream_t>(stream));
+}
+
+dipaco_status dipaco_chunk_routed_score(const float* token_nll, const int32_t* chunk_path, int32_t n_paths, int32_t batch,
+                                        int32_t seq, int32_t chunk, float* doc_loglik_out, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  using namespace dipaco;
+  TRY(check_reroute_shape(n_paths, batch, seq));
+  if (chunk < 1) return fail(DIPACO_EINVAL, "chunk must be >= 1");
+  TRY(check_ptr(token_nll, "token_nll"));
+  TRY(check_ptr(chunk_path, "chunk_path"));
+  TRY(check_ptr(doc_loglik_out, "doc_loglik_out"));
+  TRY(check_ptr(workspace, "workspace"));
+  if (workspace_bytes < dipaco_reroute_workspace_bytes(n_paths, batch, seq))
+    return fail(DIPACO_EWORKSPACE, "workspace smaller than dipaco_reroute_workspace_bytes");
+  return launch_chunk_score(token_nll, chunk_path, n_paths, batch, seq, chunk, doc_loglik_out,
+                            static_cast<double*>(workspace), static_cast<hipStream_t>(stream));
+}
+
 size_t dipaco_kmeans_workspace_bytes(int64_t N, int32_t D, int32_t K) {
   if (N < 0 || D < 1 || K < 1) return 0;
   return kmeans_workspace_bytes((long)N, D, K);

@@ -51,6 +51,17 @@ dipaco_status launch_route(const float* z, int64_t ldz, const float* c, const fl
 dipaco_status launch_logistic_rows(float* logits, const int* labels, int64_t rows, int K, float inv_n, float* nll,
                                    hipStream_t s);
 
+// ---- reroute.hip -------------------------------------------------------------------------------------
+// nll: [P, B, S] per-position negative log-likelihoods of B documents under P paths; prefix: scratch of
+// reroute_prefix_doubles(P, B, S) doubles.
+size_t reroute_prefix_doubles(int P, int B, int S);
+// targets[b, j] = argmin_p sum of nll[p, b, j .. min(S, j + L) - 1], lowest p on ties
+dipaco_status launch_window_targets(const float* nll, int P, int B, int S, int L, int* targets, double* prefix,
+                                    hipStream_t s);
+// out[b] = -sum over chunks c of W positions of the nll of path choice[b, c] on that chunk (choice clamped to [0, P))
+dipaco_status launch_chunk_score(const float* nll, const int* choice, int P, int B, int S, int W, float* out,
+                                 double* prefix, hipStream_t s);
+
 // ---- kmeans.hip --------------------------------------------------------------------------------------
 // order[0..n) = the indices 0..n-1 stably sorted by keys[i] (clamped to [0, n_keys), n_keys <= 65536);
 // scratch: sort_scratch_ints(n, n_keys) ints

@@ -296,3 +296,43 @@ def test_router_entry_points_reject_bad_arguments():
         dp.dipaco_route_linear(t, 6, t, t, 8, 8, 8, i, h, None)                     # ldz < D
     with pytest.raises(dp.DipacoError):
         dp.dipaco_route_linear(t, 8, t, None, 8, 8, 8, i, h, None)                  # bias missing
+
+
+# ---- routing more often at evaluation -------------------------------------------------------------------------------
+@pytest.mark.parametrize("P,B,S,L,W", [(4, 3, 300, 64, 128), (16, 16, 2048, 1024, 128), (1, 2, 5, 3, 2), (5, 2, 257, 1000, 257),
+                                       (3, 40, 17, 1, 1)])
+def test_window_targets_and_chunk_routed_scores_match_oracle(P, B, S, L, W):
+    print(f"reroute P={P} B={B} S={S} L={L} W={W}", flush=True)
+    rng = np.random.default_rng(80 + P)
+    nll = rng.uniform(0.2, 9.0, size=(P, B, S)).astype(np.float32)
+    nll[:, :, ::11] = 0.0                                         # ignored positions
+    if P > 2:
+        nll[2, 0] = nll[0, 0]                                     # exact ties on one document: lowest path wins
+    nbytes = dp.dipaco_reroute_workspace_bytes(P, B, S)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    tg = torch.full((B, S), -1, dtype=torch.int32, device=DEV)
+    nd = dev(nll)
+    dp.dipaco_window_targets(nd, P, B, S, L, tg, ws, nbytes)
+    got = host(tg)
+    scores = -nll.astype(np.float64)
+    want = orc.window_targets(scores, L)
+    diff = np.argwhere(got != want)
+    for b, j in diff:            # a different label must be a tie up to the rounding of a window sum of fp64 values
+        hi = min(S, j + L)
+        assert abs(scores[got[b, j], b, j:hi].sum() - scores[want[b, j], b, j:hi].sum()) <= 1e-9
+    assert len(diff) <= 0.001 * B * S
+    if P > 2:
+        assert not np.any(got[0] == 2)
+    n_chunks = (S + W - 1) // W
+    choice = np.stack([want[:, min(S - 1, c * W)] for c in range(n_chunks)], axis=1).astype(np.int32)
+    out = torch.zeros(B, dtype=torch.float32, device=DEV)
+    dp.dipaco_chunk_routed_score(nd, dev(choice), P, B, S, W, out, ws, nbytes)
+    o = orc.chunk_routed_scores(scores, choice, W)
+    assert np.abs(host(out) - o).max() <= 1e-6 * np.abs(o).max()
+    # one chunk, path 0 for every document: the plain document score
+    dp.dipaco_chunk_routed_score(nd, dev(np.zeros((B, 1), np.int32)), P, B, S, S, out, ws, nbytes)
+    assert np.abs(host(out) + nll[0].astype(np.float64).sum(1)).max() <= 1e-6 * nll[0].sum(1).max()
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_window_targets(nd, P, B, S, 0, tg, ws, nbytes)
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_chunk_routed_score(nd, dev(choice), P, B, S, W, out, ws, 8)

@@ -437,3 +437,31 @@ def test_route_linear_brute_force_and_relation_to_kmeans():
     assert np.array_equal(i_lin, i_km) and np.array_equal(h_lin, h_km)
     i1, h1, m1 = orc.route_linear(x, c[:1], np.zeros(1))
     assert np.all(i1 == 0) and np.all(np.isinf(m1))
+
+
+# ---- routing more often at evaluation -------------------------------------------------------------------------------
+def test_window_targets_and_chunk_scores_special_cases():
+    rng = np.random.default_rng(41)
+    P, n, L = 3, 4, 12
+    S = -rng.uniform(0.5, 6.0, size=(P, n, L))                    # log-likelihoods
+    # a window of one token: the per-token best path; a window past the end: the best path for the rest of the text
+    assert np.array_equal(orc.window_targets(S, 1), np.argmax(S, axis=0))
+    suffix = np.cumsum(S[:, :, ::-1], axis=2)[:, :, ::-1]
+    assert np.array_equal(orc.window_targets(S, L + 5), np.argmax(suffix, axis=0))
+    T3 = orc.window_targets(S, 3)
+    assert T3[2, 4] == int(np.argmax([S[p, 2, 4] + S[p, 2, 5] + S[p, 2, 6] for p in range(P)]))
+    assert T3[1, L - 1] == int(np.argmax(S[:, 1, L - 1]))
+    # exact ties go to the lowest path
+    S2 = S.copy()
+    S2[2] = S2[0]
+    assert not np.any(orc.window_targets(S2, 4) == 2)
+    # one chunk, one path per document: that path's document score; chunks of one token routed by the per-token
+    # best path: no worse than any single path and equal to the sum of per-token maxima
+    one = orc.chunk_routed_scores(S, [[1]] * n, L)
+    assert np.allclose(one, S[1].sum(1), atol=1e-13)
+    per_tok = orc.chunk_routed_scores(S, np.argmax(S, axis=0), 1)
+    assert np.allclose(per_tok, S.max(0).sum(1), atol=1e-13) and np.all(per_tok >= S.sum(2).max(0) - 1e-13)
+    # ragged last chunk, by hand
+    ch = [[0, 2, 1]] * n                                           # chunks [0,5) [5,10) [10,12)
+    got = orc.chunk_routed_scores(S, ch, 5)
+    assert np.allclose(got, S[0, :, :5].sum(1) + S[2, :, 5:10].sum(1) + S[1, :, 10:].sum(1), atol=1e-13)
