@@ -30,6 +30,14 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
                             void* aux_out, const void* aux_in, int32_t act, int32_t splits, float* partial,
                             void* stream);
 
+/* dipaco_k_gemm without split-K that also returns colsum_out[n] (device fp32 [N]) = sum over m of the values written
+ * to C[m, n] (after the epilogue, before rounding to C's type), added in a fixed order: the bias gradient of a linear
+ * layer when C is its output gradient.  colsum_scratch: device fp32, at least ceil(M / 32) * N elements. */
+dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                                   const void* A, const void* B, void* C, const void* bias, const void* resid,
+                                   void* aux_out, const void* aux_in, int32_t act, float* colsum_out,
+                                   float* colsum_scratch, void* stream);
+
 /* Force the GEMM workgroup tile for every later call in this process: 0 = automatic (default), 1 = 128x128,
  * 2 = 256x128, 3 = 256x256 with four waves, 4 = 256x256 with eight waves, 5 = the bf16 kernel that loads its
  * 256x256 tiles from global memory straight into LDS, for every shape it takes (K a multiple of 32, 16-byte rows;

@@ -88,6 +88,7 @@ _SIGS = {
     "dipaco_kmeans_update": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "dipaco_k_gemm": (C.c_int, [C.c_int32] * 7 + [C.c_void_p] * 7 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "dipaco_k_gemm_colsum": (C.c_int, [C.c_int32] * 6 + [C.c_void_p] * 7 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dipaco_k_set_gemm_tile": (C.c_int, [C.c_int32]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]),
@@ -379,6 +380,13 @@ def dipaco_k_gemm(dtype: int, trans_a: bool, trans_b: bool, out_f32: bool, M: in
     _check(load().dipaco_k_gemm(dtype, int(trans_a), int(trans_b), int(out_f32), M, N, K, _ptr(A), _ptr(B), _ptr(Cout),
                                 _ptr(bias), _ptr(resid), _ptr(aux_out), _ptr(aux_in), act, splits, _ptr(partial),
                                 _stream(stream)))
+
+
+def dipaco_k_gemm_colsum(dtype: int, trans_a: bool, trans_b: bool, M: int, N: int, K: int, A, B, Cout, bias, resid,
+                         aux_out, aux_in, act: int, colsum_out, colsum_scratch, stream=None):
+    _check(load().dipaco_k_gemm_colsum(dtype, int(trans_a), int(trans_b), M, N, K, _ptr(A), _ptr(B), _ptr(Cout),
+                                       _ptr(bias), _ptr(resid), _ptr(aux_out), _ptr(aux_in), act, _ptr(colsum_out),
+                                       _ptr(colsum_scratch), _stream(stream)))
 
 
 def dipaco_k_set_gemm_tile(tile: int):

@@ -840,6 +840,21 @@ dipaco_status dipaco_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int
   return dtype == DIPACO_BF16 ? launch_gemm<bf16>(g, st) : launch_gemm<float>(g, st);
 }
 
+dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                                   const void* A, const void* B, void* C, const void* bias, const void* resid,
+                                   void* aux_out, const void* aux_in, int32_t act, float* colsum_out,
+                                   float* colsum_scratch, void* stream) {
+  GemmArgs g;
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K;
+  g.lda = trans_a ? M : K; g.ldb = trans_b ? K : N; g.ldc = N;
+  g.bias = bias; g.resid = resid; g.aux_out = aux_out; g.aux_in = aux_in; g.act = act;
+  g.trans_a = trans_a; g.trans_b = trans_b; g.out_f32 = 0; g.splits = 1; g.partial = nullptr;
+  g.colsum = colsum_out; g.colsum_partial = colsum_scratch;
+  if (!A || !B || !C || !colsum_out || !colsum_scratch) return fail(DIPACO_EINVAL, "dipaco_k_gemm_colsum: NULL argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return dtype == DIPACO_BF16 ? launch_gemm<bf16>(g, st) : launch_gemm<float>(g, st);
+}
+
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
   if (tile < 0 || tile > 7) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..7");
   set_gemm_tile(tile);

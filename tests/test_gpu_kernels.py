@@ -91,6 +91,33 @@ def test_gemm_input_gradient_layout(dtype, M, N, K, gemm_tile):
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES + [(1000, 264, 64)])
+def test_gemm_column_sums_of_the_output(dtype, M, N, K, gemm_tile):
+    """The bias gradient taken in the epilogue: column sums of what the product writes (here the input-gradient
+    layout with the saved-operand multiplication, as in the step)."""
+    print(f"gemm colsum tile={gemm_tile} dtype={dtype} M={M} N={N} K={K}", flush=True)
+    A, Ar = _rand((M, K), 11, dtype)
+    Bt, Btr = _rand((N, K), 12, dtype)
+    U, Ur = _rand((M, N), 13, dtype)
+    C = torch.empty((M, N), dtype=TDT[dtype], device=DEV)
+    cs = torch.full((N,), 77.0, dtype=torch.float32, device=DEV)
+    scratch = torch.full((((M + 31) // 32) * N,), float("nan"), dtype=torch.float32, device=DEV)
+    dp.dipaco_k_gemm_colsum(dtype, False, True, M, N, K, A, Bt, C, None, None, None, U, 4, cs, scratch)
+    ref = (Ar @ Btr.T) * Ur
+    tol = 1e-5 if dtype == dp.F32 else 6e-3
+    assert rel_l2(host(C), ref) <= tol
+    want = ref.sum(0)
+    scale = np.abs(ref).sum(0).max()
+    assert np.abs(host(cs) - want).max() <= (2e-6 if dtype == dp.F32 else 2e-3) * scale
+    # forward layout with bias: same sums
+    B2, B2r = _rand((K, N), 14, dtype)
+    bias, biasr = _rand((N,), 15, dtype)
+    dp.dipaco_k_gemm_colsum(dtype, False, False, M, N, K, A, B2, C, bias, None, None, None, 0, cs, scratch)
+    ref2 = Ar @ B2r + biasr
+    assert np.abs(host(cs) - ref2.sum(0)).max() <= (2e-6 if dtype == dp.F32 else 2e-3) * np.abs(ref2).sum(0).max()
+
+
+@pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("M,N,K,splits", [(128, 128, 64, 1), (200, 136, 77, 1), (72, 264, 1000, 4), (8, 8, 5, 1),
                                           (136, 64, 4099, 16), (264, 520, 1024, 5), (8, 776, 96, 1)])
 def test_gemm_weight_gradient_layout_and_split_k(dtype, M, N, K, splits, gemm_tile):
