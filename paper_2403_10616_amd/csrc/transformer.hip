@@ -89,10 +89,11 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
                                                              const T* __restrict__ g, const float* __restrict__ mean,
                                                              const float* __restrict__ rstd,
                                                              const T* __restrict__ resid_grad, T* __restrict__ dx,
-                                                             float* __restrict__ partial, int rows, int d) {
+                                                             float* __restrict__ partial, int rows, int d,
+                                                             int rows_per_block) {
   constexpr int VEC = Vec16<T>::N;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row0 = blockIdx.x * LN_BWD_ROWS;
+  const int row0 = blockIdx.x * rows_per_block;
   float ag[NIT][VEC], ab[NIT][VEC], ac[NIT][VEC], gv[NIT][VEC];
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
@@ -102,7 +103,7 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
     if (c < d) load_vec16(g + c, gv[it]);
   }
 
-  for (int r = wave; r < LN_BWD_ROWS; r += ROWS_PER_BLOCK) {
+  for (int r = wave; r < rows_per_block; r += ROWS_PER_BLOCK) {
     const int row = row0 + r;
     if (row >= rows) break;
     const float mu = mean[row], rs = rstd[row];
@@ -484,17 +485,37 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
   constexpr int VEC = Vec16<T>::N;
   constexpr int NIT = (sizeof(T) == 4) ? 2 * LN_MAX_IT : LN_MAX_IT;
   if (d > WAVE * VEC * NIT) return fail(DIPACO_ESHAPE, "layernorm backward: d_model above 2048");
-  const int blocks = (rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS;
   const size_t lds = 3 * d * sizeof(float);
   // the kernel keeps NIT chunks per lane of seven row-shaped quantities in registers: narrow models take the
   // instantiation with half (a quarter) of them and twice (four times) the waves per SIMD
-  if (d <= WAVE * VEC * NIT / 4)
-    ln_bwd_kernel<T, NIT / 4><<<blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d);
-  else if (d <= WAVE * VEC * NIT / 2)
-    ln_bwd_kernel<T, NIT / 2><<<blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d);
-  else
-    ln_bwd_kernel<T, NIT><<<blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d);
+  int n_blocks = 0;
+  auto run = [&](auto kern) -> dipaco_status {
+    // Rows per workgroup: LN_BWD_ROWS, unless that gives a little more than a whole number of rounds of resident
+    // workgroups (1024 workgroups over 768 slots run as two rounds): then as many rows as fill the slots once.
+    static int resident = 0;   // per instantiation
+    if (resident == 0) {
+      int nb = 0;
+      DIPACO_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, ROW_THREADS, lds));
+      resident = nb > 0 ? nb : 1;
+    }
+    const long slots = 256L * resident;
+    int rpb = LN_BWD_ROWS;
+    const long base_blocks = (rows + LN_BWD_ROWS - 1) / LN_BWD_ROWS;
+    if (base_blocks > slots && base_blocks < 2 * slots) {
+      rpb = (int)((rows + slots - 1) / slots);
+      rpb = (rpb + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK * ROWS_PER_BLOCK;
+    }
+    n_blocks = (rows + rpb - 1) / rpb;
+    kern<<<n_blocks, ROW_THREADS, lds, s>>>(dy, x, g, mean, rstd, resid_grad, dx, partial, rows, d, rpb);
+    return DIPACO_OK;
+  };
+  dipaco_status st;
+  if (d <= WAVE * VEC * NIT / 4) st = run(ln_bwd_kernel<T, NIT / 4>);
+  else if (d <= WAVE * VEC * NIT / 2) st = run(ln_bwd_kernel<T, NIT / 2>);
+  else st = run(ln_bwd_kernel<T, NIT>);
+  if (st != DIPACO_OK) return st;
   DIPACO_LAUNCH_CHECK();
+  const int blocks = n_blocks;
   const int ncols = dcol ? 3 * d : 2 * d;
   sum_partials_kernel<<<(ncols + 63) / 64, 256, 0, s>>>(partial, dg, db, dcol, blocks, 3 * d, d);
   DIPACO_LAUNCH_CHECK();
