@@ -697,6 +697,8 @@ def main():
     ap.add_argument("--operands", default="normal", choices=["normal", "zeros"])
     ap.add_argument("--splits", type=int, default=1)
     ap.add_argument("--pass", default="fwd", choices=["fwd", "bwd"])
+    ap.add_argument("--attn-blocks", type=int, default=None, choices=[0, 1],
+                    help="attention workload: 0 = a long and a short causal block per workgroup, 1 = one block, longest first")
     ap.add_argument("--seq", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -704,6 +706,8 @@ def main():
         sys.exit("bench.py: this build runs one path on ONE GPU (no collectives, no sharding); use --gpus 1")
     import paper_2403_10616_amd as dp
     dp.load()   # fails loudly if libdipaco.so is not built
+    if args.attn_blocks is not None:
+        dp.dipaco_k_set_attention_blocks(args.attn_blocks)
     fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
           "outer_table": bench_outer_table, "router": bench_router, "reroute": bench_reroute,
           "attention": bench_attention}[args.workload]

@@ -45,6 +45,11 @@ dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans
  * For tests (every tile shape must give the same parity) and tuning. */
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 
+/* How the bf16 attention kernels deal the blocks of the causal triangle to workgroups, for every later call in this
+ * process (tuning and tests): 0 = a long and a short block per workgroup, 1 = one block per workgroup, launched
+ * longest first.  Results are identical. */
+dipaco_status dipaco_k_set_attention_blocks(int32_t single_block);
+
 /* Causal softmax attention.  qkv: [B*S, 3*H*dh], row = q | k | v, head h at columns h*dh of each third;
  * o: [B*S, H*dh];  lse: fp32 [B, H, S] = log sum_j exp(q_i.k_j / sqrt(dh)), j <= i.  dh in {32, 64, 128}. */
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,

@@ -90,6 +90,7 @@ _SIGS = {
     "dipaco_k_gemm": (C.c_int, [C.c_int32] * 7 + [C.c_void_p] * 7 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dipaco_k_gemm_colsum": (C.c_int, [C.c_int32] * 6 + [C.c_void_p] * 7 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dipaco_k_set_gemm_tile": (C.c_int, [C.c_int32]),
+    "dipaco_k_set_attention_blocks": (C.c_int, [C.c_int32]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]),
     "dipaco_k_attention_bwd": (C.c_int, [C.c_int32] + [C.c_void_p] * 6 + [C.c_int32] * 4 + [C.c_void_p]),
@@ -391,6 +392,10 @@ def dipaco_k_gemm_colsum(dtype: int, trans_a: bool, trans_b: bool, M: int, N: in
 
 def dipaco_k_set_gemm_tile(tile: int):
     _check(load().dipaco_k_set_gemm_tile(tile))
+
+
+def dipaco_k_set_attention_blocks(single_block: int):
+    _check(load().dipaco_k_set_attention_blocks(int(single_block)))
 
 
 def dipaco_k_attention_fwd(dtype: int, qkv, o, lse, B: int, S: int, H: int, dh: int, stream=None):

@@ -861,6 +861,12 @@ dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
   return DIPACO_OK;
 }
 
+dipaco_status dipaco_k_set_attention_blocks(int32_t single_block) {
+  if (single_block != 0 && single_block != 1) return fail(DIPACO_EINVAL, "dipaco_k_set_attention_blocks: 0 or 1");
+  set_attention_single_block(single_block);
+  return DIPACO_OK;
+}
+
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,
                                      int32_t H, int32_t dh, void* stream) {
   if (!qkv || !o || !lse || B < 1 || S < 1 || H < 1) return fail(DIPACO_EINVAL, "dipaco_k_attention_fwd: bad argument");

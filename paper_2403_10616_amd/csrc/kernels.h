@@ -181,5 +181,7 @@ dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const
 dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, int B, int S, int H, hipStream_t s);
 dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf16* d_o, const float* lse, bf16* dqkv,
                                         float* dsum, int B, int S, int H, hipStream_t s);
+// 0: a workgroup takes a long and a short block of the causal triangle; 1: one block per workgroup, longest first
+void set_attention_single_block(int on);
 
 }  // namespace dipaco

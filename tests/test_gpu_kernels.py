@@ -153,11 +153,19 @@ def _attn_ref(qkv, B, S, H, dh):
     return a, o, lse, probs
 
 
+@pytest.fixture(params=[1, 0], ids=["single_block", "paired_blocks"])
+def attn_blocks(request):
+    """Both ways of dealing the causal triangle's blocks to workgroups; 1 is the default."""
+    dp.dipaco_k_set_attention_blocks(request.param)
+    yield request.param
+    dp.dipaco_k_set_attention_blocks(1)
+
+
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("B,S,H,dh", [(2, 64, 2, 32), (1, 200, 3, 64), (2, 77, 1, 128), (1, 1, 2, 64), (1, 333, 2, 64),
-                                      (2, 1024, 2, 64), (1, 130, 1, 64)])
-def test_attention_forward_backward(dtype, B, S, H, dh):
-    print(f"attention dtype={dtype} B={B} S={S} H={H} dh={dh}", flush=True)
+                                      (2, 1024, 2, 64), (1, 130, 1, 64), (1, 900, 1, 64)])
+def test_attention_forward_backward(dtype, B, S, H, dh, attn_blocks):
+    print(f"attention dtype={dtype} B={B} S={S} H={H} dh={dh} blocks={attn_blocks}", flush=True)
     A = H * dh
     qkv, qr = _rand((B * S, 3 * A), 10, dtype)
     d_o, gr = _rand((B * S, A), 11, dtype)
