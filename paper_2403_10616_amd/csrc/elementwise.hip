@@ -15,6 +15,16 @@ inline int ew_blocks(size_t n_vec, int per_thread = 1) {
   return (int)b;
 }
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float* p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void stream_store4(float* p, float4 v) {
+  const f32x4_t o = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(p));
+}
+
 __device__ __forceinline__ void store_bf16x4(bf16* dst, float4 v) {
   bf16x4 o = {(bf16)v.x, (bf16)v.y, (bf16)v.z, (bf16)v.w};
   *reinterpret_cast<bf16x4*>(dst) = o;
@@ -77,17 +87,16 @@ __global__ void __launch_bounds__(EW_THREADS) adamw_kernel(const AdamArgs a) {
   size_t stride = (size_t)gridDim.x * EW_THREADS;
   for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
     const float decay = adam_decayed(a, (unsigned long long)i << 2) ? a.wd : 0.0f;
-    float4 th = reinterpret_cast<float4*>(a.theta)[i];
-    float4 g = reinterpret_cast<const float4*>(a.grad)[i];
-    float4 m = reinterpret_cast<float4*>(a.m)[i];
-    float4 v = reinterpret_cast<float4*>(a.v)[i];
+    // every value is touched once per step: streaming (non-temporal) loads and stores keep them out of the caches' way
+    float4 th = stream_load4(a.theta + 4 * i), g = stream_load4(a.grad + 4 * i);
+    float4 m = stream_load4(a.m + 4 * i), v = stream_load4(a.v + 4 * i);
     th.x = adam_one(th.x, g.x, m.x, v.x, a, decay);
     th.y = adam_one(th.y, g.y, m.y, v.y, a, decay);
     th.z = adam_one(th.z, g.z, m.z, v.z, a, decay);
     th.w = adam_one(th.w, g.w, m.w, v.w, a, decay);
-    reinterpret_cast<float4*>(a.theta)[i] = th;
-    reinterpret_cast<float4*>(a.m)[i] = m;
-    reinterpret_cast<float4*>(a.v)[i] = v;
+    stream_store4(a.theta + 4 * i, th);
+    stream_store4(a.m + 4 * i, m);
+    stream_store4(a.v + 4 * i, v);
     if (a.lowp) store_bf16x4(a.lowp + 4 * i, th);
   }
 }
@@ -118,13 +127,13 @@ __global__ void __launch_bounds__(EW_THREADS) outer_kernel(const OuterArgs a) {
   size_t stride = (size_t)gridDim.x * EW_THREADS;
   const int np = NP > 0 ? NP : a.n_paths;
   for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
-    float4 th = reinterpret_cast<const float4*>(a.theta)[i];
-    float4 b = reinterpret_cast<const float4*>(a.buf)[i];
+    float4 th = stream_load4(a.theta + 4 * i);
+    float4 b = stream_load4(a.buf + 4 * i);
     float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
     if (NP > 0) {
       float4 x[NP > 0 ? NP : 1];
 #pragma unroll
-      for (int p = 0; p < NP; ++p) x[p] = reinterpret_cast<const float4*>(a.in[p])[i];
+      for (int p = 0; p < NP; ++p) x[p] = stream_load4(a.in[p] + 4 * i);
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
         float al = a.alpha[p];
@@ -133,15 +142,15 @@ __global__ void __launch_bounds__(EW_THREADS) outer_kernel(const OuterArgs a) {
       }
     } else {
       for (int p = 0; p < np; ++p) {
-        float4 x = reinterpret_cast<const float4*>(a.in[p])[i];
+        float4 x = stream_load4(a.in[p] + 4 * i);
         float al = a.alpha[p];
         if (a.is_delta) { d.x += al * x.x; d.y += al * x.y; d.z += al * x.z; d.w += al * x.w; }
         else { d.x += al * (th.x - x.x); d.y += al * (th.y - x.y); d.z += al * (th.z - x.z); d.w += al * (th.w - x.w); }
       }
     }
     th = outer_one(th, d, b, a.lr, a.mu);
-    reinterpret_cast<float4*>(a.theta)[i] = th;
-    reinterpret_cast<float4*>(a.buf)[i] = b;
+    stream_store4(a.theta + 4 * i, th);
+    stream_store4(a.buf + 4 * i, b);
   }
   if (blockIdx.x == 0 && threadIdx.x < (a.n & 3)) {  // tail elements
     size_t i = (nv << 2) + threadIdx.x;
@@ -182,18 +191,18 @@ __global__ void __launch_bounds__(EW_THREADS) outer_table_kernel(const OuterTabl
       const size_t i = i0 + (size_t)it * EW_THREADS;
       d[it] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (i < nv) {
-        th[it] = reinterpret_cast<const float4*>(e.theta)[i];
-        b[it] = reinterpret_cast<const float4*>(e.momentum)[i];
+        th[it] = stream_load4(e.theta + 4 * i);
+        b[it] = stream_load4(e.momentum + 4 * i);
       }
     }
     for (int p = 0; p < e.n_paths; ++p) {
-      const float4* src = reinterpret_cast<const float4*>(in[p]);
+      const float* src = in[p];
       const float a = al[p];
       float4 x[IT];
 #pragma unroll
       for (int it = 0; it < IT; ++it) {
         const size_t i = i0 + (size_t)it * EW_THREADS;
-        x[it] = i < nv ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        x[it] = i < nv ? stream_load4(src + 4 * i) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
 #pragma unroll
       for (int it = 0; it < IT; ++it) {
@@ -209,8 +218,8 @@ __global__ void __launch_bounds__(EW_THREADS) outer_table_kernel(const OuterTabl
     for (int it = 0; it < IT; ++it) {
       const size_t i = i0 + (size_t)it * EW_THREADS;
       if (i < nv) {
-        reinterpret_cast<float4*>(e.theta)[i] = outer_one(th[it], d[it], b[it], lr, mu);
-        reinterpret_cast<float4*>(e.momentum)[i] = b[it];
+        stream_store4(e.theta + 4 * i, outer_one(th[it], d[it], b[it], lr, mu));
+        stream_store4(e.momentum + 4 * i, b[it]);
       }
     }
     // the up to three elements after the last whole vector belong to the module's last chunk
@@ -236,7 +245,7 @@ __global__ void __launch_bounds__(EW_THREADS) delta_accumulate_kernel(float* __r
   const size_t nv = n >> 2;
   const size_t stride = (size_t)gridDim.x * EW_THREADS;
   for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
-    float4 x = reinterpret_cast<const float4*>(in)[i];
+    float4 x = stream_load4(in + 4 * i);   // read once; the running sum is read again by the next call and stays cacheable
     if (!is_delta) {
       const float4 t = reinterpret_cast<const float4*>(theta_prev)[i];
       x = make_float4(t.x - x.x, t.y - x.y, t.z - x.z, t.w - x.w);
