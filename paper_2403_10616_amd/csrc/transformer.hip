@@ -369,10 +369,11 @@ __global__ void __launch_bounds__(1024) mean_loss_kernel(const float* __restrict
 // ---- embedding gradient ----------------------------------------------------------------------------------
 // d_tok[v] = sum of dx rows whose token is v, added in increasing position order (no float atomics): positions are
 // grouped by token with a stable sort (kmeans.hip), then one workgroup per vocabulary row adds its positions.
-// One workgroup (8 waves) per vocabulary row.  Wave w adds the row's positions w, w+8, ... in order (lanes over
-// 16-byte column chunks), then the eight wave sums are added in wave order: a fixed tree, so the frequent tokens
+// One workgroup (16 waves) per vocabulary row.  Wave w adds the row's positions w, w+16, ... in order (lanes over
+// 16-byte column chunks, eight row loads in flight), then the wave sums are added in wave order: a fixed tree, so the frequent tokens
 // of a Zipf batch (thousands of positions) are spread over the workgroup without any atomics.
-constexpr int TG_WAVES = 8;
+constexpr int TG_WAVES = 16;
+constexpr int TG_UNROLL = 8;   // row loads in flight per wave
 template <typename T>
 __global__ void __launch_bounds__(TG_WAVES * WAVE) tok_grad_kernel(const T* __restrict__ dx,
                                                                    const int* __restrict__ offsets,
@@ -402,14 +403,14 @@ __global__ void __launch_bounds__(TG_WAVES * WAVE) tok_grad_kernel(const T* __re
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
     int j = lo + wave;
-    for (; j + 3 * TG_WAVES < hi; j += 4 * TG_WAVES) {
-      float a0[VEC], a1[VEC], a2[VEC], a3[VEC];
-      load_vec16(dx + (size_t)order[j] * d + c, a0);
-      load_vec16(dx + (size_t)order[j + TG_WAVES] * d + c, a1);
-      load_vec16(dx + (size_t)order[j + 2 * TG_WAVES] * d + c, a2);
-      load_vec16(dx + (size_t)order[j + 3 * TG_WAVES] * d + c, a3);
+    for (; j + (TG_UNROLL - 1) * TG_WAVES < hi; j += TG_UNROLL * TG_WAVES) {
+      float a[TG_UNROLL][VEC];
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) { acc[i] += a0[i]; acc[i] += a1[i]; acc[i] += a2[i]; acc[i] += a3[i]; }
+      for (int u = 0; u < TG_UNROLL; ++u) load_vec16(dx + (size_t)order[j + u * TG_WAVES] * d + c, a[u]);
+#pragma unroll
+      for (int u = 0; u < TG_UNROLL; ++u)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += a[u][i];
     }
     for (; j < hi; j += TG_WAVES) {
       float a[VEC];
