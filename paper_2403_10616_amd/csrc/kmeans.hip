@@ -90,11 +90,11 @@ __global__ void __launch_bounds__(64) sort_scatter_kernel(const int* __restrict_
 
 // count[k] = number of keys equal to k (integer atomics: the result does not depend on their order)
 // LDS: a workgroup counts KC_BLOCK keys in LDS first (n_keys <= KC_MAX_LDS) and adds only its non-zero bins.
-constexpr int KC_BLOCK = 8192, KC_MAX_LDS = 4096;
+constexpr int KC_BLOCK = 8192, KC_MAX_LDS = 36864;   // 144 KB of counters at most
 template <bool LDS>
 __global__ void __launch_bounds__(256) key_count_kernel(const int* __restrict__ keys, long n, int n_keys,
                                                         int* __restrict__ count) {
-  __shared__ int h[LDS ? KC_MAX_LDS : 1];
+  extern __shared__ int h[];   // LDS: n_keys counters
   if (LDS) {
     for (int k = threadIdx.x; k < n_keys; k += 256) h[k] = 0;
     __syncthreads();
@@ -124,15 +124,27 @@ __global__ void __launch_bounds__(1024) key_scan_kernel(const int* __restrict__ 
   run_sum[threadIdx.x] = s;
   run_chunks[threadIdx.x] = ch;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int a = 0, b = 0;
-    for (int t = 0; t < 1024; ++t) {
-      const int x = run_sum[t], y = run_chunks[t];
-      run_sum[t] = a; run_chunks[t] = b;
-      a += x; b += y;
+  if (threadIdx.x < 64) {   // exclusive scan of the 1024 run totals: 16 per lane, then across the wave
+    const int lane = threadIdx.x;
+    int a[16], b[16], ta = 0, tb = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { a[i] = run_sum[16 * lane + i]; b[i] = run_chunks[16 * lane + i]; ta += a[i]; tb += b[i]; }
+    int ia = ta, ib = tb;   // inclusive scan over the lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int ua = __shfl_up(ia, o, 64), ub = __shfl_up(ib, o, 64);
+      if (lane >= o) { ia += ua; ib += ub; }
     }
-    start[n_keys] = a;
-    if (chunk_start) chunk_start[n_keys] = b;
+    int ea = ia - ta, eb = ib - tb;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      run_sum[16 * lane + i] = ea; run_chunks[16 * lane + i] = eb;
+      ea += a[i]; eb += b[i];
+    }
+    if (lane == 63) {
+      start[n_keys] = ia;
+      if (chunk_start) chunk_start[n_keys] = ib;
+    }
   }
   __syncthreads();
   s = run_sum[threadIdx.x];
@@ -250,8 +262,17 @@ dipaco_status launch_key_offsets(const int* keys, long n, int n_keys, int* count
   DIPACO_LAUNCH_CHECK();
   if (n > 0) {
     const unsigned blocks = (unsigned)((n + KC_BLOCK - 1) / KC_BLOCK);
-    if (n_keys <= KC_MAX_LDS) key_count_kernel<true><<<blocks, 256, 0, s>>>(keys, n, n_keys, count);
-    else key_count_kernel<false><<<blocks, 256, 0, s>>>(keys, n, n_keys, count);
+    if (n_keys <= KC_MAX_LDS) {
+      static bool attr_set = false;
+      if (!attr_set) {
+        DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(key_count_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, KC_MAX_LDS * (int)sizeof(int)));
+        attr_set = true;
+      }
+      key_count_kernel<true><<<blocks, 256, (size_t)n_keys * sizeof(int), s>>>(keys, n, n_keys, count);
+    } else {
+      key_count_kernel<false><<<blocks, 256, 0, s>>>(keys, n, n_keys, count);
+    }
     DIPACO_LAUNCH_CHECK();
   }
   key_scan_kernel<<<1, 1024, 0, s>>>(count, n_keys, start, chunk_start);
