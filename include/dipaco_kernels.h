@@ -41,7 +41,8 @@ dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans
 /* Force the GEMM workgroup tile for every later call in this process: 0 = automatic (default), 1 = 128x128,
  * 2 = 256x128, 3 = 256x256 with four waves, 4 = 256x256 with eight waves, 5 = the bf16 kernel that loads its
  * 256x256 tiles from global memory straight into LDS, for every shape it takes (K a multiple of 32, 16-byte rows;
- * other shapes and fp32 keep the automatic choice), 6 / 7 = the same kernel with its 256x256 / 256x128 tile forced.
+ * other shapes and fp32 keep the automatic choice), 6 / 7 = the same kernel with its 256x256 / 256x128 tile forced,
+ * 8 / 9 = the same with 128x512 / 512x128 tiles for weight gradients (fp32 output) and 256x256 for the rest.
  * For tests (every tile shape must give the same parity) and tuning. */
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 

@@ -32,7 +32,7 @@ namespace dipaco {
 
 namespace {
 
-constexpr int DL_BM = 256, DL_BK = 32;
+constexpr int DL_BK = 32;
 constexpr int DL_ROWB = DL_BK * 2;                          // bytes of a K-contiguous tile row
 
 typedef short v4s __attribute__((ext_vector_type(4)));
@@ -50,7 +50,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only:
 // traffic, for long K), and 256 x 128 tiles, 2 x 2 waves, 3 stages (two workgroups per compute unit, whose
 // prologues and epilogues hide behind each other's multiplications: for the short-K products of the step, where
 // those ends are a large part of a tile's life).  Either way a wave owns 128 x 64 outputs and two waves share a SIMD.
-template <typename TC, bool A_KC, bool B_KC, int DL_BN, int WGM, int WGN, int DL_STAGES>
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES>
 __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const GemmDev g) {
   constexpr int NW = WGM * WGN;
   constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;   // bytes of an operand tile (either kind)
@@ -69,9 +69,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
   // that in a tile that sticks out of C by half (896 = 3.5 x 256 is the path's width) every SIMD keeps exactly
   // one wave with work, which then has the matrix core to itself.  (Letting the idle wave of the SIMD take half of
   // every K tile of its partner's outputs was measured: no gain, the launch is not bound by that wave's latencies.)
-  static_assert(WGM == 2 && (WGN == 4 || WGN == 2), "wave placement below is written for 2 x 4 and 2 x 2 waves");
-  const int wm = WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1;
-  const int wn = WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1;
+  static_assert((WGM == 2 && (WGN == 4 || WGN == 2)) || (WGM == 1 && WGN == 8) || (WGM == 4 && WGN == 2),
+                "wave placement below is written for 2 x 4, 2 x 2, 1 x 8 and 4 x 2 waves");
+  const int wm = WGM == 1 ? 0 : WGM == 4 ? (wave & 3) : (WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1);
+  const int wn = WGM == 1 ? wave : WGM == 4 ? (wave >> 2) : (WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1);
   int split, tile_m, tile_n, k_begin, nkt;
   if (g.uneven) {
     int nsplit;
@@ -108,7 +109,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
       gp[i] = base + (long)row * ld + k_begin + chunk * 8;
       gstep[i] = DL_BK;
     } else {
-      const int sh = (is_a || DL_BN == 256) ? 5 : 4;   // log2 of the 16-byte chunks per K-row (32 or 16)
+      // log2 of the 16-byte chunks per K-row: 4, 5, 6 for tiles 128, 256, 512 wide
+      constexpr int SH_A = DL_BM == 512 ? 6 : (DL_BM == 256 ? 5 : 4), SH_B = DL_BN == 512 ? 6 : (DL_BN == 256 ? 5 : 4);
+      static_assert((DL_BM == 128 || DL_BM == 256 || DL_BM == 512) && (DL_BN == 128 || DL_BN == 256 || DL_BN == 512),
+                    "tile sides of 128, 256 or 512");
+      const int sh = is_a ? SH_A : SH_B;
       const int t = (64 >> sh) * jj + (lane >> sh);
       const int cp = lane & ((1 << sh) - 1);
       const int seg = (cp >> 2) ^ (t & 3);
@@ -250,18 +255,19 @@ double partial_tile_cost(double frac) { return 0.5 + 0.5 * frac; }
 struct UnevenPlan {
   int s[4];          // K slices per class; s[0] = the largest
   int n[4];          // tiles per class
+  double cost[4];    // cost of a K step of a tile of the class, a full tile = 1
   int full_m, full_n;
 };
 
 // The largest slice count <= max_slices such that every tile class c, cut into ceil(cost_c * s) slices, still
 // gives at most one workgroup per compute unit.  False if there is no such plan with at least two slices.
-bool plan_uneven(int M, int N, int K, int BN, int WGN, int max_slices, UnevenPlan& p) {
+bool plan_uneven(int M, int N, int K, int BM, int BN, int WGM, int WGN, int max_slices, UnevenPlan& p) {
   constexpr int CUS = 256;
-  const int tiles_m = (M + DL_BM - 1) / DL_BM, tiles_n = (N + BN - 1) / BN;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if ((long)tiles_m * tiles_n > CUS / 2) return false;
-  const int rm = M - (tiles_m - 1) * DL_BM, rn = N - (tiles_n - 1) * BN;
-  const int WM = DL_BM / 2, WN = BN / WGN;
-  const double am = (double)((rm + WM - 1) / WM) / 2, an = (double)((rn + WN - 1) / WN) / WGN;
+  const int rm = M - (tiles_m - 1) * BM, rn = N - (tiles_n - 1) * BN;
+  const int WM = BM / WGM, WN = BN / WGN;
+  const double am = (double)((rm + WM - 1) / WM) / WGM, an = (double)((rn + WN - 1) / WN) / WGN;
   p.full_m = tiles_m - (am < 1.0 ? 1 : 0);
   p.full_n = tiles_n - (an < 1.0 ? 1 : 0);
   p.n[0] = p.full_m * p.full_n;
@@ -269,6 +275,7 @@ bool plan_uneven(int M, int N, int K, int BN, int WGN, int max_slices, UnevenPla
   p.n[2] = p.full_m * (tiles_n - p.full_n);
   p.n[3] = (tiles_m - p.full_m) * (tiles_n - p.full_n);
   const double w[4] = {1.0, partial_tile_cost(am), partial_tile_cost(an), partial_tile_cost(am * an)};
+  for (int c = 0; c < 4; ++c) p.cost[c] = w[c];
   const int ktiles = K / DL_BK;
   for (int sf = std::min(max_slices, ktiles); sf >= 2; --sf) {
     long total = 0;
@@ -281,11 +288,19 @@ bool plan_uneven(int M, int N, int K, int BN, int WGN, int max_slices, UnevenPla
   return false;
 }
 
-template <typename TC, bool A_KC, bool B_KC, int BN, int WGM, int WGN, int STAGES>
+// Length of the longest workgroup of a plan, in K steps of a full tile per unit of K
+double plan_makespan(const UnevenPlan& p) {
+  double worst = 0.0;
+  for (int c = 0; c < 4; ++c)
+    if (p.n[c] > 0) worst = std::max(worst, p.cost[c] / p.s[c]);
+  return worst;
+}
+
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES>
 dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_ROWB;
   static_assert((size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
-  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, BN, WGM, WGN, STAGES>;
+  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES>;
   static bool attr_set = false;
   if (!attr_set) {
     DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -301,7 +316,7 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   g.tiles_n = (a.N + BN - 1) / BN;
   const int ktiles = a.K / DL_BK;
   UnevenPlan up;
-  if (a.splits > 1 && plan_uneven(a.M, a.N, a.K, BN, WGN, a.splits, up)) {
+  if (a.splits > 1 && plan_uneven(a.M, a.N, a.K, DL_BM, BN, WGM, WGN, a.splits, up)) {
     g.uneven = 1;
     g.splits = up.s[0];
     g.k_per_split = 0;
@@ -328,16 +343,40 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   return DIPACO_OK;
 }
 
-int g_dlds_shape = 0;   // 0 = automatic, 1 = 256 x 256, 2 = 256 x 128
+int g_dlds_shape = 0;   // 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 (weight gradients only)
+
+// Weight gradients with a side that is not a multiple of 256 (896 = 7 x 128): 128 x 512 tiles of 1 x 8 waves, or
+// 512 x 128 tiles of 4 x 2 waves, cut C into whole tiles only, so that five K slices fit on the chip where the
+// 256 x 256 shape, whose last tile row (column) is half empty but costs 0.75, gets four.  An oblong tile moves
+// 1.25 x the operand bytes per flop and has three stages: it is taken when its plan's longest workgroup is at
+// least 8 % shorter.
+// Returns 0 (keep 256 x 256), 1 (128 x 512) or 2 (512 x 128).
+int oblong_plan_wins(const GemmArgs& a) {
+  if (g_dlds_shape == 3) return 1;
+  if (g_dlds_shape == 4) return 2;
+  if (g_dlds_shape != 0 || a.splits <= 1) return 0;
+  UnevenPlan sq, ob;
+  const bool have_sq = plan_uneven(a.M, a.N, a.K, 256, 256, 2, 4, a.splits, sq);
+  double best = have_sq ? 0.92 * plan_makespan(sq) : 1e30;
+  int pick = 0;
+  if (plan_uneven(a.M, a.N, a.K, 128, 512, 1, 8, a.splits, ob) && plan_makespan(ob) < best) { best = plan_makespan(ob); pick = 1; }
+  if (plan_uneven(a.M, a.N, a.K, 512, 128, 4, 2, a.splits, ob) && plan_makespan(ob) < best) { best = plan_makespan(ob); pick = 2; }
+  return pick;
+}
 
 // Measured on the step's products (K = 896 .. 32768), the two-workgroup shape gains what it hides of a tile's ends
 // and loses as much to its extra barriers and operand traffic: it wins only on the 2688-wide QKV projection (by 6 %)
 // and is kept as a tested option; the automatic choice is the 256 x 256 shape.
 template <typename TC, bool A_KC, bool B_KC>
 dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
+  if constexpr (std::is_same<TC, float>::value) {
+    const int oblong = oblong_plan_wins(a);
+    if (oblong == 1) return run_dlds<TC, A_KC, B_KC, 128, 512, 1, 8, 3>(a, s);
+    if (oblong == 2) return run_dlds<TC, A_KC, B_KC, 512, 128, 4, 2, 3>(a, s);
+  }
   const bool narrow = g_dlds_shape == 2;
-  if (narrow) return run_dlds<TC, A_KC, B_KC, 128, 2, 2, 3>(a, s);
-  return run_dlds<TC, A_KC, B_KC, 256, 2, 4, 4>(a, s);
+  if (narrow) return run_dlds<TC, A_KC, B_KC, 256, 128, 2, 2, 3>(a, s);
+  return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4>(a, s);
 }
 
 }  // namespace
@@ -356,10 +395,16 @@ void set_gemm_dlds_shape(int shape) { g_dlds_shape = shape; }
 
 int gemm_dlds_plan_slices(int M, int N, int K, int max_slices, bool any_shape) {
   UnevenPlan up;
-  const int wide = plan_uneven(M, N, K, 256, 4, max_slices, up) ? up.s[0] : 0;
-  const int narrow = plan_uneven(M, N, K, 128, 2, max_slices, up) ? up.s[0] : 0;
-  if (any_shape) return std::max(wide, narrow);
-  return g_dlds_shape == 2 ? narrow : wide;
+  const int square = plan_uneven(M, N, K, 256, 256, 2, 4, max_slices, up) ? up.s[0] : 0;
+  const int narrow = plan_uneven(M, N, K, 256, 128, 2, 2, max_slices, up) ? up.s[0] : 0;
+  const int wide = plan_uneven(M, N, K, 128, 512, 1, 8, max_slices, up) ? up.s[0] : 0;
+  const int tall = plan_uneven(M, N, K, 512, 128, 4, 2, max_slices, up) ? up.s[0] : 0;
+  if (any_shape) return std::max(std::max(square, narrow), std::max(wide, tall));
+  GemmArgs a{};
+  a.M = M; a.N = N; a.K = K; a.splits = max_slices;
+  const int oblong = oblong_plan_wins(a);
+  if (oblong) return oblong == 1 ? wide : tall;
+  return g_dlds_shape == 2 ? narrow : square;
 }
 
 dipaco_status launch_gemm_dlds(const GemmArgs& a, hipStream_t s) {

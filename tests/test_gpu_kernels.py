@@ -22,7 +22,7 @@ def _rand(shape, seed, dtype):
     return t.to(DEV), t.to(torch.float64).numpy()
 
 
-@pytest.fixture(params=[0, 1, 2, 3, 4, 5, 6, 7], ids=lambda t: f"tile{t}")
+@pytest.fixture(params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9], ids=lambda t: f"tile{t}")
 def gemm_tile(request):
     """Every workgroup tile shape must reach the same parity; 0 is the library's own choice."""
     dp.dipaco_k_set_gemm_tile(request.param)
@@ -119,7 +119,8 @@ def test_gemm_column_sums_of_the_output(dtype, M, N, K, gemm_tile):
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("M,N,K,splits", [(128, 128, 64, 1), (200, 136, 77, 1), (72, 264, 1000, 4), (8, 8, 5, 1),
-                                          (136, 64, 4099, 16), (264, 520, 1024, 5), (8, 776, 96, 1)])
+                                          (136, 64, 4099, 16), (264, 520, 1024, 5), (8, 776, 96, 1),
+                                          (896, 1024, 2048, 8), (384, 1160, 512, 3)])
 def test_gemm_weight_gradient_layout_and_split_k(dtype, M, N, K, splits, gemm_tile):
     print(f"gemm dW tile={gemm_tile} dtype={dtype} M={M} N={N} K={K} splits={splits}", flush=True)
     At, Atr = _rand((K, M), 8, dtype)          # A stored [K, M]: contraction over rows (tokens)
