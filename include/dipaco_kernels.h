@@ -57,10 +57,12 @@ dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, fl
                                      int32_t H, int32_t dh, void* stream);
 
 /* Gradient of the above: d_o [B*S, H*dh] -> dqkv [B*S, 3*H*dh].  dsum: fp32 scratch of 2 * B * H * S128 floats,
- * S128 = S rounded up to a multiple of 128 (per-query statistics passed between the two backward kernels). */
+ * S128 = S rounded up to a multiple of 128 (per-query statistics passed between the two backward kernels).
+ * colsum_out: NULL, or fp32 [3*H*dh] = the column sums of dqkv (the bias gradient of the QKV projection), added in a
+ * fixed order; then colsum_scratch: fp32, at least max(ceil(B*S / 256), B * ceil(S / 128)) * 3*H*dh elements. */
 dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* d_o, const float* lse,
-                                     void* dqkv, float* dsum, int32_t B, int32_t S, int32_t H, int32_t dh,
-                                     void* stream);
+                                     void* dqkv, float* dsum, float* colsum_out, float* colsum_scratch, int32_t B,
+                                     int32_t S, int32_t H, int32_t dh, void* stream);
 
 #ifdef __cplusplus
 }

@@ -93,7 +93,7 @@ _SIGS = {
     "dipaco_k_set_attention_blocks": (C.c_int, [C.c_int32]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]),
-    "dipaco_k_attention_bwd": (C.c_int, [C.c_int32] + [C.c_void_p] * 6 + [C.c_int32] * 4 + [C.c_void_p]),
+    "dipaco_k_attention_bwd": (C.c_int, [C.c_int32] + [C.c_void_p] * 8 + [C.c_int32] * 4 + [C.c_void_p]),
 }
 
 EXPORTS = tuple(_SIGS)
@@ -402,6 +402,7 @@ def dipaco_k_attention_fwd(dtype: int, qkv, o, lse, B: int, S: int, H: int, dh: 
     _check(load().dipaco_k_attention_fwd(dtype, _ptr(qkv), _ptr(o), _ptr(lse), B, S, H, dh, _stream(stream)))
 
 
-def dipaco_k_attention_bwd(dtype: int, qkv, o, d_o, lse, dqkv, dsum, B: int, S: int, H: int, dh: int, stream=None):
-    _check(load().dipaco_k_attention_bwd(dtype, _ptr(qkv), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dqkv), _ptr(dsum), B, S,
-                                         H, dh, _stream(stream)))
+def dipaco_k_attention_bwd(dtype: int, qkv, o, d_o, lse, dqkv, dsum, B: int, S: int, H: int, dh: int, stream=None,
+                           colsum_out=None, colsum_scratch=None):
+    _check(load().dipaco_k_attention_bwd(dtype, _ptr(qkv), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dqkv), _ptr(dsum),
+                                         _ptr(colsum_out), _ptr(colsum_scratch), B, S, H, dh, _stream(stream)))

@@ -90,7 +90,8 @@ static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   p.dqkv = take(T * 3 * A * es); p.d_o = take(T * A * es); p.dsum = take(2 * (size_t)B * a.n_heads * ((S + 127) / 128 * 128) * 4);
   p.ln_partial = take(ln_bwd_partial_floats((int)T, (int)d) * 4);
   const size_t widest = std::max(std::max(F, 3 * A), d);
-  p.cs_partial = take(std::max(colsum_partial_floats((int)T, (int)widest), gemm_colsum_partial_floats((int)T, (int)F)) * 4);
+  p.cs_partial = take(std::max(std::max(colsum_partial_floats((int)T, (int)widest), gemm_colsum_partial_floats((int)T, (int)F)),
+                               attention_bwd_colsum_floats((int)B, (int)S, a.n_heads, a.d_head)) * 4);
   size_t sk = 0;
   auto need = [&](size_t M, size_t N) { sk = std::max(sk, (size_t)gemm_max_splits((int)M, (int)N, (int)T) * M * N); };
   need(d, 3 * A); need(A, d); need(d, F); need(F, d); need(d, V);
@@ -200,10 +201,10 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
     TRY(dweight(buf(L.o), dx_other, o.w_o, A, d));
     TRY(gemm<T>(dx_other, W + o.w_o, buf(p.d_o), T_, A, d, d, d, A, false, true, nullptr, nullptr, nullptr, nullptr, 0,
                 false, 1, nullptr, st));
-    TRY(launch_attention_bwd<T>(buf(L.qkv), buf(L.o), buf(p.d_o), fbuf(L.lse), buf(p.dqkv), fbuf(p.dsum), B, S, H, dh,
-                                st));
+    // dqkv and its column sums, the gradient of b_qkv
+    TRY(launch_attention_bwd<T>(buf(L.qkv), buf(L.o), buf(p.d_o), fbuf(L.lse), buf(p.dqkv), fbuf(p.dsum), G + o.b_qkv,
+                                csp, B, S, H, dh, st));
     TRY(dweight(buf(L.h1), buf(p.dqkv), o.w_qkv, d, 3 * A));
-    TRY(launch_colsum<T>(buf(p.dqkv), G + o.b_qkv, csp, T_, 3 * A, st));
     TRY(gemm<T>(buf(p.dqkv), W + o.w_qkv, buf(p.dh), T_, d, 3 * A, 3 * A, 3 * A, d, false, true, nullptr, nullptr,
                 nullptr, nullptr, 0, false, 1, nullptr, st));
     TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_in), W + o.ln1_g, fbuf(L.mean1), fbuf(L.rstd1), dx_other, dx,
@@ -877,18 +878,18 @@ dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, fl
 }
 
 dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* d_o, const float* lse,
-                                     void* dqkv, float* dsum, int32_t B, int32_t S, int32_t H, int32_t dh,
-                                     void* stream) {
-  if (!qkv || !o || !d_o || !lse || !dqkv || !dsum || B < 1 || S < 1 || H < 1)
+                                     void* dqkv, float* dsum, float* colsum_out, float* colsum_scratch, int32_t B,
+                                     int32_t S, int32_t H, int32_t dh, void* stream) {
+  if (!qkv || !o || !d_o || !lse || !dqkv || !dsum || B < 1 || S < 1 || H < 1 || (colsum_out && !colsum_scratch))
     return fail(DIPACO_EINVAL, "dipaco_k_attention_bwd: bad argument");
   hipStream_t st = static_cast<hipStream_t>(stream);
   return dtype == DIPACO_BF16
              ? launch_attention_bwd<bf16>(static_cast<const bf16*>(qkv), static_cast<const bf16*>(o),
-                                          static_cast<const bf16*>(d_o), lse, static_cast<bf16*>(dqkv), dsum, B, S, H,
-                                          dh, st)
+                                          static_cast<const bf16*>(d_o), lse, static_cast<bf16*>(dqkv), dsum, colsum_out,
+                                          colsum_scratch, B, S, H, dh, st)
              : launch_attention_bwd<float>(static_cast<const float*>(qkv), static_cast<const float*>(o),
-                                           static_cast<const float*>(d_o), lse, static_cast<float*>(dqkv), dsum, B, S,
-                                           H, dh, st);
+                                           static_cast<const float*>(d_o), lse, static_cast<float*>(dqkv), dsum, colsum_out,
+                                           colsum_scratch, B, S, H, dh, st);
 }
 
 }  // extern "C"

@@ -216,26 +216,34 @@ dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S,
   return fail(DIPACO_ESHAPE, "attention: d_head must be 32, 64 or 128");
 }
 
+size_t attention_bwd_colsum_floats(int B, int S, int H, int dh) {
+  return std::max(colsum_partial_floats(B * S, 3 * H * dh), dh == 64 ? attention_colsum_partial_floats(B, S, H) : 0);
+}
+
 template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv, float* dsum,
-                                   int B, int S, int H, int dh, hipStream_t s) {
-  if (is_bf16<T>() && dh == 64)
+                                   float* colsum_out, float* colsum_partial, int B, int S, int H, int dh,
+                                   hipStream_t s) {
+  if (is_bf16<T>() && dh == 64)   // the matrix-core kernels take the column sums in their epilogues
     return launch_attention_bwd_mfma(reinterpret_cast<const bf16*>(qkv), reinterpret_cast<const bf16*>(o),
-                                     reinterpret_cast<const bf16*>(d_o), lse, reinterpret_cast<bf16*>(dqkv), dsum, B, S,
-                                     H, s);
+                                     reinterpret_cast<const bf16*>(d_o), lse, reinterpret_cast<bf16*>(dqkv), dsum,
+                                     colsum_out, colsum_partial, B, S, H, s);
+  dipaco_status st;
   switch (dh) {
-    case 32: return bwd_scalar<T, 32>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s);
-    case 64: return bwd_scalar<T, 64>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s);
-    case 128: return bwd_scalar<T, 128>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s);
+    case 32: st = bwd_scalar<T, 32>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s); break;
+    case 64: st = bwd_scalar<T, 64>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s); break;
+    case 128: st = bwd_scalar<T, 128>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s); break;
+    default: return fail(DIPACO_ESHAPE, "attention: d_head must be 32, 64 or 128");
   }
-  return fail(DIPACO_ESHAPE, "attention: d_head must be 32, 64 or 128");
+  if (st != DIPACO_OK || !colsum_out) return st;
+  return launch_colsum<T>(dqkv, colsum_out, colsum_partial, B * S, 3 * H * dh, s);
 }
 
 template dipaco_status launch_attention_fwd<float>(const float*, float*, float*, int, int, int, int, hipStream_t);
 template dipaco_status launch_attention_fwd<bf16>(const bf16*, bf16*, float*, int, int, int, int, hipStream_t);
 template dipaco_status launch_attention_bwd<float>(const float*, const float*, const float*, const float*, float*,
-                                                   float*, int, int, int, int, hipStream_t);
+                                                   float*, float*, float*, int, int, int, int, hipStream_t);
 template dipaco_status launch_attention_bwd<bf16>(const bf16*, const bf16*, const bf16*, const float*, bf16*, float*,
-                                                  int, int, int, int, hipStream_t);
+                                                  float*, float*, int, int, int, int, hipStream_t);
 
 }  // namespace dipaco

@@ -190,6 +190,43 @@ __device__ __forceinline__ void store_transposed_out(bf16* row_ptr, const f32x16
     for (int g = 0; g < 4; ++g) store4(row_ptr + 32 * dt + 8 * g + 4 * h, ot[dt], g, scale);
 }
 
+// v + (v of the lane that the DPP control selects); rows outside row_mask add 0.  Pure VALU: no LDS traffic.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_add(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false);
+  return v + __builtin_bit_cast(float, t);
+}
+// Sum over each half of the wave (lanes 0..31, lanes 32..63); the result is valid in lanes 16..31 and 48..63.
+__device__ __forceinline__ float half_wave_sum(float v) {
+  v = dpp_add<0xb1, 0xf>(v);    // quad_perm [1,0,3,2]
+  v = dpp_add<0x4e, 0xf>(v);    // quad_perm [2,3,0,1]: every lane holds its quad's sum
+  v = dpp_add<0x141, 0xf>(v);   // row_half_mirror: sums of 8
+  v = dpp_add<0x140, 0xf>(v);   // row_mirror: sums of 16
+  v = dpp_add<0x142, 0xa>(v);   // row_bcast15 into rows 1 and 3: sums of 32
+  return v;
+}
+
+// Column sums of a block's 128 rows of a transposed-output tile pair (the bias gradient of the projection whose
+// output gradient the block is): every lane adds scale * its values over the 32 rows of its wave, the four waves'
+// sums are added in wave order, and the 64 sums go to out[0..64).
+// red: LDS [4][64].  All four waves call it; rows with valid = false count as zero.
+__device__ __forceinline__ void block_column_sums(const f32x16 (&ot)[2], float scale, bool valid, float (*red)[DH],
+                                                  float* __restrict__ out, int wave, int lane) {
+  const int h = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float v = half_wave_sum(valid ? ot[dt][k] * scale : 0.f);
+      if ((lane & 31) == 31) red[wave][32 * dt + 8 * (k >> 2) + 4 * h + (k & 3)] = v;
+    }
+  __syncthreads();
+  if (threadIdx.x < DH) {
+    const int c = threadIdx.x;
+    out[c] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+  }
+  __syncthreads();   // red is reused by the workgroup's next block
+}
+
 // ---- forward ---------------------------------------------------------------------------------------------------
 constexpr int FWD_STAGES = 2, DQ_STAGES = 2, DKV_STAGES = 2;
 
@@ -300,8 +337,9 @@ __global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __res
 __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                                   const bf16* __restrict__ d_o,
                                                                   const float* __restrict__ lse, bf16* __restrict__ dqkv,
-                                                                  float* __restrict__ dsum, int S, int H, int single) {
+                                                                  float* __restrict__ dsum, float* __restrict__ colsum, int S, int H, int single) {
   constexpr int NS = DQ_STAGES;
+  __shared__ float cs_red[4][DH];
   extern __shared__ __attribute__((aligned(16))) char dq_smem[];   // [stage][K | V]
   char (*smem)[2][TILE_BYTES] = reinterpret_cast<char (*)[2][TILE_BYTES]>(dq_smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -398,6 +436,8 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
     }
   }
   if (q < S) store_transposed_out(dqkv + ((long)b * S + q) * ld + hd * DH, dqt, h, 0.125f);
+  // one row of partial column sums per (document, query block): [b * nqb + qb][3 A], this head's 64 dQ columns
+  if (colsum) block_column_sums(dqt, 0.125f, q < S, cs_red, colsum + ((long)b * nqb + qb) * ld + hd * DH, wave, lane);
   }
 }
 
@@ -407,8 +447,9 @@ constexpr int DKV_STAGE = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);   // Q |
 __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* __restrict__ qkv,
                                                                    const bf16* __restrict__ d_o,
                                                                    const float* __restrict__ dsum,
-                                                                   bf16* __restrict__ dqkv, int S, int H, int single) {
+                                                                   bf16* __restrict__ dqkv, float* __restrict__ colsum, int S, int H, int single) {
   constexpr int NS = DKV_STAGES;
+  __shared__ float cs_red[4][DH];
   extern __shared__ __attribute__((aligned(16))) char dkv_smem[];   // NS stages of DKV_STAGE bytes
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, h = lane >> 5;
@@ -510,6 +551,11 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
     store_transposed_out(out + A, dkt, h, 0.125f);
     store_transposed_out(out + 2 * A, dvt, h, 1.0f);
   }
+  if (colsum) {
+    float* cs = colsum + ((long)b * nkb + kb) * ld + hd * DH;
+    block_column_sums(dkt, 0.125f, key < S, cs_red, cs + A, wave, lane);
+    block_column_sums(dvt, 1.0f, key < S, cs_red, cs + 2 * A, wave, lane);
+  }
   }
 }
 
@@ -527,8 +573,11 @@ dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, in
   return DIPACO_OK;
 }
 
+size_t attention_colsum_partial_floats(int B, int S, int H) { return (size_t)B * ((S + 127) / 128) * 3 * H * DH; }
+
 dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf16* d_o, const float* lse, bf16* dqkv,
-                                        float* dsum, int B, int S, int H, hipStream_t s) {
+                                        float* dsum, float* colsum_out, float* colsum_partial, int B, int S, int H,
+                                        hipStream_t s) {
   const int single = g_attn_single_block;
   const int nqb = (S + 127) / 128;
   dim3 grid = single ? dim3(B * H, nqb) : dim3((nqb + 1) / 2, B * H);   // one or two query (key) blocks per workgroup
@@ -540,10 +589,11 @@ dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf
                                    hipFuncAttributeMaxDynamicSharedMemorySize, DKV_STAGES * DKV_STAGE));
     attr_set = true;
   }
-  attn_bwd_dq_mfma<<<grid, AT_THREADS, DQ_STAGES * 2 * TILE_BYTES, s>>>(qkv, o, d_o, lse, dqkv, dsum, S, H, single);
+  attn_bwd_dq_mfma<<<grid, AT_THREADS, DQ_STAGES * 2 * TILE_BYTES, s>>>(qkv, o, d_o, lse, dqkv, dsum, colsum_out ? colsum_partial : nullptr, S, H, single);
   DIPACO_LAUNCH_CHECK();
-  attn_bwd_dkv_mfma<<<grid, AT_THREADS, DKV_STAGES * DKV_STAGE, s>>>(qkv, d_o, dsum, dqkv, S, H, single);
+  attn_bwd_dkv_mfma<<<grid, AT_THREADS, DKV_STAGES * DKV_STAGE, s>>>(qkv, d_o, dsum, dqkv, colsum_out ? colsum_partial : nullptr, S, H, single);
   DIPACO_LAUNCH_CHECK();
+  if (colsum_out) return launch_sum_rows(colsum_partial, colsum_out, B * nqb, 3 * H * DH, s);
   return DIPACO_OK;
 }
 

@@ -172,15 +172,23 @@ size_t embed_bwd_scratch_ints(int rows, int vocab);
 // qkv: [B*S, 3A] (q | k | v, head h at columns h*dh), o: [B*S, A], lse: [B, H, S] fp32.
 template <typename T>
 dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S, int H, int dh, hipStream_t s);
-// dqkv: [B*S, 3A];  dscratch: fp32 scratch of 2 * B * H * roundup(S, 128) floats (per-query statistics)
+// dqkv: [B*S, 3A];  dscratch: fp32 scratch of 2 * B * H * roundup(S, 128) floats (per-query statistics);
+// colsum_out (nullable): fp32 [3A] = column sums of dqkv in a fixed order, with colsum_partial =
+// attention_bwd_colsum_floats(B, S, H, dh) floats of scratch
 template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv,
-                                   float* dscratch, int B, int S, int H, int dh, hipStream_t s);
+                                   float* dscratch, float* colsum_out, float* colsum_partial, int B, int S, int H,
+                                   int dh, hipStream_t s);
+size_t attention_bwd_colsum_floats(int B, int S, int H, int dh);
 
 // ---- attention_mfma.hip: bf16, head size 64, matrix cores ---------------------------------------------
 dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, int B, int S, int H, hipStream_t s);
+// colsum_out (nullable): fp32 [3 H 64], the column sums of dqkv (the bias gradient of the QKV projection), from the
+// kernels' epilogues; colsum_partial: attention_colsum_partial_floats(B, S, H) floats of scratch
 dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf16* d_o, const float* lse, bf16* dqkv,
-                                        float* dsum, int B, int S, int H, hipStream_t s);
+                                        float* dsum, float* colsum_out, float* colsum_partial, int B, int S, int H,
+                                        hipStream_t s);
+size_t attention_colsum_partial_floats(int B, int S, int H);
 // 0: a workgroup takes a long and a short block of the causal triangle; 1: one block per workgroup, longest first
 void set_attention_single_block(int on);
 

@@ -179,7 +179,10 @@ def test_attention_forward_backward(dtype, B, S, H, dh, attn_blocks):
     assert np.abs(host(lse) - lse_ref).max() <= (1e-5 if dtype == dp.F32 else 2e-2)
     dqkv = torch.empty_like(qkv)
     dsum = torch.empty(2 * B * H * ((S + 127) // 128 * 128), dtype=torch.float32, device=DEV)
-    dp.dipaco_k_attention_bwd(dtype, qkv, o, d_o, lse, dqkv, dsum, B, S, H, dh)
+    cs = torch.full((3 * A,), 55.0, dtype=torch.float32, device=DEV)
+    cs_scratch = torch.full((max((B * S + 255) // 256, B * ((S + 127) // 128)) * 3 * A,), float("nan"),
+                            dtype=torch.float32, device=DEV)
+    dp.dipaco_k_attention_bwd(dtype, qkv, o, d_o, lse, dqkv, dsum, B, S, H, dh, colsum_out=cs, colsum_scratch=cs_scratch)
     ref = np.empty((B * S, 3 * A))
     for b in range(B):
         x = qr[b * S:(b + 1) * S]
@@ -188,3 +191,9 @@ def test_attention_forward_backward(dtype, B, S, H, dh, attn_blocks):
     got = host(dqkv)
     for name, sl in (("dq", slice(0, A)), ("dk", slice(A, 2 * A)), ("dv", slice(2 * A, 3 * A))):
         assert rel_l2(got[:, sl], ref[:, sl]) <= (2e-5 if dtype == dp.F32 else 2e-2), name
+    # column sums of dqkv (the QKV bias gradient), taken in the kernels' epilogues where the matrix-core path runs
+    scale = np.abs(ref).sum(0).max()
+    assert np.abs(host(cs) - ref.sum(0)).max() <= (1e-5 if dtype == dp.F32 else 1e-2) * scale
+    dqkv2 = torch.empty_like(qkv)
+    dp.dipaco_k_attention_bwd(dtype, qkv, o, d_o, lse, dqkv2, dsum, B, S, H, dh)            # without the sums
+    assert torch.equal(dqkv2, dqkv)
