@@ -171,29 +171,35 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
   for (int c = threadIdx.x; c < 3 * d; c += ROW_THREADS) out[c] = cols[c];
 }
 
-// out[c] = sum over p of partial[p * stride + c].  64 columns x 4 partial phases per workgroup: phase y adds
-// partials y, y+4, ... in order, then the four phase sums are added in phase order (a fixed tree).
+// out[c] = sum over p of partial[p * stride + c].  32 columns x 32 partial phases per workgroup: phase y adds
+// partials y, y+32, ... in order (four loads in flight), then the phase sums are added in phase order (a fixed tree).
 // Column c goes to out0 / out1 / out2 by c / d (a null output is skipped).
-__global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restrict__ partial, float* __restrict__ out0,
-                                                           float* __restrict__ out1, float* __restrict__ out2,
-                                                           int n_partials, int stride, int d) {
-  __shared__ float red[4][64];
-  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + x;
+constexpr int SP_COLS = 32, SP_PHASES = 32;
+__global__ void __launch_bounds__(SP_COLS * SP_PHASES) sum_partials_kernel(const float* __restrict__ partial,
+                                                                           float* __restrict__ out0,
+                                                                           float* __restrict__ out1,
+                                                                           float* __restrict__ out2, int n_partials,
+                                                                           int stride, int d) {
+  __shared__ float red[SP_PHASES][SP_COLS + 1];
+  const int x = threadIdx.x % SP_COLS, y = threadIdx.x / SP_COLS;
+  const int c = blockIdx.x * SP_COLS + x;
   float s = 0.f;
   if (c < stride) {
     int p = y;
-    for (; p + 12 < n_partials; p += 16) {   // four independent loads in flight
-      const float a0 = partial[(size_t)p * stride + c], a1 = partial[(size_t)(p + 4) * stride + c];
-      const float a2 = partial[(size_t)(p + 8) * stride + c], a3 = partial[(size_t)(p + 12) * stride + c];
+    for (; p + 3 * SP_PHASES < n_partials; p += 4 * SP_PHASES) {
+      const float a0 = partial[(size_t)p * stride + c], a1 = partial[(size_t)(p + SP_PHASES) * stride + c];
+      const float a2 = partial[(size_t)(p + 2 * SP_PHASES) * stride + c];
+      const float a3 = partial[(size_t)(p + 3 * SP_PHASES) * stride + c];
       s += a0; s += a1; s += a2; s += a3;
     }
-    for (; p < n_partials; p += 4) s += partial[(size_t)p * stride + c];
+    for (; p < n_partials; p += SP_PHASES) s += partial[(size_t)p * stride + c];
   }
   red[y][x] = s;
   __syncthreads();
   if (y == 0 && c < stride) {
-    const float t = ((red[0][x] + red[1][x]) + red[2][x]) + red[3][x];
+    float t = red[0][x];
+#pragma unroll
+    for (int q = 1; q < SP_PHASES; ++q) t += red[q][x];
     if (c < d) out0[c] = t;
     else if (c < 2 * d) out1[c - d] = t;
     else if (out2) out2[c - 2 * d] = t;
@@ -518,7 +524,7 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
   DIPACO_LAUNCH_CHECK();
   const int blocks = n_blocks;
   const int ncols = dcol ? 3 * d : 2 * d;
-  sum_partials_kernel<<<(ncols + 63) / 64, 256, 0, s>>>(partial, dg, db, dcol, blocks, 3 * d, d);
+  sum_partials_kernel<<<(ncols + SP_COLS - 1) / SP_COLS, SP_COLS * SP_PHASES, 0, s>>>(partial, dg, db, dcol, blocks, 3 * d, d);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -532,13 +538,13 @@ dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, in
   dim3 grid((cols + WAVE * VEC - 1) / (WAVE * VEC), chunks);
   colsum_kernel<T><<<grid, ROW_THREADS, 0, s>>>(x, partial, rows, cols);
   DIPACO_LAUNCH_CHECK();
-  sum_partials_kernel<<<(cols + 63) / 64, 256, 0, s>>>(partial, out, out, nullptr, chunks, cols, cols);
+  sum_partials_kernel<<<(cols + SP_COLS - 1) / SP_COLS, SP_COLS * SP_PHASES, 0, s>>>(partial, out, out, nullptr, chunks, cols, cols);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
 
 dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s) {
-  sum_partials_kernel<<<(cols + 63) / 64, 256, 0, s>>>(partial, out, out, nullptr, n_partials, cols, cols);
+  sum_partials_kernel<<<(cols + SP_COLS - 1) / SP_COLS, SP_COLS * SP_PHASES, 0, s>>>(partial, out, out, nullptr, n_partials, cols, cols);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
