@@ -110,15 +110,31 @@ template <> __device__ __forceinline__ float gelu_grad_t<bf16>(float u) {
 }
 
 // ---- wave / block reductions -----------------------------------------------------------------------
+// Wave reductions on the DPP lanes of the vector ALU (no LDS traffic): quad swaps, mirrors within rows of 16, then
+// the last lane of a row broadcast into the next rows; lane 63 ends up with the result, which is then read out as
+// a wave-uniform value.  The order of the additions is fixed.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_fetch(float v, float identity) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity),
+                                                               __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+  v += dpp_fetch<0xb1, 0xf>(v, 0.f);    // quad_perm [1,0,3,2]
+  v += dpp_fetch<0x4e, 0xf>(v, 0.f);    // quad_perm [2,3,0,1]
+  v += dpp_fetch<0x141, 0xf>(v, 0.f);   // row_half_mirror
+  v += dpp_fetch<0x140, 0xf>(v, 0.f);   // row_mirror: every lane holds the sum of its row of 16
+  v += dpp_fetch<0x142, 0xa>(v, 0.f);   // row_bcast15 into rows 1 and 3
+  v += dpp_fetch<0x143, 0xc>(v, 0.f);   // row_bcast31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-  return v;
+  const float lowest = -INFINITY;
+  v = fmaxf(v, dpp_fetch<0xb1, 0xf>(v, lowest));
+  v = fmaxf(v, dpp_fetch<0x4e, 0xf>(v, lowest));
+  v = fmaxf(v, dpp_fetch<0x141, 0xf>(v, lowest));
+  v = fmaxf(v, dpp_fetch<0x140, 0xf>(v, lowest));
+  v = fmaxf(v, dpp_fetch<0x142, 0xa>(v, lowest));
+  v = fmaxf(v, dpp_fetch<0x143, 0xc>(v, lowest));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 }  // namespace dipaco
