@@ -1,6 +1,7 @@
 // Pieces shared by the matrix-core GEMM kernels: the kernel argument block, the workgroup -> tile mapping and
 // the epilogue that turns a wave's accumulators into 16-byte row-contiguous stores.
 #pragma once
+#include <type_traits>
 #include "common.h"
 #include "mma_tile.h"
 
@@ -113,6 +114,13 @@ template <typename T> __device__ __forceinline__ void raw8_unpack(const Raw8<T>&
 template <typename T, typename TC, int TM, int TN, int WN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0, int col0,
                                               int split, const GemmDev& g) {
+  // The argument block lives in kernel-argument memory: every field the loops below use is read once, here, so
+  // that no scalar load (and the wait for it, which also stalls the LDS traffic) is left inside them.
+  const int gM = g.M, gN = g.N, g_act = g.act;
+  const long g_ldc = g.ldc;
+  TC* const gC = static_cast<TC*>(g.C);
+  float* const g_cs = g.colsum_partial;
+
   constexpr int LDW = WN + 4;
   const int col_l = lane & 31;
   constexpr int GROUPS = WN / 8;                 // 8-column groups per row
@@ -122,8 +130,8 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
   const T* aux_in = static_cast<const T*>(g.aux_in);
   T* aux_out = static_cast<T*>(g.aux_out);
   const bool to_partial = g.splits > 1;
-  float* P = to_partial ? g.partial + (size_t)split * g.M * g.N : nullptr;
-  const bool want_aux = g.act == 2 || g.act == 4;
+  float* P = to_partial ? g.partial + (size_t)split * gM * gN : nullptr;
+  const bool want_aux = g_act == 2 || g_act == 4;
   // one operand stream is requested ahead: the saved operand if there is one, else the residual (a product that
   // takes both loads its residual where it is used)
   const T* ahead = want_aux ? aux_in : resid;
@@ -135,7 +143,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
     for (int it = 0; it < ITERS; ++it) {
       const int item = lane + WAVE * it;
       const int row = row0 + 32 * i + item / GROUPS, col = col0 + 8 * (item % GROUPS);
-      if (ahead && row < g.M && col < g.N) rin[i & 1][it] = raw8_load(ahead + (size_t)row * g.ldc + col);
+      if (ahead && row < gM && col < gN) rin[i & 1][it] = raw8_load(ahead + (size_t)row * g_ldc + col);
     }
   };
   prefetch(0);
@@ -159,24 +167,24 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
       const float4 lo = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg);
       const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
       float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      if (row >= g.M || col >= g.N) continue;
+      if (row >= gM || col >= gN) continue;
       if (to_partial) {
-        OutVec<float>::store(P + (size_t)row * g.N + col, v);
+        OutVec<float>::store(P + (size_t)row * gN + col, v);
         continue;
       }
-      const size_t off = (size_t)row * g.ldc + col;
+      const size_t off = (size_t)row * g_ldc + col;
       if (bias) {
         float b[8];
         OutVec<T>::load(bias + col, b);
 #pragma unroll
         for (int c = 0; c < 8; ++c) v[c] += b[c];
       }
-      if (g.act == 1) {
+      if (g_act == 1) {
         // the saved pre-activation is what backward differentiates at: GELU is applied to the stored value
         OutVec<T>::store(aux_out + off, v);
 #pragma unroll
         for (int c = 0; c < 8; ++c) v[c] = gelu_t<T>(to_f32(from_f32<T>(v[c])));
-      } else if (g.act == 3) {
+      } else if (g_act == 3) {
         float dv[8];
 #pragma unroll
         for (int c = 0; c < 8; ++c) v[c] = gelu_with_grad_t<T>(v[c], dv[c]);
@@ -185,7 +193,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
         float u[8];
         raw8_unpack(rin[i & 1][it], u);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] *= g.act == 2 ? gelu_grad_t<T>(u[c]) : u[c];
+        for (int c = 0; c < 8; ++c) v[c] *= g_act == 2 ? gelu_grad_t<T>(u[c]) : u[c];
       }
       if (resid) {
         float rv[8];
@@ -193,23 +201,154 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
 #pragma unroll
         for (int c = 0; c < 8; ++c) v[c] += rv[c];
       }
-      OutVec<TC>::store(static_cast<TC*>(g.C) + off, v);
-      if (g.colsum_partial) {
+      OutVec<TC>::store(gC + off, v);
+      if (g_cs) {
 #pragma unroll
         for (int c = 0; c < 8; ++c) cs[c] += v[c];
       }
     }
   }
-  if (g.colsum_partial && !to_partial) {
+  if (g_cs && !to_partial) {
     // lanes l, l + GROUPS, ... hold the same columns: fixed butterfly, then one row of partial sums per wave
 #pragma unroll
     for (int m = GROUPS; m < WAVE; m <<= 1)
 #pragma unroll
       for (int c = 0; c < 8; ++c) cs[c] += __shfl_xor(cs[c], m, WAVE);
     const int col = col0 + 8 * lane;
-    if (lane < GROUPS && col < g.N && row0 < g.M)
-      OutVec<float>::store(g.colsum_partial + (size_t)(row0 / (32 * TM)) * g.N + col, cs);
+    if (lane < GROUPS && col < gN && row0 < gM)
+      OutVec<float>::store(g_cs + (size_t)(row0 / (32 * TM)) * gN + col, cs);
   }
+}
+
+// The same epilogue with everything that does not depend on the data fixed at compile time -- the activation, which
+// of bias / residual / column sums / split-K partial output are present -- for the bf16 direct-to-LDS kernel.  The
+// general function above decides all of that per 16-byte item with wave-uniform branches; a wave spends about 2000
+// instruction issues there (7 us of a 32 us tile at two waves per SIMD).  Here an item is straight-line code: the
+// bias vector is loaded once (a lane keeps its eight columns over all items), addresses advance by constants, and
+// the operand prefetch is fenced so that the conversion of the loaded values is not scheduled next to the load.
+template <typename TC, int TM, int TN, int WN, int ACT, bool BIAS, bool RESID, bool CS, bool PARTIAL>
+__device__ __forceinline__ void gemm_epilogue_fixed(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0,
+                                                    int col0, int split, const GemmDev& g) {
+  using T = bf16;
+  constexpr int LDW = WN + 4;
+  constexpr int GROUPS = WN / 8;
+  constexpr int ITERS = 32 * GROUPS / WAVE;
+  constexpr int ROWS_PER_IT = WAVE / GROUPS;
+  constexpr bool AUX_IN = ACT == 2 || ACT == 4, AUX_OUT = ACT == 1 || ACT == 3;
+  static_assert(WAVE % GROUPS == 0, "a lane keeps its column group over the items");
+  static_assert(!PARTIAL || (ACT == 0 && !BIAS && !RESID && !CS), "split-K partial planes take no epilogue");
+  const int gM = g.M, gN = g.N;
+  const long ld = PARTIAL ? (long)gN : g.ldc;
+  const int col_l = lane & 31;
+  const int rr0 = lane / GROUPS, cg = lane % GROUPS;
+  const int col = col0 + 8 * cg;
+  const bool col_ok = col < gN;
+  const long off0 = (long)(row0 + rr0) * ld + col;                      // element offset of this lane's first item
+  using TO = typename std::conditional<PARTIAL, float, TC>::type;
+  TO* const out = PARTIAL ? reinterpret_cast<TO*>(g.partial + (size_t)split * gM * gN) : static_cast<TO*>(g.C);
+  const T* const ahead = AUX_IN ? static_cast<const T*>(g.aux_in) : static_cast<const T*>(g.resid);
+  constexpr bool AHEAD = AUX_IN || RESID;
+  constexpr bool RESID_LATE = AUX_IN && RESID;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (BIAS && col_ok) OutVec<T>::load(static_cast<const T*>(g.bias) + col, bv);
+  Raw8<T> rin[2][ITERS];
+  auto prefetch = [&](int i) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int row = row0 + 32 * i + ROWS_PER_IT * it + rr0;
+      if (row < gM && col_ok) rin[i & 1][it] = raw8_load(ahead + off0 + (long)(32 * i + ROWS_PER_IT * it) * ld);
+    }
+  };
+  if (AHEAD) prefetch(0);
+  float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    if (AHEAD && i + 1 < TM) prefetch(i + 1);
+    __builtin_amdgcn_sched_barrier(0);   // the loads above are issued here; what uses them stays below
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int rr = ROWS_PER_IT * it + rr0;
+      const int row = row0 + 32 * i + rr;
+      const float4 lo = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg);
+      const float4 hi = *reinterpret_cast<const float4*>(stg + rr * LDW + 8 * cg + 4);
+      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      const long off = off0 + (long)(32 * i + ROWS_PER_IT * it) * ld;
+      if (row < gM && col_ok) {
+        if (BIAS) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] += bv[c];
+        }
+        if (ACT == 1) {
+          OutVec<T>::store(static_cast<T*>(g.aux_out) + off, v);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] = gelu_t<T>(to_f32(from_f32<T>(v[c])));
+        } else if (ACT == 3) {
+          float dv[8];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] = gelu_with_grad_t<T>(v[c], dv[c]);
+          OutVec<T>::store(static_cast<T*>(g.aux_out) + off, dv);
+        } else if (AUX_IN) {
+          float u[8];
+          raw8_unpack(rin[i & 1][it], u);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] *= ACT == 2 ? gelu_grad_t<T>(u[c]) : u[c];
+        }
+        if (RESID) {
+          float rv[8];
+          raw8_unpack(RESID_LATE ? raw8_load(static_cast<const T*>(g.resid) + off) : rin[i & 1][it], rv);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] += rv[c];
+        }
+        OutVec<TO>::store(out + off, v);
+        if (CS) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) cs[c] += v[c];
+        }
+      }
+    }
+  }
+  if (CS) {
+#pragma unroll
+    for (int m = GROUPS; m < WAVE; m <<= 1)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) cs[c] += __shfl_xor(cs[c], m, WAVE);
+    if (lane < GROUPS && col_ok && row0 < gM)
+      OutVec<float>::store(g.colsum_partial + (size_t)(row0 / (32 * TM)) * gN + col, cs);
+  }
+  (void)AUX_OUT;
+}
+
+// Picks the fixed epilogue for the combinations the training step uses; everything else takes the general one.
+template <typename TC, int TM, int TN, int WN>
+__device__ __forceinline__ void gemm_epilogue_dispatch(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0,
+                                                       int col0, int split, const GemmDev& g) {
+  const bool bias = g.bias != nullptr, resid = g.resid != nullptr, cs = g.colsum_partial != nullptr;
+  const int act = g.act;
+#define DIPACO_EPI(ACT, B, R, C, P) \
+  gemm_epilogue_fixed<TC, TM, TN, WN, ACT, B, R, C, P>(acc, stg, lane, row0, col0, split, g)
+  // (fp32 outputs -- weight gradients and their split-K planes, one round of tiles per launch -- keep the general
+  // function: the accumulators of the oblong tiles leave no registers for a second copy of the code's temporaries)
+  if constexpr (std::is_same<TC, bf16>::value) {
+    if (act == 0 && !cs) {
+      if (!bias && !resid) { DIPACO_EPI(0, false, false, false, false); return; }
+      if (bias && !resid) { DIPACO_EPI(0, true, false, false, false); return; }
+      if (bias && resid) { DIPACO_EPI(0, true, true, false, false); return; }
+    }
+    if (act == 3 && bias && !resid && !cs) { DIPACO_EPI(3, true, false, false, false); return; }
+    if (act == 4 && !bias && !resid) {
+      if (cs) { DIPACO_EPI(4, false, false, true, false); return; }
+      DIPACO_EPI(4, false, false, false, false);
+      return;
+    }
+  }
+#undef DIPACO_EPI
+  gemm_epilogue<bf16, TC, TM, TN, WN>(acc, stg, lane, row0, col0, split, g);
 }
 
 }  // namespace dipaco

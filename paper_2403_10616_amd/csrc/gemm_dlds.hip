@@ -243,8 +243,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
   // every load has landed (the last steps waited for vmcnt 0); all waves are done with the ring before it is reused
   wait_vmcnt<0>();
   __syncthreads();
-  if (active) gemm_epilogue<bf16, TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4)), lane,
-                                      m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
+  if (active) gemm_epilogue_dispatch<TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4)), lane,
+                                                     m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
 }
 
 // ---- uneven split-K ----------------------------------------------------------------------------------------
