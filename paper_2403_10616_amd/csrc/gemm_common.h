@@ -23,6 +23,10 @@ struct GemmDev {
   // step is cut into fewer K slices, so that all workgroups of the launch end together.  Class c owns workgroup
   // ids [cls_base[c], cls_base[c + 1]), slice-major; full_m / full_n = tile rows / columns of the first class.
   int uneven = 0;
+  // tile mapping without run-time divisions (filled by the host when the sizes allow, see gemm_fast_map):
+  // tiles per XCD and their remainder, and ceil(2^32 / (8 tiles_n))
+  int fast_map = 0, xcd_per = 0, xcd_rem = 0;
+  unsigned group_mul = 0;
   int cls_s[4];
   int cls_base[5];
   int full_m, full_n;
@@ -66,6 +70,35 @@ __device__ __forceinline__ void gemm_tile_of_block(const GemmDev& g, int bid, in
   const int in_group = bid - gidx * per_group;
   tile_m = first_m + in_group % gsize;
   tile_n = in_group / gsize;
+}
+
+// The same mapping for one K range per tile (splits == 1), with the divisions done on the host: a workgroup issues
+// its first loads some hundred instructions earlier.  Valid when g.fast_map is set.
+__device__ __forceinline__ void gemm_tile_of_block_fast(const GemmDev& g, int bid, int& tile_m, int& tile_n) {
+  const int x = bid & (N_XCD - 1), i = bid >> 3;
+  const int vt = x * g.xcd_per + min(x, g.xcd_rem) + i;
+  const int per_group = 8 * g.tiles_n;
+  const int gidx = (int)__umulhi((unsigned)vt, g.group_mul);   // vt / per_group, exact for vt * per_group < 2^32
+  const int first_m = gidx * 8;
+  const int in_group = vt - gidx * per_group;
+  const int gsize = g.tiles_m - first_m;
+  if (gsize >= 8) {
+    tile_m = first_m + (in_group & 7);
+    tile_n = in_group >> 3;
+  } else {   // the last, shorter group of tile rows
+    tile_m = first_m + in_group % gsize;
+    tile_n = in_group / gsize;
+  }
+}
+// host side of the above
+inline void gemm_fast_map(GemmDev& g) {
+  static_assert(N_XCD == 8, "the fast mapping is written for 8 XCDs");
+  const long tiles = (long)g.tiles_m * g.tiles_n, per_group = 8L * g.tiles_n;
+  g.fast_map = g.splits == 1 && !g.uneven && tiles * per_group < (1L << 32) && per_group > 1;
+  if (!g.fast_map) return;
+  g.xcd_per = (int)(tiles / N_XCD);
+  g.xcd_rem = (int)(tiles % N_XCD);
+  g.group_mul = (unsigned)(((1ULL << 32) + per_group - 1) / per_group);
 }
 
 // XCD x gets the contiguous range [x * per, ...) of `total` work items

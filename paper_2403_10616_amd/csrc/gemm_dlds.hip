@@ -81,6 +81,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
     const int kt0 = (int)(split * ktiles / nsplit), kt1 = (int)((split + 1) * ktiles / nsplit);
     k_begin = kt0 * DL_BK;
     nkt = kt1 - kt0;
+  } else if (g.fast_map) {
+    gemm_tile_of_block_fast(g, blockIdx.x, tile_m, tile_n);
+    split = 0;
+    k_begin = 0;
+    nkt = g.K / DL_BK;
   } else {
     gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
     k_begin = split * g.k_per_split;
@@ -335,6 +340,7 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   const long blocks = (long)g.tiles_m * g.tiles_n * g.splits;
   if (blocks > 0x7fffffffL) return fail(DIPACO_ESHAPE, "gemm: too many tiles");
   g.colsum_partial = a.colsum ? a.colsum_partial : nullptr;
+  gemm_fast_map(g);
   kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
