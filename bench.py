@@ -122,7 +122,7 @@ def bench_path_step(args):
     final_loss = float(loss.item())
 
     # ---- roofline of the dominant kernel: the forward-layout bf16 GEMM (projections, MLP, vocabulary head) ----
-    # Its 49 launches of one step are replayed with the step's own epilogues (bias, GELU + saved pre-activation,
+    # Its 49 launches of one step are replayed with the step's own epilogues (bias, GELU + saved GELU',
     # residual) on scratch operands and timed with events on the stream they are launched on.
     fwd, dx, dw = step_gemm_shapes(cfg, B, S)
     T = B * S
@@ -133,7 +133,7 @@ def bench_path_step(args):
     r_buf = torch.empty(T * cfg["d_mlp"], dtype=torch.bfloat16, device=dev).normal_()
     u_buf = torch.empty(T * cfg["d_mlp"], dtype=torch.bfloat16, device=dev)
     bias = torch.zeros(max(N for M, N, K in fwd), dtype=torch.bfloat16, device=dev)
-    epilogues = [dict(bias=bias), dict(bias=bias, resid=r_buf), dict(bias=bias, aux_out=u_buf, act=1),
+    epilogues = [dict(bias=bias), dict(bias=bias, resid=r_buf), dict(bias=bias, aux_out=u_buf, act=3),
                  dict(bias=bias, resid=r_buf)] * n_layers + [dict()]
 
     def replay():
