@@ -337,8 +337,8 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& a, hipStream_t s
   if ((a.act == 1 || a.act == 3) && !a.aux_out) return fail(DIPACO_EINVAL, "gemm: act 1 / 3 need aux_out");
   if ((a.act == 2 || a.act == 4) && !a.aux_in) return fail(DIPACO_EINVAL, "gemm: act 2 / 4 need aux_in");
   if (a.out_f32 && (a.bias || a.resid || a.act)) return fail(DIPACO_EINVAL, "gemm: fp32 output takes no epilogue");
-  if (a.colsum && (!a.colsum_partial || a.splits > 1 || !aligned16(a.colsum_partial)))
-    return fail(DIPACO_EINVAL, "gemm: column sums need their scratch and no split-K");
+  if (a.colsum && (!a.colsum_partial || a.splits > 1 || a.out_f32 || !aligned16(a.colsum_partial)))
+    return fail(DIPACO_EINVAL, "gemm: column sums need their scratch, no split-K and an output of the operands' type");
   if (a.splits > 1 && (!a.out_f32 || a.bias || a.resid || a.act || !a.partial))
     return fail(DIPACO_EINVAL, "gemm: split-K needs fp32 output, a partial buffer and no epilogue");
   if constexpr (std::is_same<T, bf16>::value) {

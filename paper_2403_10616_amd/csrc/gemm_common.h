@@ -365,8 +365,13 @@ __device__ __forceinline__ void gemm_epilogue_dispatch(const f32x16 (&acc)[TM][T
   const int act = g.act;
 #define DIPACO_EPI(ACT, B, R, C, P) \
   gemm_epilogue_fixed<TC, TM, TN, WN, ACT, B, R, C, P>(acc, stg, lane, row0, col0, split, g)
-  // (fp32 outputs -- weight gradients and their split-K planes, one round of tiles per launch -- keep the general
-  // function: the accumulators of the oblong tiles leave no registers for a second copy of the code's temporaries)
+  if constexpr (std::is_same<TC, float>::value) {
+    // fp32 outputs (weight gradients) take no bias / activation / residual (checked on the host): a split-K plane or
+    // C itself, nothing else, so the general function is not instantiated for them at all
+    if (g.splits > 1) DIPACO_EPI(0, false, false, false, true);
+    else DIPACO_EPI(0, false, false, false, false);
+    return;
+  }
   if constexpr (std::is_same<TC, bf16>::value) {
     if (act == 0 && !cs) {
       if (!bias && !resid) { DIPACO_EPI(0, false, false, false, false); return; }
@@ -381,7 +386,7 @@ __device__ __forceinline__ void gemm_epilogue_dispatch(const f32x16 (&acc)[TM][T
     }
   }
 #undef DIPACO_EPI
-  gemm_epilogue<bf16, TC, TM, TN, WN>(acc, stg, lane, row0, col0, split, g);
+  if constexpr (std::is_same<TC, bf16>::value) gemm_epilogue<bf16, TC, TM, TN, WN>(acc, stg, lane, row0, col0, split, g);
 }
 
 }  // namespace dipaco
