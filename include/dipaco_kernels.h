@@ -46,6 +46,14 @@ dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans
  * For tests (every tile shape must give the same parity) and tuning. */
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 
+/* Host-only (no GPU needed): the uneven split-K plan that the weight gradient C[M, N] = X^T dY with K = tokens is
+ * launched with when at most max_slices K slices are allowed (dipaco_k_gemm with trans_a = 1, out_f32 = 1, bf16).
+ * out (host int32 [12]): tile height and width of the shape taken (0, 0 when there is no such plan and the launch
+ * cuts K into equal slices); tile rows / columns of the class of tiles inside C; tiles per class; K slices per class.
+ * Classes: inside C, over its last rows, over its last columns, over both.  One workgroup per (tile, slice): their
+ * total never exceeds the 256 compute units. */
+dipaco_status dipaco_k_gemm_split_plan(int32_t M, int32_t N, int32_t K, int32_t max_slices, int32_t* out);
+
 /* How the bf16 attention kernels deal the blocks of the causal triangle to workgroups, for every later call in this
  * process (tuning and tests): 0 = a long and a short block per workgroup, 1 = one block per workgroup, launched
  * longest first.  Results are identical. */

@@ -90,6 +90,7 @@ _SIGS = {
     "dipaco_k_gemm": (C.c_int, [C.c_int32] * 7 + [C.c_void_p] * 7 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dipaco_k_gemm_colsum": (C.c_int, [C.c_int32] * 6 + [C.c_void_p] * 7 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dipaco_k_set_gemm_tile": (C.c_int, [C.c_int32]),
+    "dipaco_k_gemm_split_plan": (C.c_int, [C.c_int32] * 4 + [C.POINTER(C.c_int32)]),
     "dipaco_k_set_attention_blocks": (C.c_int, [C.c_int32]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]),
@@ -392,6 +393,13 @@ def dipaco_k_gemm_colsum(dtype: int, trans_a: bool, trans_b: bool, M: int, N: in
 
 def dipaco_k_set_gemm_tile(tile: int):
     _check(load().dipaco_k_set_gemm_tile(tile))
+
+
+def dipaco_k_gemm_split_plan(M: int, N: int, K: int, max_slices: int) -> dict:
+    out = (C.c_int32 * 12)()
+    _check(load().dipaco_k_gemm_split_plan(M, N, K, max_slices, out))
+    v = list(out)
+    return {"tile": (v[0], v[1]), "inside": (v[2], v[3]), "tiles": v[4:8], "slices": v[8:12]}
 
 
 def dipaco_k_set_attention_blocks(single_block: int):

@@ -862,6 +862,12 @@ dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
   return DIPACO_OK;
 }
 
+dipaco_status dipaco_k_gemm_split_plan(int32_t M, int32_t N, int32_t K, int32_t max_slices, int32_t* out) {
+  if (!out || M < 1 || N < 1 || K < 32 || K % 32) return fail(DIPACO_EINVAL, "dipaco_k_gemm_split_plan: bad argument");
+  gemm_dlds_plan_info(M, N, K, max_slices, out);
+  return DIPACO_OK;
+}
+
 dipaco_status dipaco_k_set_attention_blocks(int32_t single_block) {
   if (single_block != 0 && single_block != 1) return fail(DIPACO_EINVAL, "dipaco_k_set_attention_blocks: 0 or 1");
   set_attention_single_block(single_block);

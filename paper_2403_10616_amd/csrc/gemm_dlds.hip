@@ -413,6 +413,25 @@ int gemm_dlds_plan_slices(int M, int N, int K, int max_slices, bool any_shape) {
   return g_dlds_shape == 2 ? narrow : square;
 }
 
+// Host-only view of the split-K plan a weight gradient X^T dY of these sizes would be launched with, for tests:
+// out[0] = tile rows, out[1] = tile columns of the shape taken (0, 0: no uneven plan, the launch uses equal slices);
+// out[2], out[3] = tile rows / columns of the class "inside C"; out[4..7] = tiles per class; out[8..11] = K slices
+// per class (classes: inside C, over its last rows, over its last columns, over both).
+void gemm_dlds_plan_info(int M, int N, int K, int max_slices, int* out) {
+  GemmArgs a{};
+  a.M = M; a.N = N; a.K = K; a.splits = max_slices;
+  const int oblong = oblong_plan_wins(a);
+  const int BM = oblong == 1 ? 128 : oblong == 2 ? 512 : 256;
+  const int BN = oblong == 1 ? 512 : oblong == 2 ? 128 : (g_dlds_shape == 2 ? 128 : 256);
+  const int WGM = oblong == 1 ? 1 : oblong == 2 ? 4 : 2;
+  const int WGN = oblong == 1 ? 8 : oblong == 2 ? 2 : (g_dlds_shape == 2 ? 2 : 4);
+  UnevenPlan up;
+  for (int i = 0; i < 12; ++i) out[i] = 0;
+  if (max_slices <= 1 || !plan_uneven(M, N, K, BM, BN, WGM, WGN, max_slices, up)) return;
+  out[0] = BM; out[1] = BN; out[2] = up.full_m; out[3] = up.full_n;
+  for (int c = 0; c < 4; ++c) { out[4 + c] = up.n[c]; out[8 + c] = up.s[c]; }
+}
+
 dipaco_status launch_gemm_dlds(const GemmArgs& a, hipStream_t s) {
   if (!gemm_dlds_eligible(a)) return fail(DIPACO_EUNSUPPORTED, "gemm: shape not supported by the direct-to-LDS kernel");
   if (a.out_f32) return run_dlds_shape<float, false, false>(a, s);

@@ -125,6 +125,7 @@ dipaco_status launch_splitk_reduce_classes(const float* partial, float* C, int M
 // direct-to-LDS kernel: slices of a full tile in its uneven split-K plan with at most max_slices, 0 if it has none
 // (for the tile shape in force, or the larger count over both shapes)
 int gemm_dlds_plan_slices(int M, int N, int K, int max_slices, bool any_shape);
+void gemm_dlds_plan_info(int M, int N, int K, int max_slices, int* out);   // host-only, for tests: see gemm_dlds.hip
 constexpr int GEMM_SLICE_CAP = 32;
 // split count the weight-gradient products are launched with
 int gemm_plan_splits(int M, int N, int K, bool bf16_operands);

@@ -126,3 +126,40 @@ def test_outer_table_pack_is_host_only_and_validates():
 
 class _NoStream:
     cuda_stream = 0
+
+
+@pytest.mark.parametrize("M,N", [(896, 3584), (3584, 896), (896, 2688), (896, 896), (256, 256), (300, 200), (8, 776),
+                                 (1024, 4096), (136, 64), (896, 32000)])
+def test_uneven_split_plan_is_consistent(M, N):
+    """Host logic of the weight-gradient launch: the plan's classes cover every tile of C once, no class gets more
+    slices than allowed or than the class inside C, and one workgroup per (tile, slice) fits the 256 compute units."""
+    K, cap = 32768, 32
+    p = dp.dipaco_k_gemm_split_plan(M, N, K, cap)
+    bm, bn = p["tile"]
+    if bm == 0:                                   # no plan: too many tiles for one round (the head's gradient)
+        assert ((M + 255) // 256) * ((N + 255) // 256) > 128
+        return
+    tiles_m, tiles_n = -(-M // bm), -(-N // bn)
+    fm, fn = p["inside"]
+    assert 0 <= tiles_m - fm <= 1 and 0 <= tiles_n - fn <= 1
+    want = [fm * fn, (tiles_m - fm) * fn, fm * (tiles_n - fn), (tiles_m - fm) * (tiles_n - fn)]
+    assert p["tiles"] == want and sum(want) == tiles_m * tiles_n
+    s = p["slices"]
+    live = [c for c in range(4) if want[c] > 0]
+    assert all(1 <= s[c] <= min(cap, K // 32) for c in live)
+    assert all(s[c] <= s[0] or want[0] == 0 for c in live)
+    assert sum(want[c] * s[c] for c in range(4)) <= 256
+    assert max(s[c] for c in live) >= 2
+    # a tile with idle waves still loads whole operand panels: it never gets fewer than half the slices
+    assert all(2 * s[c] >= s[0] for c in live)
+
+
+def test_uneven_split_plan_of_the_step_shapes():
+    """The shapes of the config-2 step: 896 = 3.5 x 256 rows take oblong tiles where that frees a K slice."""
+    assert dp.dipaco_k_gemm_split_plan(896, 3584, 32768, 32)["tile"] == (128, 512)
+    assert dp.dipaco_k_gemm_split_plan(3584, 896, 32768, 32)["tile"] == (512, 128)
+    assert dp.dipaco_k_gemm_split_plan(896, 2688, 32768, 32)["tile"] == (256, 256)
+    p = dp.dipaco_k_gemm_split_plan(896, 3584, 32768, 32)
+    assert p["tiles"] == [49, 0, 0, 0] and p["slices"][0] == 5
+    with pytest.raises(dp.DipacoError):
+        dp.dipaco_k_gemm_split_plan(896, 3584, 1000, 32)
