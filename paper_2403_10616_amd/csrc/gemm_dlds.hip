@@ -371,8 +371,9 @@ int oblong_plan_wins(const GemmArgs& a) {
 }
 
 // Measured on the step's products (K = 896 .. 32768), the two-workgroup shape gains what it hides of a tile's ends
-// and loses as much to its extra barriers and operand traffic: it wins only on the 2688-wide QKV projection (by 6 %)
-// and is kept as a tested option; the automatic choice is the 256 x 256 shape.
+// and loses more to its extra barriers and operand traffic: level with the 256 x 256 shape on the GELU product, whose
+// epilogue is the longest, 3-15 % behind on all others.  It is kept as a tested option; the automatic choice is the
+// 256 x 256 shape.
 template <typename TC, bool A_KC, bool B_KC>
 dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
   if constexpr (std::is_same<TC, float>::value) {
