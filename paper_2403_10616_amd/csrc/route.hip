@@ -26,19 +26,68 @@ struct Best {
 };
 constexpr int NO_INDEX = 0x7fffffff;
 
-template <bool TOP2> __device__ __forceinline__ void best_insert(Best& b, float s, int i) {
-  if (s < b.s1 || (s == b.s1 && i < b.i1)) {
-    b.s2 = b.s1; b.s1 = s;
-    if (TOP2) b.i2 = b.i1;
-    b.i1 = i;
-  } else if (TOP2 ? (s < b.s2 || (s == b.s2 && i < b.i2)) : s < b.s2) {
-    b.s2 = s;
-    if (TOP2) b.i2 = i;
-  }
+// (s, i) before (t, j) in the lexicographic order
+__device__ __forceinline__ bool lex_less(float s, int i, float t, int j) { return s < t || (s == t && i < j); }
+
+// Candidate (s, k) whose index k is larger than every index the entry has seen: a tie keeps the earlier entry, so
+// plain < decides.  Written as selects: no branch, a NaN score never enters.
+template <bool TOP2> __device__ __forceinline__ void best_push_ascending(Best& b, float s, int k) {
+  const bool lt1 = s < b.s1, lt2 = s < b.s2;
+  if (TOP2) b.i2 = lt1 ? b.i1 : (lt2 ? k : b.i2);
+  b.s2 = lt1 ? b.s1 : (lt2 ? s : b.s2);
+  b.i1 = lt1 ? k : b.i1;
+  b.s1 = lt1 ? s : b.s1;
 }
-template <bool TOP2> __device__ __forceinline__ void best_merge(Best& a, float s1, int i1, float s2, int i2) {
-  best_insert<TOP2>(a, s1, i1);
-  best_insert<TOP2>(a, s2, i2);
+// The two best of the union of two entries over disjoint index sets.  A selection, not arithmetic: the result does
+// not depend on the order in which entries are merged.
+template <bool TOP2> __device__ __forceinline__ Best best_merge(const Best& a, const Best& b) {
+  const bool lt = lex_less(b.s1, b.i1, a.s1, a.i1);
+  Best o;
+  o.s1 = lt ? b.s1 : a.s1;
+  o.i1 = lt ? b.i1 : a.i1;
+  const float xs = lt ? a.s1 : b.s1, ys = lt ? b.s2 : a.s2;   // the first that lost, the second of the one that won
+  if (TOP2) {
+    const int xi = lt ? a.i1 : b.i1, yi = lt ? b.i2 : a.i2;
+    const bool ly = lex_less(ys, yi, xs, xi);
+    o.s2 = ly ? ys : xs;
+    o.i2 = ly ? yi : xi;
+  } else {
+    o.s2 = ys < xs ? ys : xs;
+    o.i2 = NO_INDEX;
+  }
+  return o;
+}
+
+// The value of lane l ^ MASK (MASK < 32): quad permutes on the vector ALU for 1 and 2, the LDS crossbar (no LDS
+// memory) for 4, 8, 16.
+template <int MASK> __device__ __forceinline__ int lane_xor(int v) {
+  if constexpr (MASK == 1) return __builtin_amdgcn_update_dpp(v, v, 0xb1, 0xf, 0xf, false);        // quad_perm [1,0,3,2]
+  else if constexpr (MASK == 2) return __builtin_amdgcn_update_dpp(v, v, 0x4e, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  else return __builtin_amdgcn_ds_swizzle(v, (MASK << 10) | 0x1f);   // bit mode: and 0x1f, or 0, xor MASK
+}
+template <int MASK> __device__ __forceinline__ float lane_xor(float v) {
+  return __builtin_bit_cast(float, lane_xor<MASK>(__builtin_bit_cast(int, v)));
+}
+
+// One step of the reduction over the 32 lanes that share rows.  Before it a lane holds 2 * HALF entries (entry r
+// belongs to row r of the lane's current set), the same set as its partner lane ^ MASK; the lane whose MASK bit is
+// clear keeps the even entries and hands over the odd ones, its partner the other way round, and each merges what it
+// keeps with what it receives.  Five steps (MASK 1 .. 16) leave every lane with ONE row reduced over all 32 lanes:
+// 31 merges per lane instead of the 160 of a butterfly on every row.
+template <bool TOP2, int MASK, int HALF> __device__ __forceinline__ void best_halve(Best (&b)[32], int lane) {
+  const bool up = (lane & MASK) != 0;
+#pragma unroll
+  for (int p = 0; p < HALF; ++p) {
+    const Best lo = b[2 * p], hi = b[2 * p + 1];
+    Best mine, theirs, got;
+    mine.s1 = up ? hi.s1 : lo.s1; mine.i1 = up ? hi.i1 : lo.i1; mine.s2 = up ? hi.s2 : lo.s2;
+    theirs.s1 = up ? lo.s1 : hi.s1; theirs.i1 = up ? lo.i1 : hi.i1; theirs.s2 = up ? lo.s2 : hi.s2;
+    mine.i2 = TOP2 ? (up ? hi.i2 : lo.i2) : NO_INDEX;
+    theirs.i2 = TOP2 ? (up ? lo.i2 : hi.i2) : NO_INDEX;
+    got.s1 = lane_xor<MASK>(theirs.s1); got.i1 = lane_xor<MASK>(theirs.i1); got.s2 = lane_xor<MASK>(theirs.s2);
+    got.i2 = TOP2 ? lane_xor<MASK>(theirs.i2) : NO_INDEX;
+    b[p] = best_merge<TOP2>(mine, got);
+  }
 }
 
 // z: row n at z + n * ldz.  TOP2: idx is [N, 2] (second entry -1 when K = 1) and hist counts both memberships.
@@ -68,12 +117,10 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   using LC = TileLoader<float, RBN, false>;
   const int nkt = (D + RBK - 1) / RBK;
 
-  // running best / second best for the 32 rows (2 row tiles x 16) this lane sees
-  Best best[2][16];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) { best[i][e].s1 = INFINITY; best[i][e].i1 = NO_INDEX; best[i][e].s2 = INFINITY; best[i][e].i2 = NO_INDEX; }
+  // Running best / second best of ONE row per lane: after the reduction at the end of a centroid tile lane l holds
+  // row tile i = (l & 31) >> 4, accumulator element e = l & 15 of its half.
+  Best run;
+  run.s1 = INFINITY; run.i1 = NO_INDEX; run.s2 = INFINITY; run.i2 = NO_INDEX;
 
   for (int n0 = 0; n0 < K; n0 += RBN) {
     f32x16 acc[2][4];
@@ -134,11 +181,15 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       if ((tid & 7) == 0) {
         const int col = (tid >> 3) + 32 * i;
         // linear router: the score to minimise is -(w_k.z + b_k), so -b_k takes the place of ||c_k||^2
-        cnorm[col] = lin_bias ? (n0 + col < K ? -lin_bias[n0 + col] : 0.f) : v;
+        // a column beyond K scores +inf: it never enters a best entry
+        cnorm[col] = n0 + col < K ? (lin_bias ? -lin_bias[n0 + col] : v) : INFINITY;
       }
     }
     __syncthreads();
-    // fold this centroid tile into the running best of every row this lane sees
+    // this centroid tile: best entries of the 32 rows this lane sees over its 4 columns (ascending index) ...
+    Best b[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) { b[r].s1 = INFINITY; b[r].i1 = NO_INDEX; b[r].s2 = INFINITY; b[r].i2 = NO_INDEX; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int col = wn * 128 + 32 * j + (lane & 31);
@@ -147,38 +198,32 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float s = (k < K) ? cn - dot_mul * acc[i][j][e] : INFINITY;
-          best_insert<TOP2>(best[i][e], s, k < K ? k : NO_INDEX);
-        }
+        for (int e = 0; e < 16; ++e) best_push_ascending<TOP2>(b[16 * i + e], __builtin_fmaf(-dot_mul, acc[i][j][e], cn), k);
     }
+    // ... reduced over the 32 lanes of the half (they hold the other columns of the same rows), one row per lane ...
+    best_halve<TOP2, 1, 16>(b, lane);
+    best_halve<TOP2, 2, 8>(b, lane);
+    best_halve<TOP2, 4, 4>(b, lane);
+    best_halve<TOP2, 8, 2>(b, lane);
+    best_halve<TOP2, 16, 1>(b, lane);
+    // ... and folded into the running entry of that row
+    run = best_merge<TOP2>(run, b[0]);
   }
 
-  // reduce over the 32 lanes that share a row (same lane half), then over the two waves along N
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      Best b = best[i][e];
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) {
-        const float s1 = __shfl_xor(b.s1, o, WAVE);
-        const int i1 = __shfl_xor(b.i1, o, WAVE);
-        const float s2 = __shfl_xor(b.s2, o, WAVE);
-        const int i2 = TOP2 ? __shfl_xor(b.i2, o, WAVE) : NO_INDEX;
-        best_merge<TOP2>(b, s1, i1, s2, i2);
-      }
-      if ((lane & 31) == 0) {
-        const int row = wm * 64 + 32 * i + acc_row(e, lane);
-        red_s1[wn][row] = b.s1; red_i1[wn][row] = b.i1; red_s2[wn][row] = b.s2;
-        if (TOP2) red_i2[wn][row] = b.i2;
-      }
-    }
+  // Row of this lane's entry: step t of the reduction kept the entries whose bit t equals lane bit t, so the entry
+  // left is number l & 31 = 16 i + e.  Then the two waves along N are merged through LDS.
+  {
+    const int r = lane & 31;
+    const int row = wm * 64 + 32 * (r >> 4) + acc_row(r & 15, lane);
+    red_s1[wn][row] = run.s1; red_i1[wn][row] = run.i1; red_s2[wn][row] = run.s2;
+    if (TOP2) red_i2[wn][row] = run.i2;
+  }
   __syncthreads();
   if (tid < RBM && tid < rows_left) {
-    Best b; b.s1 = red_s1[0][tid]; b.i1 = red_i1[0][tid]; b.s2 = red_s2[0][tid];
-    b.i2 = TOP2 ? red_i2[0][tid] : NO_INDEX;
-    best_merge<TOP2>(b, red_s1[1][tid], red_i1[1][tid], red_s2[1][tid], TOP2 ? red_i2[1][tid] : NO_INDEX);
+    Best b0, b1;
+    b0.s1 = red_s1[0][tid]; b0.i1 = red_i1[0][tid]; b0.s2 = red_s2[0][tid]; b0.i2 = TOP2 ? red_i2[0][tid] : NO_INDEX;
+    b1.s1 = red_s1[1][tid]; b1.i1 = red_i1[1][tid]; b1.s2 = red_s2[1][tid]; b1.i2 = TOP2 ? red_i2[1][tid] : NO_INDEX;
+    const Best b = best_merge<TOP2>(b0, b1);
     if (TOP2) {
       const bool has2 = b.i2 != NO_INDEX;
       idx[2 * (m0 + tid)] = b.i1;
