@@ -3,8 +3,9 @@
 // the work is one fp32 contraction z.C^T on the matrix cores (v_mfma_f32_32x32x2_f32) with the reduction over
 // centroids done in the epilogue: scores never reach memory.
 //
-// One workgroup (4 waves, 2 x 2) owns 128 points and walks the centroids in tiles of 256; every wave holds a
-// 64 x 128 block of scores in accumulators.  ||c_k||^2 is accumulated by the threads that stage the centroid
+// One workgroup (8 waves, 2 x 4: two per SIMD, so that one wave's staging, barriers and reductions run under the
+// other's matrix instructions) owns 128 points and walks the centroids in tiles of 256; every wave holds a 64 x 64
+// block of scores in accumulators.  ||c_k||^2 is accumulated by the threads that stage the centroid
 // tile, from the very values they put into LDS.
 #include "kernels.h"
 #include "mma_tile.h"
@@ -16,6 +17,8 @@ namespace {
 constexpr int RBM = 128;   // points per workgroup
 constexpr int RBN = 256;   // centroids per tile
 constexpr int RBK = 32;    // fp32 K tile
+constexpr int R_THREADS = 512;
+constexpr int R_WN = 4;    // waves along the centroids, 64 columns each
 constexpr int R_STAGE = (RBM + RBN) * TILE_ROW_BYTES;
 constexpr int R_MAX_K_LDS_HIST = 4096;
 
@@ -92,7 +95,7 @@ template <bool TOP2, int MASK, int HALF> __device__ __forceinline__ void best_ha
 
 // z: row n at z + n * ldz.  TOP2: idx is [N, 2] (second entry -1 when K = 1) and hist counts both memberships.
 template <bool TOP2>
-__global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __restrict__ z, long ldz,
+__global__ void __launch_bounds__(R_THREADS) route_kernel(const float* __restrict__ z, long ldz,
                                                              const float* __restrict__ c,
                                                              const float* __restrict__ lin_bias, long N, int D, int K,
                                                              int* __restrict__ idx,
@@ -100,21 +103,21 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
                                                              float* __restrict__ margin) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ float cnorm[RBN];
-  __shared__ float red_s1[2][RBM], red_s2[2][RBM];
-  __shared__ int red_i1[2][RBM], red_i2[TOP2 ? 2 : 1][TOP2 ? RBM : 1];
+  __shared__ float red_s1[R_WN][RBM], red_s2[R_WN][RBM];
+  __shared__ int red_i1[R_WN][RBM], red_i2[TOP2 ? R_WN : 1][TOP2 ? RBM : 1];
   __shared__ unsigned int lhist[R_MAX_K_LDS_HIST];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / R_WN, wn = wave % R_WN;
   const long m0 = (long)blockIdx.x * RBM;
   const int rows_left = (int)min((long)RBM, N - m0);
   const float* zb = z + m0 * ldz;
   const bool use_lhist = K <= R_MAX_K_LDS_HIST;
   const float dot_mul = lin_bias ? 1.0f : 2.0f;
-  if (use_lhist) for (int k = tid; k < K; k += GEMM_THREADS) lhist[k] = 0;
+  if (use_lhist) for (int k = tid; k < K; k += R_THREADS) lhist[k] = 0;
 
-  using LZ = TileLoader<float, RBM, false>;
-  using LC = TileLoader<float, RBN, false>;
+  using LZ = TileLoader<float, RBM, false, R_THREADS>;
+  using LC = TileLoader<float, RBN, false, R_THREADS>;
   const int nkt = (D + RBK - 1) / RBK;
 
   // Running best / second best of ONE row per lane: after the reduction at the end of a centroid tile lane l holds
@@ -123,11 +126,11 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   run.s1 = INFINITY; run.i1 = NO_INDEX; run.s2 = INFINITY; run.i2 = NO_INDEX;
 
   for (int n0 = 0; n0 < K; n0 += RBN) {
-    f32x16 acc[2][4];
+    f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     float nrm[LC::NLD];
@@ -157,7 +160,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
         LZ::load_tail(rz, zb, ldz, 0, rows_left, (kt + 1) * RBK, D, tid);
         LC::load_tail(rc, cb, D, 0, crow_left, (kt + 1) * RBK, D, tid);
       }
-      mma_ktile<float, 2, 4>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 128, lane);
+      mma_ktile<float, 2, 2>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 64, lane);
       if (more) {
         const int k0n = (kt + 1) * RBK;
         LZ::store(rz, nxt, tid, k0n, D);
@@ -171,7 +174,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       }
       __syncthreads();
     }
-    // ||c||^2: thread tid staged chunk (tid & 7) of centroid rows (tid >> 3) + 32 i
+    // ||c||^2: thread tid staged chunk (tid & 7) of centroid rows (tid >> 3) + 64 i
 #pragma unroll
     for (int i = 0; i < LC::NLD; ++i) {
       float v = nrm[i];
@@ -179,20 +182,20 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
       v += __shfl_xor(v, 2, WAVE);
       v += __shfl_xor(v, 4, WAVE);
       if ((tid & 7) == 0) {
-        const int col = (tid >> 3) + 32 * i;
+        const int col = (tid >> 3) + (R_THREADS / 8) * i;
         // linear router: the score to minimise is -(w_k.z + b_k), so -b_k takes the place of ||c_k||^2
         // a column beyond K scores +inf: it never enters a best entry
         cnorm[col] = n0 + col < K ? (lin_bias ? -lin_bias[n0 + col] : v) : INFINITY;
       }
     }
     __syncthreads();
-    // this centroid tile: best entries of the 32 rows this lane sees over its 4 columns (ascending index) ...
+    // this centroid tile: best entries of the 32 rows this lane sees over its 2 columns (ascending index) ...
     Best b[32];
 #pragma unroll
     for (int r = 0; r < 32; ++r) { b[r].s1 = INFINITY; b[r].i1 = NO_INDEX; b[r].s2 = INFINITY; b[r].i2 = NO_INDEX; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = wn * 128 + 32 * j + (lane & 31);
+    for (int j = 0; j < 2; ++j) {
+      const int col = wn * 64 + 32 * j + (lane & 31);
       const int k = n0 + col;
       const float cn = cnorm[col];
 #pragma unroll
@@ -211,7 +214,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   }
 
   // Row of this lane's entry: step t of the reduction kept the entries whose bit t equals lane bit t, so the entry
-  // left is number l & 31 = 16 i + e.  Then the two waves along N are merged through LDS.
+  // left is number l & 31 = 16 i + e.  Then the four waves along N are merged through LDS.
   {
     const int r = lane & 31;
     const int row = wm * 64 + 32 * (r >> 4) + acc_row(r & 15, lane);
@@ -220,10 +223,14 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   }
   __syncthreads();
   if (tid < RBM && tid < rows_left) {
-    Best b0, b1;
-    b0.s1 = red_s1[0][tid]; b0.i1 = red_i1[0][tid]; b0.s2 = red_s2[0][tid]; b0.i2 = TOP2 ? red_i2[0][tid] : NO_INDEX;
-    b1.s1 = red_s1[1][tid]; b1.i1 = red_i1[1][tid]; b1.s2 = red_s2[1][tid]; b1.i2 = TOP2 ? red_i2[1][tid] : NO_INDEX;
-    const Best b = best_merge<TOP2>(b0, b1);
+    Best b;
+    b.s1 = red_s1[0][tid]; b.i1 = red_i1[0][tid]; b.s2 = red_s2[0][tid]; b.i2 = TOP2 ? red_i2[0][tid] : NO_INDEX;
+#pragma unroll
+    for (int w = 1; w < R_WN; ++w) {
+      Best o;
+      o.s1 = red_s1[w][tid]; o.i1 = red_i1[w][tid]; o.s2 = red_s2[w][tid]; o.i2 = TOP2 ? red_i2[w][tid] : NO_INDEX;
+      b = best_merge<TOP2>(b, o);
+    }
     if (TOP2) {
       const bool has2 = b.i2 != NO_INDEX;
       idx[2 * (m0 + tid)] = b.i1;
@@ -241,7 +248,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) route_kernel(const float* __rest
   }
   if (use_lhist) {
     __syncthreads();
-    for (int k = tid; k < K; k += GEMM_THREADS) {
+    for (int k = tid; k < K; k += R_THREADS) {
       unsigned int v = lhist[k];
       if (v) atomicAdd(&hist[k], (unsigned long long)v);
     }
@@ -336,8 +343,8 @@ dipaco_status launch_route(const float* z, int64_t ldz, const float* c, const fl
   const int64_t blocks = (N + RBM - 1) / RBM;
   if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "route: N too large");
   auto* h = reinterpret_cast<unsigned long long*>(hist);
-  if (n_best == 2) route_kernel<true><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, lin_bias, (long)N, D, K, idx, h, margin);
-  else route_kernel<false><<<(unsigned)blocks, GEMM_THREADS, smem, s>>>(z, (long)ldz, c, lin_bias, (long)N, D, K, idx, h, margin);
+  if (n_best == 2) route_kernel<true><<<(unsigned)blocks, R_THREADS, smem, s>>>(z, (long)ldz, c, lin_bias, (long)N, D, K, idx, h, margin);
+  else route_kernel<false><<<(unsigned)blocks, R_THREADS, smem, s>>>(z, (long)ldz, c, lin_bias, (long)N, D, K, idx, h, margin);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
