@@ -298,8 +298,13 @@ static int splits_tile128(int M, int N, int smax) {
 
 size_t gemm_colsum_partial_floats(int M, int N) { return (size_t)((M + 31) / 32) * N; }
 
+// Most slices a long-K product is cut into by the register-staged kernels: a slice keeps at least 256 of K, and a
+// small output under a very long contraction (the router's 256 x 768 gradient over 2^20 documents) may still put a
+// workgroup on every compute unit.  The cost model below decides how many are actually taken.
+constexpr int GEMM_SLICE_CAP_STAGED = 128;
+
 int gemm_plan_splits(int M, int N, int K, bool bf16_operands) {
-  const int smax = (int)std::min<long>(16, std::max(1, K / 256));
+  const int smax = (int)std::min<long>(GEMM_SLICE_CAP_STAGED, std::max(1, K / 256));
   if (bf16_operands && (g_forced_tile == 0 || g_forced_tile >= 5)) {
     // direct-to-LDS kernel, one workgroup per compute unit, fewer slices for tiles that stick out of C
     const int s = gemm_dlds_plan_slices(M, N, K, (int)std::min<long>(GEMM_SLICE_CAP, std::max(1, K / 256)), false);
@@ -314,7 +319,7 @@ int gemm_plan_splits(int M, int N, int K, bool bf16_operands) {
 
 // Upper bound of gemm_plan_splits over every tile setting: sizes the partial-product workspace.
 int gemm_max_splits(int M, int N, int K) {
-  const int smax = (int)std::min<long>(16, std::max(1, K / 256));
+  const int smax = (int)std::min<long>(GEMM_SLICE_CAP_STAGED, std::max(1, K / 256));
   const int cap = (int)std::min<long>(GEMM_SLICE_CAP, std::max(1, K / 256));
   return std::max(std::max(splits_tile256(M, N, K, smax), splits_tile128(M, N, smax)),
                   gemm_dlds_plan_slices(M, N, K, cap, true));

@@ -313,15 +313,65 @@ __global__ void __launch_bounds__(256) logistic_rows_kernel(float* __restrict__ 
   if (lane == 0) nll[row] = valid ? logf(sum) - at_label : 0.f;
 }
 
+// The same for K <= 256, where a row is at most one 16-byte vector per lane: a wave takes ROWS rows at once, so that
+// ROWS loads are in flight per lane instead of one (a million one-kilobyte rows are latency-bound otherwise), and the
+// reductions run on the DPP lanes.
+constexpr int LOGIT_SMALL_ROWS = 8;
+__global__ void __launch_bounds__(256) logistic_rows_small_kernel(float* __restrict__ logits,
+                                                                  const int* __restrict__ labels, long rows, int K,
+                                                                  float inv_n, float* __restrict__ nll) {
+  constexpr int ROWS = LOGIT_SMALL_ROWS;
+  const long row0 = ((long)blockIdx.x * 4 + (threadIdx.x >> 6)) * ROWS;
+  if (row0 >= rows) return;   // whole waves leave: the reductions below see all 64 lanes
+  const int lane = threadIdx.x & 63;
+  const bool on = lane < (K >> 2);
+  float4 v[ROWS];
+  float at[ROWS];
+  int label[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    const long row = row0 + r;
+    const bool ok = row < rows;   // wave-uniform
+    v[r] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    label[r] = -1;
+    at[r] = 0.f;
+    if (ok) {
+      if (on) v[r] = reinterpret_cast<const float4*>(logits + row * K)[lane];
+      const int l = labels[row];
+      if (l >= 0 && l < K) { label[r] = l; at[r] = logits[row * K + l]; }   // read before the row is overwritten
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    const long row = row0 + r;
+    if (row >= rows) break;
+    const bool valid = label[r] >= 0;
+    const float mx = wave_max(fmaxf(fmaxf(v[r].x, v[r].y), fmaxf(v[r].z, v[r].w)));
+    float e[4] = {expf(v[r].x - mx), expf(v[r].y - mx), expf(v[r].z - mx), expf(v[r].w - mx)};   // exp(-inf) = 0 off the row
+    const float sum = wave_sum((e[0] + e[1]) + (e[2] + e[3]));
+    const float scale = valid ? inv_n / sum : 0.f;
+    if (on) {
+      float o[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = e[q] * scale - ((valid && 4 * lane + q == label[r]) ? inv_n : 0.f);
+      reinterpret_cast<float4*>(logits + row * K)[lane] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    if (lane == 0) nll[row] = valid ? logf(sum) - (at[r] - mx) : 0.f;
+  }
+}
+
 }  // namespace
 
 dipaco_status launch_logistic_rows(float* logits, const int* labels, int64_t rows, int K, float inv_n, float* nll,
                                    hipStream_t s) {
   if (K < 4 || K % 4 || K > LOGIT_MAX_K) return fail(DIPACO_ESHAPE, "logistic rows: K must be a multiple of 4 in [4, 4096]");
   if (rows == 0) return DIPACO_OK;
-  const int64_t blocks = (rows + 3) / 4;
+  const bool small = K <= 256;
+  const int64_t rows_per_block = small ? 4 * LOGIT_SMALL_ROWS : 4;
+  const int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
   if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "logistic rows: too many rows");
-  logistic_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(logits, labels, (long)rows, K, inv_n, nll);
+  if (small) logistic_rows_small_kernel<<<(unsigned)blocks, 256, 0, s>>>(logits, labels, (long)rows, K, inv_n, nll);
+  else logistic_rows_kernel<<<(unsigned)blocks, 256, 0, s>>>(logits, labels, (long)rows, K, inv_n, nll);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }

@@ -360,8 +360,25 @@ softmax_xent_kernel(T* __restrict__ logits, const int* __restrict__ targets, con
 __global__ void __launch_bounds__(1024) mean_loss_kernel(const float* __restrict__ nll, const int* __restrict__ n_valid,
                                                          float* __restrict__ loss, int rows) {
   __shared__ float red[16];
-  float s = 0.f;
-  for (int i = threadIdx.x; i < rows; i += 1024) s += nll[i];
+  // 16-byte loads, four in flight per thread (one workgroup has to pull a million values for the router's loss);
+  // the order of the additions is fixed by the indices alone
+  const float4* __restrict__ nll4 = reinterpret_cast<const float4*>(nll);
+  const int n4 = (reinterpret_cast<uintptr_t>(nll) & 15) == 0 ? rows >> 2 : 0;   // unaligned: the scalar loop takes all
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int i = threadIdx.x;
+  for (; i + 3 * 1024 < n4; i += 4 * 1024) {
+    const float4 a = nll4[i], b = nll4[i + 1024], c = nll4[i + 2048], d = nll4[i + 3072];
+    s0 += (a.x + a.y) + (a.z + a.w);
+    s1 += (b.x + b.y) + (b.z + b.w);
+    s2 += (c.x + c.y) + (c.z + c.w);
+    s3 += (d.x + d.y) + (d.z + d.w);
+  }
+  for (; i < n4; i += 1024) {
+    const float4 a = nll4[i];
+    s0 += (a.x + a.y) + (a.z + a.w);
+  }
+  for (int j = 4 * n4 + threadIdx.x; j < rows; j += 1024) s1 += nll[j];
+  float s = (s0 + s1) + (s2 + s3);
   s = wave_sum(s);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
   __syncthreads();
