@@ -231,6 +231,99 @@ def bench_outer_step(args):
                          "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_}}
 
 
+def bench_round(args):
+    """Config 5: one full round of one path = compose from the global segments, 8 inner steps (fwd + bwd + AdamW) at
+    batch 16 x seq 2048, then the outer Nesterov step of the path's two block modules, each averaged with the copies of
+    15 synthetic partner paths, and the new modules written back to the global segments.  A 'step' is one round."""
+    import torch
+    import dipaco_inputs as gen
+    import paper_2403_10616_amd as dp
+
+    cfg = gen.CONFIGS[5]
+    B, S, inner, P = cfg["batch"], cfg["seq"], cfg["inner_steps"], cfg["n_partners"]
+    ctx = dp.Context(**_arch_kwargs(cfg, dp.BF16))
+    n = dp.dipaco_path_param_count(ctx)
+    layout = {}
+    for i in range(dp.dipaco_tensor_count(ctx)):
+        name, off, rows, cols, dec = dp.dipaco_tensor_info(ctx, i)
+        layout[name] = (off, (rows, cols) if cols > 1 else (rows,), dec)
+    theta = gen.init_params(layout, sum(cfg["layers_per_level"]), cfg["seed"])
+    dev = "cuda"
+    nseg = dp.dipaco_segment_count(ctx)
+    bounds = [(dp.dipaco_segment_offset(ctx, s_), dp.dipaco_segment_offset(ctx, s_) + dp.dipaco_segment_size(ctx, s_))
+              for s_ in range(nseg)]
+    segs = [torch.from_numpy(theta[lo:hi]).to(dev) for lo, hi in bounds]          # the global modules
+    momentum = {l: torch.zeros(bounds[l][1] - bounds[l][0], dtype=torch.float32, device=dev) for l in (1, 2)}
+    # the partners' local copies of the two block modules at the end of the round: global module + N(0, 1e-3)
+    partners = {}
+    for l in (1, 2):
+        lo, hi = bounds[l]
+        partners[l] = [torch.from_numpy((theta[lo:hi] + gen.perturbation(hi - lo, cfg["delta_std"], 500 + 16 * l + i))
+                                        .astype(np.float32)).to(dev) for i in range(P)]
+    master = torch.empty(n, dtype=torch.float32, device=dev)
+    lowp = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    grads = torch.empty(n, dtype=torch.float32, device=dev)
+    m = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    ws = torch.empty(dp.dipaco_workspace_bytes(ctx, B, S), dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    seqs = gen.zipf_tokens((inner, B, S + 1), cfg["vocab"], cfg["zipf_s"], cfg["seed"])
+    toks = [torch.from_numpy(np.ascontiguousarray(seqs[i, :, :-1])).to(dev) for i in range(inner)]
+    tgts = [torch.from_numpy(np.ascontiguousarray(seqs[i, :, 1:])).to(dev) for i in range(inner)]
+    t_adam = [0]
+
+    def one_round():
+        dp.dipaco_compose_path(ctx, segs, master, lowp)
+        for i in range(inner):
+            dp.dipaco_path_fwd_bwd(ctx, master, lowp, toks[i], tgts[i], B, S, loss, None, grads, ws)
+            t_adam[0] += 1
+            dp.dipaco_inner_adamw(ctx, master, grads, m, v, lowp, t_adam[0], cfg["lr"], cfg["beta1"], cfg["beta2"],
+                                  cfg["eps"], cfg["wd"])
+        for l in (1, 2):
+            lo, hi = bounds[l]
+            dp.dipaco_module_outer_step(segs[l], momentum[l], [master[lo:hi]] + partners[l], None, hi - lo, False,
+                                        cfg["outer_lr"], cfg["outer_momentum"])
+        # stem and head are this path's own in this workload: carried over as they are
+        segs[0].copy_(master[bounds[0][0]:bounds[0][1]])
+        segs[nseg - 1].copy_(master[bounds[nseg - 1][0]:bounds[nseg - 1][1]])
+
+    for _ in range(args.warmup):
+        one_round()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_round()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    # the outer step alone, on the stream's events
+    lo, hi = bounds[1]
+    e0.record()
+    dp.dipaco_module_outer_step(segs[1], momentum[1], [master[lo:hi]] + partners[1], None, hi - lo, False,
+                                cfg["outer_lr"], cfg["outer_momentum"])
+    e1.record()
+    torch.cuda.synchronize()
+    outer_ms = e0.elapsed_time(e1)
+    outer_bytes = (P + 1 + 4) * (hi - lo) * 4.0
+    ach = outer_bytes / (outer_ms * 1e-3) / 1e9
+    ms = wall * 1e3 / args.steps
+    fwd, dx, dw = step_gemm_shapes(cfg, B, S)
+    att_f, att_b = attention_flops(cfg, B, S)
+    step_flops = 3.0 * sum(2.0 * M * N * K for M, N, K in fwd) + att_f + att_b
+    return {"metric": "full-round tokens/sec on 1 MI355X (8 inner steps + outer step of two modules)",
+            "value": inner * B * S / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "config 5: one round of one path: compose, 8 x (fwd+bwd+AdamW) at batch 16 x seq 2048, "
+                                   "outer Nesterov step of both 57.9M-parameter modules over 16 copies each",
+                       "tokens_per_round": inner * B * S, "final_loss": float(loss.item()),
+                       "model_tflops_per_round": inner * step_flops / 1e12,
+                       "model_flops_utilisation": inner * step_flops / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
+                       "outer_step_ms_per_module": outer_ms},
+            "roofline": {"bound": "hbm", "kernel": "outer_kernel<16> (copies form)", "achieved": ach, "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": outer_bytes}}
+
+
 def bench_outer_stream(args):
     import torch
     import dipaco_inputs as gen
@@ -689,7 +782,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "outer_step", "outer_stream", "outer_table", "route", "router", "reroute", "kmeans", "features", "score", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "round", "outer_step", "outer_stream", "outer_table", "route", "router", "reroute", "kmeans", "features", "score", "gemm", "attention"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
@@ -708,7 +801,7 @@ def main():
     dp.load()   # fails loudly if libdipaco.so is not built
     if args.attn_blocks is not None:
         dp.dipaco_k_set_attention_blocks(args.attn_blocks)
-    fn = {"path_step": bench_path_step, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
+    fn = {"path_step": bench_path_step, "round": bench_round, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
           "outer_table": bench_outer_table, "router": bench_router, "reroute": bench_reroute,
           "attention": bench_attention}[args.workload]
     print(json.dumps(fn(args)))
