@@ -4,9 +4,11 @@
 // centroids done in the epilogue: scores never reach memory.
 //
 // One workgroup (8 waves, 2 x 4: two per SIMD, so that one wave's staging, barriers and reductions run under the
-// other's matrix instructions) owns 128 points and walks the centroids in tiles of 256; every wave holds a 64 x 64
+// other's matrix instructions) owns 256 points and walks the centroids in tiles of 256; every wave holds a 128 x 64
 // block of scores in accumulators.  ||c_k||^2 is accumulated by the threads that stage the centroid
 // tile, from the very values they put into LDS.
+#include <type_traits>
+
 #include "kernels.h"
 #include "mma_tile.h"
 
@@ -14,13 +16,14 @@ namespace dipaco {
 
 namespace {
 
-constexpr int RBM = 128;   // points per workgroup
+constexpr int RBM = 256;   // points per workgroup
 constexpr int RBN = 256;   // centroids per tile
 constexpr int RBK = 32;    // fp32 K tile
 constexpr int R_THREADS = 512;
 constexpr int R_WN = 4;    // waves along the centroids, 64 columns each
 constexpr int R_STAGE = (RBM + RBN) * TILE_ROW_BYTES;
 constexpr int R_MAX_K_LDS_HIST = 4096;
+constexpr int R_TM = RBM / 64;   // 32-row score tiles per wave (two waves along the points)
 
 // Best and second-best (score, index) of a row, ordered lexicographically: exact ties go to the lower index.
 // TOP2 = false: the second index is not tracked (only its score, for the margin).
@@ -72,16 +75,21 @@ template <int MASK> __device__ __forceinline__ float lane_xor(float v) {
   return __builtin_bit_cast(float, lane_xor<MASK>(__builtin_bit_cast(int, v)));
 }
 
-// One step of the reduction over the 32 lanes that share rows.  Before it a lane holds 2 * HALF entries (entry r
-// belongs to row r of the lane's current set), the same set as its partner lane ^ MASK; the lane whose MASK bit is
-// clear keeps the even entries and hands over the odd ones, its partner the other way round, and each merges what it
-// keeps with what it receives.  Five steps (MASK 1 .. 16) leave every lane with ONE row reduced over all 32 lanes:
-// 31 merges per lane instead of the 160 of a butterfly on every row.
-template <bool TOP2, int MASK, int HALF> __device__ __forceinline__ void best_halve(Best (&b)[32], int lane) {
-  const bool up = (lane & MASK) != 0;
-#pragma unroll
-  for (int p = 0; p < HALF; ++p) {
-    const Best lo = b[2 * p], hi = b[2 * p + 1];
+// Reduction over the 32 lanes that share rows: the entries of 2^LEVEL rows (BASE .. BASE + 2^LEVEL - 1 of the lane's
+// 32), reduced over lane bits 0 .. LEVEL-1, as ONE entry per lane.  Two halves are reduced first; then the lane whose
+// bit LEVEL-1 is clear keeps the entry of the lower half and hands the other to its partner lane ^ 2^(LEVEL-1), the
+// partner the other way round, and each merges what it keeps with what it receives.  At LEVEL 5 every lane holds one
+// row (number l & 31) reduced over all 32 lanes: 31 merges per lane instead of the 160 of a butterfly on every row,
+// and, walked depth-first, never more than LEVEL + 1 entries alive (leaf(r) builds row r's entry when it is needed).
+template <bool TOP2, int LEVEL, int BASE, typename Leaf>
+__device__ __forceinline__ Best best_reduce_rows(const Leaf& leaf, int lane) {
+  if constexpr (LEVEL == 0) {
+    return leaf(std::integral_constant<int, BASE>{});
+  } else {
+    constexpr int MASK = 1 << (LEVEL - 1);
+    const Best lo = best_reduce_rows<TOP2, LEVEL - 1, BASE>(leaf, lane);
+    const Best hi = best_reduce_rows<TOP2, LEVEL - 1, BASE + MASK>(leaf, lane);
+    const bool up = (lane & MASK) != 0;
     Best mine, theirs, got;
     mine.s1 = up ? hi.s1 : lo.s1; mine.i1 = up ? hi.i1 : lo.i1; mine.s2 = up ? hi.s2 : lo.s2;
     theirs.s1 = up ? lo.s1 : hi.s1; theirs.i1 = up ? lo.i1 : hi.i1; theirs.s2 = up ? lo.s2 : hi.s2;
@@ -89,7 +97,7 @@ template <bool TOP2, int MASK, int HALF> __device__ __forceinline__ void best_ha
     theirs.i2 = TOP2 ? (up ? lo.i2 : hi.i2) : NO_INDEX;
     got.s1 = lane_xor<MASK>(theirs.s1); got.i1 = lane_xor<MASK>(theirs.i1); got.s2 = lane_xor<MASK>(theirs.s2);
     got.i2 = TOP2 ? lane_xor<MASK>(theirs.i2) : NO_INDEX;
-    b[p] = best_merge<TOP2>(mine, got);
+    return best_merge<TOP2>(mine, got);
   }
 }
 
@@ -103,8 +111,6 @@ __global__ void __launch_bounds__(R_THREADS) route_kernel(const float* __restric
                                                              float* __restrict__ margin) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ float cnorm[RBN];
-  __shared__ float red_s1[R_WN][RBM], red_s2[R_WN][RBM];
-  __shared__ int red_i1[R_WN][RBM], red_i2[TOP2 ? R_WN : 1][TOP2 ? RBM : 1];
   __shared__ unsigned int lhist[R_MAX_K_LDS_HIST];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -120,15 +126,16 @@ __global__ void __launch_bounds__(R_THREADS) route_kernel(const float* __restric
   using LC = TileLoader<float, RBN, false, R_THREADS>;
   const int nkt = (D + RBK - 1) / RBK;
 
-  // Running best / second best of ONE row per lane: after the reduction at the end of a centroid tile lane l holds
-  // row tile i = (l & 31) >> 4, accumulator element e = l & 15 of its half.
-  Best run;
-  run.s1 = INFINITY; run.i1 = NO_INDEX; run.s2 = INFINITY; run.i2 = NO_INDEX;
+  // Running best / second best of one row per lane and pair of row tiles: after the reduction at the end of a
+  // centroid tile lane l holds, of pair hb, row tile 2 hb + ((l & 31) >> 4), accumulator element e = l & 15.
+  Best run[R_TM / 2];
+#pragma unroll
+  for (int hb = 0; hb < R_TM / 2; ++hb) { run[hb].s1 = INFINITY; run[hb].i1 = NO_INDEX; run[hb].s2 = INFINITY; run[hb].i2 = NO_INDEX; }
 
   for (int n0 = 0; n0 < K; n0 += RBN) {
-    f32x16 acc[2][2];
+    f32x16 acc[R_TM][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < R_TM; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -160,7 +167,7 @@ __global__ void __launch_bounds__(R_THREADS) route_kernel(const float* __restric
         LZ::load_tail(rz, zb, ldz, 0, rows_left, (kt + 1) * RBK, D, tid);
         LC::load_tail(rc, cb, D, 0, crow_left, (kt + 1) * RBK, D, tid);
       }
-      mma_ktile<float, 2, 2>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * 64, wn * 64, lane);
+      mma_ktile<float, R_TM, 2>(acc, cur, cur + RBM * TILE_ROW_BYTES, wm * (RBM / 2), wn * 64, lane);
       if (more) {
         const int k0n = (kt + 1) * RBK;
         LZ::store(rz, nxt, tid, k0n, D);
@@ -189,46 +196,56 @@ __global__ void __launch_bounds__(R_THREADS) route_kernel(const float* __restric
       }
     }
     __syncthreads();
-    // this centroid tile: best entries of the 32 rows this lane sees over its 2 columns (ascending index) ...
-    Best b[32];
-#pragma unroll
-    for (int r = 0; r < 32; ++r) { b[r].s1 = INFINITY; b[r].i1 = NO_INDEX; b[r].s2 = INFINITY; b[r].i2 = NO_INDEX; }
+    // this centroid tile: for each pair of row tiles (32 rows of the lane) the best entries over the lane's 2 columns
+    // (ascending index), reduced over the 32 lanes of the half (they hold the other columns of the same rows) to one
+    // row per lane, and folded into the running entry of that row
+    float cn[2];
+    int kk[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = wn * 64 + 32 * j + (lane & 31);
-      const int k = n0 + col;
-      const float cn = cnorm[col];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) best_push_ascending<TOP2>(b[16 * i + e], __builtin_fmaf(-dot_mul, acc[i][j][e], cn), k);
+      kk[j] = n0 + col;
+      cn[j] = cnorm[col];
     }
-    // ... reduced over the 32 lanes of the half (they hold the other columns of the same rows), one row per lane ...
-    best_halve<TOP2, 1, 16>(b, lane);
-    best_halve<TOP2, 2, 8>(b, lane);
-    best_halve<TOP2, 4, 4>(b, lane);
-    best_halve<TOP2, 8, 2>(b, lane);
-    best_halve<TOP2, 16, 1>(b, lane);
-    // ... and folded into the running entry of that row
-    run = best_merge<TOP2>(run, b[0]);
+#pragma unroll
+    for (int hb = 0; hb < R_TM / 2; ++hb) {
+      auto leaf = [&](auto R) {
+        constexpr int r = decltype(R)::value;
+        Best b;
+        b.s1 = INFINITY; b.i1 = NO_INDEX; b.s2 = INFINITY; b.i2 = NO_INDEX;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          best_push_ascending<TOP2>(b, __builtin_fmaf(-dot_mul, acc[2 * hb + r / 16][j][r % 16], cn[j]), kk[j]);
+        return b;
+      };
+      run[hb] = best_merge<TOP2>(run[hb], best_reduce_rows<TOP2, 5, 0>(leaf, lane));
+    }
   }
 
-  // Row of this lane's entry: step t of the reduction kept the entries whose bit t equals lane bit t, so the entry
-  // left is number l & 31 = 16 i + e.  Then the four waves along N are merged through LDS.
-  {
+  // Row of a lane's entry: step t of the reduction kept the entries whose bit t equals lane bit t, so the entry left
+  // is number l & 31 = 16 i + e of its pair.  Then the four waves along N are merged through LDS (the operand stages
+  // are free: every wave has passed the barriers that end the last centroid tile).
+  float* const red_s1 = reinterpret_cast<float*>(smem);
+  float* const red_s2 = red_s1 + R_WN * RBM;
+  int* const red_i1 = reinterpret_cast<int*>(red_s2 + R_WN * RBM);
+  int* const red_i2 = red_i1 + R_WN * RBM;
+  static_assert(4 * R_WN * RBM * sizeof(float) <= 2 * (size_t)R_STAGE, "the merge arrays fit in the operand stages");
+#pragma unroll
+  for (int hb = 0; hb < R_TM / 2; ++hb) {
     const int r = lane & 31;
-    const int row = wm * 64 + 32 * (r >> 4) + acc_row(r & 15, lane);
-    red_s1[wn][row] = run.s1; red_i1[wn][row] = run.i1; red_s2[wn][row] = run.s2;
-    if (TOP2) red_i2[wn][row] = run.i2;
+    const int row = wm * (RBM / 2) + 64 * hb + 32 * (r >> 4) + acc_row(r & 15, lane);
+    red_s1[wn * RBM + row] = run[hb].s1; red_i1[wn * RBM + row] = run[hb].i1; red_s2[wn * RBM + row] = run[hb].s2;
+    if (TOP2) red_i2[wn * RBM + row] = run[hb].i2;
   }
   __syncthreads();
   if (tid < RBM && tid < rows_left) {
     Best b;
-    b.s1 = red_s1[0][tid]; b.i1 = red_i1[0][tid]; b.s2 = red_s2[0][tid]; b.i2 = TOP2 ? red_i2[0][tid] : NO_INDEX;
+    b.s1 = red_s1[tid]; b.i1 = red_i1[tid]; b.s2 = red_s2[tid]; b.i2 = TOP2 ? red_i2[tid] : NO_INDEX;
 #pragma unroll
     for (int w = 1; w < R_WN; ++w) {
       Best o;
-      o.s1 = red_s1[w][tid]; o.i1 = red_i1[w][tid]; o.s2 = red_s2[w][tid]; o.i2 = TOP2 ? red_i2[w][tid] : NO_INDEX;
+      o.s1 = red_s1[w * RBM + tid]; o.i1 = red_i1[w * RBM + tid]; o.s2 = red_s2[w * RBM + tid];
+      o.i2 = TOP2 ? red_i2[w * RBM + tid] : NO_INDEX;
       b = best_merge<TOP2>(b, o);
     }
     if (TOP2) {
