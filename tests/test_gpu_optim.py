@@ -205,3 +205,30 @@ def test_table_outer_step_matches_oracle_and_per_module_calls(case):
     for m, d, (th_o, _b) in zip(mods, dmods, want2):
         if m["n_elems"]:
             assert rel_l2(host(d["theta"]), th_o) <= 2e-6
+
+
+def test_synchronous_baseline_step_is_gradient_mean_plus_adamw():
+    """The fully synchronous ablation of Section 4.5 exchanges and aggregates gradients module by module at every step: on one device its arithmetic is
+    the mean of the gradients of the paths that share the parameters, followed by the inner optimiser.  Both pieces
+    exist (the accumulation entry point with ready-made inputs, then AdamW); here they are chained at config-1 size
+    and checked against the oracle's mean + AdamW over three steps."""
+    a, ctx = make_arch(SMALL, dp.F32)
+    n = orc.param_count(a)
+    mask = orc.decay_mask(a)
+    P = 4
+    rng = np.random.default_rng(11)
+    theta = rng.standard_normal(n).astype(np.float32)
+    th_d = dev(theta)
+    m_d = torch.zeros(n, dtype=torch.float32, device=DEV)
+    v_d = torch.zeros(n, dtype=torch.float32, device=DEV)
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    th_o, m_o, v_o = theta.astype(np.float64), np.zeros(n), np.zeros(n)
+    for step in (1, 2, 3):
+        gs = [rng.standard_normal(n).astype(np.float32) for _ in range(P)]
+        for i, g in enumerate(gs):
+            dp.dipaco_module_delta_accumulate(acc, None, dev(g), 1.0 / P, n, True, i == 0)
+        dp.dipaco_inner_adamw(ctx, th_d, acc, m_d, v_d, None, step, 1e-3, 0.9, 0.95, 1e-8, 0.1)
+        g_mean = sum(g.astype(np.float64) for g in gs) / P
+        assert rel_l2(host(acc), g_mean) <= 1e-6
+        th_o, m_o, v_o = orc.adamw_step(th_o, g_mean, m_o, v_o, step, 1e-3, 0.9, 0.95, 1e-8, 0.1, mask)
+        assert rel_l2(host(th_d), th_o) <= 1e-6 and rel_l2(host(m_d), m_o) <= 1e-6 and rel_l2(host(v_d), v_o) <= 2e-6
