@@ -76,6 +76,58 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_fwd_kernel(const T* __restrict
   }
 }
 
+// The same with the row held in registers (NIT chunks of 16 bytes per lane, d <= 64 * VEC * NIT): x is read once, and
+// the gain and bias vectors are requested before the reductions, so that a row costs one trip to memory instead of
+// three dependent ones.  Same order of additions as the kernel above: identical results.
+template <typename T, int NIT>
+__global__ void __launch_bounds__(ROW_THREADS) ln_fwd_reg_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                                 const T* __restrict__ b, T* __restrict__ y,
+                                                                 float* __restrict__ mean, float* __restrict__ rstd,
+                                                                 int rows, int d, float eps) {
+  constexpr int VEC = Vec16<T>::N;
+  const int row = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const T* xr = x + (size_t)row * d;
+  float a[NIT][VEC], gg[NIT][VEC], bb[NIT][VEC];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = (lane + WAVE * it) * VEC;
+    if (c < d) {
+      load_vec16(xr + c, a[it]);
+      load_vec16(g + c, gg[it]);
+      load_vec16(b + c, bb[it]);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+    if ((lane + WAVE * it) * VEC < d) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) s += a[it][i];
+    }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+    if ((lane + WAVE * it) * VEC < d) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) { float t = a[it][i] - mu; q += t * t; }
+    }
+  const float rs = 1.0f / sqrtf(wave_sum(q) / d + eps);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  T* yr = y + (size_t)row * d;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = (lane + WAVE * it) * VEC;
+    if (c < d) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) a[it][i] = (a[it][i] - mu) * rs * gg[it][i] + bb[it][i];
+      store_vec16(yr + c, a[it]);
+    }
+  }
+}
+
 // ---- LayerNorm backward -----------------------------------------------------------------------------------
 // Each workgroup owns LN_BWD_ROWS consecutive rows (one wave per row at a time), writes dx for them and one
 // partial row of dg / db / column sums of dx; a second kernel sums the partial rows in block order.  The column
@@ -103,29 +155,59 @@ __global__ void __launch_bounds__(ROW_THREADS) ln_bwd_kernel(const T* __restrict
     if (c < d) load_vec16(g + c, gv[it]);
   }
 
-  for (int r = wave; r < rows_per_block; r += ROWS_PER_BLOCK) {
+  // The rows of a wave are pipelined by hand: the 16-byte vectors of the next row (and its statistics) are requested
+  // before the current row is reduced, so that a row does not wait out a whole trip to memory.
+  uint4 nx[NIT], ndy[NIT], nres[NIT];
+  float nmu = 0.f, nrs = 0.f;
+  auto fetch = [&](int row) {
+    nmu = mean[row];
+    nrs = rstd[row];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = (lane + WAVE * it) * VEC;
+      if (c < d) {
+        nx[it] = *reinterpret_cast<const uint4*>(x + (size_t)row * d + c);
+        ndy[it] = *reinterpret_cast<const uint4*>(dy + (size_t)row * d + c);
+        if (resid_grad) nres[it] = *reinterpret_cast<const uint4*>(resid_grad + (size_t)row * d + c);
+      }
+    }
+  };
+  auto unpack = [](const uint4& raw, float (&out)[VEC]) {
+    const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) out[i] = to_f32(e[i]);
+  };
+  int r = wave;
+  bool have = r < rows_per_block && row0 + r < rows;
+  if (have) fetch(row0 + r);
+  while (have) {
     const int row = row0 + r;
-    if (row >= rows) break;
-    const float mu = mean[row], rs = rstd[row];
-    const T* xr = x + (size_t)row * d;
-    const T* dyr = dy + (size_t)row * d;
+    const float mu = nmu, rs = nrs;
     float xh[NIT][VEC], dv[NIT][VEC], out[NIT][VEC];   // the row stays in registers between the two passes
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = (lane + WAVE * it) * VEC;
+      if (c < d) {
+        unpack(nx[it], xh[it]);
+        unpack(ndy[it], dv[it]);
+        if (resid_grad) unpack(nres[it], out[it]);
+        else {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) out[it][i] = 0.f;
+        }
+      }
+    }
+    r += ROWS_PER_BLOCK;
+    have = r < rows_per_block && row0 + r < rows;
+    if (have) fetch(row0 + r);
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int c = (lane + WAVE * it) * VEC;
       if (c < d) {
-        float xv[VEC];
-        load_vec16(xr + c, xv);
-        load_vec16(dyr + c, dv[it]);
-        if (resid_grad) load_vec16(resid_grad + (size_t)row * d + c, out[it]);
-        else {
-#pragma unroll
-          for (int i = 0; i < VEC; ++i) out[it][i] = 0.f;
-        }
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-          xh[it][i] = (xv[i] - mu) * rs;
+          xh[it][i] = (xh[it][i] - mu) * rs;
           const float dxh = dv[it][i] * gv[it][i];
           s1 += dxh;
           s2 += dxh * xh[it][i];
@@ -493,7 +575,12 @@ dipaco_status launch_embed(const T* E, const T* P, const int* tokens, T* x, int 
 template <typename T>
 dipaco_status launch_layernorm_fwd(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows,
                                    int d, float eps, hipStream_t s) {
-  ln_fwd_kernel<T><<<row_blocks(rows), ROW_THREADS, 0, s>>>(x, g, b, y, mean, rstd, rows, d, eps);
+  constexpr int VEC = Vec16<T>::N;
+  const int chunks = (d + WAVE * VEC - 1) / (WAVE * VEC);   // 16-byte chunks per lane
+  if (chunks <= 1) ln_fwd_reg_kernel<T, 1><<<row_blocks(rows), ROW_THREADS, 0, s>>>(x, g, b, y, mean, rstd, rows, d, eps);
+  else if (chunks <= 2) ln_fwd_reg_kernel<T, 2><<<row_blocks(rows), ROW_THREADS, 0, s>>>(x, g, b, y, mean, rstd, rows, d, eps);
+  else if (chunks <= 4) ln_fwd_reg_kernel<T, 4><<<row_blocks(rows), ROW_THREADS, 0, s>>>(x, g, b, y, mean, rstd, rows, d, eps);
+  else ln_fwd_kernel<T><<<row_blocks(rows), ROW_THREADS, 0, s>>>(x, g, b, y, mean, rstd, rows, d, eps);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
