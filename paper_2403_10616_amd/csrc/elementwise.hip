@@ -82,22 +82,37 @@ __device__ __forceinline__ float adam_one(float th, float g, float& m, float& v,
   return th - a.lr * (mhat / (sqrtf(vhat) + a.eps) + decay * th);
 }
 
+__device__ __forceinline__ void adam_apply4(const AdamArgs& a, size_t i, float4 th, float4 g, float4 m, float4 v) {
+  const float decay = adam_decayed(a, (unsigned long long)i << 2) ? a.wd : 0.0f;
+  th.x = adam_one(th.x, g.x, m.x, v.x, a, decay);
+  th.y = adam_one(th.y, g.y, m.y, v.y, a, decay);
+  th.z = adam_one(th.z, g.z, m.z, v.z, a, decay);
+  th.w = adam_one(th.w, g.w, m.w, v.w, a, decay);
+  stream_store4(a.theta + 4 * i, th);
+  stream_store4(a.m + 4 * i, m);
+  stream_store4(a.v + 4 * i, v);
+  if (a.lowp) store_bf16x4(a.lowp + 4 * i, th);
+}
+
 __global__ void __launch_bounds__(EW_THREADS) adamw_kernel(const AdamArgs a) {
   size_t nv = a.n >> 2;  // every tensor starts and ends on a multiple of 4 elements (checked at create)
   size_t stride = (size_t)gridDim.x * EW_THREADS;
-  for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < nv; i += stride) {
-    const float decay = adam_decayed(a, (unsigned long long)i << 2) ? a.wd : 0.0f;
-    // every value is touched once per step: streaming (non-temporal) loads and stores keep them out of the caches' way
-    float4 th = stream_load4(a.theta + 4 * i), g = stream_load4(a.grad + 4 * i);
-    float4 m = stream_load4(a.m + 4 * i), v = stream_load4(a.v + 4 * i);
-    th.x = adam_one(th.x, g.x, m.x, v.x, a, decay);
-    th.y = adam_one(th.y, g.y, m.y, v.y, a, decay);
-    th.z = adam_one(th.z, g.z, m.z, v.z, a, decay);
-    th.w = adam_one(th.w, g.w, m.w, v.w, a, decay);
-    stream_store4(a.theta + 4 * i, th);
-    stream_store4(a.m + 4 * i, m);
-    stream_store4(a.v + 4 * i, v);
-    if (a.lowp) store_bf16x4(a.lowp + 4 * i, th);
+  size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+  // every value is touched once per step: streaming (non-temporal) loads and stores keep them out of the caches' way;
+  // two grid strides per turn: eight 16-byte loads in flight per thread
+  for (; i + stride < nv; i += 2 * stride) {
+    const size_t j = i + stride;
+    const float4 th0 = stream_load4(a.theta + 4 * i), g0 = stream_load4(a.grad + 4 * i);
+    const float4 m0 = stream_load4(a.m + 4 * i), v0 = stream_load4(a.v + 4 * i);
+    const float4 th1 = stream_load4(a.theta + 4 * j), g1 = stream_load4(a.grad + 4 * j);
+    const float4 m1 = stream_load4(a.m + 4 * j), v1 = stream_load4(a.v + 4 * j);
+    adam_apply4(a, i, th0, g0, m0, v0);
+    adam_apply4(a, j, th1, g1, m1, v1);
+  }
+  if (i < nv) {
+    const float4 th = stream_load4(a.theta + 4 * i), g = stream_load4(a.grad + 4 * i);
+    const float4 m = stream_load4(a.m + 4 * i), v = stream_load4(a.v + 4 * i);
+    adam_apply4(a, i, th, g, m, v);
   }
 }
 
