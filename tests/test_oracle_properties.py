@@ -7,7 +7,7 @@ from hypothesis import given, settings, strategies as st
 
 from oracle import dipaco_oracle as orc
 
-SET = dict(max_examples=40, deadline=None)
+SET = dict(max_examples=40, deadline=None, derandomize=True)   # the same examples on every run
 
 
 @settings(**SET)
