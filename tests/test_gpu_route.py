@@ -336,3 +336,27 @@ def test_window_targets_and_chunk_routed_scores_match_oracle(P, B, S, L, W):
         dp.dipaco_window_targets(nd, P, B, S, 0, tg, ws, nbytes)
     with pytest.raises(dp.DipacoError):
         dp.dipaco_chunk_routed_score(nd, dev(choice), P, B, S, W, out, ws, 8)
+
+
+# ---- exact comparison on integer points over many ragged shapes --------------------------------------------------
+_EXACT_SHAPES = [(1, 4, 1), (2, 4, 2), (255, 8, 7), (256, 8, 64), (257, 12, 65), (511, 4, 255), (513, 36, 256),
+                 (700, 8, 257), (1025, 32, 300), (300, 40, 511), (64, 4, 513), (2049, 8, 33), (90, 68, 1030)]
+
+
+@pytest.mark.parametrize("N,D,K", _EXACT_SHAPES)
+def test_route_and_top2_are_exact_on_integer_points(N, D, K):
+    """Small-integer coordinates make every fp32 score exact, and ties between centroids are the rule: the kernel's
+    selection (fold over a lane's columns, reduction over the lanes of a row, merge of the waves and of the centroid
+    tiles) must then give the oracle's indices, histogram and margins bit for bit, whatever part of a tile is empty."""
+    print(f"exact route N={N} D={D} K={K}", flush=True)
+    rng = np.random.default_rng(1000 * N + K)
+    z = rng.integers(-2, 3, size=(N, D)).astype(np.float32)
+    c = rng.integers(-2, 3, size=(K, D)).astype(np.float32)
+    idx, hist, margin = _run(z, c)
+    o_idx, o_hist, o_margin = orc.route_prefix(z, c)
+    assert np.array_equal(idx, o_idx) and np.array_equal(hist, o_hist)
+    assert np.array_equal(margin.astype(np.float64), o_margin)
+    idx2, hist2, margin2 = _run_top(z, D, 0, D, c, 2)
+    o_idx2, o_hist2 = orc.route_prefix_top2(z, c)
+    assert np.array_equal(idx2, o_idx2) and np.array_equal(hist2, o_hist2)
+    assert np.array_equal(margin2.astype(np.float64), o_margin)
