@@ -122,6 +122,24 @@ dipaco_status dipaco_path_prefix_features(dipaco_ctx* ctx, const float* path_mas
                                           const int32_t* tokens, int32_t batch, int32_t seq, float* features_out,
                                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* dipaco_path_prefix_features for callers that cannot allocate device memory or carry a workspace around (code under
+ * HIP graph capture, a tight serving loop that routes incoming documents, harnesses that forbid hipMalloc): the same
+ * kernels, with the activations kept in a device array of DIPACO_STATIC_SCRATCH_BYTES that is part of the library's
+ * code object (each GPU the library runs on holds its own copy until the process ends).  Arguments as in
+ * dipaco_path_prefix_features, without the workspace; results are identical bit for bit.
+ *   - DIPACO_EWORKSPACE when dipaco_features_workspace_bytes(ctx, batch, seq) exceeds DIPACO_STATIC_SCRATCH_BYTES
+ *     (64 MiB: 2048 prefix tokens of the 896-wide path in bf16, e.g. 64 documents x 32 tokens); nothing is enqueued.
+ *   - The call allocates and frees nothing, on the host side of the device or on it.  The first call on a device looks
+ *     up the array's address there (no allocation, no synchronisation).
+ *   - Every call on one GPU uses that GPU's single array: two calls that overlap in time on one GPU (different
+ *     streams or host threads) race.  Nothing in the array has to start at zero; its contents after a call are
+ *     undefined. */
+#define DIPACO_STATIC_SCRATCH_BYTES (64u << 20)
+size_t dipaco_static_scratch_bytes(void);   /* = DIPACO_STATIC_SCRATCH_BYTES */
+dipaco_status dipaco_path_prefix_features_static(dipaco_ctx* ctx, const float* path_master, const void* path_lowp,
+                                                 const int32_t* tokens, int32_t batch, int32_t seq,
+                                                 float* features_out, void* stream);
+
 /* Path scores for discriminative routing (Section 2.4.2; appendix on routing: the summed auto-regressive
  * log-likelihood of each document under each path, whose argmax over paths is the router's training label):
  * forward pass only.  doc_loglik_out[b] = sum over positions with target >= 0 of log p(target | prefix), natural log

@@ -55,6 +55,9 @@ _SIGS = {
     "dipaco_features_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
     "dipaco_path_prefix_features": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                               C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dipaco_static_scratch_bytes": (C.c_size_t, []),
+    "dipaco_path_prefix_features_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                                     C.c_int32, C.c_void_p, C.c_void_p]),
     "dipaco_score_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
     "dipaco_path_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -234,6 +237,16 @@ def dipaco_path_prefix_features(ctx: Context, path_master, path_lowp, tokens, ba
     _check(load().dipaco_path_prefix_features(ctx.handle, _ptr(path_master), _ptr(path_lowp), _ptr(tokens), batch, seq,
                                               _ptr(features_out), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def dipaco_static_scratch_bytes() -> int:
+    return load().dipaco_static_scratch_bytes()
+
+
+def dipaco_path_prefix_features_static(ctx: Context, path_master, path_lowp, tokens, batch: int, seq: int, features_out,
+                                       stream=None):
+    _check(load().dipaco_path_prefix_features_static(ctx.handle, _ptr(path_master), _ptr(path_lowp), _ptr(tokens), batch,
+                                                     seq, _ptr(features_out), _stream(stream)))
 
 
 def dipaco_score_workspace_bytes(ctx: Context, batch: int, seq: int) -> int:

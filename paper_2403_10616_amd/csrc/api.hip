@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -472,6 +473,57 @@ dipaco_status dipaco_path_prefix_features(dipaco_ctx* c, const float* master, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (lowprec) return run_features<bf16>(c, static_cast<const bf16*>(lowp), tokens, nullptr, B, S, features_out, nullptr, static_cast<char*>(ws), st);
   return run_features<float>(c, master, tokens, nullptr, B, S, features_out, nullptr, static_cast<char*>(ws), st);
+}
+
+// ---- router features for callers that cannot allocate ------------------------------------------------------
+// The activations of dipaco_path_prefix_features live in one file-scope device array instead of a caller's
+// workspace.  Every GPU holds its own copy of the array at its own address: the address is looked up once per device
+// (with that device current) and only that pointer is ever handed to kernels.
+namespace {
+constexpr size_t STATIC_SCRATCH_BYTES = DIPACO_STATIC_SCRATCH_BYTES;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+
+dipaco_status static_scratch(char** out) {
+  int device = -1;
+  DIPACO_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= STATIC_MAX_DEVICES) return dipaco::fail(DIPACO_EUNSUPPORTED, "device ordinal above 63");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    DIPACO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return dipaco::fail(DIPACO_EHIP, "static scratch has no usable device address");
+    g_scratch_ptr[device] = static_cast<char*>(p);
+  }
+  *out = g_scratch_ptr[device];
+  return DIPACO_OK;
+}
+}  // namespace
+
+size_t dipaco_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+dipaco_status dipaco_path_prefix_features_static(dipaco_ctx* c, const float* master, const void* lowp,
+                                                 const int32_t* tokens, int32_t B, int32_t S, float* features_out,
+                                                 void* stream) {
+  if (!c) return fail(DIPACO_EINVAL, "dipaco_path_prefix_features_static: NULL context");
+  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
+  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  const size_t need = make_feature_plan(c, B, S).total;
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(DIPACO_EWORKSPACE, "dipaco_path_prefix_features_static: this batch x seq needs " + std::to_string(need) +
+                                       " bytes of activations, the static scratch holds " +
+                                       std::to_string(STATIC_SCRATCH_BYTES) + "; use dipaco_path_prefix_features");
+  const bool lowprec = c->arch.compute == DIPACO_BF16;
+  TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
+  TRY(check_ptr(tokens, "tokens"));
+  TRY(check_ptr(features_out, "features_out"));
+  char* ws = nullptr;
+  TRY(static_scratch(&ws));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (lowprec) return run_features<bf16>(c, static_cast<const bf16*>(lowp), tokens, nullptr, B, S, features_out, nullptr, ws, st);
+  return run_features<float>(c, master, tokens, nullptr, B, S, features_out, nullptr, ws, st);
 }
 
 size_t dipaco_score_workspace_bytes(const dipaco_ctx* c, int32_t batch, int32_t seq) {
