@@ -106,3 +106,19 @@ def gaussian_mixture(N: int, D: int, K: int, noise_std: float, seed: int, dtype=
         e = min(N, s + step)
         z[s:e] = (c[comp[s:e]] + noise_std * rng.standard_normal((e - s, D), dtype=np.float32)).astype(dtype)
     return z, c.astype(dtype), comp.astype(np.int32)
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 values rounded to the nearest bf16-representable value (ties to even), returned as fp32: the bf16
+    configurations start from master weights that their 16-bit image represents exactly."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    u = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32)
+
+
+def sample_offsets(n: int, count: int, seed: int, stream: str) -> np.ndarray:
+    """`count` distinct sorted offsets in [0, n) (all of them when n <= count): which elements of a tensor the stored
+    oracle results keep."""
+    if n <= count:
+        return np.arange(n, dtype=np.int64)
+    return np.sort(_rng(seed, stream).choice(n, size=count, replace=False)).astype(np.int64)
