@@ -8,6 +8,7 @@ All draws use numpy's `default_rng(seed)` (or a (seed, stream) pair), generated 
 """
 from __future__ import annotations
 
+import hashlib
 import zlib
 from typing import Dict, Sequence, Tuple
 
@@ -122,3 +123,14 @@ def sample_offsets(n: int, count: int, seed: int, stream: str) -> np.ndarray:
     if n <= count:
         return np.arange(n, dtype=np.int64)
     return np.sort(_rng(seed, stream).choice(n, size=count, replace=False)).astype(np.int64)
+
+
+def input_hash(*arrays) -> str:
+    """SHA-256 over dtype, shape and bytes of the arrays: stored oracle results carry it, so that a test can tell
+    whether the inputs it has just drawn are the ones those results were computed from."""
+    h = hashlib.sha256()
+    for x in arrays:
+        x = np.ascontiguousarray(x)
+        h.update(str(x.dtype).encode() + str(x.shape).encode())
+        h.update(x.tobytes())
+    return h.hexdigest()

@@ -7,12 +7,19 @@
  *
  * Conventions common to every call
  *   - Every "device" pointer is HIP device memory owned by the caller; "host" pointers are ordinary host
- *     memory read during the call only.  The library allocates device memory in dipaco_create only (a few
- *     KB of tables) and frees it in dipaco_destroy.  It keeps no numerical state between calls: optimiser
- *     moments, momentum and step counters are arguments.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate on the host,
- *     enqueue kernels on that stream and return without synchronising.  A non-zero status means nothing
- *     was enqueued; dipaco_last_error() then describes why (per host thread).
+ *     memory read during the call only.  The library allocates and frees no device memory, in any call: scratch
+ *     comes from the caller's workspace arguments (one entry point uses a fixed device array instead, see
+ *     dipaco_path_prefix_features_static).  It keeps no numerical state between calls: optimiser moments,
+ *     momentum and step counters are arguments.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate every argument
+ *     and shape on the host first, then enqueue kernels on that stream and return without synchronising.
+ *     DIPACO_EINVAL / ESHAPE / EALIGN / EWORKSPACE / EUNSUPPORTED mean that nothing was enqueued.  DIPACO_EHIP
+ *     reports a failure of the HIP runtime itself (a launch or attribute call): kernels of the same call that
+ *     were enqueued before it still run, and the call's outputs are then undefined.  dipaco_last_error()
+ *     describes the last failure (per host thread).
+ *   - Thread safety: calls may be made from several host threads.  The dipaco_k_set_* switches of
+ *     dipaco_kernels.h are process-wide test and tuning hooks: changing them while another thread is inside
+ *     the library changes which kernel variant that thread's next launch takes, nothing else.
  *   - Device pointers must be 16-byte aligned.
  *   - Flat path buffer layout (elements): stem | level 1 | ... | level L | head, where
  *       stem  = tok_emb [vocab, d_model], pos_emb [max_seq, d_model]
@@ -33,7 +40,7 @@
 extern "C" {
 #endif
 
-typedef struct dipaco_ctx dipaco_ctx; /* opaque: shapes, offsets and small device tables; no numerical state */
+typedef struct dipaco_ctx dipaco_ctx; /* opaque, host-only: shapes and offsets; no numerical state */
 
 typedef enum {
   DIPACO_OK = 0,
@@ -58,8 +65,9 @@ typedef struct {
                                       Master weights, gradients and optimiser state are always fp32.     */
 } dipaco_arch;
 
-/* Requirements: d_model, n_heads*d_head, d_mlp, vocab multiples of 8; d_head in {32, 64, 128};
- * n_levels >= 1, every layers_per_level >= 0.  Otherwise DIPACO_ESHAPE.  Uses the current HIP device. */
+/* Requirements: d_model, n_heads*d_head, d_mlp, vocab multiples of 8; d_head in {32, 64, 128}; d_model <= 2048;
+ * vocab <= 65536; n_levels >= 1, every layers_per_level >= 0.  Otherwise DIPACO_ESHAPE.  Host-only: the context
+ * holds shapes and offsets, no device memory. */
 dipaco_status dipaco_create(dipaco_ctx** out, const dipaco_arch* arch);
 void dipaco_destroy(dipaco_ctx* ctx);
 
@@ -105,14 +113,15 @@ dipaco_status dipaco_compose_path(dipaco_ctx* ctx, const float* const* segment_p
  *   grads        device fp32 [param_count], overwritten (same layout as path_master; rows of pos_emb
  *                beyond seq get 0).
  *   workspace    device, >= dipaco_workspace_bytes(ctx, batch, seq), contents undefined on return.
- * seq <= max_seq.  Results are bit-reproducible from call to call on the same inputs. */
+ * seq <= max_seq; batch * seq <= 2^24 and batch * seq * (max(d_mlp, 3 * n_heads * d_head, vocab) + 1) < 2^32
+ * (DIPACO_ESHAPE otherwise).  Results are bit-reproducible from call to call on the same inputs. */
 dipaco_status dipaco_path_fwd_bwd(dipaco_ctx* ctx, const float* path_master, const void* path_lowp,
                                   const int32_t* tokens, const int32_t* targets, int32_t batch, int32_t seq,
                                   float* loss_out, float* token_nll_out, float* grads, void* workspace,
                                   size_t workspace_bytes, void* stream);
 
-/* Router features g(document) (appendix on routing: "the average of the hidden state from the last transformer block
- * ... over the first 32 tokens of a document"): the path's blocks are run forward on tokens [batch, seq] (seq = 32
+/* Router features g(document) (appendix on routing: the last block's hidden states averaged over a document's
+ * 32-token prefix): the path's blocks are run forward on tokens [batch, seq] (seq = 32
  * in the paper) and features_out[b, :] = mean over the seq positions of the residual stream that leaves the last
  * block (before the final LayerNorm; the head is not evaluated).  features_out: device fp32 [batch, d_model]; these
  * are the z of dipaco_route_prefix.  path_master / path_lowp as in dipaco_path_fwd_bwd.
@@ -152,8 +161,8 @@ dipaco_status dipaco_path_score(dipaco_ctx* ctx, const float* path_master, const
                                 const int32_t* targets, int32_t batch, int32_t seq, float* doc_loglik_out,
                                 float* token_nll_out, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Routing more often than once per document at evaluation (Section 2.4.3; appendix, "More frequent routing during
- * evaluation").  token_nll: device fp32 [n_paths, batch, seq], the per-position negative log-likelihoods that
+/* Routing more often than once per document at evaluation (Section 2.4.3; appendix on more frequent routing
+ * during evaluation).  token_nll: device fp32 [n_paths, batch, seq], the per-position negative log-likelihoods that
  * dipaco_path_score writes (token_nll_out) for each path on the same documents, i.e. -S_ijp.
  *   dipaco_window_targets: targets_out[b, j] (device int32 [batch, seq]) = argmax_p sum_{j' = j}^{min(seq, j + window) - 1}
  *     S_{b j' p}: the labels T_ij the token-level router is trained to transduce; lowest p on exact ties.  The window
@@ -192,15 +201,16 @@ dipaco_status dipaco_module_outer_step(float* theta, float* momentum, const floa
                                        const float* weights, int32_t n_paths, size_t n_elems, int32_t is_delta,
                                        float outer_lr, float outer_momentum, void* stream);
 
-/* The same outer step one path at a time (Section 5, "Online Parameter Gradient Averaging": a path's result is added
- * to the partial sum as soon as it is available), with the optional norm rescaling of Section 3.3:
+/* The same outer step one path at a time (Section 3.3, online parameter gradient averaging: a path's result joins
+ * the partial sum when it arrives, without waiting for the other paths), with the optional outer gradient norm
+ * rescaling of Section 2.7:
  *   dipaco_module_delta_accumulate:  delta_sum <- (first ? 0 : delta_sum) + weight * (theta_prev - input)   (is_delta = 0)
  *                                                                         + weight * input                  (is_delta = 1)
  *       weight: the path's un-normalised shard weight (1 for the uniform mean); theta_prev may be NULL when is_delta.
  *   dipaco_module_outer_apply:       Delta = norm_scale * delta_sum / weight_sum;
  *       momentum <- mu * momentum + Delta;   theta <- theta - outer_lr * (Delta + mu * momentum)
  *       weight_sum: the sum of the weights accumulated; norm_scale: 1, or sqrt(number of paths through the module)
- *       for "outer gradient norm rescaling" (read as a multiplication: averaging over more paths acts like a larger
+ *       for the norm rescaling (read as a multiplication: averaging over more paths acts like a larger
  *       batch, so the averaged step is made longer).
  * All buffers device fp32 [n_elems], 16-byte aligned; delta_sum is caller-owned scratch that lives across the calls.
  * With norm_scale = 1 the result equals dipaco_module_outer_step up to the order of the additions. */
@@ -217,7 +227,7 @@ dipaco_status dipaco_module_outer_apply(float* theta, float* momentum, const flo
  *   dipaco_module_desc: one module, as in dipaco_module_outer_step: theta / momentum device fp32 [n_elems], 16-byte
  *     aligned; inputs = HOST array of n_paths device pointers (fp32 [n_elems], 16-byte aligned); weights = HOST
  *     [n_paths] positive, or NULL for the plain mean; norm_scale multiplies the averaged Delta (1, or sqrt(paths
- *     through the module) for the rescaling of Section 3.3); n_elems may be 0.
+ *     through the module) for the rescaling of Section 2.7); n_elems may be 0.
  *   dipaco_outer_table_bytes: size of the table image for these modules (0 on invalid arguments).
  *   dipaco_outer_table_pack:  host-only; validates the descriptions and writes the image (normalised weights
  *     alpha_i = norm_scale * w_i / sum w in fp32, pointers, chunk offsets) into HOST memory `image`.  The caller copies
@@ -246,7 +256,12 @@ dipaco_status dipaco_outer_step_table(const void* table_host, const void* table_
  * argmin) in fp32.
  *   z device fp32 [N, D] row-major; centroids device fp32 [K, D]; idx_out device int32 [N];
  *   hist_out device int64 [K], overwritten; margin_out device fp32 [N] or NULL: second-best minus best score
- *   (+inf when K = 1).  D multiple of 4, 1 <= K <= 4096, N >= 0. */
+ *   (+inf when K = 1).  D multiple of 4, 1 <= K <= 4096, N >= 0.
+ *   Centroids must be finite.  A row of z that holds a NaN has no nearest centroid (every score is NaN, as it is
+ *   for infinite features that meet centroid entries of both signs): it is routed to centroid 0 (second choice 1 in
+ *   the top-2 form), counted there, and its margin is NaN, so that a caller can find and drop such rows.  Other rows
+ *   with infinite entries get an index in [0, K) and are counted once; which one is not specified.  Eq. 1 itself
+ *   assigns every finite document. */
 dipaco_status dipaco_route_prefix(const float* z, const float* centroids, int64_t N, int32_t D, int32_t K,
                                   int32_t* idx_out, int64_t* hist_out, float* margin_out, void* stream);
 
@@ -273,7 +288,8 @@ dipaco_status dipaco_route_prefix_top(const float* z, int64_t ldz, const float* 
  *     gradients dweights_out [K, D] (NULL: not computed), dbias_out [K], all fp32 on the device; the caller applies
  *     them with the optimiser it likes (dipaco_module_outer_step with one ready-made delta is plain / Nesterov SGD).
  *     Since dbias = mean softmax - label frequencies, descending on the bias alone (dweights_out = NULL) is the
- *     "bias term trained to match the target document-to-path distribution": it stops where the mean predicted
+ *     bias fit of the appendix on routing (a bias trained until the predicted document-to-path distribution is the
+ *     target one): it stops where the mean predicted
  *     distribution equals the labels'.  labels device int32 [N]; a label outside [0, K) drops its document from loss
  *     and gradients (the mean stays over N).  z device fp32 [N, D] contiguous.  D and K multiples of 8, K <= 4096,
  *     N * max(D, K) < 2^32.  workspace: device, >= dipaco_router_workspace_bytes(N, D, K) bytes (0 = invalid shape). */
@@ -284,8 +300,8 @@ dipaco_status dipaco_router_logistic_grad(const float* z, const int32_t* labels,
                                           int64_t N, int32_t D, int32_t K, float* loss_out, float* dweights_out,
                                           float* dbias_out, void* workspace, size_t workspace_bytes, void* stream);
 
-/* One k-means update ("we perform k-Means on the features z", Section 2.4.1; with dipaco_route_prefix as the
- * assignment step this is one Lloyd iteration): centroids[k] <- mean of the rows z_n with idx[n] = k, in place; a
+/* One k-means update (Section 2.4.1 fits the prototypes c_i by k-means on the features z; with dipaco_route_prefix
+ * as the assignment step this is one Lloyd iteration): centroids[k] <- mean of the rows z_n with idx[n] = k, in place; a
  * centroid without rows keeps its value.  idx values are clamped to [0, K).  counts_out: device int64 [K] or NULL.
  * The sums are formed in a fixed order (stable counting sort by cluster, partial sums of 512 rows added in order):
  * results are bit-reproducible.  workspace: device, >= dipaco_kmeans_workspace_bytes(N, D, K) bytes.

@@ -437,7 +437,8 @@ def route_prefix(z, centroids):
 
 
 def route_prefix_top2(z, centroids):
-    """The two closest centroids of every row (overlapping shards, Section 2.4.4: "we use the top-2 choices").
+    """The two closest centroids of every row (overlapping shards of Section 2.4.4, where a document joins the
+    shards of its two best routing choices).
 
     idx2[n] = (closest, second closest) under the order (squared distance, index): exact ties go to the lower
     index; the second entry is -1 when there is only one centroid.  hist[k] = number of rows that have k as either
@@ -487,7 +488,8 @@ def kmeans_objective(z, idx, centroids):
 def outer_step_streaming(theta_prev, momentum, inputs: Sequence[np.ndarray], weights, is_delta: bool,
                          outer_lr: float, outer_momentum: float, norm_scale: float = 1.0):
     """The outer update with the paths' results added one at a time, in arrival order, to a running weighted sum
-    (Section 5, online averaging), and the optional rescaling of the averaged outer gradient (Section 3.3):
+    (Section 3.3, online parameter gradient averaging), and the optional rescaling of the averaged outer gradient
+    (Section 2.7, outer gradient norm rescaling):
     Delta = norm_scale * (sum_i w_i d_i) / (sum_i w_i), d_i = theta_prev - theta_i (or the ready-made delta);
     then Nesterov as in outer_step.  norm_scale = sqrt(P_le) is the paper's rescaling read as a multiplication."""
     theta_prev = np.asarray(theta_prev, dtype=F64)
@@ -581,7 +583,7 @@ def logistic_loss_grad(z, labels, weights, bias):
 def outer_step_modules(modules, outer_lr: float, outer_momentum: float):
     """Outer update of every module of a grid (Algorithm 1: the loop over levels and experts; Section 2.6: a
     path-specific module has a single path and is updated by the same rule).  `modules` is a sequence of dicts with
-    theta, momentum, inputs, weights (or None), is_delta and optionally norm_scale (Section 3.3, read as a
+    theta, momentum, inputs, weights (or None), is_delta and optionally norm_scale (Section 2.7, read as a
     multiplication of the averaged Delta).  Returns a list of (theta, momentum), one per module; modules do not
     interact."""
     out = []

@@ -170,7 +170,7 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
   TRY(gemm<T>(buf(p.y), W + c->w_head, buf(p.logits), T_, V, d, d, V, V, false, false, nullptr, nullptr, nullptr,
               nullptr, 0, false, 1, nullptr, st));
   TRY(launch_count_valid(targets, T_, n_valid, st));
-  TRY(launch_softmax_xent<T>(buf(p.logits), targets, n_valid, nll, T_, V, st));
+  TRY(launch_softmax_xent<T>(buf(p.logits), targets, n_valid, nll, T_, V, true, st));
   TRY(launch_mean_loss(nll, n_valid, loss_out, T_, st));
 
   // ---------------- backward ----------------
@@ -269,11 +269,21 @@ static dipaco_status run_features(const dipaco_ctx* c, const T* W, const int* to
   TRY(launch_layernorm_fwd<T>(x, W + c->lnf_g, W + c->lnf_b, buf(p.h), fbuf(p.mean), fbuf(p.rstd), T_, d, a.ln_eps, st));
   TRY(gemm<T>(buf(p.h), W + c->w_head, buf(p.logits), T_, V, d, d, V, V, false, false, nullptr, nullptr, nullptr, nullptr,
               0, false, 1, nullptr, st));
-  int* n_valid = reinterpret_cast<int*>(ws + p.n_valid);
   float* nll = nll_out ? nll_out : fbuf(p.nll);
-  TRY(launch_count_valid(targets, T_, n_valid, st));
-  TRY(launch_softmax_xent<T>(buf(p.logits), targets, n_valid, nll, T_, V, st));
+  TRY(launch_softmax_xent<T>(buf(p.logits), targets, nullptr, nll, T_, V, false, st));   // no gradient: logits are only read
   return launch_doc_score(nll, out, B, S, st);
+}
+
+// Everything about a [batch, seq] input that a kernel of the path would refuse, checked before the first launch: the
+// kernels index their operands with 32-bit element offsets, so tokens x (widest activation row) stays below 2^32.
+static dipaco_status check_batch_shape(const dipaco_ctx* c, int B, int S, bool with_head) {
+  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
+  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  const int64_t widest = std::max<int64_t>(std::max<int64_t>(c->arch.d_mlp, 3 * (int64_t)c->A),
+                                           std::max<int64_t>(c->arch.d_model, with_head ? c->arch.vocab : 0));
+  if ((int64_t)B * S * (widest + 1) >= (1LL << 32))
+    return fail(DIPACO_ESHAPE, "batch*seq times the widest activation row (d_mlp, 3*heads*d_head, vocab) must stay below 2^32");
+  return DIPACO_OK;
 }
 
 static dipaco_status check_ptr(const void* p, const char* name) {
@@ -300,6 +310,9 @@ dipaco_status dipaco_create(dipaco_ctx** out, const dipaco_arch* arch) {
   if (a.d_head != 32 && a.d_head != 64 && a.d_head != 128) return fail(DIPACO_ESHAPE, "d_head must be 32, 64 or 128");
   if (a.d_model % 8 || a.d_mlp % 8 || a.vocab % 8) return fail(DIPACO_ESHAPE, "d_model, d_mlp and vocab must be multiples of 8");
   if (a.d_model > 2048) return fail(DIPACO_ESHAPE, "d_model above 2048 is not supported");
+  if (a.vocab > 65536) return fail(DIPACO_ESHAPE, "vocab above 65536 is not supported");
+  if ((int64_t)a.vocab * a.d_model >= (1LL << 31) || (int64_t)a.d_mlp * a.d_model >= (1LL << 31))
+    return fail(DIPACO_ESHAPE, "a weight matrix above 2^31 elements is not supported");
   if (!(a.ln_eps > 0.f)) return fail(DIPACO_EINVAL, "ln_eps must be positive");
   dipaco_ctx* c = new dipaco_ctx();
   c->arch = a;
@@ -436,8 +449,7 @@ dipaco_status dipaco_path_fwd_bwd(dipaco_ctx* c, const float* master, const void
                                   const int32_t* targets, int32_t B, int32_t S, float* loss_out, float* nll_out,
                                   float* grads, void* ws, size_t ws_bytes, void* stream) {
   if (!c) return fail(DIPACO_EINVAL, "dipaco_path_fwd_bwd: NULL context");
-  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
-  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  TRY(check_batch_shape(c, B, S, true));
   const bool lowprec = c->arch.compute == DIPACO_BF16;
   TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
   TRY(check_ptr(tokens, "tokens"));
@@ -462,8 +474,7 @@ dipaco_status dipaco_path_prefix_features(dipaco_ctx* c, const float* master, co
                                           int32_t B, int32_t S, float* features_out, void* ws, size_t ws_bytes,
                                           void* stream) {
   if (!c) return fail(DIPACO_EINVAL, "dipaco_path_prefix_features: NULL context");
-  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
-  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  TRY(check_batch_shape(c, B, S, false));
   const bool lowprec = c->arch.compute == DIPACO_BF16;
   TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
   TRY(check_ptr(tokens, "tokens"));
@@ -508,8 +519,7 @@ dipaco_status dipaco_path_prefix_features_static(dipaco_ctx* c, const float* mas
                                                  const int32_t* tokens, int32_t B, int32_t S, float* features_out,
                                                  void* stream) {
   if (!c) return fail(DIPACO_EINVAL, "dipaco_path_prefix_features_static: NULL context");
-  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
-  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  TRY(check_batch_shape(c, B, S, false));
   const size_t need = make_feature_plan(c, B, S).total;
   if (need > STATIC_SCRATCH_BYTES)
     return fail(DIPACO_EWORKSPACE, "dipaco_path_prefix_features_static: this batch x seq needs " + std::to_string(need) +
@@ -535,8 +545,7 @@ dipaco_status dipaco_path_score(dipaco_ctx* c, const float* master, const void* 
                                 const int32_t* targets, int32_t B, int32_t S, float* doc_loglik_out, float* nll_out,
                                 void* ws, size_t ws_bytes, void* stream) {
   if (!c) return fail(DIPACO_EINVAL, "dipaco_path_score: NULL context");
-  if (B < 1 || S < 1 || S > c->arch.max_seq) return fail(DIPACO_ESHAPE, "batch >= 1 and 1 <= seq <= max_seq required");
-  if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
+  TRY(check_batch_shape(c, B, S, true));
   const bool lowprec = c->arch.compute == DIPACO_BF16;
   TRY(check_ptr(lowprec ? lowp : static_cast<const void*>(master), lowprec ? "path_lowp" : "path_master"));
   TRY(check_ptr(tokens, "tokens"));

@@ -561,7 +561,7 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
 
 }  // namespace
 
-int g_attn_single_block = 1;   // measured 3-5 % faster than pairing a long with a short block
+std::atomic<int> g_attn_single_block{1};   // test / tuning hook; measured 3-5 % faster than pairing a long with a short block
 void set_attention_single_block(int on) { g_attn_single_block = on ? 1 : 0; }
 
 dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, int B, int S, int H, hipStream_t s) {
@@ -581,14 +581,9 @@ dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf
   const int single = g_attn_single_block;
   const int nqb = (S + 127) / 128;
   dim3 grid = single ? dim3(B * H, nqb) : dim3((nqb + 1) / 2, B * H);   // one or two query (key) blocks per workgroup
-  static bool attr_set = false;
-  if (!attr_set) {
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, DQ_STAGES * 2 * TILE_BYTES));
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, DKV_STAGES * DKV_STAGE));
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> dq_lds{0}, dkv_lds{0};
+  if (dipaco_status st = ensure_dynamic_lds(reinterpret_cast<const void*>(attn_bwd_dq_mfma), DQ_STAGES * 2 * TILE_BYTES, dq_lds)) return st;
+  if (dipaco_status st = ensure_dynamic_lds(reinterpret_cast<const void*>(attn_bwd_dkv_mfma), DKV_STAGES * DKV_STAGE, dkv_lds)) return st;
   attn_bwd_dq_mfma<<<grid, AT_THREADS, DQ_STAGES * 2 * TILE_BYTES, s>>>(qkv, o, d_o, lse, dqkv, dsum, colsum_out ? colsum_partial : nullptr, S, H, single);
   DIPACO_LAUNCH_CHECK();
   attn_bwd_dkv_mfma<<<grid, AT_THREADS, DKV_STAGES * DKV_STAGE, s>>>(qkv, d_o, dsum, dqkv, colsum_out ? colsum_partial : nullptr, S, H, single);

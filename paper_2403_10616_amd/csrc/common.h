@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <string>
 
 #include "../../include/dipaco.h"
@@ -28,6 +29,18 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
     if (_st != DIPACO_OK) return _st;                                 \
   } while (0)
 #define DIPACO_LAUNCH_CHECK() DIPACO_HIP(hipGetLastError())
+
+// Raises a kernel's dynamic-LDS limit to `bytes`, once per device: `done` is a call site's own bit mask of the
+// devices already served.  Host threads may race here; the worst case is a repeated, identical attribute call.
+inline dipaco_status ensure_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int device = 0;
+  DIPACO_HIP(hipGetDevice(&device));
+  const unsigned long long bit = 1ull << (device & 63);
+  if (done.load(std::memory_order_acquire) & bit) return DIPACO_OK;
+  DIPACO_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  done.fetch_or(bit, std::memory_order_release);
+  return DIPACO_OK;
+}
 
 // ---- scalar conversions (device) -------------------------------------------------------------------
 __device__ __forceinline__ float to_f32(float x) { return x; }

@@ -216,12 +216,8 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   constexpr size_t smem_epi = (size_t)WGM * WGN * 32 * (size_t)(BN / WGN + 4) * sizeof(float);
   constexpr size_t smem = smem_loop > smem_epi ? smem_loop : smem_epi;
   auto kern = gemm_kernel<T, TC, TA, TB, BM, BN, WGM, WGN, NS>;
-  static bool attr_set = false;   // one attribute call per instantiation and process
-  if (!attr_set) {
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)smem));
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> lds_set{0};   // per instantiation
+  if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return e;
   GemmDev g;
   g.A = a.A; g.B = a.B; g.C = a.C; g.M = a.M; g.N = a.N; g.K = a.K;
   g.lda = a.lda; g.ldb = a.ldb; g.ldc = a.ldc;
@@ -246,7 +242,7 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   return DIPACO_OK;
 }
 
-int g_forced_tile = 0;
+std::atomic<int> g_forced_tile{0};   // test / tuning hook (dipaco_k_set_gemm_tile), not a per-call setting
 
 // Measured on the training step's shapes: the eight-wave 256 x 256 tile is the fastest wherever its workgroups
 // can fill most of the chip's 256 compute units; below that the 128 x 128 tile (two workgroups per unit) wins.

@@ -306,12 +306,8 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_ROWB;
   static_assert((size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
   auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)smem));
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> lds_set{0};   // per instantiation
+  if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return e;
   GemmDev g;
   g.A = a.A; g.B = a.B; g.C = a.C; g.M = a.M; g.N = a.N; g.K = a.K;
   g.lda = a.lda; g.ldb = a.ldb; g.ldc = a.ldc;
@@ -349,7 +345,7 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   return DIPACO_OK;
 }
 
-int g_dlds_shape = 0;   // 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 (weight gradients only)
+std::atomic<int> g_dlds_shape{0};   // test / tuning hook; 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 (weight gradients only)
 
 // Weight gradients with a side that is not a multiple of 256 (896 = 7 x 128): 128 x 512 tiles of 1 x 8 waves, or
 // 512 x 128 tiles of 4 x 2 waves, cut C into whole tiles only, so that five K slices fit on the chip where the

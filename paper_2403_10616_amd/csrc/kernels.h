@@ -157,10 +157,11 @@ template <typename T> dipaco_status launch_mean_pool(const T* x, float* out, int
 dipaco_status launch_doc_score(const float* nll, float* out, int B, int S, hipStream_t s);
 // n_valid[0] = #targets >= 0
 dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStream_t s);
-// logits [rows, V] (T) -> nll[rows] fp32 and, in place, dlogits = (softmax - onehot)/n_valid (0 on ignored rows)
+// logits [rows, V] (T) -> nll[rows] fp32 and, when want_grad, in place dlogits = (softmax - onehot)/n_valid (0 on
+// ignored rows); without want_grad the logits are only read (n_valid is then not used)
 template <typename T>
 dipaco_status launch_softmax_xent(T* logits, const int* targets, const int* n_valid, float* nll, int rows, int V,
-                                  hipStream_t s);
+                                  bool want_grad, hipStream_t s);
 // loss = sum(nll) / n_valid, fixed-order tree
 dipaco_status launch_mean_loss(const float* nll, const int* n_valid, float* loss, int rows, hipStream_t s);
 // token/position embedding gradients (deterministic).  ints: embed_bwd_scratch_ints(rows, vocab) scratch.

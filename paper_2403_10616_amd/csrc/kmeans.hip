@@ -263,12 +263,8 @@ dipaco_status launch_key_offsets(const int* keys, long n, int n_keys, int* count
   if (n > 0) {
     const unsigned blocks = (unsigned)((n + KC_BLOCK - 1) / KC_BLOCK);
     if (n_keys <= KC_MAX_LDS) {
-      static bool attr_set = false;
-      if (!attr_set) {
-        DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(key_count_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, KC_MAX_LDS * (int)sizeof(int)));
-        attr_set = true;
-      }
+      static std::atomic<unsigned long long> lds_set{0};
+      if (dipaco_status st = ensure_dynamic_lds(reinterpret_cast<const void*>(key_count_kernel<true>), KC_MAX_LDS * (int)sizeof(int), lds_set)) return st;
       key_count_kernel<true><<<blocks, 256, (size_t)n_keys * sizeof(int), s>>>(keys, n, n_keys, count);
     } else {
       key_count_kernel<false><<<blocks, 256, 0, s>>>(keys, n, n_keys, count);

@@ -248,6 +248,14 @@ __global__ void __launch_bounds__(R_THREADS) route_kernel(const float* __restric
       o.i2 = TOP2 ? red_i2[w * RBM + tid] : NO_INDEX;
       b = best_merge<TOP2>(b, o);
     }
+    // A row none of whose scores compares below +inf (NaN or infinite features: a diverged path) never entered an
+    // entry.  It is given the first centroid (the first two with TOP2) and a NaN margin, which is what the plain
+    // definition's argmin over a row of NaN distances yields; it must not reach the histogram with an unset index.
+    if (b.i1 == NO_INDEX) {
+      b.i1 = 0;
+      b.i2 = K > 1 ? 1 : NO_INDEX;
+      b.s1 = b.s2 = __builtin_nanf("");
+    }
     if (TOP2) {
       const bool has2 = b.i2 != NO_INDEX;
       idx[2 * (m0 + tid)] = b.i1;
@@ -399,14 +407,9 @@ dipaco_status launch_route(const float* z, int64_t ldz, const float* c, const fl
   if (st != DIPACO_OK) return st;
   if (N == 0) return DIPACO_OK;
   constexpr size_t smem = 2 * (size_t)R_STAGE;
-  static bool attr_set = false;
-  if (!attr_set) {
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    DIPACO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> lds_one{0}, lds_two{0};
+  if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(route_kernel<false>), (int)smem, lds_one)) return e;
+  if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(route_kernel<true>), (int)smem, lds_two)) return e;
   const int64_t blocks = (N + RBM - 1) / RBM;
   if (blocks > 0x7fffffffLL) return fail(DIPACO_ESHAPE, "route: N too large");
   auto* h = reinterpret_cast<unsigned long long*>(hist);

@@ -3,6 +3,8 @@
 // All are HBM-bound: I/O in the activation type T (fp32 or bf16), arithmetic in fp32, 16-byte accesses.
 #include <algorithm>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace dipaco {
@@ -363,7 +365,8 @@ template <> __device__ __forceinline__ float softmax_exp<float>(float x) { retur
 template <> __device__ __forceinline__ float softmax_exp<bf16>(float x) {
   return __builtin_amdgcn_exp2f(x * 1.4426950408889634f);
 }
-template <typename T, int NV>
+// GRAD = false: the negative log-likelihood alone (scoring passes); the logits are left as they are.
+template <typename T, int NV, bool GRAD>
 __global__ void __launch_bounds__(NV > 0 ? XENT_THREADS : ROW_THREADS)
 softmax_xent_kernel(T* __restrict__ logits, const int* __restrict__ targets, const int* __restrict__ n_valid,
                     float* __restrict__ nll, int V) {
@@ -378,7 +381,8 @@ softmax_xent_kernel(T* __restrict__ logits, const int* __restrict__ targets, con
     float zero[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) zero[i] = 0.f;
-    for (int c = threadIdx.x * VEC; c < V; c += NTH * VEC) store_vec16(lr + c, zero);
+    if (GRAD)
+      for (int c = threadIdx.x * VEC; c < V; c += NTH * VEC) store_vec16(lr + c, zero);
     if (threadIdx.x == 0) nll[row] = 0.f;
     return;
   }
@@ -422,6 +426,7 @@ softmax_xent_kernel(T* __restrict__ logits, const int* __restrict__ targets, con
   se = block_reduce(se, red, false);
   const int t = tgt >= V ? V - 1 : tgt;
   if (threadIdx.x == 0) nll[row] = logf(se) - (to_f32(lr[t]) - mx);
+  if (!GRAD) return;
   __syncthreads();   // lr[t] is read before anyone overwrites it
   const float inv = 1.0f / se;
   const float scale = 1.0f / (float)n_valid[0];
@@ -479,6 +484,7 @@ __global__ void __launch_bounds__(1024) mean_loss_kernel(const float* __restrict
 // of a Zipf batch (thousands of positions) are spread over the workgroup without any atomics.
 constexpr int TG_WAVES = 16;
 constexpr int TG_UNROLL = 8;   // row loads in flight per wave
+constexpr int TG_MAX_D = 2048;   // widest model: 16 partial rows of 2048 floats = 128 KB of the 160 KB of LDS
 template <typename T>
 __global__ void __launch_bounds__(TG_WAVES * WAVE) tok_grad_kernel(const T* __restrict__ dx,
                                                                    const int* __restrict__ offsets,
@@ -600,14 +606,19 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
   // the kernel keeps NIT chunks per lane of seven row-shaped quantities in registers: narrow models take the
   // instantiation with half (a quarter) of them and twice (four times) the waves per SIMD
   int n_blocks = 0;
-  auto run = [&](auto kern) -> dipaco_status {
+  // resident workgroups per compute unit of each instantiation, remembered with the LDS size they were asked for
+  // (packed lds << 8 | resident; a host thread that loses a race merely asks again)
+  static std::atomic<unsigned long long> occupancy[3];
+  auto run = [&](auto kern, int variant) -> dipaco_status {
     // Rows per workgroup: LN_BWD_ROWS, unless that gives a little more than a whole number of rounds of resident
     // workgroups (1024 workgroups over 768 slots run as two rounds): then as many rows as fill the slots once.
-    static int resident = 0;   // per instantiation
+    const unsigned long long seen = occupancy[variant].load(std::memory_order_relaxed);
+    int resident = (seen >> 8) == lds ? (int)(seen & 255) : 0;
     if (resident == 0) {
       int nb = 0;
       DIPACO_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, ROW_THREADS, lds));
-      resident = nb > 0 ? nb : 1;
+      resident = nb > 0 ? (nb < 255 ? nb : 255) : 1;
+      occupancy[variant].store(((unsigned long long)lds << 8) | (unsigned)resident, std::memory_order_relaxed);
     }
     const long slots = 256L * resident;
     int rpb = LN_BWD_ROWS;
@@ -621,9 +632,9 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
     return DIPACO_OK;
   };
   dipaco_status st;
-  if (d <= WAVE * VEC * NIT / 4) st = run(ln_bwd_kernel<T, NIT / 4>);
-  else if (d <= WAVE * VEC * NIT / 2) st = run(ln_bwd_kernel<T, NIT / 2>);
-  else st = run(ln_bwd_kernel<T, NIT>);
+  if (d <= WAVE * VEC * NIT / 4) st = run(ln_bwd_kernel<T, NIT / 4>, 0);
+  else if (d <= WAVE * VEC * NIT / 2) st = run(ln_bwd_kernel<T, NIT / 2>, 1);
+  else st = run(ln_bwd_kernel<T, NIT>, 2);
   if (st != DIPACO_OK) return st;
   DIPACO_LAUNCH_CHECK();
   const int blocks = n_blocks;
@@ -661,11 +672,16 @@ dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStr
 
 template <typename T>
 dipaco_status launch_softmax_xent(T* logits, const int* targets, const int* n_valid, float* nll, int rows, int V,
-                                  hipStream_t s) {
+                                  bool want_grad, hipStream_t s) {
   const size_t vectors = ((size_t)V * sizeof(T) + 15) / 16;
-  if (vectors <= 4 * (size_t)XENT_THREADS) softmax_xent_kernel<T, 4><<<rows, XENT_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
-  else if (vectors <= 8 * (size_t)XENT_THREADS) softmax_xent_kernel<T, 8><<<rows, XENT_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
-  else softmax_xent_kernel<T, 0><<<rows, ROW_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+  auto go = [&](auto grad) {
+    constexpr bool G = decltype(grad)::value;
+    if (vectors <= 4 * (size_t)XENT_THREADS) softmax_xent_kernel<T, 4, G><<<rows, XENT_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+    else if (vectors <= 8 * (size_t)XENT_THREADS) softmax_xent_kernel<T, 8, G><<<rows, XENT_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+    else softmax_xent_kernel<T, 0, G><<<rows, ROW_THREADS, 0, s>>>(logits, targets, n_valid, nll, V);
+  };
+  if (want_grad) go(std::true_type{});
+  else go(std::false_type{});
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -694,6 +710,11 @@ dipaco_status launch_embed_bwd(const T* dx, const int* tokens, float* d_tok, flo
   if (st != DIPACO_OK) return st;
   st = launch_stable_sort_indices(tokens, rows, vocab, order, sort_scratch, s);
   if (st != DIPACO_OK) return st;
+  // 16 partial rows of d floats: above 64 KB (d_model > 1024) the kernel's dynamic-LDS limit has to be raised
+  static std::atomic<unsigned long long> tg_lds{0};
+  st = ensure_dynamic_lds(reinterpret_cast<const void*>(tok_grad_kernel<T>), TG_WAVES * TG_MAX_D * (int)sizeof(float), tg_lds);
+  if (st != DIPACO_OK) return st;
+  if (d > TG_MAX_D) return fail(DIPACO_ESHAPE, "embedding gradient: d_model above 2048");
   tok_grad_kernel<T><<<vocab, TG_WAVES * WAVE, TG_WAVES * d * sizeof(float), s>>>(dx, offsets, order, d_tok, d);
   DIPACO_LAUNCH_CHECK();
   pos_grad_kernel<T><<<max_seq, 128, 0, s>>>(dx, d_pos, B, S, d);
@@ -745,7 +766,7 @@ dipaco_status launch_mean_pool(const T* x, float* out, int B, int S, int d, hipS
                                                  T*, float*, float*, float*, float*, int, int, hipStream_t);        \
   template dipaco_status launch_colsum<T>(const T*, float*, float*, int, int, hipStream_t);                          \
   template dipaco_status launch_mean_pool<T>(const T*, float*, int, int, int, hipStream_t);                          \
-  template dipaco_status launch_softmax_xent<T>(T*, const int*, const int*, float*, int, int, hipStream_t);          \
+  template dipaco_status launch_softmax_xent<T>(T*, const int*, const int*, float*, int, int, bool, hipStream_t);          \
   template dipaco_status launch_embed_bwd<T>(const T*, const int*, float*, float*, int*, int, int, int, int, int,    \
                                              hipStream_t);
 INSTANTIATE(float)

@@ -14,7 +14,6 @@ the values at up to SAMPLES_PER_TENSOR seeded offsets (every element of the smal
 """
 from __future__ import annotations
 
-import hashlib
 import os
 import sys
 import time
@@ -37,13 +36,7 @@ def say(msg):
     print(time.strftime("%H:%M:%S"), msg, flush=True)
 
 
-def input_hash(*arrays) -> str:
-    h = hashlib.sha256()
-    for x in arrays:
-        x = np.ascontiguousarray(x)
-        h.update(str(x.dtype).encode() + str(x.shape).encode())
-        h.update(x.tobytes())
-    return h.hexdigest()
+input_hash = gen.input_hash
 
 
 def arch_of(cfg) -> orc.Arch:

@@ -1,4 +1,6 @@
 """Helpers shared by the GPU parity tests: device buffers, tolerances, oracle/GPU architecture twins."""
+import os
+
 import numpy as np
 import torch
 
@@ -77,6 +79,54 @@ def per_tensor_rel(layout, got, want, skip_zero=True):
             assert not np.any(g), f"{name}: expected all zeros"
             continue
         r = rel_l2(g, w)
+        if r > worst:
+            worst, where = r, name
+    return worst, where
+
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def load_golden(name):
+    """Stored oracle results (written by tests/golden/make_golden.py from the oracle alone)."""
+    path = os.path.join(GOLDEN, name)
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path}: run `python tests/golden/make_golden.py`")
+    return np.load(path, allow_pickle=False)
+
+
+def sampled_tensor_errors(gold, got_flat, samples_key, norms_key=None, got_norm=None):
+    """Per tensor, on the stored sample of its elements: L2 error relative to the sample's L2 norm, largest absolute
+    error relative to the sample's largest magnitude and, when the stored full norms are given, the ratio of the whole
+    tensor's norm to the oracle's.  Returns a list of (name, rel_l2, rel_max, norm_ratio); tensors whose oracle values
+    are all zero are checked to be zero."""
+    names = [str(n) for n in gold["tensor_names"]]
+    starts, flat = gold["sample_starts"], gold["sample_offsets"]
+    want_all = gold[samples_key]
+    out = []
+    for t, name in enumerate(names):
+        sl = slice(int(starts[t]), int(starts[t + 1]))
+        want = want_all[sl]
+        got = np.asarray(got_flat[flat[sl]], dtype=np.float64)
+        if not np.any(want):
+            assert not np.any(got), f"{name}: expected zeros"
+            continue
+        rel = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+        mx = float(np.abs(got - want).max() / np.abs(want).max())
+        ratio = float(got_norm(name) / gold[norms_key][t]) if norms_key is not None else 1.0
+        out.append((name, rel, mx, ratio))
+    return out
+
+
+def per_tensor_maxabs(layout, got, want):
+    """max over tensors of max|got - want| / max|want|, and the tensor where it occurs (all-zero tensors skipped)."""
+    worst, where = 0.0, None
+    for name, (off, shape, _) in layout.items():
+        n = int(np.prod(shape))
+        w = np.asarray(want[off:off + n], dtype=np.float64)
+        if not np.any(w):
+            continue
+        r = float(np.abs(np.asarray(got[off:off + n], dtype=np.float64) - w).max() / np.abs(w).max())
         if r > worst:
             worst, where = r, name
     return worst, where

@@ -16,7 +16,7 @@ def _lines(name):
 
 
 def test_module_sharing_of_the_three_level_toy_example():
-    """Section 2.5: the order in which the module choices collapse into one path number.  With level 1 as the most
+    """Section 2.6: the order in which the module choices collapse into one path number.  With level 1 as the most
     significant digit the oracle reproduces every sharing set of the illustration; the other order would give
     {1, 3} for the first module of level 2."""
     rows = _lines("module_sharing_toy_example.txt")

@@ -164,7 +164,8 @@ def attn_blocks(request):
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
 @pytest.mark.parametrize("B,S,H,dh", [(2, 64, 2, 32), (1, 200, 3, 64), (2, 77, 1, 128), (1, 1, 2, 64), (1, 333, 2, 64),
-                                      (2, 1024, 2, 64), (1, 130, 1, 64), (1, 900, 1, 64)])
+                                      (2, 1024, 2, 64), (1, 130, 1, 64), (1, 900, 1, 64), (1, 2048, 2, 64),
+                                      (1, 1100, 1, 64)])
 def test_attention_forward_backward(dtype, B, S, H, dh, attn_blocks):
     print(f"attention dtype={dtype} B={B} S={S} H={H} dh={dh} blocks={attn_blocks}", flush=True)
     A = H * dh
@@ -176,6 +177,10 @@ def test_attention_forward_backward(dtype, B, S, H, dh, attn_blocks):
     a, o_ref, lse_ref, probs = _attn_ref(qr, B, S, H, dh)
     tol = 2e-5 if dtype == dp.F32 else 1e-2
     assert rel_l2(host(o), o_ref) <= tol
+    # every element: the probabilities enter the second product rounded to bf16 (relative 2^-9 each, averaging out
+    # over a row) and the result is rounded once more
+    o_err = np.abs(host(o) - o_ref).max() / np.abs(o_ref).max()
+    assert o_err <= (1e-5 if dtype == dp.F32 else 8e-3), o_err
     assert np.abs(host(lse) - lse_ref).max() <= (1e-5 if dtype == dp.F32 else 2e-2)
     dqkv = torch.empty_like(qkv)
     dsum = torch.empty(2 * B * H * ((S + 127) // 128 * 128), dtype=torch.float32, device=DEV)
@@ -191,9 +196,117 @@ def test_attention_forward_backward(dtype, B, S, H, dh, attn_blocks):
     got = host(dqkv)
     for name, sl in (("dq", slice(0, A)), ("dk", slice(A, 2 * A)), ("dv", slice(2 * A, 3 * A))):
         assert rel_l2(got[:, sl], ref[:, sl]) <= (2e-5 if dtype == dp.F32 else 2e-2), name
+        top = np.abs(ref[:, sl]).max()
+        worst = np.abs(got[:, sl] - ref[:, sl]).max() / (top if top > 0 else 1.0)      # S = 1: dq and dk are zero
+        print(f"  {name}: max-abs error / max |{name}| = {worst:.2e}, o: {o_err:.2e}", flush=True)
+        assert worst <= (2e-5 if dtype == dp.F32 else 2e-2), (name, worst)
     # column sums of dqkv (the QKV bias gradient), taken in the kernels' epilogues where the matrix-core path runs
     scale = np.abs(ref).sum(0).max()
     assert np.abs(host(cs) - ref.sum(0)).max() <= (1e-5 if dtype == dp.F32 else 1e-2) * scale
     dqkv2 = torch.empty_like(qkv)
     dp.dipaco_k_attention_bwd(dtype, qkv, o, d_o, lse, dqkv2, dsum, B, S, H, dh)            # without the sums
     assert torch.equal(dqkv2, dqkv)
+
+
+# ---- the benchmarked kernels at the step's own shapes, element by element ---------------------------------------
+def _bf16_ulp(x):
+    """Spacing of bf16 numbers at |x| (8 significant bits)."""
+    mag = np.maximum(np.abs(x), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(mag)) - 7)
+
+
+def _assert_within_one_bf16_ulp(got, ref, what):
+    """The kernels accumulate exactly representable bf16 products in fp32 and round once: the stored value is the
+    fp64 result rounded to bf16, give or take the fp32 accumulation error (which can tip a rounding, and is all that
+    is left of elements near zero: 2e-5 of the result's typical magnitude covers it)."""
+    got = got.astype(np.float64)
+    slack = 2e-5 * math.sqrt(float(np.mean(ref * ref)))
+    excess = np.abs(got - ref) - (_bf16_ulp(np.maximum(np.abs(ref), np.abs(got))) + slack)
+    worst = int(np.argmax(excess))
+    assert excess.flat[worst] <= 0, (what, np.unravel_index(worst, ref.shape), got.flat[worst], ref.flat[worst])
+
+
+STEP_M = 32768
+# (name, M, N, K): the forward products of one block at config 2 and a 4096-row slice of the vocabulary head
+STEP_FORWARD = [("qkv", STEP_M, 2688, 896), ("out_proj", STEP_M, 896, 896), ("mlp_up", STEP_M, 3584, 896),
+                ("mlp_down", STEP_M, 896, 3584), ("head_rows", 4096, 32000, 896)]
+
+
+@pytest.mark.parametrize("name,M,N,K", STEP_FORWARD, ids=[s[0] for s in STEP_FORWARD])
+def test_bf16_forward_products_of_the_step_element_by_element(name, M, N, K):
+    print(f"step-shape forward product {name} M={M} N={N} K={K}", flush=True)
+    A, Ar = _rand((M, K), 21, dp.BF16)
+    B, Br = _rand((K, N), 22, dp.BF16)
+    Br *= 0.05                                   # weight-sized entries keep GELU in its curved range
+    B = torch.from_numpy(Br).to(torch.bfloat16)
+    Br = B.to(torch.float64).numpy()
+    B = B.to(DEV)
+    bias, br = _rand((N,), 23, dp.BF16)
+    resid, rr = _rand((M, N), 24, dp.BF16)
+    ref = Ar @ Br
+    C = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    if name == "head_rows":                      # plain product
+        dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, A, B, C)
+        _assert_within_one_bf16_ulp(host(C), ref, name)
+        return
+    if name == "mlp_up":                         # + bias, GELU out, GELU' saved
+        U = torch.empty_like(C)
+        dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, A, B, C, bias=bias, aux_out=U, act=3)
+        u = ref + br
+        cdf = 0.5 * (1 + erf(u / math.sqrt(2)))
+        _assert_within_one_bf16_ulp(host(C), u * cdf, name + " GELU")
+        _assert_within_one_bf16_ulp(host(U), cdf + u * np.exp(-0.5 * u * u) / math.sqrt(2 * math.pi), name + " GELU'")
+        return
+    if name == "qkv":                            # + bias
+        dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, A, B, C, bias=bias)
+        _assert_within_one_bf16_ulp(host(C), ref + br, name)
+        return
+    dp.dipaco_k_gemm(dp.BF16, False, False, False, M, N, K, A, B, C, bias=bias, resid=resid)   # + bias + residual
+    _assert_within_one_bf16_ulp(host(C), ref + br + rr, name)
+
+
+# input-gradient products dX = dY W^T (W stored [N_out = rows here, K]) of one block, and a slice of the head's
+STEP_INPUT_GRAD = [("d_qkv_in", STEP_M, 896, 2688), ("d_out_proj_in", STEP_M, 896, 896), ("d_mlp_up_in", STEP_M, 896, 3584),
+                   ("d_mlp_down_in", STEP_M, 3584, 896), ("d_head_in_rows", 4096, 896, 32000)]
+
+
+@pytest.mark.parametrize("name,M,N,K", STEP_INPUT_GRAD, ids=[s[0] for s in STEP_INPUT_GRAD])
+def test_bf16_input_gradient_products_of_the_step_element_by_element(name, M, N, K):
+    print(f"step-shape input-gradient product {name} M={M} N={N} K={K}", flush=True)
+    A, Ar = _rand((M, K), 25, dp.BF16)
+    Bt, Btr = _rand((N, K), 26, dp.BF16)
+    ref = Ar @ Btr.T
+    C = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    if name != "d_mlp_down_in":
+        dp.dipaco_k_gemm(dp.BF16, False, True, False, M, N, K, A, Bt, C)
+        _assert_within_one_bf16_ulp(host(C), ref, name)
+        return
+    # the product that writes dU: multiplied by the saved GELU', with the column sums (the gradient of b_up)
+    U, Ur = _rand((M, N), 27, dp.BF16)
+    cs = torch.full((N,), 77.0, dtype=torch.float32, device=DEV)
+    scratch = torch.full((((M + 31) // 32) * N,), float("nan"), dtype=torch.float32, device=DEV)
+    dp.dipaco_k_gemm_colsum(dp.BF16, False, True, M, N, K, A, Bt, C, None, None, None, U, 4, cs, scratch)
+    ref = ref * Ur
+    _assert_within_one_bf16_ulp(host(C), ref, name)
+    assert np.abs(host(cs) - ref.sum(0)).max() <= 1e-5 * np.abs(ref).sum(0).max()   # fp32 sums of unrounded values
+
+
+STEP_WEIGHT_GRAD = [("d_w_qkv", 896, 2688), ("d_w_o", 896, 896), ("d_w_up", 896, 3584), ("d_w_down", 3584, 896)]
+
+
+@pytest.mark.parametrize("name,M,N", STEP_WEIGHT_GRAD, ids=[s[0] for s in STEP_WEIGHT_GRAD])
+def test_bf16_weight_gradient_products_of_the_step_element_by_element(name, M, N):
+    """dW = X^T dY over the 32768 tokens, fp32 out, with the split-K plan the step launches them with."""
+    K = STEP_M
+    print(f"step-shape weight-gradient product {name} M={M} N={N} K={K}", flush=True)
+    At, Atr = _rand((K, M), 28, dp.BF16)
+    B, Br = _rand((K, N), 29, dp.BF16)
+    plan = dp.dipaco_k_gemm_split_plan(M, N, K, 32)
+    splits = max(plan["slices"]) if plan["tile"][0] else 8
+    C = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    partial = torch.empty((splits, M, N), dtype=torch.float32, device=DEV)
+    dp.dipaco_k_gemm(dp.BF16, True, False, True, M, N, K, At, B, C, splits=splits, partial=partial)
+    ref = Atr.T @ Br
+    rms = math.sqrt(float(np.mean(ref * ref)))
+    err = np.abs(host(C).astype(np.float64) - ref)
+    assert err.max() <= 1e-4 * rms, (name, np.unravel_index(int(np.argmax(err)), ref.shape), err.max() / rms)

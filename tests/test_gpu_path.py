@@ -14,7 +14,7 @@ import torch
 import dipaco_inputs as gen
 import paper_2403_10616_amd as dp
 from oracle import dipaco_oracle as orc
-from gpu_util import DEV, PathState, dev, host, make_arch, per_tensor_rel, rel_l2
+from gpu_util import DEV, PathState, dev, host, make_arch, per_tensor_maxabs, per_tensor_rel, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -25,6 +25,9 @@ SHAPES = {
     "one_level": dict(layers_per_level=(2,), d_model=64, n_heads=1, d_head=128, d_mlp=64, vocab=64, max_seq=16),
     # a vocabulary row too long for the register-resident cross-entropy kernel: the three-pass kernel runs
     "big_vocab": dict(layers_per_level=(1,), d_model=64, n_heads=2, d_head=32, d_mlp=64, vocab=40000, max_seq=8),
+    # the widest models the library takes: the embedding gradient's 16 partial rows need 96 / 128 KB of LDS
+    "d1536": dict(layers_per_level=(1,), d_model=1536, n_heads=2, d_head=64, d_mlp=264, vocab=512, max_seq=24),
+    "d2048": dict(layers_per_level=(1, 1), d_model=2048, n_heads=1, d_head=128, d_mlp=136, vocab=264, max_seq=16),
 }
 
 
@@ -41,13 +44,16 @@ def _batch(cfg, B, S, seed, mask_prefix=0, zipf=False):
 
 
 @pytest.mark.parametrize("name,B,S,mask", [("ragged", 3, 50, 0), ("ragged", 2, 56, 5), ("wide", 2, 160, 32),
-                                           ("one_level", 5, 16, 0), ("one_level", 1, 1, 0), ("big_vocab", 2, 8, 1)])
+                                           ("one_level", 5, 16, 0), ("one_level", 1, 1, 0), ("big_vocab", 2, 8, 1),
+                                           ("d1536", 3, 24, 0), ("d2048", 4, 16, 2)])
 def test_fp32_loss_and_gradients_match_oracle(name, B, S, mask):
     print(f"fp32 path {name} B={B} S={S} mask={mask}", flush=True)
     cfg = SHAPES[name]
     a, ctx = make_arch(cfg, dp.F32)
     lay = orc.param_layout(a)
-    theta = gen.random_params(orc.param_count(a), seed=5, scale=0.08)
+    # entries of N(0, 0.08), narrower for the widest models so that pre-activations stay O(1) (at width 2048 a scale
+    # of 0.08 gives attention scores of +-13, a softmax so peaked that fp32 gradients lose three digits on both sides)
+    theta = gen.random_params(orc.param_count(a), seed=5, scale=min(0.08, 1.5 / math.sqrt(cfg["d_model"])))
     # LayerNorm gains near 1 so that activations keep a realistic scale
     for n_, (off, shape, _) in lay.items():
         if n_.endswith("_g"):
@@ -146,7 +152,8 @@ def test_config1_full_round_matches_oracle():
         assert rel_l2(host(th_d) - theta_prev, th_o - theta_prev) <= 2e-3, (level, e)
 
 
-@pytest.mark.parametrize("name,B,S,mask", [("ragged", 3, 50, 4), ("wide", 2, 160, 0)])
+@pytest.mark.parametrize("name,B,S,mask", [("ragged", 3, 50, 4), ("wide", 2, 160, 0), ("d1536", 3, 24, 0),
+                                           ("d2048", 4, 16, 2)])
 def test_bf16_loss_and_gradients_close_to_oracle(name, B, S, mask):
     print(f"bf16 path {name} B={B} S={S}", flush=True)
     cfg = SHAPES[name]
@@ -162,7 +169,10 @@ def test_bf16_loss_and_gradients_close_to_oracle(name, B, S, mask):
     assert abs(loss - o_loss) <= 2e-2 * abs(o_loss)
     assert abs(loss - o_loss) <= 2e-3 * abs(o_loss)      # in practice an order of magnitude closer
     worst, where = per_tensor_rel(lay, host(st.grads), o_grad)
-    assert worst <= 6e-2, (where, worst)
+    assert worst <= 3e-2, (where, worst)                    # observed 4e-3 .. 1.2e-2
+    worst_abs, where_abs = per_tensor_maxabs(lay, host(st.grads), o_grad)     # every element, on its tensor's scale
+    print(f"  worst tensor rel-L2 {worst:.2e} ({where}), worst max-abs/max {worst_abs:.2e} ({where_abs})", flush=True)
+    assert worst_abs <= 3e-2, (where_abs, worst_abs)        # observed 4e-3 .. 1.2e-2
     g0 = host(st.grads).copy()
     assert st.fwd_bwd(tok, tgt) == loss and np.array_equal(g0, host(st.grads))
 

@@ -360,3 +360,38 @@ def test_route_and_top2_are_exact_on_integer_points(N, D, K):
     o_idx2, o_hist2 = orc.route_prefix_top2(z, c)
     assert np.array_equal(idx2, o_idx2) and np.array_equal(hist2, o_hist2)
     assert np.array_equal(margin2.astype(np.float64), o_margin)
+
+
+def test_rows_without_a_nearest_centroid_go_to_centroid_zero_with_nan_margin():
+    """A document whose features hold a NaN (a diverged path) has no nearest centroid: every score is NaN.  The library
+    routes it to centroid 0 (second choice 1), counts it there and marks it with a NaN margin -- what the plain
+    definition's argmin over a row of NaN distances gives -- and the other rows are not disturbed.  Infinite features
+    also end in NaN scores when they meet centroid entries of both signs; a row they leave with scores of -inf gets
+    some index in range, and the histogram stays consistent."""
+    print("route: rows with NaN / infinite features", flush=True)
+    z, c, _ = gen.gaussian_mixture(700, 64, 40, 0.3, seed=9)
+    bad = [3, 255, 699]
+    z[3, 5] = np.nan
+    z[255, :] = np.inf
+    z[699, 63] = np.nan
+    z[256, 0] = -np.inf                      # one infinite entry: unspecified, but in range and counted once
+    good = np.setdiff1d(np.arange(700), bad + [256])
+    idx, hist, margin = _run(z, c)
+    with np.errstate(invalid="ignore"):
+        o_idx, o_hist, o_margin = orc.route_prefix(z, c)
+    assert np.array_equal(o_idx[bad], [0, 0, 0]) and np.all(np.isnan(o_margin[bad]))      # the definition's own answer
+    assert np.array_equal(idx[bad], [0, 0, 0]) and np.all(np.isnan(margin[bad]))
+    assert np.array_equal(idx[good], o_idx[good]) and 0 <= idx[256] < 40
+    assert hist.sum() == 700 and np.array_equal(hist, np.bincount(idx, minlength=40))
+    # top-2 form: (0, 1) for such rows, both memberships counted
+    idx2 = torch.full((700 * 2,), -5, dtype=torch.int32, device=DEV)
+    hist2 = torch.full((40,), -7, dtype=torch.int64, device=DEV)
+    m2 = torch.zeros(700, dtype=torch.float32, device=DEV)
+    dp.dipaco_route_prefix_top(dev(z), 64, dev(c), 700, 64, 40, 2, idx2, hist2, m2)
+    i2 = host(idx2).reshape(700, 2)
+    with np.errstate(invalid="ignore"):
+        o2, _ = orc.route_prefix_top2(z, c)
+    assert np.array_equal(o2[[3, 699]], [[0, 1]] * 2)          # NaN rows: the definition's own answer
+    assert np.array_equal(i2[bad], [[0, 1]] * 3) and np.all(np.isnan(host(m2)[bad]))
+    assert np.array_equal(i2[good], o2[good]) and i2[256].min() >= 0 and i2[256].max() < 40
+    assert np.array_equal(host(hist2), np.bincount(i2.ravel(), minlength=40)) and host(hist2).sum() == 1400

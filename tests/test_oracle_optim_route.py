@@ -465,3 +465,22 @@ def test_window_targets_and_chunk_scores_special_cases():
     ch = [[0, 2, 1]] * n                                           # chunks [0,5) [5,10) [10,12)
     got = orc.chunk_routed_scores(S, ch, 5)
     assert np.allclose(got, S[0, :, :5].sum(1) + S[2, :, 5:10].sum(1) + S[1, :, 10:].sum(1), atol=1e-13)
+
+
+def test_route_rows_of_nan_distances_take_the_first_centroid():
+    """What eq. (1) written out with numpy gives for a document whose features hold a NaN (every distance is NaN):
+    the first centroid, a NaN margin, and (first, second) centroid in the top-2 form.  The library documents the same
+    rule for such rows; rows of finite features are not affected by their presence."""
+    rng = np.random.default_rng(3)
+    c = rng.standard_normal((6, 5))
+    z = rng.standard_normal((9, 5))
+    clean_idx, _, clean_margin = orc.route_prefix(z, c)
+    z_bad = z.copy()
+    z_bad[4, 2] = np.nan
+    with np.errstate(invalid="ignore"):
+        idx, hist, margin = orc.route_prefix(z_bad, c)
+        idx2, _ = orc.route_prefix_top2(z_bad, c)
+    assert idx[4] == 0 and np.isnan(margin[4]) and tuple(idx2[4]) == (0, 1)
+    keep = np.arange(9) != 4
+    assert np.array_equal(idx[keep], clean_idx[keep]) and np.array_equal(margin[keep], clean_margin[keep])
+    assert hist.sum() == 9
