@@ -190,10 +190,12 @@ def test_config5_full_round_against_stored_oracle_results():
     theta, lay = _bf16_params(cfg, a, cfg["seed"])
     bounds = orc.segment_bounds(a)
     seqs = gen.zipf_tokens((steps, B, S + 1), cfg["vocab"], cfg["zipf_s"], cfg["seed"])
-    gold = load_golden("config5_oracle.npz")
+    try:
+        gold = load_golden("config5_oracle.npz")
+    except FileNotFoundError as e:          # about three hours of oracle time: absent from a fresh checkout until written
+        pytest.skip(str(e))
     assert gen.input_hash(theta, seqs) == str(gold["input_sha256"]), "inputs differ from the stored results' inputs"
-    done = int(gold["steps_done"])          # the generator stores the chain step by step
-    assert done == steps, "the stored chain is incomplete: rerun tests/golden/make_golden.py 5"
+    assert int(gold["steps_done"]) == steps, "the stored chain is incomplete: rerun tests/golden/make_golden.py 5"
     o_losses = gold["losses"]
     st = PathState(ctx, theta, B, S)
     losses = []
