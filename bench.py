@@ -75,6 +75,8 @@ def bench_path_step(args):
     cfg = gen.CONFIGS[2]
     B, S = cfg["batch"], cfg["seq"]
     ctx = dp.Context(**_arch_kwargs(cfg, dp.BF16))
+    if args.gemm_tile:
+        dp.dipaco_k_set_gemm_tile(args.gemm_tile)
     n = dp.dipaco_path_param_count(ctx)
     layout = {}
     for i in range(dp.dipaco_tensor_count(ctx)):
@@ -710,6 +712,9 @@ def bench_gemm(args):
         splits = args.splits
         partial = torch.empty(splits * M * N, dtype=torch.float32, device=dev)
 
+    if args.gemm_tile:
+        dp.dipaco_k_set_gemm_tile(args.gemm_tile)
+
     def step():
         dp.dipaco_k_gemm(dp.BF16, ta, tb, out_f32, M, N, K, a, b, c, bias, resid, aux_out, aux_in, act, splits, partial)
     for _ in range(args.warmup):
@@ -740,6 +745,8 @@ def bench_attention(args):
     B, S, H, dh = cfg["batch"], args.seq or cfg["seq"], cfg["n_heads"], cfg["d_head"]
     if args.seq:
         B = max(1, B * cfg["seq"] // S)
+    if args.batch:
+        B = args.batch
     dev = "cuda"
     A = H * dh
     qkv = torch.empty(B * S * 3 * A, dtype=torch.bfloat16, device=dev).normal_()
@@ -789,10 +796,12 @@ def main():
     ap.add_argument("--epilogue", default="none", choices=["none", "bias", "gelu", "dgelu", "resid"])
     ap.add_argument("--operands", default="normal", choices=["normal", "zeros"])
     ap.add_argument("--splits", type=int, default=1)
+    ap.add_argument("--gemm-tile", type=int, default=0, help="gemm / path_step workloads: force a tile shape (dipaco_k_set_gemm_tile)")
     ap.add_argument("--pass", default="fwd", choices=["fwd", "bwd"])
     ap.add_argument("--attn-blocks", type=int, default=None, choices=[0, 1],
                     help="attention workload: 0 = a long and a short causal block per workgroup, 1 = one block, longest first")
     ap.add_argument("--seq", type=int, default=0)
+    ap.add_argument("--batch", type=int, default=0, help="attention workload: sequences (default: the config's token count / seq)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

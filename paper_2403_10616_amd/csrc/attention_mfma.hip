@@ -8,6 +8,10 @@
 //   dK, dV:        S   = Q.K^T  (rows = queries, columns = keys)  ->  dV^T += dO^T.P,   dK^T += Q^T.dS
 // Softmax state (running max, sum, log-sum-exp, D = rowsum(dO*O)) is per query: per lane in the first family, per
 // accumulator row in the second.  Exponentials are base 2 with log2(e) folded into the score scale.
+// On this chip matrix-core and vector-ALU instructions of the waves of one SIMD do not run side by side (measured:
+// 16 MFMAs + 256 FMAs take the sum of their times at two or more waves per SIMD), so every vector instruction of the
+// inner loops is paid in full: the forward kernel adds its row sums two bf16 values per instruction on the packed
+// probabilities, walks its two stages with compile-time LDS offsets, and leaves the sum over a lane pair to the end.
 //
 // One workgroup = 4 waves, each wave owns 32 queries (or 32 keys).  K / V (or Q / dO) tiles of 64 rows x 64
 // columns go from global memory straight into LDS (16-byte global_load_lds: lane l of a wave-level load writes
@@ -24,6 +28,8 @@
 // of read are then free of bank conflicts (rows two apart land in different 64-byte groups for the transposing
 // read; the lane groups that a ds_read_b128 serves together see eight different swizzles per row parity).
 // No atomics: every output element has exactly one writer and a fixed summation order.
+#include <type_traits>
+
 #include "kernels.h"
 #include "mma_tile.h"
 
@@ -76,46 +82,54 @@ template <int LPW> __device__ __forceinline__ void wait_stages_but(int n) {
   else wait_vmcnt<0>();
 }
 
+// global -> LDS with a wave-uniform base address and a 32-bit per-lane byte offset
+__device__ __forceinline__ void load16_to_lds_at(const bf16* base, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
+}
+
 // This wave's share of the loads of a stage made of two 64x64 tiles: 4 of the 16 wave-level loads (each fills 8
 // tile rows = 1024 LDS bytes).  Load i of wave w is number j = w + 4i: tile j / 8, rows 8 (j % 8) .. + 7.
+// A lane keeps one 32-bit byte offset per load (its row and 16-byte chunk inside a tile that starts at the operand's
+// row 0); the tile's first row is added to the wave-uniform base address, so a stage costs four vector registers.
 struct StageLoader {
-  const bf16* col[4];   // per lane: tile source + the 16-byte chunk this lane fetches (row 0 of the operand)
-  const bf16* src[4];   // per lane: the same for this lane's row of the tile that starts at operand row 0
-  int row[4];           // per lane: row inside the tile
-  uint32_t dst[4];      // wave-uniform: byte offset of the load inside the stage
+  uint32_t off[4];      // per lane: (row inside the tile) * row bytes + chunk * 16
+  uint32_t chunk[4];    // per lane: chunk * 16 alone (ragged last tile)
 };
-__device__ __forceinline__ StageLoader make_loader(const bf16* tile0, const bf16* tile1, long ld0, long ld1, int wave,
-                                                   int lane) {
+__device__ __forceinline__ int loader_row(int i, int wave, int lane) { return 8 * ((wave + 4 * i) & 7) + (lane >> 3); }
+__device__ __forceinline__ StageLoader make_loader(long ld0, long ld1, int wave, int lane) {
   StageLoader L;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int j = wave + 4 * i;
-    const int rit = 8 * (j & 7) + (lane >> 3);
-    const int chunk = (lane & 7) ^ swz64(rit);
-    L.col[i] = (j < 8 ? tile0 : tile1) + chunk * 8;
-    L.src[i] = L.col[i] + rit * (j < 8 ? ld0 : ld1);
-    L.row[i] = rit;
-    L.dst[i] = (uint32_t)((j >> 3) * TILE_BYTES + (j & 7) * 1024);
+    const int rit = loader_row(i, wave, lane);
+    L.chunk[i] = (uint32_t)(((lane & 7) ^ swz64(rit)) * 16);
+    L.off[i] = (uint32_t)(rit * (j < 8 ? ld0 : ld1) * 2) + L.chunk[i];
   }
   return L;
 }
+// tile0 / tile1: the two operands (row 0 of this sequence and head), ld0 / ld1 their row strides in elements.
 // Rows at or beyond rows_total re-read the last valid row: callers give such rows zero weight (masked
 // probabilities, -inf statistics), so any finite value will do, and no branch surrounds a load.  Only the last
-// tile of an operand can stick out; every other tile adds a wave-uniform offset to the per-lane pointers.
-__device__ __forceinline__ void issue_stage(const StageLoader& L, int row0, int rows_total, long ld0, long ld1, int wave,
-                                            uint32_t stage_addr) {
+// tile of an operand can stick out; every other tile only moves the wave-uniform base.
+// Byte offsets are 32-bit: rows_total * row stride * 2 stays below 2^32 (checked by the launchers).
+__device__ __forceinline__ void issue_stage(const StageLoader& L, const bf16* tile0, const bf16* tile1, int row0,
+                                            int rows_total, long ld0, long ld1, int wave, int lane, uint32_t stage_addr) {
   if (row0 + 64 <= rows_total) {   // wave-uniform
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const long ld = (wave + 4 * i) < 8 ? ld0 : ld1;
-      load16_to_lds(L.src[i] + row0 * ld, stage_addr + L.dst[i]);
+      const bool first = (wave + 4 * i) < 8;   // wave-uniform
+      const int j = wave + 4 * i;
+      load16_to_lds_at((first ? tile0 : tile1) + (long)row0 * (first ? ld0 : ld1), L.off[i],
+                       stage_addr + (uint32_t)((j >> 3) * TILE_BYTES + (j & 7) * 1024));
     }
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int r = min(row0 + L.row[i], rows_total - 1);
-      const long ld = (wave + 4 * i) < 8 ? ld0 : ld1;
-      load16_to_lds(L.col[i] + (long)r * ld, stage_addr + L.dst[i]);
+      const bool first = (wave + 4 * i) < 8;
+      const int j = wave + 4 * i;
+      const int r = min(row0 + loader_row(i, wave, lane), rows_total - 1);
+      load16_to_lds_at(first ? tile0 : tile1, (uint32_t)r * (uint32_t)((first ? ld0 : ld1) * 2) + L.chunk[i],
+                       stage_addr + (uint32_t)((j >> 3) * TILE_BYTES + (j & 7) * 1024));
     }
   }
 }
@@ -176,6 +190,29 @@ __device__ __forceinline__ void mma_transposed(f32x16 (&acc)[2], const char* til
   }
 }
 
+// The same with the probabilities already packed to bf16: pk[t][0 / 1] = pack8<0 / 8>(src[t]).
+__device__ __forceinline__ void mma_transposed_packed(f32x16 (&acc)[2], const char* tile, const TrOff& to,
+                                                      const uint4 (&pk)[2][2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+      acc[dt] = mfma16(tr_read(tile, to, dt, 2 * t), pk[t][0], acc[dt]);
+      acc[dt] = mfma16(tr_read(tile, to, dt, 2 * t + 1), pk[t][1], acc[dt]);
+    }
+}
+// acc + the eight bf16 values of v, two per instruction (v_dot2c_f32_bf16 with a vector of ones: products with 1 and
+// the fp32 additions are exact operations on the rounded values, the ones the matrix core then multiplies)
+typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float add8_bf16(float acc, const uint4& v) {
+  const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.x), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.y), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.z), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.w), ones, acc, false);
+  return acc;
+}
+
 // store 4 consecutive head columns (accumulator elements 4g..4g+3 of a transposed-output tile) as bf16
 __device__ __forceinline__ void store4(bf16* dst, const f32x16& v, int g, float scale) {
   bf16x4 o = {(bf16)(v[4 * g + 0] * scale), (bf16)(v[4 * g + 1] * scale), (bf16)(v[4 * g + 2] * scale),
@@ -230,7 +267,7 @@ __device__ __forceinline__ void block_column_sums(const f32x16 (&ot)[2], float s
 // ---- forward ---------------------------------------------------------------------------------------------------
 constexpr int FWD_STAGES = 2, DQ_STAGES = 2, DKV_STAGES = 2;
 
-__global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+__global__ void __launch_bounds__(AT_THREADS, 3) attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                                float* __restrict__ lse, int S, int H, int single) {
   constexpr int NS = FWD_STAGES;
   __shared__ __attribute__((aligned(16))) char smem[NS][2][TILE_BYTES];   // [stage][K | V]
@@ -245,7 +282,9 @@ __global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __res
   const FragOff fo = frag_offsets(lane);
   const TrOff to = tr_offsets(lane);
   const uint32_t smem_addr = (uint32_t)(uintptr_t)&smem[0][0][0];
-  const StageLoader L = make_loader(base + A, base + 2 * A, ld, ld, wave, lane);
+  const StageLoader L = make_loader(ld, ld, wave, lane);
+  const bf16* const ktile = base + A;
+  const bf16* const vtile = base + 2 * A;
   // A workgroup takes a long and a short query block (block x from the end, then block x from the start), so that
   // every workgroup walks the same number of tiles whatever the causal triangle gives its blocks.
   const int nqb = (S + 127) / 128;
@@ -271,13 +310,15 @@ __global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __res
 
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
-    if (s < ntiles) issue_stage(L, s * 64, S, ld, ld, wave, smem_addr + s * 2 * TILE_BYTES);
-  int cur = 0;
-  for (int kt = 0; kt < ntiles; ++kt, cur = cur + 1 == NS ? 0 : cur + 1) {
+    if (s < ntiles) issue_stage(L, ktile, vtile, s * 64, S, ld, ld, wave, lane, smem_addr + s * 2 * TILE_BYTES);
+  static_assert(NS == 2, "the tile loop below is unrolled over the two stages, so that every LDS offset is a constant");
+  // one key / value tile; CUR: the stage it sits in
+  auto tile = [&](auto CUR, int kt) {
+    constexpr int cur = decltype(CUR)::value;
     wait_stages_but<4>(min(NS - 2, ntiles - 1 - kt));
     __syncthreads();   // tile kt is in LDS; nobody still reads the stage of tile kt - 1, which is refilled now
     if (kt + NS - 1 < ntiles)
-      issue_stage(L, (kt + NS - 1) * 64, S, ld, ld, wave, smem_addr + (cur == 0 ? NS - 1 : cur - 1) * 2 * TILE_BYTES);
+      issue_stage(L, ktile, vtile, (kt + NS - 1) * 64, S, ld, ld, wave, lane, smem_addr + (cur == 0 ? NS - 1 : cur - 1) * 2 * TILE_BYTES);
     const int kv0 = kt * 64;
     if (kv0 <= qw0 + 31) {   // wave-uniform: at least one query of this wave sees this tile
       const char* k_ = smem[cur][0];
@@ -297,7 +338,7 @@ __global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __res
       }
       float mx = fmaxf(st[0][0], st[1][0]);
 #pragma unroll
-      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(st[0][e], st[1][e]));
+      for (int e = 1; e < 16; ++e) mx = fmaxf(fmaxf(mx, st[0][e]), st[1][e]);   // one three-input maximum each
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
       // The reference exponent m only has to stay within 2^8 of the true running maximum (probabilities then stay
       // below 256, harmless in fp32 sums and in bf16 operands, and the final O / l and lse do not depend on the
@@ -312,23 +353,33 @@ __global__ void __launch_bounds__(AT_THREADS, 4) attn_fwd_mfma(const bf16* __res
           for (int e = 0; e < 16; ++e) ot[dt][e] *= corr;
         m = mn;
       }
-      float rs = 0.f;
+      // probabilities, rounded to bf16 once: the rounded values are both what the matrix core multiplies with V and
+      // what the row sum adds up (two per instruction), so numerator and denominator of the softmax agree exactly.
+      // l is this lane's half of the row (keys 4h + 0..3 of every eight); the halves meet after the last tile.
+      uint4 pk[2][2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, -m));
-          st[t][e] = p;
-          rs += p;
-        }
-      rs += __shfl_xor(rs, 32, WAVE);
-      l += rs;
-      mma_transposed(ot, v_, to, st);
+        for (int e = 0; e < 16; ++e) st[t][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][e], sc, -m));
+        pk[t][0] = pack8<0>(st[t]);
+        pk[t][1] = pack8<8>(st[t]);
+        l = add8_bf16(add8_bf16(l, pk[t][0]), pk[t][1]);
+      }
+      mma_transposed_packed(ot, v_, to, pk);
     }
+  };
+  for (int kt = 0; kt < ntiles; kt += 2) {
+    tile(std::integral_constant<int, 0>{}, kt);
+    if (kt + 1 < ntiles) tile(std::integral_constant<int, 1>{}, kt + 1);
   }
-  if (q < S) {
-    store_transposed_out(o + ((long)b * S + q) * A + hd * DH, ot, h, 1.0f / l);
-    if (h == 0) lse[(long)bh * S + q] = (m + __builtin_amdgcn_logf(l)) * LN2;   // v_log_f32 is log2
+  l += __shfl_xor(l, 32, WAVE);
+  // the output addresses are formed from here on (an opaque copy of the row index: formed before the loop they would
+  // sit in sixteen registers through it)
+  int q_out = q;
+  asm volatile("" : "+v"(q_out));
+  if (q_out < S) {
+    store_transposed_out(o + ((long)b * S + q_out) * A + hd * DH, ot, h, 1.0f / l);
+    if (h == 0) lse[(long)bh * S + q_out] = (m + __builtin_amdgcn_logf(l)) * LN2;   // v_log_f32 is log2
   }
   }
 }
@@ -353,7 +404,9 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
   const FragOff fo = frag_offsets(lane);
   const TrOff to = tr_offsets(lane);
   const uint32_t smem_addr = (uint32_t)(uintptr_t)dq_smem;
-  const StageLoader L = make_loader(base + A, base + 2 * A, ld, ld, wave, lane);
+  const StageLoader L = make_loader(ld, ld, wave, lane);
+  const bf16* const ktile = base + A;
+  const bf16* const vtile = base + 2 * A;
   const int nqb = (S + 127) / 128;
   for (int pass = 0; pass < 2; ++pass) {   // a long and a short query block per workgroup (see the forward kernel)
   const int qb = pass == 0 ? nqb - 1 - bx : bx;
@@ -399,13 +452,13 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dq_mfma(const bf16* __
 
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
-    if (s < ntiles) issue_stage(L, s * 64, S, ld, ld, wave, smem_addr + s * 2 * TILE_BYTES);
+    if (s < ntiles) issue_stage(L, ktile, vtile, s * 64, S, ld, ld, wave, lane, smem_addr + s * 2 * TILE_BYTES);
   int cur = 0;
   for (int kt = 0; kt < ntiles; ++kt, cur = cur + 1 == NS ? 0 : cur + 1) {
     wait_stages_but<4>(min(NS - 2, ntiles - 1 - kt));
     __syncthreads();   // tile kt is in LDS; nobody still reads the stage of tile kt - 1, which is refilled now
     if (kt + NS - 1 < ntiles)
-      issue_stage(L, (kt + NS - 1) * 64, S, ld, ld, wave, smem_addr + (cur == 0 ? NS - 1 : cur - 1) * 2 * TILE_BYTES);
+      issue_stage(L, ktile, vtile, (kt + NS - 1) * 64, S, ld, ld, wave, lane, smem_addr + (cur == 0 ? NS - 1 : cur - 1) * 2 * TILE_BYTES);
     const int kv0 = kt * 64;
     if (kv0 <= qw0 + 31) {
       const char* k_ = smem[cur][0];
@@ -471,9 +524,9 @@ __global__ void __launch_bounds__(AT_THREADS, 2) attn_bwd_dkv_mfma(const bf16* _
   const long Sp = (long)nkb * 128;
   const float* stat_src = dsum + ((wave & 1) ? 0 : (long)n_bh * Sp) + bh * Sp + lane;
   const uint32_t stat_dst = 2 * TILE_BYTES + ((wave & 1) ? 256 : 0);
-  const StageLoader L = make_loader(base, gbase, ld, A, wave, lane);
+  const StageLoader L = make_loader(ld, A, wave, lane);
   auto issue = [&](int qt, int stage) {
-    issue_stage(L, qt * 64, S, ld, A, wave, smem_addr + stage * DKV_STAGE);
+    issue_stage(L, base, gbase, qt * 64, S, ld, A, wave, lane, smem_addr + stage * DKV_STAGE);
     load4_to_lds(stat_src + qt * 64, smem_addr + stage * DKV_STAGE + stat_dst);
   };
   for (int pass = 0; pass < 2; ++pass) {   // an early (long) and a late (short) key block per workgroup

@@ -386,7 +386,17 @@ __device__ __forceinline__ void gemm_epilogue_dispatch(const f32x16 (&acc)[TM][T
     }
   }
 #undef DIPACO_EPI
-  if constexpr (std::is_same<TC, bf16>::value) gemm_epilogue<bf16, TC, TM, TN, WN>(acc, stg, lane, row0, col0, split, g);
+  // the general function only where a wave owns four row blocks (the kernels' standard shapes); launches of other
+  // shapes are restricted on the host to the combinations above (gemm_epilogue_is_fixed)
+  if constexpr (std::is_same<TC, bf16>::value && TM == 4) gemm_epilogue<bf16, TC, TM, TN, WN>(acc, stg, lane, row0, col0, split, g);
+}
+
+// host: does a bf16-output product with these epilogue options take one of the compile-time epilogues above?
+inline bool gemm_epilogue_is_fixed(int act, bool bias, bool resid, bool colsum) {
+  if (act == 0 && !colsum) return (!bias && !resid) || bias;
+  if (act == 3) return bias && !resid && !colsum;
+  if (act == 4) return !bias && !resid;
+  return false;
 }
 
 }  // namespace dipaco

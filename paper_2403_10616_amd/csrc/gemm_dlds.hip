@@ -46,54 +46,26 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only:
 }
 
 // A_KC: A is [M, K] (contiguous along K), else [K, M].  B_KC: B is [N, K], else [K, N].
-// Two shapes are built: 256 x 256 tiles, 2 x 4 waves, 4 stages (one workgroup per compute unit; least operand
-// traffic, for long K), and 256 x 128 tiles, 2 x 2 waves, 3 stages (two workgroups per compute unit, whose
-// prologues and epilogues hide behind each other's multiplications: for the short-K products of the step, where
-// those ends are a large part of a tile's life).  Either way a wave owns 128 x 64 outputs and two waves share a SIMD.
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES>
-__global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const GemmDev g) {
+// Shapes built: 256 x 256 tiles, 2 x 4 waves, 4 stages (one workgroup per compute unit; least operand traffic, for
+// long K); 256 x 128 tiles, 2 x 2 waves, 3 stages (two workgroups per compute unit); 128 x 512 and 512 x 128 for
+// weight gradients.  In all of these a wave owns 128 x 64 outputs and two waves share a SIMD.
+// N_STEP = 224 (with DL_BN = 256), an option: the tile is staged exactly like a 256 x 256 one, but tile columns start
+// every 224 columns and only the first 224 are computed and stored.  The path's widths (896, 2688, 3584) are
+// multiples of 224 = 7 x 32 and not of 256: 896 columns are 4 such tiles instead of 3.5, so a launch is a whole
+// number of equal workgroups.  The 7 x 8 blocks of 32 x 32 are dealt so that every SIMD gets 14: waves 0..3 take
+// 64 rows x 128 columns, waves 4..7 the same rows x the last 96.
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP,
+          int TM, int TN>
+__device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int lane, int wave, int rb0, int cb0, int m0,
+                                               int n0, int k_begin, int nkt, int split) {
   constexpr int NW = WGM * WGN;
   constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;   // bytes of an operand tile (either kind)
   constexpr int DL_STAGE = DL_TILE_A + DL_TILE_B;
   constexpr int KROW_A = DL_BM * 2, KROW_B = DL_BN * 2;     // bytes of a K-row of a row-contiguous tile
   constexpr int NLA = DL_TILE_A / 1024;                     // wave-level loads of the A tile
   constexpr int LPS = DL_STAGE / 1024 / NW;                 // wave-level loads per wave and stage
-  constexpr int TM = DL_BM / (32 * WGM), TN = DL_BN / (32 * WGN);
-  constexpr int WN = DL_BN / WGN;
   constexpr int NM = TM * TN, NR = TM + TN;
-  static_assert(TM == 4 && TN == 2, "a wave owns 128 x 64 outputs");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // Waves w and w + 4 share a SIMD.  They are given different halves of the tile's rows AND of its columns, so
-  // that in a tile that sticks out of C by half (896 = 3.5 x 256 is the path's width) every SIMD keeps exactly
-  // one wave with work, which then has the matrix core to itself.  (Letting the idle wave of the SIMD take half of
-  // every K tile of its partner's outputs was measured: no gain, the launch is not bound by that wave's latencies.)
-  static_assert((WGM == 2 && (WGN == 4 || WGN == 2)) || (WGM == 1 && WGN == 8) || (WGM == 4 && WGN == 2),
-                "wave placement below is written for 2 x 4, 2 x 2, 1 x 8 and 4 x 2 waves");
-  const int wm = WGM == 1 ? 0 : WGM == 4 ? (wave & 3) : (WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1);
-  const int wn = WGM == 1 ? wave : WGM == 4 ? (wave >> 2) : (WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1);
-  int split, tile_m, tile_n, k_begin, nkt;
-  if (g.uneven) {
-    int nsplit;
-    gemm_uneven_of_block(g, blockIdx.x, split, nsplit, tile_m, tile_n);
-    const long ktiles = g.K / DL_BK;
-    const int kt0 = (int)(split * ktiles / nsplit), kt1 = (int)((split + 1) * ktiles / nsplit);
-    k_begin = kt0 * DL_BK;
-    nkt = kt1 - kt0;
-  } else if (g.fast_map) {
-    gemm_tile_of_block_fast(g, blockIdx.x, tile_m, tile_n);
-    split = 0;
-    k_begin = 0;
-    nkt = g.K / DL_BK;
-  } else {
-    gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
-    k_begin = split * g.k_per_split;
-    nkt = (min(g.K, k_begin + g.k_per_split) - k_begin) / DL_BK;
-  }
-  const int m0 = tile_m * DL_BM, n0 = tile_n * DL_BN;
-  const bool active = m0 + wm * (DL_BM / WGM) < g.M && n0 + wn * (DL_BN / WGN) < g.N;   // wave-uniform
-
+  const bool active = m0 + rb0 * 32 < g.M && n0 + cb0 * 32 < g.N;   // wave-uniform
   // ---- loads: wave-level load j fills LDS bytes [1024 j, 1024 j + 1024) of a stage; j < NLA: A tile, else B tile.
   // Rows (columns) beyond the operand re-read its last ones: they only feed outputs that are never stored.
   const bf16* gp[LPS];
@@ -145,12 +117,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
   int toffa[TM], toffb[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
-    toffa[i] = (8 * (g4 >> 1) + ep) * KROW_A + (((wm * (DL_BM / WGM) / 32 + i) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+    toffa[i] = (8 * (g4 >> 1) + ep) * KROW_A + (((rb0 + i) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
 #pragma unroll
   for (int j = 0; j < TN; ++j)
-    toffb[j] = (8 * (g4 >> 1) + ep) * KROW_B + (((wn * (DL_BN / WGN) / 32 + j) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
-  const char* a_base = smem + (A_KC ? wm * (DL_BM / WGM) * DL_ROWB : 0);
-  const char* b_base = smem + DL_TILE_A + (B_KC ? wn * (DL_BN / WGN) * DL_ROWB : 0);
+    toffb[j] = (8 * (g4 >> 1) + ep) * KROW_B + (((cb0 + j) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+  const char* a_base = smem + (A_KC ? rb0 * 32 * DL_ROWB : 0);
+  const char* b_base = smem + DL_TILE_A + (B_KC ? cb0 * 32 * DL_ROWB : 0);
   uint4 fa[2][TM], fb[2][TN];
   auto tr_read = [&](const char* p, int krow) {
     const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)p);
@@ -248,8 +220,75 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
   // every load has landed (the last steps waited for vmcnt 0); all waves are done with the ring before it is reused
   wait_vmcnt<0>();
   __syncthreads();
-  if (active) gemm_epilogue_dispatch<TC, TM, TN, WN>(acc, reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4)), lane,
-                                                     m0 + wm * (DL_BM / WGM), n0 + wn * WN, split, g);
+  if (!active) return;
+  // the epilogue takes column blocks of two (or one) 32-wide tiles at a time through the wave's staging region
+  float* const stg = reinterpret_cast<float*>(smem) + wave * (32 * (64 + 4));
+  const int row0 = m0 + rb0 * 32;
+#pragma unroll
+  for (int j0 = 0; j0 < TN; j0 += 2) {
+    if (n0 + (cb0 + j0) * 32 >= g.N) break;   // wave-uniform
+    if constexpr (TN % 2 == 1) {
+      if (j0 + 1 == TN) {
+        f32x16 part[TM][1];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) part[i][0] = acc[i][j0];
+        gemm_epilogue_dispatch<TC, TM, 1, 32>(part, stg, lane, row0, n0 + (cb0 + j0) * 32, split, g);
+        break;
+      }
+    }
+    f32x16 part[TM][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) { part[i][0] = acc[i][j0]; part[i][1] = acc[i][j0 + 1]; }
+    gemm_epilogue_dispatch<TC, TM, 2, 64>(part, stg, lane, row0, n0 + (cb0 + j0) * 32, split, g);
+  }
+}
+
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP>
+__global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const GemmDev g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int split, tile_m, tile_n, k_begin, nkt;
+  if (g.uneven) {
+    int nsplit;
+    gemm_uneven_of_block(g, blockIdx.x, split, nsplit, tile_m, tile_n);
+    const long ktiles = g.K / DL_BK;
+    const int kt0 = (int)(split * ktiles / nsplit), kt1 = (int)((split + 1) * ktiles / nsplit);
+    k_begin = kt0 * DL_BK;
+    nkt = kt1 - kt0;
+  } else if (g.fast_map) {
+    gemm_tile_of_block_fast(g, blockIdx.x, tile_m, tile_n);
+    split = 0;
+    k_begin = 0;
+    nkt = g.K / DL_BK;
+  } else {
+    gemm_tile_of_block(g, blockIdx.x, split, tile_m, tile_n);
+    k_begin = split * g.k_per_split;
+    nkt = (min(g.K, k_begin + g.k_per_split) - k_begin) / DL_BK;
+  }
+  const int m0 = tile_m * DL_BM, n0 = tile_n * N_STEP;
+  if constexpr (N_STEP == 224) {
+    static_assert(DL_BM == 256 && DL_BN == 256 && WGM == 2 && WGN == 4, "the 224-column tile is staged as 256 x 256");
+    // waves w and w + 4 share a SIMD: 2 x 4 + 2 x 3 = 14 blocks of 32 x 32 each
+    if (wave < 4)
+      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, 2, 4>(g, smem, lane, wave, 2 * wave, 0, m0,
+                                                                                      n0, k_begin, nkt, split);
+    else
+      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, 2, 3>(g, smem, lane, wave, 2 * (wave - 4), 4,
+                                                                                      m0, n0, k_begin, nkt, split);
+  } else {
+    static_assert(N_STEP == DL_BN, "tiles tile C");
+    // Waves w and w + 4 share a SIMD.  They are given different halves of the tile's rows AND of its columns, so
+    // that in a tile that sticks out of C by half (896 = 3.5 x 256 is the path's width) every SIMD keeps exactly
+    // one wave with work, which then has the matrix core to itself.  (Letting the idle wave of the SIMD take half of
+    // every K tile of its partner's outputs was measured: no gain, the launch is not bound by that wave's latencies.)
+    static_assert((WGM == 2 && (WGN == 4 || WGN == 2)) || (WGM == 1 && WGN == 8) || (WGM == 4 && WGN == 2),
+                  "wave placement below is written for 2 x 4, 2 x 2, 1 x 8 and 4 x 2 waves");
+    static_assert(DL_BM / (32 * WGM) == 4 && DL_BN / (32 * WGN) == 2, "a wave owns 128 x 64 outputs");
+    const int wm = WGM == 1 ? 0 : WGM == 4 ? (wave & 3) : (WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1);
+    const int wn = WGM == 1 ? wave : WGM == 4 ? (wave >> 2) : (WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1);
+    gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, 4, 2>(g, smem, lane, wave, 4 * wm, 2 * wn, m0, n0,
+                                                                                    k_begin, nkt, split);
+  }
 }
 
 // ---- uneven split-K ----------------------------------------------------------------------------------------
@@ -301,11 +340,11 @@ double plan_makespan(const UnevenPlan& p) {
   return worst;
 }
 
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES>
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES, int N_STEP = BN>
 dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_ROWB;
-  static_assert((size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
-  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES>;
+  static_assert((size_t)WGM * WGN * 32 * (64 + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
+  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES, N_STEP>;
   static std::atomic<unsigned long long> lds_set{0};   // per instantiation
   if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return e;
   GemmDev g;
@@ -314,9 +353,10 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   g.bias = a.bias; g.resid = a.resid; g.aux_out = a.aux_out; g.aux_in = a.aux_in; g.act = a.act;
   g.partial = a.partial;
   g.tiles_m = (a.M + DL_BM - 1) / DL_BM;
-  g.tiles_n = (a.N + BN - 1) / BN;
+  g.tiles_n = (a.N + N_STEP - 1) / N_STEP;
   const int ktiles = a.K / DL_BK;
   UnevenPlan up;
+  if (N_STEP != BN && (a.splits > 1 || a.N % N_STEP)) return fail(DIPACO_EUNSUPPORTED, "gemm: 224-column tiles need N % 224 == 0 and no split-K");
   if (a.splits > 1 && plan_uneven(a.M, a.N, a.K, DL_BM, BN, WGM, WGN, a.splits, up)) {
     g.uneven = 1;
     g.splits = up.s[0];
@@ -340,12 +380,14 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   kern<<<(unsigned)blocks, 64 * WGM * WGN, smem, s>>>(g);
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
-  constexpr int WAVE_ROWS = DL_BM / WGM;
+  constexpr int WAVE_ROWS = N_STEP != BN ? 64 : DL_BM / WGM;   // rows whose column sums one wave leaves
   if (a.colsum) return launch_sum_rows(a.colsum_partial, a.colsum, (a.M + WAVE_ROWS - 1) / WAVE_ROWS, a.N, s);
   return DIPACO_OK;
 }
 
-std::atomic<int> g_dlds_shape{0};   // test / tuning hook; 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 (weight gradients only)
+// 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 (weight gradients only), 5 = 224-column tiles
+// wherever N is a multiple of 224.  A process-wide test and tuning hook.
+std::atomic<int> g_dlds_shape{0};
 
 // Weight gradients with a side that is not a multiple of 256 (896 = 7 x 128): 128 x 512 tiles of 1 x 8 waves, or
 // 512 x 128 tiles of 4 x 2 waves, cut C into whole tiles only, so that five K slices fit on the chip where the
@@ -366,6 +408,13 @@ int oblong_plan_wins(const GemmArgs& a) {
   return pick;
 }
 
+// Tile columns every 224 instead of 256 (N a multiple of 224; see the kernel): one workgroup per compute unit either
+// way, 7/8 of the matrix-core work per tile, whole rounds of 256 workgroups.  Measured on the step's products at
+// equal flops: within +-2 % of the 256-column tiles where it removes a half-empty tile column or a quarter-full last
+// round (N = 896, 2688), 8-10 % behind where it does not (N = 3584: one more tile column).  A tile's time follows the
+// operand bytes it stages, not its matrix-core work, and the launch as a whole follows the power limit, so the
+// saved work is not seen.  Kept as a tested option (tile setting 10); the automatic choice stays 256 x 256.
+
 // Measured on the step's products (K = 896 .. 32768), the two-workgroup shape gains what it hides of a tile's ends
 // and loses more to its extra barriers and operand traffic: level with the 256 x 256 shape on the GELU product, whose
 // epilogue is the longest, 3-15 % behind on all others.  It is kept as a tested option; the automatic choice is the
@@ -379,6 +428,10 @@ dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
   }
   const bool narrow = g_dlds_shape == 2;
   if (narrow) return run_dlds<TC, A_KC, B_KC, 256, 128, 2, 2, 3>(a, s);
+  if constexpr (std::is_same<TC, bf16>::value) {
+    if (g_dlds_shape == 5 && a.splits <= 1 && a.N % 224 == 0 && gemm_epilogue_is_fixed(a.act, a.bias, a.resid, a.colsum))
+      return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4, 224>(a, s);
+  }
   return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4>(a, s);
 }
 

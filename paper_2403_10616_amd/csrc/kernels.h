@@ -111,11 +111,11 @@ template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s
 // gemm_dlds_eligible holds (whole K tiles of 32, 16-byte rows); launch_gemm routes to it by itself
 bool gemm_dlds_eligible(const GemmArgs& g);
 dipaco_status launch_gemm_dlds(const GemmArgs& g, hipStream_t s);
-void set_gemm_dlds_shape(int shape);   // 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 for weight gradients
+void set_gemm_dlds_shape(int shape);   // 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 for weight gradients, 5 = 224-column tiles where N % 224 == 0
 // C[m, n] = sum over z < splits of partial[z, m, n], in index order
 dipaco_status launch_splitk_reduce(const float* partial, float* C, int M, int N, long ldc, int splits, hipStream_t s);
 // 0 = automatic; 1 = 128x128, 2 = 256x128, 3 / 4 = 256x256 workgroup tiles with four / eight waves, 5 = the
-// direct-to-LDS kernel wherever the shape allows, 6 / 7 / 8 / 9 = the same with its 256x256 / 256x128 / 128x512 / 512x128 (the last two: weight gradients) shape forced
+// direct-to-LDS kernel wherever the shape allows, 6 / 7 / 8 / 9 / 10 = the same with its 256x256 / 256x128 / 128x512 / 512x128 (these two: weight gradients) / 224-column shape forced
 // (tuning and tests)
 void set_gemm_tile(int t);
 // the same where the number of slices depends on the tile class of the element:

@@ -22,7 +22,7 @@ def _rand(shape, seed, dtype):
     return t.to(DEV), t.to(torch.float64).numpy()
 
 
-@pytest.fixture(params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9], ids=lambda t: f"tile{t}")
+@pytest.fixture(params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], ids=lambda t: f"tile{t}")
 def gemm_tile(request):
     """Every workgroup tile shape must reach the same parity; 0 is the library's own choice."""
     dp.dipaco_k_set_gemm_tile(request.param)
@@ -32,7 +32,9 @@ def gemm_tile(request):
 
 # (M, N, K): several tiles with ragged tails in every direction; K not a multiple of the K tile
 GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (1, 8, 8), (300, 264, 520), (64, 512, 1000), (520, 776, 160),
-               (257, 8, 32)]
+               (257, 8, 32),
+               # widths that are multiples of 224: the tile shape with columns every 224 takes them (tile 10)
+               (300, 448, 544), (520, 224, 160), (257, 896, 64)]
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
