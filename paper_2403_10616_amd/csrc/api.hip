@@ -281,6 +281,8 @@ static dipaco_status check_batch_shape(const dipaco_ctx* c, int B, int S, bool w
   if ((int64_t)B * S > (1 << 24)) return fail(DIPACO_ESHAPE, "batch*seq above 2^24 is not supported");
   const int64_t widest = std::max<int64_t>(std::max<int64_t>(c->arch.d_mlp, 3 * (int64_t)c->A),
                                            std::max<int64_t>(c->arch.d_model, with_head ? c->arch.vocab : 0));
+  if ((int64_t)S * 3 * c->A * 2 >= (1LL << 32))   // the attention kernels address one sequence's q | k | v rows with 32-bit byte offsets
+    return fail(DIPACO_ESHAPE, "seq * 3 * heads * d_head * 2 bytes must stay below 2^32");
   if ((int64_t)B * S * (widest + 1) >= (1LL << 32))
     return fail(DIPACO_ESHAPE, "batch*seq times the widest activation row (d_mlp, 3*heads*d_head, vocab) must stay below 2^32");
   return DIPACO_OK;
@@ -938,6 +940,8 @@ dipaco_status dipaco_k_set_attention_blocks(int32_t single_block) {
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,
                                      int32_t H, int32_t dh, void* stream) {
   if (!qkv || !o || !lse || B < 1 || S < 1 || H < 1) return fail(DIPACO_EINVAL, "dipaco_k_attention_fwd: bad argument");
+  if ((int64_t)S * 3 * H * dh * 2 >= (1LL << 32) || (int64_t)B * S * 3 * H * dh >= (1LL << 32))
+    return fail(DIPACO_ESHAPE, "dipaco_k_attention_fwd: sequence or batch too large for 32-bit offsets");
   hipStream_t st = static_cast<hipStream_t>(stream);
   return dtype == DIPACO_BF16
              ? launch_attention_fwd<bf16>(static_cast<const bf16*>(qkv), static_cast<bf16*>(o), lse, B, S, H, dh, st)
@@ -949,6 +953,8 @@ dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void*
                                      int32_t S, int32_t H, int32_t dh, void* stream) {
   if (!qkv || !o || !d_o || !lse || !dqkv || !dsum || B < 1 || S < 1 || H < 1 || (colsum_out && !colsum_scratch))
     return fail(DIPACO_EINVAL, "dipaco_k_attention_bwd: bad argument");
+  if ((int64_t)S * 3 * H * dh * 2 >= (1LL << 32) || (int64_t)B * S * 3 * H * dh >= (1LL << 32))
+    return fail(DIPACO_ESHAPE, "dipaco_k_attention_bwd: sequence or batch too large for 32-bit offsets");
   hipStream_t st = static_cast<hipStream_t>(stream);
   return dtype == DIPACO_BF16
              ? launch_attention_bwd<bf16>(static_cast<const bf16*>(qkv), static_cast<const bf16*>(o),

@@ -167,23 +167,30 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
 namespace {
 // As splitk_reduce_kernel, for partial planes in which the number of K slices depends on where the element lies:
 // n_slices[(row >= row_edge) + 2 * (col >= col_edge)]
-__global__ void __launch_bounds__(256) splitk_reduce_classes_kernel(const float* __restrict__ partial,
+__global__ void __launch_bounds__(128) splitk_reduce_classes_kernel(const float* __restrict__ partial,
                                                                     float* __restrict__ C, int M, int N, long ldc,
                                                                     int row_edge, int col_edge, int s0, int s1, int s2,
                                                                     int s3) {
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
   const size_t total = (size_t)M * N, quads = total / 4;
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < quads; q += stride) {
+  const size_t stride = (size_t)gridDim.x * 128;
+  // one 16-byte vector per thread in the usual launch; a plane is read once (streaming loads), the first eight
+  // slices are requested together and added in slice order
+  for (size_t q = (size_t)blockIdx.x * 128 + threadIdx.x; q < quads; q += stride) {
     const size_t i = 4 * q;
     const size_t row = i / N, col = i - row * N;   // N is a multiple of 8: the four elements share a row
     const bool er = (int)row >= row_edge, ec = (int)col >= col_edge;
     const int n = er ? (ec ? s3 : s1) : (ec ? s2 : s0);
-    float4 acc = *reinterpret_cast<const float4*>(partial + i);
-    for (int z = 1; z < n; ++z) {
-      const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)z * total + i);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    *reinterpret_cast<float4*>(C + row * ldc + col) = acc;
+    f32x4_t v[8];
+#pragma unroll
+    for (int z = 0; z < 8; ++z)
+      if (z < n) v[z] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(partial + (size_t)z * total + i));
+    f32x4_t acc = v[0];
+#pragma unroll
+    for (int z = 1; z < 8; ++z)
+      if (z < n) acc += v[z];
+    for (int z = 8; z < n; ++z) acc += __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(partial + (size_t)z * total + i));
+    *reinterpret_cast<f32x4_t*>(C + row * ldc + col) = acc;
   }
 }
 }  // namespace
@@ -192,8 +199,8 @@ dipaco_status launch_splitk_reduce_classes(const float* partial, float* C, int M
                                            int col_edge, const int (&n_slices)[4], hipStream_t s) {
   if (N % 8 || ldc % 4 || col_edge % 4) return fail(DIPACO_ESHAPE, "split-K reduce: N, ldc, col_edge must be multiples of 8, 4, 4");
   const size_t quads = (size_t)M * N / 4;
-  const int rb = (int)std::min<size_t>((quads + 255) / 256, 256 * 32);
-  splitk_reduce_classes_kernel<<<rb, 256, 0, s>>>(partial, C, M, N, ldc, row_edge, col_edge, n_slices[0], n_slices[1],
+  const unsigned rb = (unsigned)std::min<size_t>((quads + 127) / 128, 0x7fffffffu);
+  splitk_reduce_classes_kernel<<<rb, 128, 0, s>>>(partial, C, M, N, ldc, row_edge, col_edge, n_slices[0], n_slices[1],
                                                   n_slices[2], n_slices[3]);
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
