@@ -17,6 +17,7 @@ Other workloads (for profiling single kernels; same JSON shape):
   --workload kmeans       one Lloyd iteration on the config-4 data: top-1 (or --n-best 2) assignment + centroid update
   --workload gemm         one bf16 GEMM of the step: --mnk M,N,K --layout nn|nt|tn --epilogue none|bias|gelu|dgelu|resid
   --workload attention    causal attention of one layer of the step (batch 32 x 14 heads x 1024 x 64): --pass fwd|bwd
+  --workload issue_probe  register-only loops: do matrix-core and vector-ALU instructions of a SIMD overlap?
 """
 from __future__ import annotations
 
@@ -64,7 +65,9 @@ def attention_flops(cfg, B, S):
     H, dh = cfg["n_heads"], cfg["d_head"]
     NL = sum(cfg["layers_per_level"])
     fwd = NL * B * H * (2 * 2 * S * S * dh) / 2          # QK^T and PV over the causal half
-    return fwd, 2.5 * fwd                                 # backward: five matmuls of the same size
+    # backward: the four products the definition has (dV, dP, dQ, dK), twice the forward pass; the scores that the
+    # kernels recompute are not model work and are not counted
+    return fwd, 2.0 * fwd
 
 
 def bench_path_step(args):
@@ -186,15 +189,46 @@ def cpu_baseline_path_step(cfg, theta, seqs, layout):
     orc.adamw_step(theta, g, np.zeros_like(g), np.zeros_like(g), 1, cfg["lr"], cfg["beta1"], cfg["beta2"], cfg["eps"],
                    cfg["wd"], mask)
     dt = time.perf_counter() - t0
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count()
-    return {"value": tok.size / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+    return {"value": tok.size / dt, "unit": "tokens/s", "cores": _oracle_threads(), "kind": "oracle",
             "sample": f"{tok.shape[0]} of the 32 sequences ({tok.size} tokens) of the same batch, fwd+bwd+AdamW in fp64 numpy, "
                       f"{dt:.1f} s",
             "loss": loss}
+
+
+def _oracle_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
+    except Exception:
+        return int(os.cpu_count() or 1)
+
+
+def cpu_baseline_outer_step(cfg):
+    """The oracle's outer step (numpy fp64, as it stands) on the whole config-3 module: 16 weighted deltas of
+    57,872,640 parameters, Nesterov update."""
+    import dipaco_inputs as gen
+    from oracle import dipaco_oracle as orc
+    n, P = cfg["n_elems"], cfg["n_paths"]
+    theta = gen.perturbation(n, 0.02, cfg["seed"])
+    deltas = [gen.perturbation(n, cfg["delta_std"], 300 + i) for i in range(P)]
+    w = gen.shard_weights(P, cfg["seed"])
+    t0 = time.perf_counter()
+    orc.outer_step(theta, np.zeros(n), deltas, w, True, cfg["outer_lr"], cfg["outer_momentum"])
+    dt = time.perf_counter() - t0
+    # elementwise numpy: one host thread
+    return {"value": n / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": f"the whole module: {P} deltas x {n} parameters, weighted mean + Nesterov in fp64 numpy, {dt:.1f} s"}
+
+
+def cpu_baseline_route(cfg, z, c, rows=16384):
+    """The oracle's eq. (1) (numpy fp64 distances, as it stands) on the first `rows` points of the same set."""
+    from oracle import dipaco_oracle as orc
+    t0 = time.perf_counter()
+    orc.route_prefix(z[:rows], c)
+    dt = time.perf_counter() - t0
+    # a python loop over the rows with elementwise numpy inside: one host thread
+    return {"value": rows / dt, "unit": "documents/s", "cores": 1, "kind": "oracle",
+            "sample": f"the first {rows} of the {len(z)} embeddings against the same {len(c)} centroids, {dt:.1f} s"}
 
 
 def bench_outer_step(args):
@@ -225,12 +259,16 @@ def bench_outer_step(args):
     ms = e0.elapsed_time(e1) / args.steps
     bytes_ = (P + 4) * n * 4.0
     ach = bytes_ / (ms * 1e-3) / 1e9
-    return {"metric": "module outer-step parameters/sec on 1 MI355X", "value": n / (wall / args.steps), "unit": "params/s",
-            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": "config 3: 57,872,640-parameter module, 16 weighted deltas, Nesterov"},
-            "roofline": {"bound": "hbm", "kernel": "outer_kernel<16>", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_}}
+    out = {"metric": "module outer-step parameters/sec on 1 MI355X", "value": n / (wall / args.steps), "unit": "params/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "config 3: 57,872,640-parameter module, 16 weighted deltas, Nesterov"},
+           "roofline": {"bound": "hbm", "kernel": "outer_kernel<16>", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": bytes_}}
+    if not args.no_cpu_baseline:
+        del deltas, theta, buf
+        out["cpu_baseline"] = cpu_baseline_outer_step(cfg)
+    return out
 
 
 def bench_round(args):
@@ -441,13 +479,16 @@ def bench_route(args):
     ms = e0.elapsed_time(e1) / args.steps
     flops = 2.0 * N * D * K
     ach = flops / (ms * 1e-3) / 1e12
-    return {"metric": "prefix-routing documents/sec on 1 MI355X", "value": N / (wall / args.steps), "unit": "documents/s",
-            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": "config 4: 1,048,576 x 768 embeddings from a 256-Gaussian mixture vs 256 centroids"},
-            "roofline": {"bound": "mfma", "kernel": "route_kernel", "achieved": ach, "peak": PEAK_F32_TFLOPS,
-                         "unit": "TFLOP/s", "frac": ach / PEAK_F32_TFLOPS, "traffic": None, "flops_per_launch": flops,
-                         "hbm_gbs": (N * D * 4.0 + N * 8.0) / (ms * 1e-3) / 1e9}}
+    out = {"metric": "prefix-routing documents/sec on 1 MI355X", "value": N / (wall / args.steps), "unit": "documents/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "config 4: 1,048,576 x 768 embeddings from a 256-Gaussian mixture vs 256 centroids"},
+           "roofline": {"bound": "mfma", "kernel": "route_kernel", "achieved": ach, "peak": PEAK_F32_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / PEAK_F32_TFLOPS, "traffic": None, "flops_per_launch": flops,
+                        "hbm_gbs": (N * D * 4.0 + N * 8.0) / (ms * 1e-3) / 1e9}}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_route(cfg, z, c)
+    return out
 
 
 def bench_features(args):
@@ -737,6 +778,35 @@ def bench_gemm(args):
                          "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "flops_per_launch": flops}}
 
 
+def bench_issue_probe(args):
+    """How matrix-core and vector-ALU instructions share a SIMD: register-only loops (dipaco_k_issue_probe) at one to
+    four waves per SIMD.  'value' is the time of mode 2 (16 MFMA then 256 FMA) over the sum of modes 0 and 1 at four waves
+    per SIMD: 1 = the two kinds of work do not overlap at all, 0.5 = they overlap completely."""
+    import torch
+    import paper_2403_10616_amd as dp
+    dev = "cuda"
+    out = torch.empty(256 * 1024, dtype=torch.float32, device=dev)
+    iters = 20000
+    names = ["16 MFMA", "256 FMA", "16 MFMA then 256 FMA", "16 x (1 MFMA, 16 FMA)", "256 x (exp2, mul, add)"]
+    table = {}
+    e0, e1 = _events(torch)
+    for waves in (1, 2, 3, 4):
+        for mode in range(5):
+            dp.dipaco_k_issue_probe(mode, waves, 100, out)
+            torch.cuda.synchronize()
+            e0.record()
+            dp.dipaco_k_issue_probe(mode, waves, iters, out)
+            e1.record()
+            torch.cuda.synchronize()
+            table[f"{waves} waves/SIMD: {names[mode]}"] = round(e0.elapsed_time(e1) * 1e6 / iters, 1)
+    ratio = table["4 waves/SIMD: 16 MFMA then 256 FMA"] / (table["4 waves/SIMD: 16 MFMA"] + table["4 waves/SIMD: 256 FMA"])
+    return {"metric": "time of (16 MFMA then 256 FMA) over the sum of the two alone, 4 waves per SIMD", "value": ratio,
+            "unit": "ratio", "n_gpus": 1, "steps": iters, "warmup": 100, "ms_per_step": None, "higher_is_better": False,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "instruction-issue probe: one workgroup per compute unit, no memory traffic",
+                       "ns_per_iteration": table}}
+
+
 def bench_attention(args):
     import torch
     import dipaco_inputs as gen
@@ -789,7 +859,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="path_step", choices=["path_step", "round", "outer_step", "outer_stream", "outer_table", "route", "router", "reroute", "kmeans", "features", "score", "gemm", "attention"])
+    ap.add_argument("--workload", default="path_step", choices=["path_step", "round", "outer_step", "outer_stream", "outer_table", "route", "router", "reroute", "kmeans", "features", "score", "gemm", "attention", "issue_probe"])
     ap.add_argument("--n-best", type=int, default=1, choices=[1, 2])
     ap.add_argument("--mnk", default="32768,3584,896")
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
@@ -812,7 +882,7 @@ def main():
         dp.dipaco_k_set_attention_blocks(args.attn_blocks)
     fn = {"path_step": bench_path_step, "round": bench_round, "outer_step": bench_outer_step, "route": bench_route, "gemm": bench_gemm, "kmeans": bench_kmeans, "features": bench_features, "score": bench_score, "outer_stream": bench_outer_stream,
           "outer_table": bench_outer_table, "router": bench_router, "reroute": bench_reroute,
-          "attention": bench_attention}[args.workload]
+          "attention": bench_attention, "issue_probe": bench_issue_probe}[args.workload]
     print(json.dumps(fn(args)))
 
 

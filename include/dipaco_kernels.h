@@ -73,6 +73,16 @@ dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void*
                                      void* dqkv, float* dsum, float* colsum_out, float* colsum_scratch, int32_t B,
                                      int32_t S, int32_t H, int32_t dh, void* stream);
 
+/* Measurement aid, no part of the method: register-only loops that show how the matrix cores and the vector ALU of a
+ * SIMD share instruction issue (the inner loops of the attention kernels are priced with it).  One workgroup of
+ * 256 * waves_per_simd threads per compute unit (256 workgroups) runs `iters` iterations of
+ *   mode 0: 16 v_mfma_f32_32x32x16_bf16 on four independent accumulators;   mode 1: 256 independent v_fma_f32;
+ *   mode 2: the 16 MFMA, then the 256 FMA;   mode 3: sixteen times (1 MFMA, 16 FMA) in program order;
+ *   mode 4: 256 times (v_exp_f32, multiply, add).
+ * The caller times the launch.  out: device fp32, 256 * 256 * waves_per_simd elements, overwritten (keeps the loops
+ * alive).  mode in 0..4, waves_per_simd in 1..4, iters >= 1, else DIPACO_EINVAL. */
+dipaco_status dipaco_k_issue_probe(int32_t mode, int32_t waves_per_simd, int32_t iters, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

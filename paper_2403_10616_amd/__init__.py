@@ -95,6 +95,7 @@ _SIGS = {
     "dipaco_k_set_gemm_tile": (C.c_int, [C.c_int32]),
     "dipaco_k_gemm_split_plan": (C.c_int, [C.c_int32] * 4 + [C.POINTER(C.c_int32)]),
     "dipaco_k_set_attention_blocks": (C.c_int, [C.c_int32]),
+    "dipaco_k_issue_probe": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dipaco_k_attention_fwd": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p]),
     "dipaco_k_attention_bwd": (C.c_int, [C.c_int32] + [C.c_void_p] * 8 + [C.c_int32] * 4 + [C.c_void_p]),
@@ -413,6 +414,10 @@ def dipaco_k_gemm_split_plan(M: int, N: int, K: int, max_slices: int) -> dict:
     _check(load().dipaco_k_gemm_split_plan(M, N, K, max_slices, out))
     v = list(out)
     return {"tile": (v[0], v[1]), "inside": (v[2], v[3]), "tiles": v[4:8], "slices": v[8:12]}
+
+
+def dipaco_k_issue_probe(mode: int, waves_per_simd: int, iters: int, out, stream=None):
+    _check(load().dipaco_k_issue_probe(mode, waves_per_simd, iters, _ptr(out), _stream(stream)))
 
 
 def dipaco_k_set_attention_blocks(single_block: int):

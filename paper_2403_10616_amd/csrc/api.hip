@@ -62,6 +62,7 @@ struct Plan {
   size_t x_final, meanf, rstdf, y, logits, nll, n_valid;
   size_t dxa, dxb, dh, du, dqkv, d_o, dsum;
   size_t ln_partial, cs_partial, splitk_partial, embed_ints;
+  size_t ln_partial_stride, cs_partial_stride;   // bytes between the buffers of consecutive producers
   size_t total;
 };
 
@@ -89,10 +90,15 @@ static Plan make_plan(const dipaco_ctx* c, int B, int S) {
   p.logits = take(T * V * es); p.nll = take(T * 4); p.n_valid = take(256);
   p.dxa = take(T * d * es); p.dxb = take(T * d * es); p.dh = take(T * d * es); p.du = take(T * F * es);
   p.dqkv = take(T * 3 * A * es); p.d_o = take(T * A * es); p.dsum = take(2 * (size_t)B * a.n_heads * ((S + 127) / 128 * 128) * 4);
-  p.ln_partial = take(ln_bwd_partial_floats((int)T, (int)d) * 4);
+  // Partial rows of the backward pass's fixed-order sums.  Their final reductions run as one launch at the end of the
+  // step, so every producer keeps a buffer of its own: one per LayerNorm, two per block (the column sums of dU and
+  // of dqkv).
+  p.ln_partial_stride = (ln_bwd_partial_floats((int)T, (int)d) * 4 + 255) & ~(size_t)255;
+  p.ln_partial = take(p.ln_partial_stride * (2 * (size_t)c->n_layers + 1));
   const size_t widest = std::max(std::max(F, 3 * A), d);
-  p.cs_partial = take(std::max(std::max(colsum_partial_floats((int)T, (int)widest), gemm_colsum_partial_floats((int)T, (int)F)),
-                               attention_bwd_colsum_floats((int)B, (int)S, a.n_heads, a.d_head)) * 4);
+  p.cs_partial_stride = (std::max(std::max(colsum_partial_floats((int)T, (int)widest), gemm_colsum_partial_floats((int)T, (int)F)),
+                                  attention_bwd_colsum_floats((int)B, (int)S, a.n_heads, a.d_head)) * 4 + 255) & ~(size_t)255;
+  p.cs_partial = take(p.cs_partial_stride * std::max<size_t>(1, 2 * (size_t)c->n_layers));
   size_t sk = 0;
   auto need = [&](size_t M, size_t N) { sk = std::max(sk, (size_t)gemm_max_splits((int)M, (int)N, (int)T) * M * N); };
   need(d, 3 * A); need(A, d); need(d, F); need(F, d); need(d, V);
@@ -107,9 +113,9 @@ template <typename T>
 static dipaco_status gemm(const T* A, const T* B, void* C, int M, int N, int K, long lda, long ldb, long ldc,
                           bool ta, bool tb, const T* bias, const T* resid, T* aux_out, const T* aux_in, int act,
                           bool out_f32, int splits, float* partial, hipStream_t s, float* colsum = nullptr,
-                          float* colsum_partial = nullptr) {
+                          float* colsum_partial = nullptr, SumBatch* sum_batch = nullptr) {
   GemmArgs g;
-  g.colsum = colsum; g.colsum_partial = colsum_partial;
+  g.colsum = colsum; g.colsum_partial = colsum_partial; g.sum_batch = sum_batch;
   g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.bias = bias; g.resid = resid; g.aux_out = aux_out; g.aux_in = aux_in; g.act = act;
   g.trans_a = ta; g.trans_b = tb; g.out_f32 = out_f32; g.splits = splits; g.partial = partial;
@@ -131,8 +137,10 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
   auto buf = [&](size_t off) { return reinterpret_cast<T*>(ws + off); };
   auto fbuf = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
   float* skp = fbuf(p.splitk_partial);
-  float* csp = fbuf(p.cs_partial);
-  float* lnp = fbuf(p.ln_partial);
+  SumBatch sums;            // the backward pass's final reductions, run as one launch at the end
+  int ln_jobs = 0, cs_jobs = 0;
+  auto next_lnp = [&]() { return fbuf(p.ln_partial + p.ln_partial_stride * (size_t)ln_jobs++); };
+  auto next_csp = [&]() { return fbuf(p.cs_partial + p.cs_partial_stride * (size_t)cs_jobs++); };
   int* n_valid = reinterpret_cast<int*>(ws + p.n_valid);
   float* nll = nll_out ? nll_out : fbuf(p.nll);
   const int NL = c->n_layers;
@@ -183,8 +191,8 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
   // every LayerNorm backward also leaves the column sums of the dx it writes: the bias gradient of the linear
   // layer below it in the residual stream (W_down of the block before, W_o of its own block)
   TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(p.x_final), W + c->lnf_g, fbuf(p.meanf), fbuf(p.rstdf), nullptr, dx,
-                              G + c->lnf_g, G + c->lnf_b, NL > 0 ? G + c->blocks[NL - 1].b_down : nullptr, lnp, T_, d,
-                              st));
+                              G + c->lnf_g, G + c->lnf_b, NL > 0 ? G + c->blocks[NL - 1].b_down : nullptr, next_lnp(), T_, d,
+                              st, &sums));
   for (int l = NL - 1; l >= 0; --l) {
     const LayerBufs& L = p.layers[l];
     const BlockOff& o = c->blocks[l];
@@ -192,25 +200,27 @@ static dipaco_status run_fwd_bwd(const dipaco_ctx* c, const T* W, const int* tok
     TRY(dweight(buf(L.act), dx, o.w_down, F, d));
     // du = (dx W_down^T) * GELU'(u); its column sums, the gradient of b_up, come out of the same product
     TRY(gemm<T>(dx, W + o.w_down, buf(p.du), T_, F, d, d, d, F, false, true, nullptr, nullptr, nullptr, buf(L.u), 4,
-                false, 1, nullptr, st, G + o.b_up, csp));
+                false, 1, nullptr, st, G + o.b_up, next_csp(), &sums));
     TRY(dweight(buf(L.h2), buf(p.du), o.w_up, d, F));
     TRY(gemm<T>(buf(p.du), W + o.w_up, buf(p.dh), T_, d, F, F, F, d, false, true, nullptr, nullptr, nullptr, nullptr, 0,
                 false, 1, nullptr, st));
     TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_mid), W + o.ln2_g, fbuf(L.mean2), fbuf(L.rstd2), dx, dx_other,
-                                G + o.ln2_g, G + o.ln2_b, G + o.b_o, lnp, T_, d, st));
+                                G + o.ln2_g, G + o.ln2_b, G + o.b_o, next_lnp(), T_, d, st, &sums));
     // x_mid = x_in + attn(...) W_o + b_o          (dx_other = gradient at x_mid)
     TRY(dweight(buf(L.o), dx_other, o.w_o, A, d));
     TRY(gemm<T>(dx_other, W + o.w_o, buf(p.d_o), T_, A, d, d, d, A, false, true, nullptr, nullptr, nullptr, nullptr, 0,
                 false, 1, nullptr, st));
     // dqkv and its column sums, the gradient of b_qkv
     TRY(launch_attention_bwd<T>(buf(L.qkv), buf(L.o), buf(p.d_o), fbuf(L.lse), buf(p.dqkv), fbuf(p.dsum), G + o.b_qkv,
-                                csp, B, S, H, dh, st));
+                                next_csp(), B, S, H, dh, st, &sums));
     TRY(dweight(buf(L.h1), buf(p.dqkv), o.w_qkv, d, 3 * A));
     TRY(gemm<T>(buf(p.dqkv), W + o.w_qkv, buf(p.dh), T_, d, 3 * A, 3 * A, 3 * A, d, false, true, nullptr, nullptr,
                 nullptr, nullptr, 0, false, 1, nullptr, st));
     TRY(launch_layernorm_bwd<T>(buf(p.dh), buf(L.x_in), W + o.ln1_g, fbuf(L.mean1), fbuf(L.rstd1), dx_other, dx,
-                                G + o.ln1_g, G + o.ln1_b, l > 0 ? G + c->blocks[l - 1].b_down : nullptr, lnp, T_, d, st));
+                                G + o.ln1_g, G + o.ln1_b, l > 0 ? G + c->blocks[l - 1].b_down : nullptr, next_lnp(), T_, d, st,
+                                &sums));
   }
+  TRY(flush_sum_batch(sums, st));
   TRY(launch_embed_bwd<T>(dx, tokens, G + c->tok_emb, G + c->pos_emb, reinterpret_cast<int*>(ws + p.embed_ints), B, S,
                           d, V, a.max_seq, st));
   return DIPACO_OK;
@@ -935,6 +945,12 @@ dipaco_status dipaco_k_set_attention_blocks(int32_t single_block) {
   if (single_block != 0 && single_block != 1) return fail(DIPACO_EINVAL, "dipaco_k_set_attention_blocks: 0 or 1");
   set_attention_single_block(single_block);
   return DIPACO_OK;
+}
+
+dipaco_status dipaco_k_issue_probe(int32_t mode, int32_t waves_per_simd, int32_t iters, float* out, void* stream) {
+  if (mode < 0 || mode > 4 || waves_per_simd < 1 || waves_per_simd > 4 || iters < 1 || !out)
+    return fail(DIPACO_EINVAL, "dipaco_k_issue_probe: mode 0..4, waves_per_simd 1..4, iters >= 1, out not NULL");
+  return launch_issue_probe(mode, waves_per_simd, iters, out, static_cast<hipStream_t>(stream));
 }
 
 dipaco_status dipaco_k_attention_fwd(int32_t dtype, const void* qkv, void* o, float* lse, int32_t B, int32_t S,

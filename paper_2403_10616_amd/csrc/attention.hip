@@ -223,11 +223,11 @@ size_t attention_bwd_colsum_floats(int B, int S, int H, int dh) {
 template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv, float* dsum,
                                    float* colsum_out, float* colsum_partial, int B, int S, int H, int dh,
-                                   hipStream_t s) {
+                                   hipStream_t s, SumBatch* batch) {
   if (is_bf16<T>() && dh == 64)   // the matrix-core kernels take the column sums in their epilogues
     return launch_attention_bwd_mfma(reinterpret_cast<const bf16*>(qkv), reinterpret_cast<const bf16*>(o),
                                      reinterpret_cast<const bf16*>(d_o), lse, reinterpret_cast<bf16*>(dqkv), dsum,
-                                     colsum_out, colsum_partial, B, S, H, s);
+                                     colsum_out, colsum_partial, B, S, H, s, batch);
   dipaco_status st;
   switch (dh) {
     case 32: st = bwd_scalar<T, 32>(qkv, o, d_o, lse, dqkv, dsum, B, S, H, s); break;
@@ -242,8 +242,8 @@ dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const
 template dipaco_status launch_attention_fwd<float>(const float*, float*, float*, int, int, int, int, hipStream_t);
 template dipaco_status launch_attention_fwd<bf16>(const bf16*, bf16*, float*, int, int, int, int, hipStream_t);
 template dipaco_status launch_attention_bwd<float>(const float*, const float*, const float*, const float*, float*,
-                                                   float*, float*, float*, int, int, int, int, hipStream_t);
+                                                   float*, float*, float*, int, int, int, int, hipStream_t, SumBatch*);
 template dipaco_status launch_attention_bwd<bf16>(const bf16*, const bf16*, const bf16*, const float*, bf16*, float*,
-                                                  float*, float*, int, int, int, int, hipStream_t);
+                                                  float*, float*, int, int, int, int, hipStream_t, SumBatch*);
 
 }  // namespace dipaco

@@ -245,7 +245,7 @@ dipaco_status run(const GemmArgs& a, hipStream_t s) {
   DIPACO_LAUNCH_CHECK();
   if (g.splits > 1) return launch_splitk_reduce(a.partial, static_cast<float*>(a.C), a.M, a.N, a.ldc, g.splits, s);
   constexpr int WAVE_ROWS = BM / WGM;
-  if (a.colsum) return launch_sum_rows(a.colsum_partial, a.colsum, (a.M + WAVE_ROWS - 1) / WAVE_ROWS, a.N, s);
+  if (a.colsum) return launch_sum_rows(a.colsum_partial, a.colsum, (a.M + WAVE_ROWS - 1) / WAVE_ROWS, a.N, s, a.sum_batch);
   return DIPACO_OK;
 }
 

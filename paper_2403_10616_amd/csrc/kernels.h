@@ -4,6 +4,8 @@
 
 namespace dipaco {
 
+struct SumBatch;   // deferred fixed-order reductions, see transformer.hip below
+
 // ---- elementwise.hip ---------------------------------------------------------------------------------
 dipaco_status launch_copy_cast(const float* src, float* dst, bf16* lowp, size_t n, hipStream_t s);
 // where weight decay applies in the flat path buffer: [0, stem_end) all; blocks of block_size elements up to
@@ -104,6 +106,7 @@ struct GemmArgs {
   // colsum_partial = gemm_colsum_partial_floats(M, N) floats of scratch.  Not with split-K.
   float* colsum = nullptr;
   float* colsum_partial = nullptr;
+  SumBatch* sum_batch = nullptr;   // where the final sum of colsum_partial is deferred to (nullptr: summed at once)
 };
 size_t gemm_colsum_partial_floats(int M, int N);
 template <typename T> dipaco_status launch_gemm(const GemmArgs& g, hipStream_t s);
@@ -143,10 +146,31 @@ dipaco_status launch_layernorm_fwd(const T* x, const T* g, const T* b, T* y, flo
 template <typename T>
 dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const float* mean, const float* rstd,
                                    const T* resid_grad, T* dx, float* dg, float* db, float* dcol, float* partial,
-                                   int rows, int d, hipStream_t s);
+                                   int rows, int d, hipStream_t s, SumBatch* batch = nullptr);
 size_t ln_bwd_partial_floats(int rows, int d);
+// Fixed-order sums of rows of partial results (column sums of a product's output, LayerNorm parameter gradients):
+//   column c of sum over p < n_partials of partial[p * stride + c] goes to out0 / out1 / out2 by c / d (a null output
+//   is skipped).
+// A producer hands its reduction to a SumBatch when the caller gives it one: the path step collects the 49
+// reductions of its backward pass and runs them as one launch at the end (each on a partial buffer of its own)
+// instead of 49 launches of a few microseconds between the big kernels.
+struct SumJob {
+  const float* partial;
+  float* out0; float* out1; float* out2;
+  int n_partials, stride, d;
+};
+constexpr int SUM_BATCH_MAX = 64;   // 64 jobs of 48 bytes travel as kernel arguments
+struct SumBatch {
+  SumJob job[SUM_BATCH_MAX];
+  int count = 0;
+};
+// runs the reduction now (batch == nullptr) or appends it to the batch (a full batch is flushed first)
+dipaco_status sum_partials(const float* partial, float* out0, float* out1, float* out2, int n_partials, int stride,
+                           int d, SumBatch* batch, hipStream_t s);
+dipaco_status flush_sum_batch(SumBatch& batch, hipStream_t s);
 // out[c] = sum over p < n_partials of partial[p * cols + c], fixed order
-dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s);
+dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s,
+                              SumBatch* batch = nullptr);
 // out[n] = sum_m x[m,n] (fp32, fixed order);  partial: colsum_partial_floats scratch
 template <typename T>
 dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, int cols, hipStream_t s);
@@ -180,8 +204,13 @@ dipaco_status launch_attention_fwd(const T* qkv, T* o, float* lse, int B, int S,
 template <typename T>
 dipaco_status launch_attention_bwd(const T* qkv, const T* o, const T* d_o, const float* lse, T* dqkv,
                                    float* dscratch, float* colsum_out, float* colsum_partial, int B, int S, int H,
-                                   int dh, hipStream_t s);
+                                   int dh, hipStream_t s, SumBatch* batch = nullptr);
 size_t attention_bwd_colsum_floats(int B, int S, int H, int dh);
+
+// ---- probe.hip: register-only instruction-issue loops (measurement aid) --------------------------------
+constexpr int ISSUE_PROBE_BLOCKS = 256;   // one workgroup per compute unit
+// out: ISSUE_PROBE_BLOCKS * 256 * waves_per_simd floats
+dipaco_status launch_issue_probe(int mode, int waves_per_simd, int iters, float* out, hipStream_t s);
 
 // ---- attention_mfma.hip: bf16, head size 64, matrix cores ---------------------------------------------
 dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, int B, int S, int H, hipStream_t s);
@@ -189,7 +218,7 @@ dipaco_status launch_attention_fwd_mfma(const bf16* qkv, bf16* o, float* lse, in
 // kernels' epilogues; colsum_partial: attention_colsum_partial_floats(B, S, H) floats of scratch
 dipaco_status launch_attention_bwd_mfma(const bf16* qkv, const bf16* o, const bf16* d_o, const float* lse, bf16* dqkv,
                                         float* dsum, float* colsum_out, float* colsum_partial, int B, int S, int H,
-                                        hipStream_t s);
+                                        hipStream_t s, SumBatch* batch = nullptr);
 size_t attention_colsum_partial_floats(int B, int S, int H);
 // 0: a workgroup takes a long and a short block of the causal triangle; 1: one block per workgroup, longest first
 void set_attention_single_block(int on);

@@ -290,6 +290,39 @@ __global__ void __launch_bounds__(SP_COLS * SP_PHASES) sum_partials_kernel(const
   }
 }
 
+// The same for a batch of jobs: blockIdx.y is the job, blockIdx.x its block of 32 columns.
+struct SumBatchArgs { SumJob job[SUM_BATCH_MAX]; };
+__global__ void __launch_bounds__(SP_COLS * SP_PHASES) sum_partials_batch_kernel(const SumBatchArgs a) {
+  __shared__ float red[SP_PHASES][SP_COLS + 1];
+  const SumJob& j = a.job[blockIdx.y];
+  const int n_partials = j.n_partials, stride = j.stride, d = j.d;
+  if ((int)blockIdx.x * SP_COLS >= stride) return;   // workgroup-uniform: this job has fewer columns than the widest
+  const float* __restrict__ partial = j.partial;
+  const int x = threadIdx.x % SP_COLS, y = threadIdx.x / SP_COLS;
+  const int c = blockIdx.x * SP_COLS + x;
+  float s = 0.f;
+  if (c < stride) {
+    int p = y;
+    for (; p + 3 * SP_PHASES < n_partials; p += 4 * SP_PHASES) {
+      const float a0 = partial[(size_t)p * stride + c], a1 = partial[(size_t)(p + SP_PHASES) * stride + c];
+      const float a2 = partial[(size_t)(p + 2 * SP_PHASES) * stride + c];
+      const float a3 = partial[(size_t)(p + 3 * SP_PHASES) * stride + c];
+      s += a0; s += a1; s += a2; s += a3;
+    }
+    for (; p < n_partials; p += SP_PHASES) s += partial[(size_t)p * stride + c];
+  }
+  red[y][x] = s;
+  __syncthreads();
+  if (y == 0 && c < stride) {
+    float t = red[0][x];
+#pragma unroll
+    for (int q = 1; q < SP_PHASES; ++q) t += red[q][x];
+    if (c < d) j.out0[c] = t;
+    else if (c < 2 * d) j.out1[c - d] = t;
+    else if (j.out2) j.out2[c - 2 * d] = t;
+  }
+}
+
 // ---- column sums -----------------------------------------------------------------------------------------
 constexpr int CS_ROWS = 256;   // rows per workgroup
 template <typename T>
@@ -598,7 +631,7 @@ size_t ln_bwd_partial_floats(int rows, int d) {
 template <typename T>
 dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const float* mean, const float* rstd,
                                    const T* resid_grad, T* dx, float* dg, float* db, float* dcol, float* partial,
-                                   int rows, int d, hipStream_t s) {
+                                   int rows, int d, hipStream_t s, SumBatch* batch) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int NIT = (sizeof(T) == 4) ? 2 * LN_MAX_IT : LN_MAX_IT;
   if (d > WAVE * VEC * NIT) return fail(DIPACO_ESHAPE, "layernorm backward: d_model above 2048");
@@ -637,9 +670,37 @@ dipaco_status launch_layernorm_bwd(const T* dy, const T* x, const T* g, const fl
   else st = run(ln_bwd_kernel<T, NIT>, 2);
   if (st != DIPACO_OK) return st;
   DIPACO_LAUNCH_CHECK();
-  const int blocks = n_blocks;
-  const int ncols = dcol ? 3 * d : 2 * d;
-  sum_partials_kernel<<<(ncols + SP_COLS - 1) / SP_COLS, SP_COLS * SP_PHASES, 0, s>>>(partial, dg, db, dcol, blocks, 3 * d, d);
+  return sum_partials(partial, dg, db, dcol, n_blocks, 3 * d, d, batch, s);
+}
+
+dipaco_status sum_partials(const float* partial, float* out0, float* out1, float* out2, int n_partials, int stride,
+                           int d, SumBatch* batch, hipStream_t s) {
+  if (batch) {
+    if (batch->count == SUM_BATCH_MAX) {
+      const dipaco_status st = flush_sum_batch(*batch, s);
+      if (st != DIPACO_OK) return st;
+    }
+    batch->job[batch->count++] = SumJob{partial, out0, out1, out2, n_partials, stride, d};
+    return DIPACO_OK;
+  }
+  // columns of a null third output are not computed
+  const int ncols = (!out2 && stride > 2 * d) ? 2 * d : stride;
+  sum_partials_kernel<<<(ncols + SP_COLS - 1) / SP_COLS, SP_COLS * SP_PHASES, 0, s>>>(partial, out0, out1, out2, n_partials, stride, d);
+  DIPACO_LAUNCH_CHECK();
+  return DIPACO_OK;
+}
+
+dipaco_status flush_sum_batch(SumBatch& batch, hipStream_t s) {
+  if (batch.count == 0) return DIPACO_OK;
+  SumBatchArgs a;
+  int widest = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    a.job[i] = batch.job[i];
+    widest = std::max(widest, batch.job[i].stride);
+  }
+  dim3 grid((widest + SP_COLS - 1) / SP_COLS, batch.count);
+  sum_partials_batch_kernel<<<grid, SP_COLS * SP_PHASES, 0, s>>>(a);
+  batch.count = 0;
   DIPACO_LAUNCH_CHECK();
   return DIPACO_OK;
 }
@@ -658,10 +719,8 @@ dipaco_status launch_colsum(const T* x, float* out, float* partial, int rows, in
   return DIPACO_OK;
 }
 
-dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s) {
-  sum_partials_kernel<<<(cols + SP_COLS - 1) / SP_COLS, SP_COLS * SP_PHASES, 0, s>>>(partial, out, out, nullptr, n_partials, cols, cols);
-  DIPACO_LAUNCH_CHECK();
-  return DIPACO_OK;
+dipaco_status launch_sum_rows(const float* partial, float* out, int n_partials, int cols, hipStream_t s, SumBatch* batch) {
+  return sum_partials(partial, out, out, nullptr, n_partials, cols, cols, batch, s);
 }
 
 dipaco_status launch_count_valid(const int* targets, int n, int* n_valid, hipStream_t s) {
@@ -763,7 +822,8 @@ dipaco_status launch_mean_pool(const T* x, float* out, int B, int S, int d, hipS
   template dipaco_status launch_layernorm_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float,  \
                                                  hipStream_t);                                                      \
   template dipaco_status launch_layernorm_bwd<T>(const T*, const T*, const T*, const float*, const float*, const T*, \
-                                                 T*, float*, float*, float*, float*, int, int, hipStream_t);        \
+                                                 T*, float*, float*, float*, float*, int, int, hipStream_t,         \
+                                                 SumBatch*);                                                        \
   template dipaco_status launch_colsum<T>(const T*, float*, float*, int, int, hipStream_t);                          \
   template dipaco_status launch_mean_pool<T>(const T*, float*, int, int, int, hipStream_t);                          \
   template dipaco_status launch_softmax_xent<T>(T*, const int*, const int*, float*, int, int, bool, hipStream_t);          \
