@@ -35,11 +35,22 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # MI355X fp32 MFMA
 PEAK_HBM_GBS = 8000.0
-# Bytes that crossed the L2 / memory-fabric boundary per launch of the forward-layout GEMM, averaged over the 49
-# launches of one config-2 step: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two runs), each scaled by what the same
-# counter reads for the plain copy kernel of known size in the same run (fetch x 2.0, write x 1.0).  The summary is
-# profiles/gemm_fwd_config2_traffic.txt; the algorithmic figure beside it is 366.3 MB per launch.
-FWD_GEMM_TRAFFIC_BYTES = 339.4e6 + 201.0e6
+TRAFFIC_PROFILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "path_step_config2_traffic.txt")
+
+
+def fwd_gemm_traffic_bytes():
+    """Bytes that crossed the L2 / memory-fabric boundary per launch of the forward-layout GEMM, averaged over its
+    launches in the config-2 step: the last line of the committed counter summary (read requests x 128 B + write
+    requests x 64 B, from two `rocprofv3 --pmc` runs; that file derives the request sizes from kernels of known
+    traffic and states the algorithmic figure, 366.2 MB, beside it).  None when the summary is not there."""
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            for line in f:
+                if line.startswith("TRAFFIC_BYTES_PER_LAUNCH_FWD_GEMM"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
 
 
 def _events(torch):
@@ -168,7 +179,7 @@ def bench_path_step(args):
                    "model_flops_utilisation": step_flops / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)},
         "roofline": {"bound": "mfma", "kernel": "gemm_dlds_kernel<bf16 out, A [M,K], B [K,N]> (forward layout)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": FWD_GEMM_TRAFFIC_BYTES, "traffic_unit": "bytes per launch (fetch + write)",
+                     "traffic": fwd_gemm_traffic_bytes(), "traffic_unit": "bytes per launch (fetch + write)",
                      "launches_per_step": len(fwd), "flops_per_launch": fwd_flops / len(fwd),
                      "avg_launch_us": gemm_ms * 1e3 / len(fwd)},
     }

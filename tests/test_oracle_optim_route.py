@@ -265,6 +265,19 @@ def test_kmeans_update_invariants():
     assert orc.kmeans_objective(z, idx, c) <= orc.kmeans_objective(z, idx, c + 1e-3 * rng.standard_normal(c.shape))
 
 
+def test_kmeans_objective_hand_value():
+    """Section 2.4.1 (k-means on the prefix features): the within-cluster squared error of three points in the plane,
+    worked by hand: (0,0) and (2,0) around (1,0) cost 1 each, (0,4) around (0,3) costs 1, (5,5) around (1,0) costs 41."""
+    z = np.array([[0.0, 0.0], [2.0, 0.0], [0.0, 4.0], [5.0, 5.0]])
+    c = np.array([[1.0, 0.0], [0.0, 3.0]])
+    assert orc.kmeans_objective(z, [0, 0, 1, 0], c) == 44.0
+    assert orc.kmeans_objective(z[:3], [0, 0, 1], c) == 3.0
+    # it is the sum over points of eq. (1)'s minimum when every point sits with its closest centroid
+    idx, _, _ = orc.route_prefix(z, c)
+    direct = sum(min((zn[0] - ck[0]) ** 2 + (zn[1] - ck[1]) ** 2 for ck in c) for zn in z)
+    assert orc.kmeans_objective(z, idx, c) == direct
+
+
 def test_lloyd_iterations_never_raise_the_objective():
     z, c0, _ = gen.gaussian_mixture(600, 16, 12, 0.3, seed=7, dtype=np.float64)
     c = c0 + 0.2 * np.random.default_rng(8).standard_normal(c0.shape)
