@@ -930,7 +930,7 @@ dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans
 }
 
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile) {
-  if (tile < 0 || tile > 10) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..10");
+  if (tile < 0 || tile > 13) return fail(DIPACO_EINVAL, "dipaco_k_set_gemm_tile: tile must be 0..13");
   set_gemm_tile(tile);
   return DIPACO_OK;
 }

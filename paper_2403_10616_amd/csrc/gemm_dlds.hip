@@ -32,8 +32,7 @@ namespace dipaco {
 
 namespace {
 
-constexpr int DL_BK = 32;
-constexpr int DL_ROWB = DL_BK * 2;                          // bytes of a K-contiguous tile row
+constexpr int DL_BK_MIN = 32;                               // K tiles are 32 or 64 deep
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
@@ -54,11 +53,14 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only:
 // multiples of 224 = 7 x 32 and not of 256: 896 columns are 4 such tiles instead of 3.5, so a launch is a whole
 // number of equal workgroups.  The 7 x 8 blocks of 32 x 32 are dealt so that every SIMD gets 14: waves 0..3 take
 // 64 rows x 128 columns, waves 4..7 the same rows x the last 96.
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP,
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP, int DL_BK,
           int TM, int TN>
 __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int lane, int wave, int rb0, int cb0, int m0,
                                                int n0, int k_begin, int nkt, int split) {
   constexpr int NW = WGM * WGN;
+  constexpr int DL_ROWB = DL_BK * 2;                        // bytes of a K-contiguous tile row: 64 or 128
+  constexpr int KS = DL_BK / 16;                            // 16-deep matrix-core steps per K tile
+  static_assert(DL_BK == 32 || DL_BK == 64, "K tiles of 32 or 64");
   constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;   // bytes of an operand tile (either kind)
   constexpr int DL_STAGE = DL_TILE_A + DL_TILE_B;
   constexpr int KROW_A = DL_BM * 2, KROW_B = DL_BN * 2;     // bytes of a K-row of a row-contiguous tile
@@ -81,8 +83,11 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
     const long ld = is_a ? g.lda : g.ldb;
     const int r0 = is_a ? m0 : n0, rtot = is_a ? g.M : g.N;
     if (is_a ? A_KC : B_KC) {
-      const int row = min(r0 + 16 * jj + (lane >> 2), rtot - 1);
-      const int chunk = (lane & 3) ^ ((lane >> 4) & 3);
+      // a wave-level load covers 16 rows of 64 bytes or 8 rows of 128 bytes (whole cache lines: half the requests)
+      constexpr int LPR = DL_ROWB / 16, RPL = 64 / LPR;     // lanes per row, rows per load
+      const int trow = RPL * jj + lane / LPR;               // row within the tile
+      const int row = min(r0 + trow, rtot - 1);
+      const int chunk = DL_BK == 32 ? (lane & 3) ^ ((trow >> 2) & 3) : (lane & 7) ^ ((trow >> 1) & 7);
       gp[i] = base + (long)row * ld + k_begin + chunk * 8;
       gstep[i] = DL_BK;
     } else {
@@ -111,8 +116,10 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
 
   // ---- fragment addresses ----
   const int r = lane & 31, h = lane >> 5;
-  const int sw = (r >> 2) & 3;
-  const int foff[2] = {r * DL_ROWB + ((0 + h) ^ sw) * 16, r * DL_ROWB + ((2 + h) ^ sw) * 16};
+  const int sw = DL_BK == 32 ? (r >> 2) & 3 : (r >> 1) & 7;
+  int foff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) foff[ks] = r * DL_ROWB + ((2 * ks + h) ^ sw) * 16;
   const int g4 = lane >> 4, ep = (lane & 15) >> 2, qp = lane & 3;
   int toffa[TM], toffb[TN];
 #pragma unroll
@@ -155,7 +162,9 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
     else if (n == 1) wait_vmcnt<LPS>();
     else wait_vmcnt<0>();
   };
-  static_assert(DL_STAGES == 3 || DL_STAGES == 4, "wait_newer handles rings of three and four");
+  static_assert(DL_STAGES >= 2 && DL_STAGES <= 4, "wait_newer handles rings of two to four");
+  static_assert(3 * LPS < 64, "the counter of outstanding loads has six bits");
+  static_assert(LPS <= NM, "a stage's loads are dealt over the MFMAs of one step");
 
   // prologue: the first DL_STAGES tiles, one per stage
 #pragma unroll
@@ -171,40 +180,50 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
     for (int q = 0; q < NR; ++q) read_frag(0, q, a_base, b_base, 0);
   }
 
-  // One K tile.  FULL: tile kt + DL_STAGES exists (steady state: no conditions).
+  // One K tile of KS matrix-core steps.  FULL: tile kt + DL_STAGES exists (steady state: no conditions).  Fragment sets
+  // alternate (KS is even, so the first step of every tile uses set 0); the fragments of step ks + 1 are read under the
+  // MFMAs of step ks; the barrier stands in front of the tile's last step, whose MFMAs cover the refill of this stage
+  // and the first fragments of the next.
   auto step = [&](auto FULL, int kt, int stage) {
     constexpr bool full = decltype(FULL)::value;
     const char* as = a_base + stage * DL_STAGE;
     const char* bs = b_base + stage * DL_STAGE;
-    if (active) {
-#pragma unroll
-      for (int m = 0; m < NM; ++m) {
-        if ((m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(1, (m * NR) / NM, as, bs, 1);
-        mfma(0, m);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    if (full) wait_vmcnt<(DL_STAGES - 2) * LPS>();
-    else wait_newer(max(nkt - 2 - kt, 0));
-    __syncthreads();
     const int nst = stage + 1 == DL_STAGES ? 0 : stage + 1;
     const char* as2 = a_base + nst * DL_STAGE;
     const char* bs2 = b_base + nst * DL_STAGE;
     const bool have_next = full || kt + 1 < nkt;
-    if (active) {
 #pragma unroll
-      for (int m = 0; m < NM; ++m) {
-        if (full && (m * LPS) % NM < LPS && (m * LPS) / NM < LPS) {
-          const int q = (m * LPS) / NM;
-          load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks + 1 < KS) {
+        if (active) {
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
+            if ((m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(nxt, (m * NR) / NM, as, bs, ks + 1);
+            mfma(cur, m);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
-        if (have_next && (m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(0, (m * NR) / NM, as2, bs2, 0);
-        mfma(1, m);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    } else if (full) {   // a wave without output still loads its share of the tiles
+      } else {
+        if (full) wait_vmcnt<(DL_STAGES - 2) * LPS>();
+        else wait_newer(max(nkt - 2 - kt, 0));
+        __syncthreads();
+        if (active) {
 #pragma unroll
-      for (int q = 0; q < LPS; ++q) load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+          for (int m = 0; m < NM; ++m) {
+            if (full && (m * LPS) % NM < LPS && (m * LPS) / NM < LPS) {
+              const int q = (m * LPS) / NM;
+              load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+            }
+            if (have_next && (m * NR) % NM < NR && (m * NR) / NM < NR) read_frag(nxt, (m * NR) / NM, as2, bs2, 0);
+            mfma(cur, m);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        } else if (full) {   // a wave without output still loads its share of the tiles
+#pragma unroll
+          for (int q = 0; q < LPS; ++q) load16_to_lds(gp[q] + (kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+        }
+      }
     }
   };
   int stage = 0, kt = 0;
@@ -224,27 +243,31 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
   // the epilogue takes column blocks of two (or one) 32-wide tiles at a time through the wave's staging region
   float* const stg = reinterpret_cast<float*>(smem) + wave * (32 * (64 + 4));
   const int row0 = m0 + rb0 * 32;
+  // (column blocks by compile-time index: a run-time loop over acc would move the accumulators to scratch memory)
+  auto block = [&](auto J0) {
+    constexpr int j0 = decltype(J0)::value;
+    if constexpr (j0 + 1 == TN) {
+      f32x16 part[TM][1];
 #pragma unroll
-  for (int j0 = 0; j0 < TN; j0 += 2) {
-    if (n0 + (cb0 + j0) * 32 >= g.N) break;   // wave-uniform
-    if constexpr (TN % 2 == 1) {
-      if (j0 + 1 == TN) {
-        f32x16 part[TM][1];
+      for (int i = 0; i < TM; ++i) part[i][0] = acc[i][j0];
+      gemm_epilogue_dispatch<TC, TM, 1, 32>(part, stg, lane, row0, n0 + (cb0 + j0) * 32, split, g);
+    } else {
+      f32x16 part[TM][2];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) part[i][0] = acc[i][j0];
-        gemm_epilogue_dispatch<TC, TM, 1, 32>(part, stg, lane, row0, n0 + (cb0 + j0) * 32, split, g);
-        break;
-      }
+      for (int i = 0; i < TM; ++i) { part[i][0] = acc[i][j0]; part[i][1] = acc[i][j0 + 1]; }
+      gemm_epilogue_dispatch<TC, TM, 2, 64>(part, stg, lane, row0, n0 + (cb0 + j0) * 32, split, g);
     }
-    f32x16 part[TM][2];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) { part[i][0] = acc[i][j0]; part[i][1] = acc[i][j0 + 1]; }
-    gemm_epilogue_dispatch<TC, TM, 2, 64>(part, stg, lane, row0, n0 + (cb0 + j0) * 32, split, g);
+  };
+  static_assert(TN >= 1 && TN <= 4, "one or two column blocks per wave");
+  block(std::integral_constant<int, 0>{});
+  if constexpr (TN > 2) {
+    if (n0 + (cb0 + 2) * 32 < g.N) block(std::integral_constant<int, 2>{});   // wave-uniform
   }
 }
 
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP>
-__global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const GemmDev g) {
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP, int DL_BK>
+__global__ void __launch_bounds__(64 * WGM * WGN, (DL_BM / (32 * WGM)) * (DL_BN / (32 * WGN)) > 8 ? 1 : 2)
+gemm_dlds_kernel(const GemmDev g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int split, tile_m, tile_n, k_begin, nkt;
@@ -270,10 +293,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
     static_assert(DL_BM == 256 && DL_BN == 256 && WGM == 2 && WGN == 4, "the 224-column tile is staged as 256 x 256");
     // waves w and w + 4 share a SIMD: 2 x 4 + 2 x 3 = 14 blocks of 32 x 32 each
     if (wave < 4)
-      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, 2, 4>(g, smem, lane, wave, 2 * wave, 0, m0,
+      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, DL_BK, 2, 4>(g, smem, lane, wave, 2 * wave, 0, m0,
                                                                                       n0, k_begin, nkt, split);
     else
-      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, 2, 3>(g, smem, lane, wave, 2 * (wave - 4), 4,
+      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, DL_BK, 2, 3>(g, smem, lane, wave, 2 * (wave - 4), 4,
                                                                                       m0, n0, k_begin, nkt, split);
   } else {
     static_assert(N_STEP == DL_BN, "tiles tile C");
@@ -283,11 +306,13 @@ __global__ void __launch_bounds__(64 * WGM * WGN, 2) gemm_dlds_kernel(const Gemm
     // every K tile of its partner's outputs was measured: no gain, the launch is not bound by that wave's latencies.)
     static_assert((WGM == 2 && (WGN == 4 || WGN == 2)) || (WGM == 1 && WGN == 8) || (WGM == 4 && WGN == 2),
                   "wave placement below is written for 2 x 4, 2 x 2, 1 x 8 and 4 x 2 waves");
-    static_assert(DL_BM / (32 * WGM) == 4 && DL_BN / (32 * WGN) == 2, "a wave owns 128 x 64 outputs");
+    constexpr int TNW = DL_BN / (32 * WGN);
+    static_assert(DL_BM / (32 * WGM) == 4 && (TNW == 2 || (TNW == 4 && WGM == 2 && WGN == 2)),
+                  "a wave owns 128 x 64 outputs (128 x 128 in the four-wave 256 x 256 shape)");
     const int wm = WGM == 1 ? 0 : WGM == 4 ? (wave & 3) : (WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1);
     const int wn = WGM == 1 ? wave : WGM == 4 ? (wave >> 2) : (WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1);
-    gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, 4, 2>(g, smem, lane, wave, 4 * wm, 2 * wn, m0, n0,
-                                                                                    k_begin, nkt, split);
+    gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, DL_BK, 4, TNW>(g, smem, lane, wave, 4 * wm, TNW * wn,
+                                                                                      m0, n0, k_begin, nkt, split);
   }
 }
 
@@ -320,7 +345,7 @@ bool plan_uneven(int M, int N, int K, int BM, int BN, int WGM, int WGN, int max_
   p.n[3] = (tiles_m - p.full_m) * (tiles_n - p.full_n);
   const double w[4] = {1.0, partial_tile_cost(am), partial_tile_cost(an), partial_tile_cost(am * an)};
   for (int c = 0; c < 4; ++c) p.cost[c] = w[c];
-  const int ktiles = K / DL_BK;
+  const int ktiles = K / DL_BK_MIN;
   for (int sf = std::min(max_slices, ktiles); sf >= 2; --sf) {
     long total = 0;
     for (int c = 0; c < 4; ++c) {
@@ -340,11 +365,11 @@ double plan_makespan(const UnevenPlan& p) {
   return worst;
 }
 
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES, int N_STEP = BN>
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES, int N_STEP = BN, int DL_BK = 32>
 dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
-  constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_ROWB;
+  constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_BK * 2;
   static_assert((size_t)WGM * WGN * 32 * (64 + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
-  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES, N_STEP>;
+  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES, N_STEP, DL_BK>;
   static std::atomic<unsigned long long> lds_set{0};   // per instantiation
   if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return e;
   GemmDev g;
@@ -426,6 +451,9 @@ dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
     if (oblong == 1) return run_dlds<TC, A_KC, B_KC, 128, 512, 1, 8, 3>(a, s);
     if (oblong == 2) return run_dlds<TC, A_KC, B_KC, 512, 128, 4, 2, 3>(a, s);
   }
+  if (g_dlds_shape == 6 && a.splits <= 1) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 2, 4>(a, s);
+  if (g_dlds_shape == 7 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64>(a, s);
+  if (g_dlds_shape == 8 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 2, 2, 256, 64>(a, s);
   const bool narrow = g_dlds_shape == 2;
   if (narrow) return run_dlds<TC, A_KC, B_KC, 256, 128, 2, 2, 3>(a, s);
   if constexpr (std::is_same<TC, bf16>::value) {
@@ -440,7 +468,7 @@ dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
 // The shapes this kernel takes: whole K tiles of 32, 16-byte rows, and at least 8 rows (columns) where the
 // operand is read along them.
 bool gemm_dlds_eligible(const GemmArgs& a) {
-  if (a.K < DL_BK || a.K % DL_BK || a.lda % 8 || a.ldb % 8) return false;
+  if (a.K < DL_BK_MIN || a.K % DL_BK_MIN || a.lda % 8 || a.ldb % 8) return false;
   if (a.trans_a && (a.M % 8 || a.M < 8)) return false;
   if (!a.trans_b && (a.N % 8 || a.N < 8)) return false;
   if (a.out_f32 ? !(a.trans_a && !a.trans_b) : a.trans_a) return false;

@@ -22,7 +22,7 @@ def _rand(shape, seed, dtype):
     return t.to(DEV), t.to(torch.float64).numpy()
 
 
-@pytest.fixture(params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], ids=lambda t: f"tile{t}")
+@pytest.fixture(params=[0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13], ids=lambda t: f"tile{t}")
 def gemm_tile(request):
     """Every workgroup tile shape must reach the same parity; 0 is the library's own choice."""
     dp.dipaco_k_set_gemm_tile(request.param)
