@@ -43,9 +43,9 @@ dipaco_status dipaco_k_gemm_colsum(int32_t dtype, int32_t trans_a, int32_t trans
  * 256x256 tiles from global memory straight into LDS, for every shape it takes (K a multiple of 32, 16-byte rows;
  * other shapes and fp32 keep the automatic choice), 6 / 7 = the same kernel with its 256x256 / 256x128 tile forced,
  * 8 / 9 = the same with 128x512 / 512x128 tiles for weight gradients (fp32 output) and 256x256 for the rest,
- * 10 = the same with tile columns every 224 wherever N is a multiple of 224 (bf16 output), 11 = its 256x256 tile on four
- * waves of 128x128 outputs (no split-K), 12 / 13 = the eight-wave / four-wave 256x256 tile with K tiles of 64 in a ring of
- * two (K a multiple of 64, no split-K).
+ * 10 = the same with tile columns every 224 wherever N is a multiple of 224 (bf16 output), 11 = its eight-wave 256x256
+ * tile with K tiles of 64 in a ring of two (K a multiple of 64, no split-K), 12 / 13 = the 256x256 tile computed with
+ * 16x16x32 matrix-core instructions, K tiles of 32 in a ring of four / of 64 in a ring of two.
  * For tests (every tile shape must give the same parity) and tuning: a process-wide switch, not a per-call setting. */
 dipaco_status dipaco_k_set_gemm_tile(int32_t tile);
 

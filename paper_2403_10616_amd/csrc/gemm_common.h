@@ -138,14 +138,36 @@ template <typename T> __device__ __forceinline__ void raw8_unpack(const Raw8<T>&
   for (int c = 0; c < 8; ++c) out[c] = to_f32(e[c]);
 }
 
+// Rows 32 i .. 32 i + 31 of a wave's accumulators into its staging region (row stride LDW floats), for the two
+// accumulator layouts: 32 x 32 tiles of v_mfma_f32_32x32x16 (lane: column l % 32, rows acc_row(e, l)) and 16 x 16 tiles
+// of v_mfma_f32_16x16x32 (lane: column l % 16, rows 4 (l / 16) + e); the latter come as [2 TM][2 TN] tiles.
+template <int LDW, int TM, int TN>
+__device__ __forceinline__ void stage_block(const f32x16 (&acc)[TM][TN], int i, float* stg, int lane) {
+  const int col_l = lane & 31;
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
+}
+template <int LDW, int TM2, int TN2>
+__device__ __forceinline__ void stage_block(const f32x4 (&acc)[TM2][TN2], int i, float* stg, int lane) {
+  const int col_l = lane & 15, row_l = 4 * (lane >> 4);
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int j = 0; j < TN2; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) stg[(16 * a + row_l + e) * LDW + 16 * j + col_l] = acc[2 * i + a][j][e];
+}
+
 // Epilogue of one wave: its TM x TN accumulator tiles (32 x 32 each, rows from row0, columns from col0) go
 // through stg, a wave-private LDS region of 32 x (WN + 4) floats, 32 rows at a time, so that bias / GELU /
 // residual are applied on, and C is written with, 16-byte row-contiguous accesses.  N is a multiple of 8 (checked
 // on the host), so an 8-column group is either inside C or outside.  The residual / auxiliary input vectors of a
 // block of 32 rows are requested one block ahead (two register buffers), so that their latency hides behind the
 // staging, arithmetic and stores of the block before.
-template <typename T, typename TC, int TM, int TN, int WN>
-__device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0, int col0,
+template <typename T, typename TC, int TM, int TN, int WN, typename ACC>
+__device__ __forceinline__ void gemm_epilogue(const ACC& acc, float* stg, int lane, int row0, int col0,
                                               int split, const GemmDev& g) {
   // The argument block lives in kernel-argument memory: every field the loops below use is read once, here, so
   // that no scalar load (and the wait for it, which also stalls the LDS traffic) is left inside them.
@@ -155,7 +177,6 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
   float* const g_cs = g.colsum_partial;
 
   constexpr int LDW = WN + 4;
-  const int col_l = lane & 31;
   constexpr int GROUPS = WN / 8;                 // 8-column groups per row
   constexpr int ITERS = 32 * GROUPS / WAVE;
   const T* bias = static_cast<const T*>(g.bias);
@@ -186,10 +207,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
   for (int i = 0; i < TM; ++i) {
     if (i + 1 < TM) prefetch(i + 1);   // in flight while block i is staged, combined and stored
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
+    stage_block<LDW>(acc, i, stg, lane);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
@@ -259,8 +277,8 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], float
 // instruction issues there (7 us of a 32 us tile at two waves per SIMD).  Here an item is straight-line code: the
 // bias vector is loaded once (a lane keeps its eight columns over all items), addresses advance by constants, and
 // the operand prefetch is fenced so that the conversion of the loaded values is not scheduled next to the load.
-template <typename TC, int TM, int TN, int WN, int ACT, bool BIAS, bool RESID, bool CS, bool PARTIAL>
-__device__ __forceinline__ void gemm_epilogue_fixed(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0,
+template <typename TC, int TM, int TN, int WN, int ACT, bool BIAS, bool RESID, bool CS, bool PARTIAL, typename ACC>
+__device__ __forceinline__ void gemm_epilogue_fixed(const ACC& acc, float* stg, int lane, int row0,
                                                     int col0, int split, const GemmDev& g) {
   using T = bf16;
   constexpr int LDW = WN + 4;
@@ -272,7 +290,6 @@ __device__ __forceinline__ void gemm_epilogue_fixed(const f32x16 (&acc)[TM][TN],
   static_assert(!PARTIAL || (ACT == 0 && !BIAS && !RESID && !CS), "split-K partial planes take no epilogue");
   const int gM = g.M, gN = g.N;
   const long ld = PARTIAL ? (long)gN : g.ldc;
-  const int col_l = lane & 31;
   const int rr0 = lane / GROUPS, cg = lane % GROUPS;
   const int col = col0 + 8 * cg;
   const bool col_ok = col < gN;
@@ -299,10 +316,7 @@ __device__ __forceinline__ void gemm_epilogue_fixed(const f32x16 (&acc)[TM][TN],
     if (AHEAD && i + 1 < TM) prefetch(i + 1);
     __builtin_amdgcn_sched_barrier(0);   // the loads above are issued here; what uses them stays below
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) stg[acc_row(e, lane) * LDW + 32 * j + col_l] = acc[i][j][e];
+    stage_block<LDW>(acc, i, stg, lane);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
@@ -358,8 +372,8 @@ __device__ __forceinline__ void gemm_epilogue_fixed(const f32x16 (&acc)[TM][TN],
 }
 
 // Picks the fixed epilogue for the combinations the training step uses; everything else takes the general one.
-template <typename TC, int TM, int TN, int WN>
-__device__ __forceinline__ void gemm_epilogue_dispatch(const f32x16 (&acc)[TM][TN], float* stg, int lane, int row0,
+template <typename TC, int TM, int TN, int WN, typename ACC>
+__device__ __forceinline__ void gemm_epilogue_dispatch(const ACC& acc, float* stg, int lane, int row0,
                                                        int col0, int split, const GemmDev& g) {
   const bool bias = g.bias != nullptr, resid = g.resid != nullptr, cs = g.colsum_partial != nullptr;
   const int act = g.act;

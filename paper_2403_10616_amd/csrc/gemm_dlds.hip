@@ -44,35 +44,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only:
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// A_KC: A is [M, K] (contiguous along K), else [K, M].  B_KC: B is [N, K], else [K, N].
-// Shapes built: 256 x 256 tiles, 2 x 4 waves, 4 stages (one workgroup per compute unit; least operand traffic, for
-// long K); 256 x 128 tiles, 2 x 2 waves, 3 stages (two workgroups per compute unit); 128 x 512 and 512 x 128 for
-// weight gradients.  In all of these a wave owns 128 x 64 outputs and two waves share a SIMD.
-// N_STEP = 224 (with DL_BN = 256), an option: the tile is staged exactly like a 256 x 256 one, but tile columns start
-// every 224 columns and only the first 224 are computed and stored.  The path's widths (896, 2688, 3584) are
-// multiples of 224 = 7 x 32 and not of 256: 896 columns are 4 such tiles instead of 3.5, so a launch is a whole
-// number of equal workgroups.  The 7 x 8 blocks of 32 x 32 are dealt so that every SIMD gets 14: waves 0..3 take
-// 64 rows x 128 columns, waves 4..7 the same rows x the last 96.
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP, int DL_BK,
-          int TM, int TN>
-__device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int lane, int wave, int rb0, int cb0, int m0,
-                                               int n0, int k_begin, int nkt, int split) {
-  constexpr int NW = WGM * WGN;
-  constexpr int DL_ROWB = DL_BK * 2;                        // bytes of a K-contiguous tile row: 64 or 128
-  constexpr int KS = DL_BK / 16;                            // 16-deep matrix-core steps per K tile
-  static_assert(DL_BK == 32 || DL_BK == 64, "K tiles of 32 or 64");
-  constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;   // bytes of an operand tile (either kind)
-  constexpr int DL_STAGE = DL_TILE_A + DL_TILE_B;
-  constexpr int KROW_A = DL_BM * 2, KROW_B = DL_BN * 2;     // bytes of a K-row of a row-contiguous tile
-  constexpr int NLA = DL_TILE_A / 1024;                     // wave-level loads of the A tile
-  constexpr int LPS = DL_STAGE / 1024 / NW;                 // wave-level loads per wave and stage
-  constexpr int NM = TM * TN, NR = TM + TN;
-  const bool active = m0 + rb0 * 32 < g.M && n0 + cb0 * 32 < g.N;   // wave-uniform
-  // ---- loads: wave-level load j fills LDS bytes [1024 j, 1024 j + 1024) of a stage; j < NLA: A tile, else B tile.
-  // Rows (columns) beyond the operand re-read its last ones: they only feed outputs that are never stored.
-  const bf16* gp[LPS];
-  long gstep[LPS];
-  uint32_t ldst[LPS];
+// Load plan of one wave: wave-level load j of a stage fills LDS bytes [1024 j, 1024 j + 1024) of it; j < NLA: A tile, else
+// B tile.  Load i of this wave is j = wave + NW i: its lane's source at K tile 0 (gp), the source's advance per K tile
+// (gstep) and the LDS address in stage 0 (ldst).  Rows (columns) beyond the operand re-read its last ones: they only
+// feed outputs that are never stored.
+template <bool A_KC, bool B_KC, int DL_BM, int DL_BN, int NW, int DL_BK, int LPS>
+__device__ __forceinline__ void dlds_load_plan(const GemmDev& g, const char* smem, int lane, int wave, int m0, int n0,
+                                               int k_begin, const bf16* (&gp)[LPS], long (&gstep)[LPS],
+                                               uint32_t (&ldst)[LPS]) {
+  constexpr int DL_ROWB = DL_BK * 2;
+  constexpr int NLA = DL_BM * DL_ROWB / 1024;
   const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
 #pragma unroll
   for (int i = 0; i < LPS; ++i) {
@@ -105,6 +86,36 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
     }
     ldst[i] = smem_base + j * 1024;
   }
+}
+
+// A_KC: A is [M, K] (contiguous along K), else [K, M].  B_KC: B is [N, K], else [K, N].
+// Shapes built: 256 x 256 tiles, 2 x 4 waves, 4 stages (one workgroup per compute unit; least operand traffic, for
+// long K); 256 x 128 tiles, 2 x 2 waves, 3 stages (two workgroups per compute unit); 128 x 512 and 512 x 128 for
+// weight gradients.  In all of these a wave owns 128 x 64 outputs and two waves share a SIMD.
+// N_STEP = 224 (with DL_BN = 256), an option: the tile is staged exactly like a 256 x 256 one, but tile columns start
+// every 224 columns and only the first 224 are computed and stored.  The path's widths (896, 2688, 3584) are
+// multiples of 224 = 7 x 32 and not of 256: 896 columns are 4 such tiles instead of 3.5, so a launch is a whole
+// number of equal workgroups.  The 7 x 8 blocks of 32 x 32 are dealt so that every SIMD gets 14: waves 0..3 take
+// 64 rows x 128 columns, waves 4..7 the same rows x the last 96.
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP, int DL_BK,
+          int TM, int TN>
+__device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int lane, int wave, int rb0, int cb0, int m0,
+                                               int n0, int k_begin, int nkt, int split) {
+  constexpr int NW = WGM * WGN;
+  constexpr int DL_ROWB = DL_BK * 2;                        // bytes of a K-contiguous tile row: 64 or 128
+  constexpr int KS = DL_BK / 16;                            // 16-deep matrix-core steps per K tile
+  static_assert(DL_BK == 32 || DL_BK == 64, "K tiles of 32 or 64");
+  constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;   // bytes of an operand tile (either kind)
+  constexpr int DL_STAGE = DL_TILE_A + DL_TILE_B;
+  constexpr int KROW_A = DL_BM * 2, KROW_B = DL_BN * 2;     // bytes of a K-row of a row-contiguous tile
+  constexpr int NLA = DL_TILE_A / 1024;                     // wave-level loads of the A tile
+  constexpr int LPS = DL_STAGE / 1024 / NW;                 // wave-level loads per wave and stage
+  constexpr int NM = TM * TN, NR = TM + TN;
+  const bool active = m0 + rb0 * 32 < g.M && n0 + cb0 * 32 < g.N;   // wave-uniform
+  const bf16* gp[LPS];
+  long gstep[LPS];
+  uint32_t ldst[LPS];
+  dlds_load_plan<A_KC, B_KC, DL_BM, DL_BN, NW, DL_BK, LPS>(g, smem, lane, wave, m0, n0, k_begin, gp, gstep, ldst);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -265,8 +276,199 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
   }
 }
 
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP, int DL_BK>
-__global__ void __launch_bounds__(64 * WGM * WGN, (DL_BM / (32 * WGM)) * (DL_BN / (32 * WGN)) > 8 ? 1 : 2)
+// The same tile pipeline on v_mfma_f32_16x16x32_bf16 (a wave's 128 x 64 outputs are 8 x 4 tiles of 16 x 16; one
+// matrix-core step is 32 deep).  On operands that are not all zero the chip sustains about 15 % more of these than of
+// the 32 x 32 x 16 shape at its power limit: half the accumulator traffic per flop.
+//   fragments: lane l holds row (column) l % 16 and K positions 8 (l / 16) .. + 7 of the step: in a K-contiguous tile
+//   that is one ds_read_b128 (chunk 4 s + l / 16 of the row, at its swizzled position); in a row-contiguous tile two
+//   transposing reads of K-rows 32 s + 8 (l / 16) + 0..3 and + 4..7.
+// Registers: the four B fragments of a step are double-buffered (the next step's are read under rows 4..7 of this
+// one); the eight A fragments pass through a window of four slots, each read three rows of MFMAs ahead of its use.
+// The barrier of a K tile stands in row 4 of its last step, behind the read of the tile's last A fragment: after it
+// the stage is refilled and every read goes to the next stage.
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int DL_BK>
+__device__ __forceinline__ void gemm_dlds_wave16(const GemmDev& g, char* smem, int lane, int wave, int rb0, int cb0, int m0,
+                                                 int n0, int k_begin, int nkt, int split) {
+  constexpr int NW = WGM * WGN;
+  constexpr int DL_ROWB = DL_BK * 2;
+  constexpr int KS = DL_BK / 32;                            // 32-deep matrix-core steps per K tile
+  static_assert(DL_BK == 32 || DL_BK == 64, "K tiles of 32 or 64");
+  constexpr int DL_TILE_A = DL_BM * DL_ROWB, DL_TILE_B = DL_BN * DL_ROWB;
+  constexpr int DL_STAGE = DL_TILE_A + DL_TILE_B;
+  constexpr int KROW_A = DL_BM * 2, KROW_B = DL_BN * 2;
+  constexpr int LPS = DL_STAGE / 1024 / NW;
+  constexpr int NA = 8, NB = 4, AHEAD = 3, SLOTS = 4;
+  static_assert(LPS <= 16, "a stage's loads are dealt over the sixteen MFMAs behind the barrier");
+  static_assert(DL_STAGES >= 2 && DL_STAGES <= 4 && 3 * LPS < 64, "ring of two to four stages; six-bit load counter");
+  const bool active = m0 + rb0 * 32 < g.M && n0 + cb0 * 32 < g.N;   // wave-uniform
+  const bf16* gp[LPS];
+  long gstep[LPS];
+  uint32_t ldst[LPS];
+  dlds_load_plan<A_KC, B_KC, DL_BM, DL_BN, NW, DL_BK, LPS>(g, smem, lane, wave, m0, n0, k_begin, gp, gstep, ldst);
+
+  f32x4 acc[NA][NB];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+
+  // ---- fragment addresses (byte offsets within a stage's A or B tile) ----
+  const int m16 = lane & 15, g4 = lane >> 4, ep = (lane & 15) >> 2, qp = lane & 3;
+  const int sw = DL_BK == 32 ? (m16 >> 2) & 3 : (m16 >> 1) & 7;
+  int koff[KS];                                             // K-contiguous tile: chunk of step s in this lane's row
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = m16 * DL_ROWB + ((4 * ks + g4) ^ sw) * 16;
+  int toffa[NA], toffb[NB];                                 // row-contiguous tile: this lane's 8 bytes of K-row 8 g4 + ep
+#pragma unroll
+  for (int q = 0; q < NA; ++q) {
+    const int blk = 2 * rb0 + q;                            // 16-row block within the tile
+    toffa[q] = (8 * g4 + ep) * KROW_A + (((blk >> 1) ^ ep) * 64) + 32 * (blk & 1) + 8 * qp;
+  }
+#pragma unroll
+  for (int q = 0; q < NB; ++q) {
+    const int blk = 2 * cb0 + q;
+    toffb[q] = (8 * g4 + ep) * KROW_B + (((blk >> 1) ^ ep) * 64) + 32 * (blk & 1) + 8 * qp;
+  }
+  const char* a_base = smem + (A_KC ? rb0 * 32 * DL_ROWB : 0);
+  const char* b_base = smem + DL_TILE_A + (B_KC ? cb0 * 32 * DL_ROWB : 0);
+  auto tr_read = [&](const char* p, int krow) {
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)p);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(uintptr_t)(uint32_t)(uintptr_t)(p + 4 * krow));
+    uint4 o;
+    o.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+    o.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+    o.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+    o.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+    return o;
+  };
+  uint4 aw[SLOTS], bf[2][NB];
+  auto read_a = [&](int q, const char* as, int ks) {        // A fragment q of step ks of the stage at `as`
+    if (A_KC) aw[q % SLOTS] = *reinterpret_cast<const uint4*>(as + q * 16 * DL_ROWB + koff[ks]);
+    else aw[q % SLOTS] = tr_read(as + toffa[q] + ks * 32 * KROW_A, KROW_A);
+  };
+  auto read_b = [&](int set, int q, const char* bs, int ks) {
+    if (B_KC) bf[set][q] = *reinterpret_cast<const uint4*>(bs + q * 16 * DL_ROWB + koff[ks]);
+    else bf[set][q] = tr_read(bs + toffb[q] + ks * 32 * KROW_B, KROW_B);
+  };
+  // own loads of every tile but the n newest have landed
+  auto wait_newer = [&](int n) {
+    if (DL_STAGES > 3 && n >= 2) wait_vmcnt<2 * LPS>();
+    else if (DL_STAGES > 2 && n == 1) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+  };
+
+  // prologue: the first DL_STAGES tiles, one per stage
+#pragma unroll
+  for (int s = 0; s < DL_STAGES; ++s)
+    if (s < nkt) {
+#pragma unroll
+      for (int i = 0; i < LPS; ++i) load16_to_lds(gp[i] + s * gstep[i], ldst[i] + s * DL_STAGE);
+    }
+  // tile 0 has landed when at most the loads of the tiles behind it are outstanding
+  if (nkt >= 4 && DL_STAGES >= 4) wait_vmcnt<3 * LPS>();
+  else if (nkt >= 3 && DL_STAGES >= 3) wait_vmcnt<2 * LPS>();
+  else if (nkt >= 2) wait_vmcnt<LPS>();
+  else wait_vmcnt<0>();
+  __syncthreads();
+  if (active) {
+#pragma unroll
+    for (int q = 0; q < NB; ++q) read_b(0, q, b_base, 0);
+#pragma unroll
+    for (int q = 0; q < AHEAD; ++q) read_a(q, a_base, 0);
+  }
+
+  // One matrix-core step (32 deep).  SET: which B buffer it multiplies with (steps alternate).  STEADY: tile
+  // kt + DL_STAGES exists, so the refill and every prefetch are unconditional.  ks: the step within its K tile.
+  auto kstep = [&](auto SETc, auto STEADYc, auto KSc, int kt, int stage) {
+    constexpr int set = decltype(SETc)::value, ks = decltype(KSc)::value;
+    constexpr bool steady = decltype(STEADYc)::value;
+    constexpr bool last = ks == KS - 1;                      // the tile's last step: barrier, refill, on to the next stage
+    const char* as = a_base + stage * DL_STAGE;
+    const char* bs = b_base + stage * DL_STAGE;
+    const int nst = stage + 1 == DL_STAGES ? 0 : stage + 1;
+    const char* as2 = last ? a_base + nst * DL_STAGE : as;   // where the next step's fragments are
+    const char* bs2 = last ? b_base + nst * DL_STAGE : bs;
+    constexpr int ks2 = last ? 0 : ks + 1;
+    const bool have_next = steady || !last || kt + 1 < nkt;
+    const bool refill = steady || kt + DL_STAGES < nkt;
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      if (active) {
+        if (i + AHEAD < NA) read_a(i + AHEAD, as, ks);
+        else if (have_next) read_a(i + AHEAD - NA, as2, ks2);
+      }
+      if (last && i == 4) {
+        // own loads of tile kt + 1 have landed: all but those of the tiles behind it that are already requested
+        if (steady) wait_vmcnt<(DL_STAGES - 2) * LPS>();
+        else wait_newer(min(DL_STAGES - 2, max(nkt - 2 - kt, 0)));
+        __syncthreads();
+      }
+      if (active) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          if (last && i >= 4) {
+            const int mm = (i - 4) * NB + j;                 // 0..15: the MFMAs behind the barrier
+            if (refill && (mm * LPS) % 16 < LPS && (mm * LPS) / 16 < LPS) {
+              const int q = (mm * LPS) / 16;
+              load16_to_lds(gp[q] + (long)(kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+            }
+          }
+          if (i >= 4 && j == 0 && have_next) read_b(set ^ 1, i - 4, bs2, ks2);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aw[i % SLOTS]),
+                                                              __builtin_bit_cast(bf16x8, bf[set][j]), acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else if (last && i == 4 && refill) {   // a wave without output still loads its share of the tiles
+#pragma unroll
+        for (int q = 0; q < LPS; ++q) load16_to_lds(gp[q] + (long)(kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+      }
+    }
+  };
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  int stage = 0, kt = 0;
+  auto next_stage = [&] { stage = stage + 1 == DL_STAGES ? 0 : stage + 1; };
+  if constexpr (KS == 2) {
+    for (; kt + DL_STAGES < nkt; ++kt) {
+      kstep(C0{}, std::true_type{}, C0{}, kt, stage);
+      kstep(C1{}, std::true_type{}, C1{}, kt, stage);
+      next_stage();
+    }
+    for (; kt < nkt; ++kt) {
+      kstep(C0{}, std::false_type{}, C0{}, kt, stage);
+      kstep(C1{}, std::false_type{}, C1{}, kt, stage);
+      next_stage();
+    }
+  } else {
+    for (; kt + 1 + DL_STAGES < nkt; kt += 2) {
+      kstep(C0{}, std::true_type{}, C0{}, kt, stage);
+      next_stage();
+      kstep(C1{}, std::true_type{}, C0{}, kt + 1, stage);
+      next_stage();
+    }
+    for (; kt < nkt; kt += 2) {
+      kstep(C0{}, std::false_type{}, C0{}, kt, stage);
+      next_stage();
+      if (kt + 1 < nkt) {
+        kstep(C1{}, std::false_type{}, C0{}, kt + 1, stage);
+        next_stage();
+      }
+    }
+  }
+
+  // every load has landed (the last steps waited for vmcnt 0); all waves are done with the ring before it is reused
+  wait_vmcnt<0>();
+  __syncthreads();
+  if (!active) return;
+  float* const stg = reinterpret_cast<float*>(smem) + wave * (32 * (64 + 4));
+  gemm_epilogue_dispatch<TC, 4, 2, 64>(acc, stg, lane, m0 + rb0 * 32, n0 + cb0 * 32, split, g);
+}
+
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int DL_BN, int WGM, int WGN, int DL_STAGES, int N_STEP, int DL_BK,
+          int MI>
+__global__ void __launch_bounds__(64 * WGM * WGN, 2)
 gemm_dlds_kernel(const GemmDev g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -307,12 +509,17 @@ gemm_dlds_kernel(const GemmDev g) {
     static_assert((WGM == 2 && (WGN == 4 || WGN == 2)) || (WGM == 1 && WGN == 8) || (WGM == 4 && WGN == 2),
                   "wave placement below is written for 2 x 4, 2 x 2, 1 x 8 and 4 x 2 waves");
     constexpr int TNW = DL_BN / (32 * WGN);
-    static_assert(DL_BM / (32 * WGM) == 4 && (TNW == 2 || (TNW == 4 && WGM == 2 && WGN == 2)),
-                  "a wave owns 128 x 64 outputs (128 x 128 in the four-wave 256 x 256 shape)");
+    static_assert(DL_BM / (32 * WGM) == 4 && TNW == 2, "a wave owns 128 x 64 outputs");
     const int wm = WGM == 1 ? 0 : WGM == 4 ? (wave & 3) : (WGN == 4 ? (wave & 1) ^ (wave >> 2) : wave >> 1);
     const int wn = WGM == 1 ? wave : WGM == 4 ? (wave >> 2) : (WGN == 4 ? 2 * (wave >> 2) + ((wave >> 1) & 1) : wave & 1);
-    gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, DL_BK, 4, TNW>(g, smem, lane, wave, 4 * wm, TNW * wn,
-                                                                                      m0, n0, k_begin, nkt, split);
+    if constexpr (MI == 16) {
+      static_assert(TNW == 2, "the 16 x 16 x 32 pipeline is written for 128 x 64 outputs per wave");
+      gemm_dlds_wave16<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, DL_BK>(g, smem, lane, wave, 4 * wm, 2 * wn, m0, n0,
+                                                                                k_begin, nkt, split);
+    } else {
+      gemm_dlds_wave<TC, A_KC, B_KC, DL_BM, DL_BN, WGM, WGN, DL_STAGES, N_STEP, DL_BK, 4, TNW>(g, smem, lane, wave, 4 * wm,
+                                                                                        TNW * wn, m0, n0, k_begin, nkt, split);
+    }
   }
 }
 
@@ -365,11 +572,12 @@ double plan_makespan(const UnevenPlan& p) {
   return worst;
 }
 
-template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES, int N_STEP = BN, int DL_BK = 32>
+template <typename TC, bool A_KC, bool B_KC, int DL_BM, int BN, int WGM, int WGN, int STAGES, int N_STEP = BN, int DL_BK = 32,
+          int MI = 32>
 dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (DL_BM + BN) * DL_BK * 2;
   static_assert((size_t)WGM * WGN * 32 * (64 + 4) * sizeof(float) <= smem, "epilogue staging fits in the ring");
-  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES, N_STEP, DL_BK>;
+  auto kern = gemm_dlds_kernel<TC, A_KC, B_KC, DL_BM, BN, WGM, WGN, STAGES, N_STEP, DL_BK, MI>;
   static std::atomic<unsigned long long> lds_set{0};   // per instantiation
   if (dipaco_status e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_set)) return e;
   GemmDev g;
@@ -410,8 +618,10 @@ dipaco_status run_dlds(const GemmArgs& a, hipStream_t s) {
   return DIPACO_OK;
 }
 
-// 0 = automatic, 1 = 256 x 256, 2 = 256 x 128, 3 / 4 = 128 x 512 / 512 x 128 (weight gradients only), 5 = 224-column tiles
-// wherever N is a multiple of 224.  A process-wide test and tuning hook.
+// 0 = automatic (the 16 x 16 x 32 pipeline), 1 = 256 x 256 and 2 = 256 x 128 on the 32 x 32 x 16 pipeline, 3 / 4 = 128 x 512 /
+// 512 x 128 forced for weight gradients, 5 = 224-column tiles wherever N is a multiple of 224, 6 = K tiles of 64 on the
+// 32 x 32 x 16 pipeline, 7 / 8 = the 16 x 16 x 32 pipeline with K tiles of 32 only / of 64 where K allows.  A process-wide
+// test and tuning hook.
 std::atomic<int> g_dlds_shape{0};
 
 // Weight gradients with a side that is not a multiple of 256 (896 = 7 x 128): 128 x 512 tiles of 1 x 8 waves, or
@@ -446,21 +656,25 @@ int oblong_plan_wins(const GemmArgs& a) {
 // 256 x 256 shape.
 template <typename TC, bool A_KC, bool B_KC>
 dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
+  const int shape = g_dlds_shape;
+  // forced shapes of the 32 x 32 x 16 pipeline (tests and comparisons)
+  if (shape == 1) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4>(a, s);
+  if (shape == 2) return run_dlds<TC, A_KC, B_KC, 256, 128, 2, 2, 3>(a, s);
+  if constexpr (std::is_same<TC, bf16>::value) {
+    if (shape == 5 && a.splits <= 1 && a.N % 224 == 0 && gemm_epilogue_is_fixed(a.act, a.bias, a.resid, a.colsum))
+      return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4, 224>(a, s);
+    if (shape == 6 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64>(a, s);
+  }
+  // the 16 x 16 x 32 pipeline: oblong tiles for the weight gradients whose plan they shorten; K tiles of 64 in a ring of
+  // two wherever K allows and the product is not cut along K (whole cache lines per request; measured 2-5 % ahead of the
+  // ring of four K tiles of 32 on every product of the step), else K tiles of 32 in a ring of four
   if constexpr (std::is_same<TC, float>::value) {
     const int oblong = oblong_plan_wins(a);
-    if (oblong == 1) return run_dlds<TC, A_KC, B_KC, 128, 512, 1, 8, 3>(a, s);
-    if (oblong == 2) return run_dlds<TC, A_KC, B_KC, 512, 128, 4, 2, 3>(a, s);
+    if (oblong == 1) return run_dlds<TC, A_KC, B_KC, 128, 512, 1, 8, 3, 512, 32, 16>(a, s);
+    if (oblong == 2) return run_dlds<TC, A_KC, B_KC, 512, 128, 4, 2, 3, 128, 32, 16>(a, s);
   }
-  if (g_dlds_shape == 6 && a.splits <= 1) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 2, 4>(a, s);
-  if (g_dlds_shape == 7 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64>(a, s);
-  if (g_dlds_shape == 8 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 2, 2, 256, 64>(a, s);
-  const bool narrow = g_dlds_shape == 2;
-  if (narrow) return run_dlds<TC, A_KC, B_KC, 256, 128, 2, 2, 3>(a, s);
-  if constexpr (std::is_same<TC, bf16>::value) {
-    if (g_dlds_shape == 5 && a.splits <= 1 && a.N % 224 == 0 && gemm_epilogue_is_fixed(a.act, a.bias, a.resid, a.colsum))
-      return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4, 224>(a, s);
-  }
-  return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4>(a, s);
+  if (shape != 7 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64, 16>(a, s);
+  return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4, 256, 32, 16>(a, s);
 }
 
 }  // namespace
