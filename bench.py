@@ -781,10 +781,26 @@ def bench_gemm(args):
     ms = e0.elapsed_time(e1) / args.steps
     flops = 2.0 * M * N * K
     ach = flops / (ms * 1e-3) / 1e12
+    library = None
+    if args.library_reference and not out_f32 and ep == "none":
+        # context, not a target: the vendor library's product of the same operands on the same box (no epilogue)
+        a2 = a.view(K, M).t() if ta else a.view(M, K)
+        b2 = b.view(N, K).t() if tb else b.view(K, N)
+        for _ in range(args.warmup):
+            torch.matmul(a2, b2)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            torch.matmul(a2, b2)
+        e1.record()
+        torch.cuda.synchronize()
+        lib_ms = e0.elapsed_time(e1) / args.steps
+        library = {"ms": lib_ms, "tflops": flops / (lib_ms * 1e-3) / 1e12, "what": "torch.matmul (vendor GEMM library)"}
     return {"metric": "GEMM TFLOP/s on 1 MI355X", "value": ach, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"gemm {args.layout} M={M} N={N} K={K} epilogue={ep} splits={splits} operands={args.operands}"},
+            "config": {"workload": f"gemm {args.layout} M={M} N={N} K={K} epilogue={ep} splits={splits} operands={args.operands}",
+                       "library_reference": library},
             "roofline": {"bound": "mfma", "kernel": "gemm_kernel", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                          "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "flops_per_launch": flops}}
 
@@ -810,12 +826,22 @@ def bench_issue_probe(args):
             e1.record()
             torch.cuda.synchronize()
             table[f"{waves} waves/SIMD: {names[mode]}"] = round(e0.elapsed_time(e1) * 1e6 / iters, 1)
+    # the two bf16 matrix-core shapes at the chip's power limit (two waves per SIMD, 60000 iterations = some 30 ms each)
+    shapes = {}
+    for mode, name in ((5, "32x32x16 zeros"), (7, "16x16x32 zeros"), (6, "32x32x16 random"), (8, "16x16x32 random")):
+        dp.dipaco_k_issue_probe(mode, 2, 2000, out)
+        torch.cuda.synchronize()
+        e0.record()
+        dp.dipaco_k_issue_probe(mode, 2, 60000, out)
+        e1.record()
+        torch.cuda.synchronize()
+        shapes[name] = round(256 * 8 * 60000 * 524288.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
     ratio = table["4 waves/SIMD: 16 MFMA then 256 FMA"] / (table["4 waves/SIMD: 16 MFMA"] + table["4 waves/SIMD: 256 FMA"])
     return {"metric": "time of (16 MFMA then 256 FMA) over the sum of the two alone, 4 waves per SIMD", "value": ratio,
             "unit": "ratio", "n_gpus": 1, "steps": iters, "warmup": 100, "ms_per_step": None, "higher_is_better": False,
             "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "instruction-issue probe: one workgroup per compute unit, no memory traffic",
-                       "ns_per_iteration": table}}
+                       "ns_per_iteration": table, "mfma_shape_tflops": shapes}}
 
 
 def bench_attention(args):
@@ -833,6 +859,9 @@ def bench_attention(args):
     qkv = torch.empty(B * S * 3 * A, dtype=torch.bfloat16, device=dev).normal_()
     o = torch.empty(B * S * A, dtype=torch.bfloat16, device=dev)
     d_o = torch.empty(B * S * A, dtype=torch.bfloat16, device=dev).normal_()
+    if args.operands == "zeros":          # the same launches on all-zero inputs: what the chip's power limit costs
+        qkv.zero_()
+        d_o.zero_()
     dqkv = torch.empty(B * S * 3 * A, dtype=torch.bfloat16, device=dev)
     lse = torch.empty(B * H * S, dtype=torch.float32, device=dev)
     dsum = torch.empty(2 * B * H * ((S + 127) // 128 * 128), dtype=torch.float32, device=dev)
@@ -876,6 +905,8 @@ def main():
     ap.add_argument("--layout", default="nn", choices=["nn", "nt", "tn"])
     ap.add_argument("--epilogue", default="none", choices=["none", "bias", "gelu", "dgelu", "resid"])
     ap.add_argument("--operands", default="normal", choices=["normal", "zeros"])
+    ap.add_argument("--library-reference", action="store_true",
+                    help="gemm workload, no epilogue, bf16 output: also time torch.matmul on the same operands (context)")
     ap.add_argument("--splits", type=int, default=1)
     ap.add_argument("--gemm-tile", type=int, default=0, help="gemm / path_step workloads: force a tile shape (dipaco_k_set_gemm_tile)")
     ap.add_argument("--pass", default="fwd", choices=["fwd", "bwd"])

@@ -80,9 +80,13 @@ dipaco_status dipaco_k_attention_bwd(int32_t dtype, const void* qkv, const void*
  * 256 * waves_per_simd threads per compute unit (256 workgroups) runs `iters` iterations of
  *   mode 0: 16 v_mfma_f32_32x32x16_bf16 on four independent accumulators;   mode 1: 256 independent v_fma_f32;
  *   mode 2: the 16 MFMA, then the 256 FMA;   mode 3: sixteen times (1 MFMA, 16 FMA) in program order;
- *   mode 4: 256 times (v_exp_f32, multiply, add).
- * The caller times the launch.  out: device fp32, 256 * 256 * waves_per_simd elements, overwritten (keeps the loops
- * alive).  mode in 0..4, waves_per_simd in 1..4, iters >= 1, else DIPACO_EINVAL. */
+ *   mode 4: 256 times (v_exp_f32, multiply, add);
+ *   modes 5..8 (always 512 threads per workgroup, two waves per SIMD; waves_per_simd is ignored): what the chip sustains
+ *   of the two bf16 matrix-core shapes, a wave's 128 x 64 outputs computed 32 deep per iteration (524,288 flop per wave
+ *   and iteration) from operands held in registers: 5 / 6 = v_mfma_f32_32x32x16_bf16 on all-zero / pseudo-random
+ *   operands, 7 / 8 = v_mfma_f32_16x16x32_bf16 likewise (the GEMM kernel's choice of shape rests on 6 against 8).
+ * The caller times the launch.  out: device fp32, 256 * 256 * waves_per_simd elements (at least 256 * 512 for modes
+ * 5..8), overwritten (keeps the loops alive).  mode in 0..8, waves_per_simd in 1..4, iters >= 1, else DIPACO_EINVAL. */
 dipaco_status dipaco_k_issue_probe(int32_t mode, int32_t waves_per_simd, int32_t iters, float* out, void* stream);
 
 #ifdef __cplusplus

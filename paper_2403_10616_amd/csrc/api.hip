@@ -948,8 +948,8 @@ dipaco_status dipaco_k_set_attention_blocks(int32_t single_block) {
 }
 
 dipaco_status dipaco_k_issue_probe(int32_t mode, int32_t waves_per_simd, int32_t iters, float* out, void* stream) {
-  if (mode < 0 || mode > 4 || waves_per_simd < 1 || waves_per_simd > 4 || iters < 1 || !out)
-    return fail(DIPACO_EINVAL, "dipaco_k_issue_probe: mode 0..4, waves_per_simd 1..4, iters >= 1, out not NULL");
+  if (mode < 0 || mode > 8 || waves_per_simd < 1 || waves_per_simd > 4 || iters < 1 || !out)
+    return fail(DIPACO_EINVAL, "dipaco_k_issue_probe: mode 0..8, waves_per_simd 1..4, iters >= 1, out not NULL");
   return launch_issue_probe(mode, waves_per_simd, iters, out, static_cast<hipStream_t>(stream));
 }
 

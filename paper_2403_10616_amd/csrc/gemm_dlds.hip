@@ -665,15 +665,18 @@ dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
       return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4, 224>(a, s);
     if (shape == 6 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64>(a, s);
   }
-  // the 16 x 16 x 32 pipeline: oblong tiles for the weight gradients whose plan they shorten; K tiles of 64 in a ring of
-  // two wherever K allows and the product is not cut along K (whole cache lines per request; measured 2-5 % ahead of the
-  // ring of four K tiles of 32 on every product of the step), else K tiles of 32 in a ring of four
+  // the 16 x 16 x 32 pipeline: oblong tiles for the weight gradients whose plan they shorten; else K tiles of 64 in a ring
+  // of two wherever K allows (whole cache lines per request, half the barriers; measured 2-5 % ahead of the ring of four
+  // K tiles of 32 on every product of the step), else K tiles of 32 in a ring of four.  Measured on this pipeline and left
+  // out: the 256 x 128 tile with two workgroups per compute unit (3-20 % behind on every product), and four waves of
+  // 128 x 128 outputs, one per SIMD, which read a third less from LDS (12-20 % behind: one wave per SIMD does not cover
+  // its own LDS and barrier latencies)
   if constexpr (std::is_same<TC, float>::value) {
     const int oblong = oblong_plan_wins(a);
     if (oblong == 1) return run_dlds<TC, A_KC, B_KC, 128, 512, 1, 8, 3, 512, 32, 16>(a, s);
     if (oblong == 2) return run_dlds<TC, A_KC, B_KC, 512, 128, 4, 2, 3, 128, 32, 16>(a, s);
   }
-  if (shape != 7 && a.splits <= 1 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64, 16>(a, s);
+  if (shape != 7 && a.K % 64 == 0) return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 2, 256, 64, 16>(a, s);
   return run_dlds<TC, A_KC, B_KC, 256, 256, 2, 4, 4, 256, 32, 16>(a, s);
 }
 
