@@ -9,10 +9,12 @@
 //     ds_read_b128, free of bank conflicts for the lane groups the LDS serves together.
 //   * operand contiguous along its rows ([K, rows] in memory: the forward weights, both operands of a weight
 //     gradient): tile K-row t is 512 bytes = 8 segments of 32 rows; segment s sits at segment position
-//     s ^ (t & 3).  Fragments are read with ds_read_b64_tr_b16, which transposes 4 x 4 halfword blocks across
-//     each group of 16 lanes: when lane 4e+q of a group points at rows 4q..4q+3 of K-row T(e), lane i receives
-//     row i of K-rows T(0..3).  Two such reads (K-rows 8h+0..3 and 8h+4..7 of the 16-deep step) build the same
-//     8-deep fragment a K-contiguous operand gives, so any mix of the two kinds multiplies correctly.
+//     s ^ (t & 3), and K-rows whose index has bit 3 set keep the two 16-row halves of every segment swapped (the
+//     sixteen-lane groups of one fragment read then fall on different banks in both pipelines below).  Fragments
+//     are read with ds_read_b64_tr_b16, which transposes 4 x 4 halfword blocks across each group of 16 lanes: when
+//     lane 4e+q of a group points at rows 4q..4q+3 of K-row T(e), lane i receives row i of K-rows T(0..3).  Two such
+//     reads (K-rows 8h+0..3 and 8h+4..7) build the same 8-deep fragment a K-contiguous operand gives, so any mix of
+//     the two kinds multiplies correctly.
 // No operand passes through registers on its way to LDS, which leaves room for the 256 x 256 accumulator at two
 // waves per SIMD and lets loads run three K tiles ahead.
 //
@@ -80,7 +82,8 @@ __device__ __forceinline__ void dlds_load_plan(const GemmDev& g, const char* sme
       const int t = (64 >> sh) * jj + (lane >> sh);
       const int cp = lane & ((1 << sh) - 1);
       const int seg = (cp >> 2) ^ (t & 3);
-      const int col = min(r0 + (seg * 4 + (cp & 3)) * 8, rtot - 8);
+      const int c4 = (cp & 3) ^ (((t >> 3) & 1) << 1);       // K-rows 8..15 (mod 16) keep their 16-row halves swapped
+      const int col = min(r0 + (seg * 4 + c4) * 8, rtot - 8);
       gp[i] = base + (long)(k_begin + t) * ld + col;
       gstep[i] = (long)DL_BK * ld;
     }
@@ -135,10 +138,10 @@ __device__ __forceinline__ void gemm_dlds_wave(const GemmDev& g, char* smem, int
   int toffa[TM], toffb[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
-    toffa[i] = (8 * (g4 >> 1) + ep) * KROW_A + (((rb0 + i) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+    toffa[i] = (8 * (g4 >> 1) + ep) * KROW_A + (((rb0 + i) ^ ep) * 64) + 32 * ((g4 & 1) ^ (g4 >> 1)) + 8 * qp;
 #pragma unroll
   for (int j = 0; j < TN; ++j)
-    toffb[j] = (8 * (g4 >> 1) + ep) * KROW_B + (((cb0 + j) ^ ep) * 64) + 32 * (g4 & 1) + 8 * qp;
+    toffb[j] = (8 * (g4 >> 1) + ep) * KROW_B + (((cb0 + j) ^ ep) * 64) + 32 * ((g4 & 1) ^ (g4 >> 1)) + 8 * qp;
   const char* a_base = smem + (A_KC ? rb0 * 32 * DL_ROWB : 0);
   const char* b_base = smem + DL_TILE_A + (B_KC ? cb0 * 32 * DL_ROWB : 0);
   uint4 fa[2][TM], fb[2][TN];
@@ -324,12 +327,12 @@ __device__ __forceinline__ void gemm_dlds_wave16(const GemmDev& g, char* smem, i
 #pragma unroll
   for (int q = 0; q < NA; ++q) {
     const int blk = 2 * rb0 + q;                            // 16-row block within the tile
-    toffa[q] = (8 * g4 + ep) * KROW_A + (((blk >> 1) ^ ep) * 64) + 32 * (blk & 1) + 8 * qp;
+    toffa[q] = (8 * g4 + ep) * KROW_A + (((blk >> 1) ^ ep) * 64) + 32 * ((blk ^ g4) & 1) + 8 * qp;
   }
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
     const int blk = 2 * cb0 + q;
-    toffb[q] = (8 * g4 + ep) * KROW_B + (((blk >> 1) ^ ep) * 64) + 32 * (blk & 1) + 8 * qp;
+    toffb[q] = (8 * g4 + ep) * KROW_B + (((blk >> 1) ^ ep) * 64) + 32 * ((blk ^ g4) & 1) + 8 * qp;
   }
   const char* a_base = smem + (A_KC ? rb0 * 32 * DL_ROWB : 0);
   const char* b_base = smem + DL_TILE_A + (B_KC ? cb0 * 32 * DL_ROWB : 0);
