@@ -1,12 +1,15 @@
 // bf16 matrix-core GEMM whose operand tiles go from global memory straight into LDS (gfx950's 16-byte
 // global_load_lds), for all three operand layouts of the path step.
 //
-// Tile 256 x 256, K tile 32, a ring of 4 LDS stages of 32 KB (A tile | B tile).  One wave-level load writes 1024
+// Tile 256 x 256 (A tile | B tile per stage), eight waves of 128 x 64 outputs, and a ring of LDS stages: K tiles of 32
+// in a ring of four stages of 32 KB, or K tiles of 64 in a ring of two of 64 KB.  One wave-level load writes 1024
 // consecutive LDS bytes (lane l writes bytes [16 l, 16 l + 16)), so the LDS layout is linear in the lane and
 // every permutation is applied on the global side, by choosing which 16 bytes a lane fetches:
-//   * operand contiguous along K ([rows, K] in memory): tile row r is 64 bytes = 4 chunks; chunk c sits at chunk
-//     position c ^ ((r >> 2) & 3).  A fragment of v_mfma_f32_32x32x16_bf16 (lane l: row l%32, K half l/32) is one
-//     ds_read_b128, free of bank conflicts for the lane groups the LDS serves together.
+//   * operand contiguous along K ([rows, K] in memory): tile row r is 64 bytes = 4 chunks, chunk c at chunk position
+//     c ^ ((r >> 2) & 3) (K tile 32), or 128 bytes = 8 chunks = one whole cache line per row and request, chunk c at
+//     c ^ ((r >> 1) & 7) (K tile 64).  A fragment is one ds_read_b128, free of bank conflicts for the lane groups
+//     the LDS serves together: lane l reads row l % 32, K half l / 32 of a 16-deep step for v_mfma_f32_32x32x16_bf16,
+//     row l % 16, K quarter l / 16 of a 32-deep step for v_mfma_f32_16x16x32_bf16.
 //   * operand contiguous along its rows ([K, rows] in memory: the forward weights, both operands of a weight
 //     gradient): tile K-row t is 512 bytes = 8 segments of 32 rows; segment s sits at segment position
 //     s ^ (t & 3), and K-rows whose index has bit 3 set keep the two 16-row halves of every segment swapped (the
@@ -16,13 +19,16 @@
 //     reads (K-rows 8h+0..3 and 8h+4..7) build the same 8-deep fragment a K-contiguous operand gives, so any mix of
 //     the two kinds multiplies correctly.
 // No operand passes through registers on its way to LDS, which leaves room for the 256 x 256 accumulator at two
-// waves per SIMD and lets loads run three K tiles ahead.
+// waves per SIMD and lets loads run up to three K tiles ahead.
 //
-// Pipeline of one K tile (one barrier): [fragments of the tile's second half are read under the MFMAs of its
-// first half] -> own loads of the next tile have landed (s_waitcnt vmcnt) -> barrier (everybody's have, and
-// everybody is done reading this stage) -> [this stage is refilled with the tile four ahead and the next tile's
-// first fragments are read, both under the MFMAs of the second half].  The loads are inline assembly: written
-// with the builtin, the compiler puts a full vmcnt(0) in front of every later LDS read, which serialises the ring.
+// Two pipelines share all of this and the epilogues: gemm_dlds_wave16 on v_mfma_f32_16x16x32_bf16, the default (the
+// chip sustains about 15 % more of that shape at its power limit), and gemm_dlds_wave on v_mfma_f32_32x32x16_bf16,
+// kept as a tested option.  Pipeline of one K tile in the latter (one barrier): [fragments of the tile's second half
+// are read under the MFMAs of its first half] -> own loads of the next tile have landed (s_waitcnt vmcnt) -> barrier
+// (everybody's have, and everybody is done reading this stage) -> [this stage is refilled with the tile one ring
+// ahead and the next tile's first fragments are read, both under the MFMAs of the second half]; the former is
+// described at its function.  The loads are inline assembly: written with the builtin, the compiler puts a full
+// vmcnt(0) in front of every later LDS read, which serialises the ring.
 #include <algorithm>
 #include <cmath>
 #include <type_traits>
