@@ -48,6 +48,10 @@ typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
 __device__ __forceinline__ void load16_to_lds(const bf16* gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
 }
+// the same with a wave-uniform base address (scalar registers) and a 32-bit per-lane byte offset
+__device__ __forceinline__ void load16_to_lds_at(const char* base, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
+}
 template <int N> __device__ __forceinline__ void wait_vmcnt() {   // vmcnt only: expcnt and lgkmcnt fields at maximum
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
@@ -95,6 +99,53 @@ __device__ __forceinline__ void dlds_load_plan(const GemmDev& g, const char* sme
     }
     ldst[i] = smem_base + j * 1024;
   }
+}
+
+// The same plan with wave-uniform bases: a lane keeps one 32-bit byte offset per load (its place inside the operand, K
+// tile 0), the operand's base and its advance per K tile are scalars, so a load costs no vector address arithmetic.
+// Offsets stay below 2^32: rows x row stride x 2 of a K-contiguous operand is checked on the host.
+struct DldsBases {
+  const char* a;      // operand A at this product's first K position
+  const char* b;
+  long adv_a, adv_b;  // bytes per K tile
+};
+template <bool A_KC, bool B_KC, int DL_BM, int DL_BN, int NW, int DL_BK, int LPS>
+__device__ __forceinline__ DldsBases dlds_load_plan_s(const GemmDev& g, const char* smem, int lane, int wave, int m0, int n0,
+                                                      int k_begin, uint32_t (&off)[LPS], uint32_t (&ldst)[LPS]) {
+  constexpr int DL_ROWB = DL_BK * 2;
+  constexpr int NLA = DL_BM * DL_ROWB / 1024;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+  DldsBases o;
+  o.a = static_cast<const char*>(g.A) + (A_KC ? (long)k_begin : (long)k_begin * g.lda) * 2;
+  o.b = static_cast<const char*>(g.B) + (B_KC ? (long)k_begin : (long)k_begin * g.ldb) * 2;
+  o.adv_a = A_KC ? DL_ROWB : (long)DL_BK * g.lda * 2;
+  o.adv_b = B_KC ? DL_ROWB : (long)DL_BK * g.ldb * 2;
+#pragma unroll
+  for (int i = 0; i < LPS; ++i) {
+    const int j = wave + NW * i;
+    const bool is_a = j < NLA;
+    const int jj = is_a ? j : j - NLA;
+    const uint32_t ld = (uint32_t)(is_a ? g.lda : g.ldb);
+    const int r0 = is_a ? m0 : n0, rtot = is_a ? g.M : g.N;
+    if (is_a ? A_KC : B_KC) {
+      constexpr int LPR = DL_ROWB / 16, RPL = 64 / LPR;
+      const int trow = RPL * jj + lane / LPR;
+      const int row = min(r0 + trow, rtot - 1);
+      const int chunk = DL_BK == 32 ? (lane & 3) ^ ((trow >> 2) & 3) : (lane & 7) ^ ((trow >> 1) & 7);
+      off[i] = ((uint32_t)row * ld + (uint32_t)chunk * 8u) * 2u;
+    } else {
+      constexpr int SH_A = DL_BM == 512 ? 6 : (DL_BM == 256 ? 5 : 4), SH_B = DL_BN == 512 ? 6 : (DL_BN == 256 ? 5 : 4);
+      const int sh = is_a ? SH_A : SH_B;
+      const int t = (64 >> sh) * jj + (lane >> sh);
+      const int cp = lane & ((1 << sh) - 1);
+      const int seg = (cp >> 2) ^ (t & 3);
+      const int c4 = (cp & 3) ^ (((t >> 3) & 1) << 1);
+      const int col = min(r0 + (seg * 4 + c4) * 8, rtot - 8);
+      off[i] = ((uint32_t)t * ld + (uint32_t)col) * 2u;
+    }
+    ldst[i] = smem_base + j * 1024;
+  }
+  return o;
 }
 
 // A_KC: A is [M, K] (contiguous along K), else [K, M].  B_KC: B is [N, K], else [K, N].
@@ -310,10 +361,15 @@ __device__ __forceinline__ void gemm_dlds_wave16(const GemmDev& g, char* smem, i
   static_assert(LPS <= 16, "a stage's loads are dealt over the sixteen MFMAs behind the barrier");
   static_assert(DL_STAGES >= 2 && DL_STAGES <= 4 && 3 * LPS < 64, "ring of two to four stages; six-bit load counter");
   const bool active = m0 + rb0 * 32 < g.M && n0 + cb0 * 32 < g.N;   // wave-uniform
-  const bf16* gp[LPS];
-  long gstep[LPS];
-  uint32_t ldst[LPS];
-  dlds_load_plan<A_KC, B_KC, DL_BM, DL_BN, NW, DL_BK, LPS>(g, smem, lane, wave, m0, n0, k_begin, gp, gstep, ldst);
+  constexpr int NLA = DL_TILE_A / 1024;
+  uint32_t off[LPS], ldst[LPS];
+  const DldsBases bases = dlds_load_plan_s<A_KC, B_KC, DL_BM, DL_BN, NW, DL_BK, LPS>(g, smem, lane, wave, m0, n0, k_begin, off, ldst);
+  // load q of this wave for K tile kt into `stage` (which operand it belongs to is wave-uniform)
+  auto issue = [&](int q, int kt, int stage) {
+    const bool is_a = wave + NW * q < NLA;
+    const char* base = (is_a ? bases.a : bases.b) + (long)kt * (is_a ? bases.adv_a : bases.adv_b);
+    load16_to_lds_at(base, off[q], ldst[q] + stage * DL_STAGE);
+  };
 
   f32x4 acc[NA][NB];
 #pragma unroll
@@ -373,7 +429,7 @@ __device__ __forceinline__ void gemm_dlds_wave16(const GemmDev& g, char* smem, i
   for (int s = 0; s < DL_STAGES; ++s)
     if (s < nkt) {
 #pragma unroll
-      for (int i = 0; i < LPS; ++i) load16_to_lds(gp[i] + s * gstep[i], ldst[i] + s * DL_STAGE);
+      for (int i = 0; i < LPS; ++i) issue(i, s, s);
     }
   // tile 0 has landed when at most the loads of the tiles behind it are outstanding
   if (nkt >= 4 && DL_STAGES >= 4) wait_vmcnt<3 * LPS>();
@@ -421,7 +477,7 @@ __device__ __forceinline__ void gemm_dlds_wave16(const GemmDev& g, char* smem, i
             const int mm = (i - 4) * NB + j;                 // 0..15: the MFMAs behind the barrier
             if (refill && (mm * LPS) % 16 < LPS && (mm * LPS) / 16 < LPS) {
               const int q = (mm * LPS) / 16;
-              load16_to_lds(gp[q] + (long)(kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+              issue(q, kt + DL_STAGES, stage);
             }
           }
           if (i >= 4 && j == 0 && have_next) read_b(set ^ 1, i - 4, bs2, ks2);
@@ -431,7 +487,7 @@ __device__ __forceinline__ void gemm_dlds_wave16(const GemmDev& g, char* smem, i
         }
       } else if (last && i == 4 && refill) {   // a wave without output still loads its share of the tiles
 #pragma unroll
-        for (int q = 0; q < LPS; ++q) load16_to_lds(gp[q] + (long)(kt + DL_STAGES) * gstep[q], ldst[q] + stage * DL_STAGE);
+        for (int q = 0; q < LPS; ++q) issue(q, kt + DL_STAGES, stage);
       }
     }
   };
@@ -698,6 +754,11 @@ bool gemm_dlds_eligible(const GemmArgs& a) {
   if (a.trans_a && (a.M % 8 || a.M < 8)) return false;
   if (!a.trans_b && (a.N % 8 || a.N < 8)) return false;
   if (a.out_f32 ? !(a.trans_a && !a.trans_b) : a.trans_a) return false;
+  // 32-bit per-lane offsets into an operand: (rows - 1) x row stride + K tile of a K-contiguous one, 64 K-rows of a
+  // row-contiguous one
+  const long span_a = a.trans_a ? 64 * a.lda + a.M : (long)a.M * a.lda;
+  const long span_b = a.trans_b ? (long)a.N * a.ldb : 64 * a.ldb + a.N;
+  if (span_a >= (1L << 31) || span_b >= (1L << 31)) return false;
   return true;
 }
 
