@@ -734,8 +734,8 @@ dipaco_status run_dlds_shape(const GemmArgs& a, hipStream_t s) {
   // of two wherever K allows (whole cache lines per request, half the barriers; measured 2-5 % ahead of the ring of four
   // K tiles of 32 on every product of the step), else K tiles of 32 in a ring of four.  Measured on this pipeline and left
   // out: the 256 x 128 tile with two workgroups per compute unit (3-20 % behind on every product), and four waves of
-  // 128 x 128 outputs, one per SIMD, which read a third less from LDS (12-20 % behind: one wave per SIMD does not cover
-  // its own LDS and barrier latencies)
+  // 128 x 128 outputs, one per SIMD, which read a third less from LDS (5-20 % behind, the smaller figure with the
+  // accumulators pinned to the accumulation registers: one wave per SIMD does not cover its own LDS and barrier latencies)
   if constexpr (std::is_same<TC, float>::value) {
     const int oblong = oblong_plan_wins(a);
     if (oblong == 1) return run_dlds<TC, A_KC, B_KC, 128, 512, 1, 8, 3, 512, 32, 16>(a, s);
