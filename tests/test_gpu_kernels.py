@@ -34,7 +34,10 @@ def gemm_tile(request):
 GEMM_SHAPES = [(128, 128, 64), (200, 136, 72), (1, 8, 8), (300, 264, 520), (64, 512, 1000), (520, 776, 160),
                (257, 8, 32),
                # widths that are multiples of 224: the tile shape with columns every 224 takes them (tile 10)
-               (300, 448, 544), (520, 224, 160), (257, 896, 64)]
+               (300, 448, 544), (520, 224, 160), (257, 896, 64),
+               # short contractions around the depth of the LDS rings (K tiles of 64 in a ring of two, of 32 in a ring of
+               # four): one to five K tiles of either size, so that every prologue / steady / tail split runs
+               (130, 72, 128), (300, 264, 192), (264, 520, 320), (200, 136, 96), (72, 264, 384)]
 
 
 @pytest.mark.parametrize("dtype", [dp.F32, dp.BF16])
