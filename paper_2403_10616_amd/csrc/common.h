@@ -84,14 +84,16 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
 // reciprocal and one exponential, and the exponential exp(-u^2 / 2) is the one the derivative's density term needs.
 // The lower tail is formed as 0.5 erfc(z) directly, without cancellation.
 __device__ __forceinline__ void normal_cdf_fast(float u, float& cdf, float& gauss) {
-  const float z = fabsf(u) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
-  float poly = __builtin_fmaf(t, 1.061405429f, -1.453152027f);
-  poly = __builtin_fmaf(poly, t, 1.421413741f);
-  poly = __builtin_fmaf(poly, t, -0.284496736f);
-  poly = __builtin_fmaf(poly, t, 0.254829592f);
-  gauss = __builtin_amdgcn_exp2f(z * z * -1.4426950408889634f);   // exp(-u^2 / 2)
-  const float q = 0.5f * poly * t * gauss;                        // 0.5 erfc(|u| / sqrt 2)
+  // constants folded: t = 1 / (1 + p |u| / sqrt 2); the polynomial carries the factor 0.5; exp(-u^2 / 2) = 2^(-w^2) with
+  // w = u sqrt(log2(e) / 2)
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(fabsf(u), 0.3275911f * 0.70710678118654752f, 1.0f));
+  float poly = __builtin_fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+  poly = __builtin_fmaf(poly, t, 0.5f * 1.421413741f);
+  poly = __builtin_fmaf(poly, t, 0.5f * -0.284496736f);
+  poly = __builtin_fmaf(poly, t, 0.5f * 0.254829592f);
+  const float w = u * 0.84932180028801904f;                       // sqrt(log2(e) / 2)
+  gauss = __builtin_amdgcn_exp2f(-(w * w));                       // exp(-u^2 / 2)
+  const float q = poly * t * gauss;                               // 0.5 erfc(|u| / sqrt 2)
   cdf = u >= 0.f ? 1.0f - q : q;
 }
 template <typename T> __device__ __forceinline__ float gelu_t(float u);
